@@ -1,0 +1,166 @@
+/*
+ * libpatconv -- pattern-sparse 3x3 convolution for training on AMD MI355X (gfx950).
+ *
+ * C ABI of the data-parallel hot path of ClickTrain (arXiv 2011.10170): every kept 3x3
+ * kernel retains exactly 4 of its 9 taps, chosen from a small pattern pool, and connectivity
+ * pruning removes whole kernels (Section 2, "Fine-grained pattern-based pruning").
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are caller-owned DEVICE memory on the context's GPU (for example a
+ *     torch tensor's data_ptr()). The library never frees them and does not keep them after
+ *     the stream-ordered work of the call has run. Pointers named *_host are HOST memory and
+ *     are copied before the call returns.
+ *   - pc_ctx and pc_packed are library-owned handles, released by pc_destroy / pc_packed_free
+ *     (both accept NULL).
+ *   - Work is enqueued on the context's HIP stream and is asynchronous to the host unless
+ *     stated. One context per host thread; calls on one context must not overlap.
+ *   - Arguments are validated on the host before anything is launched. Errors are return
+ *     codes only; pc_last_error() gives a message for the last failure on that context.
+ *   - Kernel tap index t = 3*r + s (kernel row r, column s, spatial offset (r-1, s-1)).
+ *     A pattern is a 9-bit mask with bit t set when tap t is kept; exactly 4 bits are set.
+ *   - Weights W and their gradient G are float32 [F][C][3][3] (= [F][C][9]).
+ *     Activations are NHWC: x, dx [N][H][W][C]; y, dy [N][Ho][Wo][F]; Ho = (H-1)/stride + 1,
+ *     Wo likewise (3x3 window, zero padding 1, stride 1 or 2). Their element type is
+ *     desc.dtype: float32, or bfloat16 with float32 accumulation.
+ *   - Non-finite inputs give unspecified results.
+ */
+#ifndef PATCONV_PC_H
+#define PATCONV_PC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pc_ctx pc_ctx;
+typedef struct pc_packed pc_packed;
+
+typedef enum {
+    PC_OK = 0,
+    PC_ERR_INVALID_ARG = 1,   /* null pointer, negative count, handle/descriptor mismatch */
+    PC_ERR_BAD_LIBRARY = 2,   /* P outside 1..126, a mask >= 512, popcount != 4, duplicate masks */
+    PC_ERR_BAD_SHAPE = 3,     /* N,H,W,C,F < 1, C or F > 65535, stride not 1 or 2 */
+    PC_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for */
+    PC_ERR_NOMEM = 5,         /* device or host allocation failed */
+    PC_ERR_DEVICE = 6         /* a HIP call failed (no GPU, launch failure, ...) */
+} pc_status;
+
+typedef enum { PC_F32 = 0, PC_BF16 = 1 } pc_dtype;
+
+/* Which kernels connectivity pruning keeps (Section 4.3 asks for a user-set number of
+ * unimportant kernels per layer; Section 5.2 asks that every filter keeps the same number):
+ * PER_FILTER keeps the n_keep best kernels of every filter, PER_LAYER the n_keep best of the layer. */
+typedef enum { PC_KEEP_PER_FILTER = 0, PC_KEEP_PER_LAYER = 1 } pc_keep_mode;
+
+/* Score that ranks kernels: RETAINED = Eq. 1 evaluated at the chosen pattern (importance that
+ * survives the hard prune); KERNEL = Eq. 2 (all 9 taps). */
+typedef enum { PC_SCORE_RETAINED = 0, PC_SCORE_KERNEL = 1 } pc_score_mode;
+
+/* Kernel family used by the three conv passes of a packed layer. */
+typedef enum {
+    PC_VARIANT_AUTO = 0,  /* chosen at pack time from dtype and shape */
+    PC_VARIANT_VALU = 1,  /* pattern-grouped gather on the vector ALUs: only kept taps are multiplied */
+    PC_VARIANT_MFMA = 2   /* bf16 only: matrix-core contraction over tap-major zero-filled weight tiles */
+} pc_variant;
+
+typedef struct {
+    int32_t N, H, W, C, F;
+    int32_t stride;        /* 1 or 2 */
+    pc_dtype dtype;        /* element type of x, y, dy, dx */
+} pc_conv_desc;
+
+/* ---- context ---------------------------------------------------------------------------- */
+
+/* Creates a context on HIP device `device`. hip_stream is a hipStream_t the caller owns
+ * (NULL = the default stream); all later work of this context is enqueued there.
+ * Fails with PC_ERR_DEVICE when the device cannot be used. */
+pc_status pc_create(pc_ctx **out, int device, void *hip_stream);
+void pc_destroy(pc_ctx *ctx);
+const char *pc_status_str(pc_status s);
+const char *pc_last_error(const pc_ctx *ctx);
+
+/* Forces the kernel family for later pc_pack / pc_conv_* calls on this context (default AUTO).
+ * PC_VARIANT_MFMA on a layer it cannot serve makes pc_pack return PC_ERR_UNSUPPORTED. */
+pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
+
+/* Host-only argument checks (usable without a GPU). */
+pc_status pc_check_library(const uint16_t *lib_host, int32_t P);
+pc_status pc_check_conv_desc(const pc_conv_desc *desc);
+
+/* ---- pattern and kernel selection (Section 4.1, Eq. 1 and Eq. 2) ------------------------- */
+
+/* For every kernel (f,c): tap importance s_t = (g_t*w_t)^2 (G_dev == NULL: s_t = w_t^2, the
+ * magnitude criterion); pattern importance I_p = sum of s_t over the 4 taps of pattern p;
+ * pid[f][c] = the pool index with the largest I_p (lowest index on ties), written for every
+ * kernel. keep[f][c] = 1 for the n_keep kernels with the largest ranking score of their filter
+ * (PER_FILTER, 0 <= n_keep <= C) or of the layer (PER_LAYER, 0 <= n_keep <= F*C), equal scores
+ * ordered by lower index; else 0.
+ * Arithmetic is float32 in a fixed order without fused multiply-add, so results are
+ * reproducible bit for bit: s_t = (g*w)*(g*w); I_p = ((s_a+s_b)+s_c)+s_d for taps a<b<c<d;
+ * Eq. 2 adds s_0..s_8 left to right.
+ *   W_dev, G_dev : float32 [F][C][9] device (G_dev may be NULL)
+ *   lib_host     : uint16 [P] host, the pattern pool
+ *   pid_dev, keep_dev : uint8 [F][C] device, outputs */
+pc_status pc_pattern_select(pc_ctx *ctx, const float *W_dev, const float *G_dev,
+                            int32_t F, int32_t C, const uint16_t *lib_host, int32_t P,
+                            pc_keep_mode keep_mode, int64_t n_keep, pc_score_mode score_mode,
+                            uint8_t *pid_dev, uint8_t *keep_dev);
+
+/* ---- packing (Section 5.1: fixed index arrays generated once, values gathered from the
+ *      dense weight tensor; the hard prune W (.) M of Section 6) -------------------------- */
+
+/* Builds the compact layout of one layer from its dense weights and the selection result:
+ * a filter-major table of the kept kernels (per filter ordered by pattern id, then channel,
+ * with per-pattern group offsets), a channel-major table for the backward-data pass, the
+ * 4 kept weights of every kept kernel (rounded to bf16, nearest-even, when compute_dtype is
+ * PC_BF16), and for the MFMA variant tap-major zero-filled bf16 weight tiles.
+ * Compact slot order (used by dw_compact and pc_scatter_dense): filters ascending; inside a
+ * filter by pattern id, then by channel; the 4 entries of a slot are the kept taps in
+ * ascending tap index.
+ * *out == NULL: a new handle is allocated (device memory sized for F*C kernels).
+ * *out != NULL: that handle is re-packed in place; it must have the same F, C and dtype.
+ * pid/keep values are trusted to be < P and 0/1. */
+pc_status pc_pack(pc_ctx *ctx, const float *W_dev, const uint8_t *pid_dev, const uint8_t *keep_dev,
+                  int32_t F, int32_t C, const uint16_t *lib_host, int32_t P,
+                  pc_dtype compute_dtype, pc_packed **out);
+
+/* Re-gathers the kept weights from a dense tensor with unchanged tables (the per-iteration
+ * dense-to-sparse conversion of Section 5.1). */
+pc_status pc_update_values(pc_ctx *ctx, pc_packed *pk, const float *W_dev);
+
+/* nnz_kernels = number of kept kernels (waits for the pack to finish); variant = family in use. */
+pc_status pc_packed_info(pc_ctx *ctx, const pc_packed *pk, int64_t *nnz_kernels, int32_t *variant);
+void pc_packed_free(pc_packed *pk);
+
+/* Expands a compact [nnz_kernels][4] float32 array to dense [F][C][9] float32 with zeros at
+ * every pruned position. */
+pc_status pc_scatter_dense(pc_ctx *ctx, const pc_packed *pk, const float *compact_dev, float *dense_dev);
+
+/* Writes the hard-pruned weights W (.) M as dense [F][C][9] float32 (values as stored in the
+ * pack, i.e. bf16-rounded for a bf16 pack). */
+pc_status pc_unpack_dense(pc_ctx *ctx, const pc_packed *pk, float *dense_dev);
+
+/* ---- the three passes (Section 5.2, forward and backward phase) -------------------------- */
+
+/* y[n,oy,ox,f] = sum over kept (c,t) of filter f of x[n, oy*stride+r-1, ox*stride+s-1, c] * w[f,c,t]
+ * (zero padding, no bias). */
+pc_status pc_conv_fwd(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
+                      const void *x_dev, void *y_dev);
+
+/* dx = dy (*) rot180(W): dx[n,iy,ix,c] = sum over kept (f,t) of channel c with
+ * (iy+1-r) and (ix+1-s) divisible by stride and in range of
+ * dy[n,(iy+1-r)/stride,(ix+1-s)/stride,f] * w[f,c,t]. The activation derivative is not applied. */
+pc_status pc_conv_bwd_data(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
+                           const void *dy_dev, void *dx_dev);
+
+/* Weight gradient at kept taps only, float32 [nnz_kernels][4] in compact slot order:
+ * dw[f,c,t] = sum_{n,oy,ox} dy[n,oy,ox,f] * x[n, oy*stride+r-1, ox*stride+s-1, c].
+ * Deterministic: no floating-point atomics. */
+pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
+                             const void *x_dev, const void *dy_dev, float *dw_compact_dev);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PATCONV_PC_H */

@@ -1,0 +1,180 @@
+"""ctypes binding of libpatconv.so: the same entry points as include/pc.h, argument marshalling only.
+
+Device buffers are passed as anything with a ``data_ptr()`` method (torch tensors on the context's
+GPU) or as integer addresses. Nothing here computes: every step runs in the library's kernels.
+There is no fallback: if the library is missing, load() raises.
+"""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpatconv.so")
+
+PC_OK = 0
+PC_ERR_INVALID_ARG, PC_ERR_BAD_LIBRARY, PC_ERR_BAD_SHAPE, PC_ERR_UNSUPPORTED, PC_ERR_NOMEM, PC_ERR_DEVICE = range(1, 7)
+PC_F32, PC_BF16 = 0, 1
+PC_KEEP_PER_FILTER, PC_KEEP_PER_LAYER = 0, 1
+PC_SCORE_RETAINED, PC_SCORE_KERNEL = 0, 1
+PC_VARIANT_AUTO, PC_VARIANT_VALU, PC_VARIANT_MFMA = 0, 1, 2
+
+EXPORTS = [
+    "pc_create", "pc_destroy", "pc_status_str", "pc_last_error", "pc_set_variant",
+    "pc_check_library", "pc_check_conv_desc", "pc_pattern_select", "pc_pack", "pc_update_values",
+    "pc_packed_info", "pc_packed_free", "pc_scatter_dense", "pc_unpack_dense",
+    "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
+]
+
+
+class pc_conv_desc(ct.Structure):
+    _fields_ = [("N", ct.c_int32), ("H", ct.c_int32), ("W", ct.c_int32), ("C", ct.c_int32), ("F", ct.c_int32),
+                ("stride", ct.c_int32), ("dtype", ct.c_int)]
+
+
+class PcError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("libpatconv status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Loads libpatconv.so. Raises if it has not been built (paper_2011_10170_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libpatconv.so is not built: run `python -m paper_2011_10170_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = ct.CDLL(LIB_PATH)
+    vp, i32, i64 = ct.c_void_p, ct.c_int32, ct.c_int64
+    lib.pc_create.argtypes = [ct.POINTER(vp), ct.c_int, vp]
+    lib.pc_destroy.argtypes = [vp]
+    lib.pc_destroy.restype = None
+    lib.pc_status_str.argtypes = [ct.c_int]
+    lib.pc_status_str.restype = ct.c_char_p
+    lib.pc_last_error.argtypes = [vp]
+    lib.pc_last_error.restype = ct.c_char_p
+    lib.pc_set_variant.argtypes = [vp, ct.c_int]
+    lib.pc_check_library.argtypes = [vp, i32]
+    lib.pc_check_conv_desc.argtypes = [ct.POINTER(pc_conv_desc)]
+    lib.pc_pattern_select.argtypes = [vp, vp, vp, i32, i32, vp, i32, ct.c_int, i64, ct.c_int, vp, vp]
+    lib.pc_pack.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, ct.c_int, ct.POINTER(vp)]
+    lib.pc_update_values.argtypes = [vp, vp, vp]
+    lib.pc_packed_info.argtypes = [vp, vp, ct.POINTER(i64), ct.POINTER(i32)]
+    lib.pc_packed_free.argtypes = [vp]
+    lib.pc_packed_free.restype = None
+    lib.pc_scatter_dense.argtypes = [vp, vp, vp, vp]
+    lib.pc_unpack_dense.argtypes = [vp, vp, vp]
+    lib.pc_conv_fwd.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp]
+    lib.pc_conv_bwd_data.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp]
+    lib.pc_conv_bwd_weight.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp, vp]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if name not in ("pc_destroy", "pc_packed_free", "pc_status_str", "pc_last_error"):
+            fn.restype = ct.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return int(t)
+
+
+def _lib_arr(masks: Sequence[int]):
+    arr = (ct.c_uint16 * len(masks))(*[int(m) for m in masks])
+    return arr
+
+
+def _check(ctx, status: int):
+    if status != PC_OK:
+        lib = load()
+        msg = lib.pc_status_str(status).decode()
+        if ctx:
+            detail = lib.pc_last_error(ctx).decode()
+            if detail:
+                msg += " (" + detail + ")"
+        raise PcError(status, msg)
+
+
+def make_desc(N, H, W, C, F, stride, dtype) -> pc_conv_desc:
+    return pc_conv_desc(int(N), int(H), int(W), int(C), int(F), int(stride), int(dtype))
+
+
+def pc_create(device: int = 0, hip_stream: Optional[int] = None) -> int:
+    ctx = ct.c_void_p()
+    _check(None, load().pc_create(ct.byref(ctx), int(device), hip_stream))
+    return ctx.value
+
+
+def pc_destroy(ctx) -> None:
+    load().pc_destroy(ctx)
+
+
+def pc_set_variant(ctx, variant: int) -> None:
+    _check(ctx, load().pc_set_variant(ctx, int(variant)))
+
+
+def pc_check_library(masks: Sequence[int]) -> int:
+    return load().pc_check_library(ct.cast(_lib_arr(masks), ct.c_void_p), len(masks))
+
+
+def pc_check_conv_desc(desc: pc_conv_desc) -> int:
+    return load().pc_check_conv_desc(ct.byref(desc))
+
+
+def pc_pattern_select(ctx, W, G, F, C, masks, keep_mode, n_keep, score_mode, pid, keep) -> None:
+    arr = _lib_arr(masks)
+    _check(ctx, load().pc_pattern_select(ctx, _ptr(W), _ptr(G), int(F), int(C), ct.cast(arr, ct.c_void_p), len(masks),
+                                         int(keep_mode), int(n_keep), int(score_mode), _ptr(pid), _ptr(keep)))
+
+
+def pc_pack(ctx, W, pid, keep, F, C, masks, compute_dtype, reuse: Optional[int] = None) -> int:
+    arr = _lib_arr(masks)
+    out = ct.c_void_p(reuse)
+    _check(ctx, load().pc_pack(ctx, _ptr(W), _ptr(pid), _ptr(keep), int(F), int(C), ct.cast(arr, ct.c_void_p),
+                               len(masks), int(compute_dtype), ct.byref(out)))
+    return out.value
+
+
+def pc_update_values(ctx, pk, W) -> None:
+    _check(ctx, load().pc_update_values(ctx, pk, _ptr(W)))
+
+
+def pc_packed_info(ctx, pk):
+    nnz = ct.c_int64()
+    var = ct.c_int32()
+    _check(ctx, load().pc_packed_info(ctx, pk, ct.byref(nnz), ct.byref(var)))
+    return nnz.value, var.value
+
+
+def pc_packed_free(pk) -> None:
+    load().pc_packed_free(pk)
+
+
+def pc_scatter_dense(ctx, pk, compact, dense) -> None:
+    _check(ctx, load().pc_scatter_dense(ctx, pk, _ptr(compact), _ptr(dense)))
+
+
+def pc_unpack_dense(ctx, pk, dense) -> None:
+    _check(ctx, load().pc_unpack_dense(ctx, pk, _ptr(dense)))
+
+
+def pc_conv_fwd(ctx, desc, pk, x, y) -> None:
+    _check(ctx, load().pc_conv_fwd(ctx, ct.byref(desc), pk, _ptr(x), _ptr(y)))
+
+
+def pc_conv_bwd_data(ctx, desc, pk, dy, dx) -> None:
+    _check(ctx, load().pc_conv_bwd_data(ctx, ct.byref(desc), pk, _ptr(dy), _ptr(dx)))
+
+
+def pc_conv_bwd_weight(ctx, desc, pk, x, dy, dw_compact) -> None:
+    _check(ctx, load().pc_conv_bwd_weight(ctx, ct.byref(desc), pk, _ptr(x), _ptr(dy), _ptr(dw_compact)))

@@ -1,0 +1,372 @@
+// Host side of libpatconv: argument validation, handles, dispatch. No kernels here.
+#include <stdarg.h>
+#include <stdlib.h>
+
+#include <new>
+
+#include "pc_internal.h"
+
+// ------------------------------------------------------------------ errors
+pc_status pc_fail(pc_ctx *ctx, pc_status s, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return s;
+}
+
+pc_status pc_hip_check(pc_ctx *ctx, hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return PC_OK;
+    pc_status s = (e == hipErrorOutOfMemory) ? PC_ERR_NOMEM : PC_ERR_DEVICE;
+    return pc_fail(ctx, s, "%s: %s", what, hipGetErrorString(e));
+}
+
+extern "C" const char *pc_status_str(pc_status s)
+{
+    switch (s) {
+    case PC_OK: return "ok";
+    case PC_ERR_INVALID_ARG: return "invalid argument";
+    case PC_ERR_BAD_LIBRARY: return "bad pattern library";
+    case PC_ERR_BAD_SHAPE: return "bad shape";
+    case PC_ERR_UNSUPPORTED: return "unsupported";
+    case PC_ERR_NOMEM: return "out of memory";
+    case PC_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+extern "C" const char *pc_last_error(const pc_ctx *ctx) { return ctx ? ctx->err : "no context"; }
+
+// ------------------------------------------------------------------ host-only checks
+extern "C" pc_status pc_check_library(const uint16_t *lib, int32_t P)
+{
+    if (!lib) return PC_ERR_INVALID_ARG;
+    if (P < 1 || P > PC_MAX_P) return PC_ERR_BAD_LIBRARY;
+    for (int i = 0; i < P; ++i) {
+        if (lib[i] >= 512 || __builtin_popcount(lib[i]) != 4) return PC_ERR_BAD_LIBRARY;
+        for (int j = 0; j < i; ++j)
+            if (lib[j] == lib[i]) return PC_ERR_BAD_LIBRARY;
+    }
+    return PC_OK;
+}
+
+extern "C" pc_status pc_check_conv_desc(const pc_conv_desc *d)
+{
+    if (!d) return PC_ERR_INVALID_ARG;
+    if (d->N < 1 || d->H < 1 || d->W < 1 || d->C < 1 || d->F < 1) return PC_ERR_BAD_SHAPE;
+    if (d->C > 65535 || d->F > 65535) return PC_ERR_BAD_SHAPE;
+    if (d->stride != 1 && d->stride != 2) return PC_ERR_BAD_SHAPE;
+    if (d->dtype != PC_F32 && d->dtype != PC_BF16) return PC_ERR_INVALID_ARG;
+    // flat element indices are computed in 64 bits; per-image extents must fit 32 bits
+    if ((int64_t)d->H * d->W * d->C >= (1ll << 31) || (int64_t)d->H * d->W * d->F >= (1ll << 31))
+        return PC_ERR_BAD_SHAPE;
+    return PC_OK;
+}
+
+void pc_fill_lib(LibArg *la, const uint16_t *lib, int P)
+{
+    memset(la, 0, sizeof(*la));
+    la->P = P;
+    for (int i = 0; i < P; ++i) {
+        la->mask[i] = lib[i];
+        int j = 0;
+        for (int t = 0; t < 9; ++t)
+            if (lib[i] & (1u << t)) la->taps[i][j++] = (uint8_t)t;
+    }
+}
+
+// ------------------------------------------------------------------ context
+extern "C" pc_status pc_create(pc_ctx **out, int device, void *hip_stream)
+{
+    if (!out) return PC_ERR_INVALID_ARG;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return PC_ERR_DEVICE;
+    if (hipSetDevice(device) != hipSuccess) return PC_ERR_DEVICE;
+    pc_ctx *ctx = new (std::nothrow) pc_ctx();
+    if (!ctx) return PC_ERR_NOMEM;
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->forced = PC_VARIANT_AUTO;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) { delete ctx; return PC_ERR_DEVICE; }
+    ctx->num_cu = prop.multiProcessorCount;
+    if (hipHostMalloc((void **)&ctx->nnz_pinned, sizeof(int64_t), hipHostMallocDefault) != hipSuccess) {
+        delete ctx;
+        return PC_ERR_NOMEM;
+    }
+    *out = ctx;
+    return PC_OK;
+}
+
+extern "C" void pc_destroy(pc_ctx *ctx)
+{
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->scratch) (void)hipFree(ctx->scratch);
+    if (ctx->nnz_pinned) (void)hipHostFree(ctx->nnz_pinned);
+    delete ctx;
+}
+
+extern "C" pc_status pc_set_variant(pc_ctx *ctx, pc_variant v)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (v != PC_VARIANT_AUTO && v != PC_VARIANT_VALU && v != PC_VARIANT_MFMA)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_set_variant: unknown variant %d", (int)v);
+    ctx->forced = v;
+    return PC_OK;
+}
+
+pc_status pc_scratch(pc_ctx *ctx, size_t bytes, void **out)
+{
+    if (bytes > ctx->scratch_bytes) {
+        // earlier work on the stream may still read the old buffer
+        PC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (ctx->scratch) PC_HIP(ctx, hipFree(ctx->scratch));
+        ctx->scratch = nullptr;
+        ctx->scratch_bytes = 0;
+        size_t want = bytes + bytes / 4 + (1u << 20);
+        PC_HIP(ctx, hipMalloc(&ctx->scratch, want));
+        ctx->scratch_bytes = want;
+    }
+    *out = ctx->scratch;
+    return PC_OK;
+}
+
+// ------------------------------------------------------------------ select
+extern "C" pc_status pc_pattern_select(pc_ctx *ctx, const float *W, const float *G, int32_t F, int32_t C,
+                                       const uint16_t *lib, int32_t P, pc_keep_mode km, int64_t n_keep,
+                                       pc_score_mode sm, uint8_t *pid, uint8_t *keep)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (!W || !pid || !keep || !lib) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select: null pointer");
+    if (F < 1 || C < 1 || F > 65535 || C > 65535)
+        return pc_fail(ctx, PC_ERR_BAD_SHAPE, "pc_pattern_select: F=%d C=%d out of range", F, C);
+    pc_status s = pc_check_library(lib, P);
+    if (s != PC_OK) return pc_fail(ctx, s, "pc_pattern_select: bad library (P=%d)", P);
+    if (km != PC_KEEP_PER_FILTER && km != PC_KEEP_PER_LAYER)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select: keep_mode %d", (int)km);
+    if (sm != PC_SCORE_RETAINED && sm != PC_SCORE_KERNEL)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select: score_mode %d", (int)sm);
+    int64_t lim = (km == PC_KEEP_PER_FILTER) ? (int64_t)C : (int64_t)F * C;
+    if (n_keep < 0 || n_keep > lim)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select: n_keep %lld outside 0..%lld",
+                       (long long)n_keep, (long long)lim);
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    LibArg la;
+    pc_fill_lib(&la, lib, P);
+    return pc_launch_select(ctx, W, G, F, C, la, km, n_keep, sm, pid, keep);
+}
+
+// ------------------------------------------------------------------ pack
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Carves the slab. With base == nullptr only the size is computed.
+static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
+{
+    size_t off = 0;
+    size_t cap = (size_t)F * C;
+    auto take = [&](size_t bytes) {
+        char *p = base ? base + off : nullptr;
+        off = align_up(off + bytes, 256);
+        return p;
+    };
+    v->F = F;
+    v->C = C;
+    v->Fp = (F + 31) / 32 * 32;
+    v->Cp = (C + 31) / 32 * 32;
+    v->fm_rowptr = (int32_t *)take(sizeof(int32_t) * (F + 1));
+    v->fm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)F * (PC_MAX_P + 1));
+    v->fm_c = (uint16_t *)take(sizeof(uint16_t) * cap);
+    v->fm_pid = (uint8_t *)take(cap);
+    v->slot_f = (uint16_t *)take(sizeof(uint16_t) * cap);
+    v->fm_val = (float4 *)take(sizeof(float4) * cap);
+    v->slot_of = (int32_t *)take(sizeof(int32_t) * cap);
+    v->cm_rowptr = (int32_t *)take(sizeof(int32_t) * (C + 1));
+    v->cm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)C * (PC_MAX_P + 1));
+    v->cm_f = (uint16_t *)take(sizeof(uint16_t) * cap);
+    v->cm_slot = (int32_t *)take(sizeof(int32_t) * cap);
+    v->cm_val = (float4 *)take(sizeof(float4) * cap);
+    if (mfma) {
+        size_t tile = sizeof(uint16_t) * 9 * (size_t)v->Fp * v->Cp;
+        v->wz_fwd = (uint16_t *)take(tile);
+        v->wz_bwd = (uint16_t *)take(tile);
+    } else {
+        v->wz_fwd = v->wz_bwd = nullptr;
+    }
+    return off;
+}
+
+extern "C" void pc_packed_free(pc_packed *pk)
+{
+    if (!pk) return;
+    (void)hipSetDevice(pk->device);
+    if (pk->packed_evt) {
+        (void)hipEventSynchronize(pk->packed_evt);
+        (void)hipEventDestroy(pk->packed_evt);
+    }
+    (void)hipDeviceSynchronize();
+    if (pk->slab) (void)hipFree(pk->slab);
+    delete pk;
+}
+
+extern "C" pc_status pc_pack(pc_ctx *ctx, const float *W, const uint8_t *pid, const uint8_t *keep,
+                             int32_t F, int32_t C, const uint16_t *lib, int32_t P, pc_dtype dt, pc_packed **out)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (!W || !pid || !keep || !lib || !out) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack: null pointer");
+    if (F < 1 || C < 1 || F > 65535 || C > 65535)
+        return pc_fail(ctx, PC_ERR_BAD_SHAPE, "pc_pack: F=%d C=%d out of range", F, C);
+    if (dt != PC_F32 && dt != PC_BF16) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack: dtype %d", (int)dt);
+    pc_status s = pc_check_library(lib, P);
+    if (s != PC_OK) return pc_fail(ctx, s, "pc_pack: bad library (P=%d)", P);
+
+    int variant;
+    bool can_mfma = (dt == PC_BF16) && pc_mfma_supports(F, C);
+    if (ctx->forced == PC_VARIANT_MFMA) {
+        if (!can_mfma)
+            return pc_fail(ctx, PC_ERR_UNSUPPORTED, "pc_pack: MFMA variant needs bf16 and supported F=%d C=%d", F, C);
+        variant = PC_VARIANT_MFMA;
+    } else if (ctx->forced == PC_VARIANT_VALU) {
+        variant = PC_VARIANT_VALU;
+    } else {
+        variant = can_mfma ? PC_VARIANT_MFMA : PC_VARIANT_VALU;
+    }
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+
+    pc_packed *pk = *out;
+    if (pk) {
+        if (pk->v.F != F || pk->v.C != C || pk->dtype != dt || pk->device != ctx->device)
+            return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack: handle was packed for another layer shape or dtype");
+        if (variant == PC_VARIANT_MFMA && !pk->v.wz_fwd) variant = PC_VARIANT_VALU;  // no tiles in this slab
+    } else {
+        pk = new (std::nothrow) pc_packed();
+        if (!pk) return pc_fail(ctx, PC_ERR_NOMEM, "pc_pack: host allocation failed");
+        memset(pk, 0, sizeof(*pk));
+        pk->device = ctx->device;
+        pk->dtype = dt;
+        bool tiles = (dt == PC_BF16) && pc_mfma_supports(F, C);
+        pk->slab_bytes = carve(&pk->v, nullptr, F, C, tiles);
+        hipError_t e = hipMalloc(&pk->slab, pk->slab_bytes);
+        if (e != hipSuccess) {
+            delete pk;
+            return pc_hip_check(ctx, e, "pc_pack: hipMalloc");
+        }
+        carve(&pk->v, (char *)pk->slab, F, C, tiles);
+        if (hipEventCreateWithFlags(&pk->packed_evt, hipEventDisableTiming) != hipSuccess) {
+            (void)hipFree(pk->slab);
+            delete pk;
+            return pc_fail(ctx, PC_ERR_DEVICE, "pc_pack: event creation failed");
+        }
+    }
+    pk->variant = variant;
+    pk->v.P = P;
+    pk->nnzk = -1;
+    memcpy(pk->lib, lib, sizeof(uint16_t) * P);
+    LibArg la;
+    pc_fill_lib(&la, lib, P);
+    memcpy(pk->taps, la.taps, sizeof(pk->taps));
+    s = pc_launch_pack(ctx, pk, W, pid, keep);
+    if (s == PC_OK) s = pc_hip_check(ctx, hipEventRecord(pk->packed_evt, ctx->stream), "hipEventRecord");
+    if (s != PC_OK) {
+        if (!*out) pc_packed_free(pk);
+        return s;
+    }
+    *out = pk;
+    return PC_OK;
+}
+
+extern "C" pc_status pc_update_values(pc_ctx *ctx, pc_packed *pk, const float *W)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (!pk || !W) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_update_values: null pointer");
+    if (pk->device != ctx->device) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_update_values: other device");
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    return pc_launch_update_values(ctx, pk, W);
+}
+
+extern "C" pc_status pc_packed_info(pc_ctx *ctx, const pc_packed *pk, int64_t *nnz, int32_t *variant)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (!pk) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_packed_info: null handle");
+    if (nnz) {
+        pc_packed *m = const_cast<pc_packed *>(pk);
+        if (m->nnzk < 0) {
+            PC_HIP(ctx, hipSetDevice(ctx->device));
+            PC_HIP(ctx, hipEventSynchronize(pk->packed_evt));
+            int32_t n = 0;
+            PC_HIP(ctx, hipMemcpy(&n, pk->v.fm_rowptr + pk->v.F, sizeof(int32_t), hipMemcpyDeviceToHost));
+            m->nnzk = n;
+        }
+        *nnz = m->nnzk;
+    }
+    if (variant) *variant = pk->variant;
+    return PC_OK;
+}
+
+extern "C" pc_status pc_scatter_dense(pc_ctx *ctx, const pc_packed *pk, const float *compact, float *dense)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (!pk || !compact || !dense) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_scatter_dense: null pointer");
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    return pc_launch_scatter(ctx, pk, compact, dense, 0);
+}
+
+extern "C" pc_status pc_unpack_dense(pc_ctx *ctx, const pc_packed *pk, float *dense)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (!pk || !dense) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_unpack_dense: null pointer");
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    return pc_launch_scatter(ctx, pk, nullptr, dense, 1);
+}
+
+// ------------------------------------------------------------------ conv passes
+static pc_status check_conv(pc_ctx *ctx, const char *who, const pc_conv_desc *d, const pc_packed *pk,
+                            const void *a, const void *b, const void *c)
+{
+    if (!d || !pk || !a || !b || !c) return pc_fail(ctx, PC_ERR_INVALID_ARG, "%s: null pointer", who);
+    pc_status s = pc_check_conv_desc(d);
+    if (s != PC_OK)
+        return pc_fail(ctx, s, "%s: bad descriptor N=%d H=%d W=%d C=%d F=%d stride=%d dtype=%d", who, d->N, d->H,
+                       d->W, d->C, d->F, d->stride, (int)d->dtype);
+    if (d->C != pk->v.C || d->F != pk->v.F)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "%s: descriptor C=%d F=%d but the pack holds C=%d F=%d", who, d->C,
+                       d->F, pk->v.C, pk->v.F);
+    if (d->dtype != pk->dtype)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "%s: descriptor dtype differs from the pack's compute dtype", who);
+    if (pk->device != ctx->device) return pc_fail(ctx, PC_ERR_INVALID_ARG, "%s: pack lives on another device", who);
+    return pc_hip_check(ctx, hipSetDevice(ctx->device), "hipSetDevice");
+}
+
+extern "C" pc_status pc_conv_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    pc_status s = check_conv(ctx, "pc_conv_fwd", d, pk, x, y, y);
+    if (s != PC_OK) return s;
+    return pk->variant == PC_VARIANT_MFMA ? pc_mfma_fwd(ctx, d, pk, x, y) : pc_valu_fwd(ctx, d, pk, x, y);
+}
+
+extern "C" pc_status pc_conv_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy,
+                                      void *dx)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    pc_status s = check_conv(ctx, "pc_conv_bwd_data", d, pk, dy, dx, dx);
+    if (s != PC_OK) return s;
+    return pk->variant == PC_VARIANT_MFMA ? pc_mfma_bwd_data(ctx, d, pk, dy, dx) : pc_valu_bwd_data(ctx, d, pk, dy, dx);
+}
+
+extern "C" pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,
+                                        const void *dy, float *dw)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    pc_status s = check_conv(ctx, "pc_conv_bwd_weight", d, pk, x, dy, dw);
+    if (s != PC_OK) return s;
+    return pk->variant == PC_VARIANT_MFMA ? pc_mfma_bwd_weight(ctx, d, pk, x, dy, dw)
+                                          : pc_valu_bwd_weight(ctx, d, pk, x, dy, dw);
+}

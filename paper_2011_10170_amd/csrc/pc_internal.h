@@ -1,0 +1,113 @@
+// Internal declarations shared by the translation units of libpatconv (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "pc.h"
+
+#define PC_MAX_P 126
+
+struct pc_ctx {
+    int device;
+    hipStream_t stream;
+    pc_variant forced;
+    int num_cu;
+    char err[256];
+    // scratch owned by the context (grown on demand, never shrunk)
+    void *scratch;
+    size_t scratch_bytes;
+    int64_t *nnz_pinned;   // pinned host word for reading back a pack's kernel count
+};
+
+// Device-side view of a packed layer. All pointers point into one slab.
+struct PackView {
+    int32_t F, C, P;
+    // filter-major table: rows = filters, kernels ordered (pattern id, channel)
+    int32_t *fm_rowptr;   // [F+1]   slot range of filter f
+    int32_t *fm_grp;      // [F][P+1] first slot of pattern group p in filter f; [P] = row end
+    uint16_t *fm_c;       // [cap]   input channel of the slot
+    uint8_t *fm_pid;      // [cap]   pattern id of the slot
+    uint16_t *slot_f;     // [cap]   filter of the slot
+    float4 *fm_val;       // [cap]   the 4 kept weights, ascending tap index
+    int32_t *slot_of;     // [F][C]  slot of kernel (f,c), -1 when pruned
+    // channel-major table for backward-data: rows = channels, kernels ordered (pattern id, filter)
+    int32_t *cm_rowptr;   // [C+1]
+    int32_t *cm_grp;      // [C][P+1]
+    uint16_t *cm_f;       // [cap]
+    int32_t *cm_slot;     // [cap]   filter-major slot of the entry
+    float4 *cm_val;       // [cap]
+    // MFMA operand tiles (bf16 bit patterns, zero at every pruned position), fragment order
+    uint16_t *wz_fwd;     // A operand of the forward pass
+    uint16_t *wz_bwd;     // A operand of the backward-data pass
+    int32_t Fp, Cp;       // F and C rounded up to the MFMA tile (32)
+};
+
+struct pc_packed {
+    int device;
+    pc_dtype dtype;
+    int variant;                 // PC_VARIANT_VALU or PC_VARIANT_MFMA
+    uint16_t lib[PC_MAX_P];
+    uint8_t taps[PC_MAX_P][4];   // kept taps of every pattern, ascending
+    void *slab;
+    size_t slab_bytes;
+    PackView v;
+    hipEvent_t packed_evt;       // recorded after the last pack on this handle
+    int64_t nnzk;                // -1 until read back
+};
+
+// Pattern pool passed to kernels by value.
+struct LibArg {
+    int32_t P;
+    uint16_t mask[PC_MAX_P];
+    uint8_t taps[PC_MAX_P][4];
+};
+
+pc_status pc_fail(pc_ctx *ctx, pc_status s, const char *fmt, ...);
+pc_status pc_hip_check(pc_ctx *ctx, hipError_t e, const char *what);
+pc_status pc_scratch(pc_ctx *ctx, size_t bytes, void **out);
+void pc_fill_lib(LibArg *la, const uint16_t *lib, int P);
+
+#define PC_HIP(ctx, call)                                              \
+    do {                                                               \
+        pc_status _s = pc_hip_check((ctx), (call), #call);             \
+        if (_s != PC_OK) return _s;                                    \
+    } while (0)
+
+// ---- launches implemented in the other translation units ----
+pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, int C, const LibArg &la,
+                           pc_keep_mode km, int64_t n_keep, pc_score_mode sm, uint8_t *pid, uint8_t *keep);
+pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8_t *pid, const uint8_t *keep);
+pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W);
+pc_status pc_launch_scatter(pc_ctx *ctx, const pc_packed *pk, const float *compact, float *dense, int from_pack);
+
+pc_status pc_valu_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y);
+pc_status pc_valu_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx);
+pc_status pc_valu_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,
+                             const void *dy, float *dw);
+
+bool pc_mfma_supports(int F, int C);
+pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W);
+pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y);
+pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx);
+pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,
+                             const void *dy, float *dw);
+
+// ---- small device helpers ----
+#ifdef __HIPCC__
+__device__ __forceinline__ float pc_bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t pc_f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);   // round to nearest, ties to even (finite inputs)
+    return (uint16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float pc_load(const T *p);
+template <> __device__ __forceinline__ float pc_load<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float pc_load<uint16_t>(const uint16_t *p) { return pc_bf16_to_f32(*p); }
+template <typename T> __device__ __forceinline__ void pc_store(T *p, float v);
+template <> __device__ __forceinline__ void pc_store<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void pc_store<uint16_t>(uint16_t *p, float v) { *p = pc_f32_to_bf16(v); }
+#endif

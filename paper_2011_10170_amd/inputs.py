@@ -243,17 +243,24 @@ def gen_weight_grads(F: int, C: int, seed: int, tag) -> np.ndarray:
     return normal(seed, stream_id("G", tag, F, C), F * C * 9).reshape(F, C, 9)
 
 
+PERIOD = 8388593   # prime; tensors longer than this repeat their first PERIOD values cyclically
+
+
 def gen_activations(shape: Tuple[int, ...], seed: int, tag, relu: bool, dtype: str):
     """NHWC activations. relu=True gives max(0, N(0,1)) (post-ReLU feature maps),
-    relu=False gives N(0,1) (incoming output gradients).
+    relu=False gives N(0,1) (incoming output gradients). Tensors with more than PERIOD
+    elements repeat their first PERIOD values cyclically (generation time; the period is
+    prime, so it never lines up with a tensor dimension).
 
     Returns (values_f32, storage): values_f32 holds exactly the numbers the
     kernels see (already rounded to bf16 when dtype == "bf16"); storage is the
     array to upload (float32, or uint16 bf16 bit patterns)."""
     n = int(np.prod(shape))
-    a = normal(seed, stream_id("act", tag, tuple(shape), relu), n)
+    a = normal(seed, stream_id("act", tag, tuple(shape), relu), min(n, PERIOD))
     if relu:
         np.maximum(a, np.float32(0), out=a)
+    if n > PERIOD:
+        a = np.resize(a, n)
     if dtype == "bf16":
         bits = f32_to_bf16_bits(a)
         return bf16_bits_to_f32(bits).reshape(shape), bits.reshape(shape)

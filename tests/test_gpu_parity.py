@@ -1,0 +1,272 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs. Masks and pattern ids must be bit-exact; conv outputs within 1e-4 relative L2 (float32)
+or 2e-2 (bf16 inputs, float32 accumulation); float32 weight gradients within 1e-4 in both cases."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2011_10170_amd import inputs as I
+from tests._harness import Case, GpuLayer, oracle_masks, rel_l2, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+TOL_DW = 1e-4
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2011_10170_amd import binding
+    binding.load()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(B):
+    import torch
+    c = B.pc_create(0, torch.cuda.current_stream().cuda_stream)
+    yield c
+    B.pc_destroy(c)
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+# N, H, W, C, F, stride: small enough for the full oracle, spanning several tiles with ragged tails
+SMALL = [
+    (8, 32, 32, 16, 16, 1),     # the single-layer float32 configuration
+    (2, 13, 19, 5, 7, 1),
+    (3, 9, 11, 6, 10, 2),
+    (1, 1, 1, 3, 4, 1),
+    (2, 2, 2, 8, 8, 2),
+    (1, 40, 37, 12, 20, 1),
+    (1, 12, 12, 200, 24, 1),    # more channels than one LDS pass holds
+    (2, 33, 35, 7, 18, 2),
+    (5, 4, 4, 32, 48, 1),
+    (20, 2, 2, 16, 32, 1),
+    (2, 16, 16, 3, 64, 1),      # first-layer shape: 3 input channels
+]
+MEDIUM_BF16 = [
+    (4, 16, 16, 64, 64, 1),
+    (4, 16, 16, 64, 128, 2),
+    (8, 4, 4, 128, 128, 1),
+    (16, 2, 2, 64, 64, 1),
+    (2, 28, 28, 32, 96, 1),
+    (2, 14, 14, 96, 32, 2),
+    (3, 7, 7, 64, 64, 1),
+]
+
+
+def run_case(B, ctx, oracle, shape, dtype, P, keep, variant, tag):
+    N, H, W, C, F, stride = shape
+    layer = I.Layer(N, H, W, C, F, stride)
+    case = Case(layer, dtype, P, I.kept_per_filter(keep, C), tag=(tag, shape, dtype))
+    say("case", tag, shape, dtype, "P", P, "keep", keep, "variant", variant)
+    pid, kp, M, Wm = oracle_masks(oracle, case)
+    g = GpuLayer(B, ctx, case, variant=variant)
+    try:
+        gpid, gkeep = g.masks()
+        assert np.array_equal(gpid, pid), "pattern ids differ"
+        assert np.array_equal(gkeep, kp), "keep mask differs"
+        assert g.nnzk == int(kp.sum())
+        assert np.array_equal(g.unpack(), Wm), "unpacked weights differ from W (.) M"
+        y_ref = oracle.conv_fwd(case.x, Wm, stride)
+        y = g.fwd()
+        e = rel_l2(y, y_ref)
+        say("  fwd rel_l2", e)
+        assert e <= TOL[dtype]
+        dx_ref = oracle.conv_bwd_data(case.dy, Wm, case.x.shape, stride)
+        dx = g.bwd_data()
+        e = rel_l2(dx, dx_ref)
+        say("  bwd_data rel_l2", e)
+        assert e <= TOL[dtype]
+        dw_ref_dense = oracle.conv_bwd_weight(case.x, case.dy, M, stride)
+        sf, sc = oracle.compact_order(pid, kp, P)
+        dw_ref = oracle.gather_compact(dw_ref_dense, pid, case.lib, sf, sc)
+        dw, guard = g.bwd_weight()
+        e = rel_l2(dw, dw_ref)
+        say("  bwd_weight rel_l2", e)
+        assert e <= TOL_DW
+        dense = g.scatter(guard.body)
+        assert np.all(dense[M == 0] == 0.0)
+        assert rel_l2(dense, dw_ref_dense) <= TOL_DW
+        return g.variant
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_f32(B, ctx, oracle, shape):
+    run_case(B, ctx, oracle, shape, "f32", 4 if shape[3] == 16 else 8, 0.5, B.PC_VARIANT_AUTO, "small")
+
+
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_bf16_valu(B, ctx, oracle, shape):
+    run_case(B, ctx, oracle, shape, "bf16", 8, 0.4, B.PC_VARIANT_VALU, "small")
+
+
+@pytest.mark.parametrize("shape", MEDIUM_BF16)
+def test_medium_bf16_valu(B, ctx, oracle, shape):
+    run_case(B, ctx, oracle, shape, "bf16", 12, 0.3, B.PC_VARIANT_VALU, "medium")
+
+
+@pytest.mark.parametrize("shape", MEDIUM_BF16)
+def test_medium_bf16_auto(B, ctx, oracle, shape):
+    run_case(B, ctx, oracle, shape, "bf16", 16, 0.25, B.PC_VARIANT_AUTO, "medium")
+
+
+def test_full_pool_and_every_pattern_f32(B, ctx, oracle):
+    run_case(B, ctx, oracle, (2, 10, 10, 24, 16, 1), "f32", 126, 0.5, B.PC_VARIANT_AUTO, "p126")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_keep_counts(B, ctx, oracle, dtype):
+    """n_keep = 0 prunes everything (outputs are zero, no slots); n_keep = C is pattern-only pruning."""
+    layer = I.Layer(2, 6, 7, 5, 6, 1)
+    for n_keep in (0, 5):
+        case = Case(layer, dtype, 8, n_keep, tag=("degenerate", n_keep))
+        pid, kp, M, Wm = oracle_masks(oracle, case)
+        g = GpuLayer(B, ctx, case)
+        try:
+            gpid, gkeep = g.masks()
+            assert np.array_equal(gpid, pid) and np.array_equal(gkeep, kp)
+            assert g.nnzk == n_keep * layer.F
+            y = g.fwd()
+            dx = g.bwd_data()
+            if n_keep == 0:
+                assert not y.any() and not dx.any()
+                dw, _ = g.bwd_weight()
+                assert dw.size == 0
+            else:
+                assert rel_l2(y, oracle.conv_fwd(case.x, Wm, 1)) <= TOL[dtype]
+                assert rel_l2(dx, oracle.conv_bwd_data(case.dy, Wm, case.x.shape, 1)) <= TOL[dtype]
+        finally:
+            g.close()
+
+
+@pytest.mark.parametrize("score_mode", [0, 1])
+@pytest.mark.parametrize("keep_mode", [0, 1])
+@pytest.mark.parametrize("with_grad", [True, False])
+def test_select_modes_bit_exact(B, ctx, oracle, score_mode, keep_mode, with_grad):
+    layer = I.Layer(1, 4, 4, 37, 29, 1)
+    n_keep = 11 if keep_mode == 0 else 333
+    case = Case(layer, "f32", 12, n_keep, tag=("modes", score_mode, keep_mode, with_grad))
+    pid, kp, _, _ = oracle_masks(oracle, case, score_mode=score_mode, keep_mode=keep_mode, with_grad=with_grad)
+    g = GpuLayer(B, ctx, case, score_mode=score_mode, keep_mode=keep_mode, with_grad=with_grad)
+    try:
+        gpid, gkeep = g.masks()
+        assert np.array_equal(gpid, pid) and np.array_equal(gkeep, kp)
+    finally:
+        g.close()
+
+
+def test_select_ties_and_zero_weights(B, ctx, oracle):
+    """All-zero and constant weights: every score ties; lowest pattern id and lowest channels win."""
+    import torch
+    F, C, P = 3, 10, 8
+    lib = I.make_library(P)
+    for fill in (0.0, 1.0):
+        Wn = np.full((F, C, 9), fill, np.float32)
+        pid, kp = oracle.select(Wn, None, lib, 4)
+        Wd = to_dev(Wn)
+        gp = torch.empty((F, C), dtype=torch.uint8, device="cuda")
+        gk = torch.empty((F, C), dtype=torch.uint8, device="cuda")
+        B.pc_pattern_select(ctx, Wd, None, F, C, lib, 0, 4, 0, gp, gk)
+        torch.cuda.synchronize()
+        assert np.array_equal(gp.cpu().numpy(), pid) and np.array_equal(gk.cpu().numpy(), kp)
+
+
+def test_select_full_layer_sizes_bit_exact(B, ctx, oracle):
+    """Selection at the largest layer of the benchmark stacks (512x512 kernels), both score modes."""
+    import torch
+    F = C = 512
+    for P, keep in ((8, 0.3), (16, 0.2)):
+        lib = I.make_library(P)
+        Wn = I.gen_weights(F, C, I.BASE_SEED, ("sel_full", P))
+        Gn = I.gen_weight_grads(F, C, I.BASE_SEED, ("sel_full", P))
+        k = I.kept_per_filter(keep, C)
+        Wd, Gd = to_dev(Wn), to_dev(Gn)
+        for sm in (0, 1):
+            pid, kp = oracle.select(Wn, Gn, lib, k, score_mode=sm)
+            gp = torch.empty((F, C), dtype=torch.uint8, device="cuda")
+            gk = torch.empty((F, C), dtype=torch.uint8, device="cuda")
+            B.pc_pattern_select(ctx, Wd, Gd, F, C, lib, 0, k, sm, gp, gk)
+            torch.cuda.synchronize()
+            assert np.array_equal(gp.cpu().numpy(), pid)
+            assert np.array_equal(gk.cpu().numpy(), kp)
+            assert int(kp.sum()) == F * k
+
+
+def test_runs_are_bit_reproducible(B, ctx, oracle):
+    layer = I.Layer(4, 16, 16, 64, 64, 1)
+    for dtype in ("f32", "bf16"):
+        case = Case(layer, dtype, 8, 19, tag=("repro", dtype))
+        g = GpuLayer(B, ctx, case)
+        try:
+            a = (g.fwd(), g.bwd_data(), g.bwd_weight()[0])
+            b = (g.fwd(), g.bwd_data(), g.bwd_weight()[0])
+            for u, v in zip(a, b):
+                assert np.array_equal(u, v)
+        finally:
+            g.close()
+
+
+def test_update_values_and_repack(B, ctx, oracle):
+    """pc_update_values re-gathers from new dense weights with the same tables; pc_pack can re-pack
+    an existing handle with a new selection."""
+    layer = I.Layer(2, 8, 8, 16, 24, 1)
+    case = Case(layer, "f32", 8, 6, tag="upd")
+    pid, kp, M, Wm = oracle_masks(oracle, case)
+    g = GpuLayer(B, ctx, case)
+    try:
+        W2 = I.gen_weights(layer.F, layer.C, 99, "upd2")
+        B.pc_update_values(ctx, g.pk, to_dev(W2))
+        Wm2 = oracle.apply_mask(W2, M)
+        assert np.array_equal(g.unpack(), Wm2)
+        assert rel_l2(g.fwd(), oracle.conv_fwd(case.x, Wm2, 1)) <= 1e-4
+        assert rel_l2(g.bwd_data(), oracle.conv_bwd_data(case.dy, Wm2, case.x.shape, 1)) <= 1e-4
+        # new selection from the new weights, packed into the same handle
+        pid3, kp3 = oracle.select(W2, None, case.lib, 9)
+        M3 = oracle.mask(pid3, kp3, case.lib)
+        W2d = to_dev(W2)
+        B.pc_pattern_select(ctx, W2d, None, layer.F, layer.C, case.lib, 0, 9, 0, g.pid, g.keep)
+        pk2 = B.pc_pack(ctx, W2d, g.pid, g.keep, layer.F, layer.C, case.lib, g.dt, reuse=g.pk)
+        assert pk2 == g.pk
+        g.nnzk, _ = B.pc_packed_info(ctx, g.pk)
+        assert g.nnzk == 9 * layer.F
+        assert np.array_equal(g.unpack(), oracle.apply_mask(W2, M3))
+        assert rel_l2(g.fwd(), oracle.conv_fwd(case.x, oracle.apply_mask(W2, M3), 1)) <= 1e-4
+    finally:
+        g.close()
+
+
+def test_mismatched_descriptor_is_rejected(B, ctx, oracle):
+    layer = I.Layer(1, 4, 4, 8, 8, 1)
+    case = Case(layer, "f32", 4, 4, tag="mismatch")
+    g = GpuLayer(B, ctx, case)
+    try:
+        import torch
+        y = torch.zeros(1 * 4 * 4 * 8, device="cuda")
+        bad = B.make_desc(1, 4, 4, 9, 8, 1, B.PC_F32)
+        with pytest.raises(B.PcError) as ei:
+            B.pc_conv_fwd(ctx, bad, g.pk, g.x, y)
+        assert ei.value.status == B.PC_ERR_INVALID_ARG
+        bad = B.make_desc(1, 4, 4, 8, 8, 1, B.PC_BF16)
+        with pytest.raises(B.PcError):
+            B.pc_conv_fwd(ctx, bad, g.pk, g.x, y)
+        bad = B.make_desc(1, 4, 4, 8, 8, 3, B.PC_F32)
+        with pytest.raises(B.PcError) as ei:
+            B.pc_conv_fwd(ctx, bad, g.pk, g.x, y)
+        assert ei.value.status == B.PC_ERR_BAD_SHAPE
+        with pytest.raises(B.PcError) as ei:
+            B.pc_pattern_select(ctx, g.W, None, 8, 8, [0b111], 0, 1, 0, g.pid, g.keep)
+        assert ei.value.status == B.PC_ERR_BAD_LIBRARY
+        with pytest.raises(B.PcError):
+            B.pc_pattern_select(ctx, g.W, None, 8, 8, case.lib, 0, 9, 0, g.pid, g.keep)   # n_keep > C
+    finally:
+        g.close()
