@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the pattern-sparse convolution hot path on one MI355X.
+
+One step = pc_conv_fwd + pc_conv_bwd_data + pc_conv_bwd_weight over every layer of the workload
+(plus pc_pattern_select + pc_pack per layer when the workload's step includes re-selection), on
+seeded synthetic inputs already resident in HBM. Prints ONE JSON line on stdout; a per-layer table
+goes to stderr.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16_cifar] [--variant auto|valu|mfma]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_BF16_MFMA_TFLOPS = 2500.0
+PEAK_F32_VALU_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vgg16_cifar")
+    ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the batch would shard across GPUs with one "
+              "all-reduce of the compact weight gradient); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2011_10170_amd import binding as B
+    from paper_2011_10170_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    B.load()   # raises if the HIP library is missing: there is no fallback
+    wl = I.WORKLOADS[args.workload]
+    dt = B.PC_BF16 if wl.dtype == "bf16" else B.PC_F32
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    esz = 2 if wl.dtype == "bf16" else 4
+    stream = torch.cuda.current_stream()
+    ctx = B.pc_create(0, stream.cuda_stream)
+    B.pc_set_variant(ctx, {"auto": B.PC_VARIANT_AUTO, "valu": B.PC_VARIANT_VALU, "mfma": B.PC_VARIANT_MFMA}[args.variant])
+    lib = I.make_library(wl.P)
+
+    def up(arr):
+        if arr.dtype == np.uint16:
+            return torch.from_numpy(arr.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+    # ---- set-up: inputs to HBM, selection and packing once
+    t_setup = time.time()
+    layers = []
+    for li, L in enumerate(wl.layers):
+        tag = (wl.name, li)
+        W = up(I.gen_weights(L.F, L.C, I.BASE_SEED, tag))
+        G = up(I.gen_weight_grads(L.F, L.C, I.BASE_SEED, tag))
+        x = up(I.gen_activations((L.N, L.H, L.W, L.C), I.BASE_SEED, (tag, "x"), True, wl.dtype)[1])
+        dy = up(I.gen_activations((L.N, L.Ho, L.Wo, L.F), I.BASE_SEED, (tag, "dy"), False, wl.dtype)[1])
+        k = I.kept_per_filter(wl.keep, L.C)
+        pid = torch.empty((L.F, L.C), dtype=torch.uint8, device="cuda")
+        keep = torch.empty((L.F, L.C), dtype=torch.uint8, device="cuda")
+        B.pc_pattern_select(ctx, W, G, L.F, L.C, lib, B.PC_KEEP_PER_FILTER, k, B.PC_SCORE_RETAINED, pid, keep)
+        pk = B.pc_pack(ctx, W, pid, keep, L.F, L.C, lib, dt)
+        nnzk, variant = B.pc_packed_info(ctx, pk)
+        assert nnzk == k * L.F
+        layers.append(dict(
+            L=L, W=W, G=G, x=x, dy=dy, k=k, pid=pid, keep=keep, pk=pk, nnzk=nnzk, variant=variant,
+            desc=B.make_desc(L.N, L.H, L.W, L.C, L.F, L.stride, dt),
+            y=torch.empty((L.N, L.Ho, L.Wo, L.F), dtype=tdt, device="cuda"),
+            dx=torch.empty((L.N, L.H, L.W, L.C), dtype=tdt, device="cuda"),
+            dw=torch.empty((max(nnzk, 1), 4), dtype=torch.float32, device="cuda"),
+            flops=8.0 * L.N * L.Ho * L.Wo * nnzk,                  # nonzero MACs x 2, per pass
+            dense_flops=18.0 * L.N * L.Ho * L.Wo * L.F * L.C,      # what a zero-filled contraction issues
+            act_in=L.N * L.H * L.W * L.C * esz, act_out=L.N * L.Ho * L.Wo * L.F * esz,
+        ))
+    torch.cuda.synchronize()
+    log("set-up %.1f s, %d layers, workload %s" % (time.time() - t_setup, len(layers), wl.name))
+
+    def run_pass(d, which):
+        if which == "select":
+            B.pc_pattern_select(ctx, d["W"], d["G"], d["L"].F, d["L"].C, lib, B.PC_KEEP_PER_FILTER, d["k"],
+                                B.PC_SCORE_RETAINED, d["pid"], d["keep"])
+        elif which == "pack":
+            B.pc_pack(ctx, d["W"], d["pid"], d["keep"], d["L"].F, d["L"].C, lib, dt, reuse=d["pk"])
+        elif which == "fwd":
+            B.pc_conv_fwd(ctx, d["desc"], d["pk"], d["x"], d["y"])
+        elif which == "bwd_data":
+            B.pc_conv_bwd_data(ctx, d["desc"], d["pk"], d["dy"], d["dx"])
+        else:
+            B.pc_conv_bwd_weight(ctx, d["desc"], d["pk"], d["x"], d["dy"], d["dw"])
+
+    passes = (["select", "pack"] if wl.with_select else []) + ["fwd", "bwd_data", "bwd_weight"]
+
+    def step(events=None):
+        for li, d in enumerate(layers):
+            for which in passes:
+                if events is not None:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                run_pass(d, which)
+                if events is not None:
+                    e1.record(stream)
+                    events.append((li, which, e0, e1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    total_flops = sum(3.0 * d["flops"] for d in layers)
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-call durations inside the same step sequence (library kernels run on torch's current stream)
+    events = []
+    n_inst = max(3, min(args.steps, 10))
+    for _ in range(n_inst):
+        step(events)
+    torch.cuda.synchronize()
+    per_call = {}
+    for li, which, e0, e1 in events:
+        per_call.setdefault((li, which), []).append(e0.elapsed_time(e1))
+    kinds = {}
+    log("%-3s %-22s %-10s %-5s %9s %10s %10s %8s" % ("#", "layer", "pass", "var", "us", "nz TF/s", "dense TF/s", "GB/s"))
+    for (li, which), ts in sorted(per_call.items()):
+        d = layers[li]
+        L = d["L"]
+        us = float(np.median(ts)) * 1e3
+        var = "mfma" if d["variant"] == B.PC_VARIANT_MFMA else "valu"
+        if which in ("select", "pack"):
+            kind = which
+            byts = L.F * L.C * (74 if which == "select" else 38 + 0.0)
+            fl = dfl = 0.0
+        else:
+            kind = "%s_%s" % (var, which)
+            fl, dfl = d["flops"], d["dense_flops"]
+            wbytes = d["nnzk"] * (4 * esz + 2)
+            if which == "fwd":
+                byts = d["act_in"] + d["act_out"] + wbytes
+            elif which == "bwd_data":
+                byts = d["act_out"] + d["act_in"] + wbytes
+            else:
+                byts = d["act_in"] + d["act_out"] + 16 * d["nnzk"]
+        kk = kinds.setdefault(kind, dict(us=0.0, flops=0.0, dense=0.0, bytes=0.0, n=0))
+        kk["us"] += us; kk["flops"] += fl; kk["dense"] += dfl; kk["bytes"] += byts; kk["n"] += 1
+        log("%-3d %-22s %-10s %-5s %9.1f %10.2f %10.1f %8.0f" % (
+            li, "%dx%d %d->%d s%d" % (L.H, L.W, L.C, L.F, L.stride), which, var, us,
+            fl / us / 1e6, dfl / us / 1e6, byts / us / 1e3))
+    dom = max(kinds.items(), key=lambda kv: kv[1]["us"])
+    dk, dv = dom
+    t_hbm = dv["bytes"] / (PEAK_HBM_GBS * 1e9) * 1e6
+    if dk.startswith("mfma"):
+        # the contraction issues the dense zero-filled tile flops; its utilisation is issued / peak
+        t_unit = dv["dense"] / (PEAK_BF16_MFMA_TFLOPS * 1e12) * 1e6
+        bound, unit, peak = "mfma", "TFLOP/s", PEAK_BF16_MFMA_TFLOPS
+        achieved = dv["dense"] / dv["us"] / 1e6
+    else:
+        t_unit = dv["flops"] / (PEAK_F32_VALU_TFLOPS * 1e12) * 1e6
+        bound, unit, peak = "alu", "TFLOP/s", PEAK_F32_VALU_TFLOPS
+        achieved = dv["flops"] / dv["us"] / 1e6
+    if t_hbm > t_unit:
+        bound, unit, peak = "hbm", "GB/s", PEAK_HBM_GBS
+        achieved = dv["bytes"] / dv["us"] / 1e3
+    roofline = {
+        "kernel": dk, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+        "frac": round(achieved / peak, 4), "traffic": None,
+        "launches_per_step": dv["n"], "avg_launch_us": round(dv["us"] / dv["n"], 2),
+        "achieved_nonzero_tflops": round(dv["flops"] / dv["us"] / 1e6, 3),
+        "algorithmic_gbs": round(dv["bytes"] / dv["us"] / 1e3, 1),
+        "ideal_sparse_frac": round(max(t_hbm, dv["flops"] / (PEAK_F32_VALU_TFLOPS * 1e12) * 1e6) / dv["us"], 4),
+        "share_of_step": round(dv["us"] / sum(k["us"] for k in kinds.values()), 3),
+    }
+    for kname, kv in sorted(kinds.items()):
+        log("kind %-18s launches %3d  total %9.1f us  nz %8.2f TF/s  dense %8.1f TF/s  alg %7.0f GB/s" % (
+            kname, kv["n"], kv["us"], kv["flops"] / kv["us"] / 1e6, kv["dense"] / kv["us"] / 1e6, kv["bytes"] / kv["us"] / 1e3))
+
+    # ---- the CPU oracle on a bounded sample of the same workload (reported, not a target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import pc_oracle as oracle
+        ns = min(args.cpu_sample_batch, wl.layers[0].N)
+        t_cpu, f_cpu = 0.0, 0.0
+        for li, L in enumerate(wl.layers):
+            tag = (wl.name, li)
+            Wn = I.gen_weights(L.F, L.C, I.BASE_SEED, tag)
+            Gn = I.gen_weight_grads(L.F, L.C, I.BASE_SEED, tag)
+            k = I.kept_per_filter(wl.keep, L.C)
+            xs = I.gen_activations((ns, L.H, L.W, L.C), I.BASE_SEED, (tag, "x", "cpu"), True, wl.dtype)[0]
+            dys = I.gen_activations((ns, L.Ho, L.Wo, L.F), I.BASE_SEED, (tag, "dy", "cpu"), False, wl.dtype)[0]
+            c0 = time.perf_counter()
+            pid, kp = oracle.select(Wn, Gn, lib, k)
+            M = oracle.mask(pid, kp, lib)
+            Wm = oracle.apply_mask(oracle.bf16_round(Wn) if wl.dtype == "bf16" else Wn, M)
+            c1 = time.perf_counter()
+            oracle.conv_fwd(xs, Wm, L.stride)
+            oracle.conv_bwd_data(dys, Wm, xs.shape, L.stride)
+            oracle.conv_bwd_weight(xs, dys, M, L.stride)
+            c2 = time.perf_counter()
+            t_cpu += (c2 - c1) + ((c1 - c0) if wl.with_select else 0.0)
+            f_cpu += 3.0 * 8.0 * ns * L.Ho * L.Wo * int(kp.sum())
+        cpu = {"value": round(f_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "all %d layers of %s at batch %d (of %d), fwd+bwd_data+bwd_weight%s, %.1f s" % (
+                   len(wl.layers), wl.name, ns, wl.layers[0].N, " + select" if wl.with_select else "", t_cpu)}
+
+    out = {
+        "metric": "effective nonzero-MAC TFLOP/s for pattern-conv fwd+bwd; % of MI355X roofline",
+        "value": round(value, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": len(wl.layers), "batch": wl.layers[0].N, "patterns": wl.P,
+                   "keep": wl.keep, "variant": args.variant, "passes": "+".join(passes),
+                   "nonzero_gflop_per_step": round(total_flops / 1e9, 3)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    for d in layers:
+        B.pc_packed_free(d["pk"])
+    B.pc_destroy(ctx)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

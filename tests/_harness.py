@@ -69,7 +69,9 @@ class Guarded:
         self.n = n_elem
         self.buf = torch.full((n_elem + 2 * CANARY,), 7.0, dtype=torch_dtype, device="cuda")
         self.body = self.buf[CANARY:CANARY + n_elem]
-        self.body.fill_(float("nan")) if n_elem else None
+        if n_elem:
+            self.body.fill_(float("nan"))
+        self.ptr = self.buf.data_ptr() + CANARY * self.buf.element_size()   # valid even when n_elem == 0
 
     def margins_intact(self) -> bool:
         torch = _torch()
@@ -102,7 +104,7 @@ class GpuLayer:
     def fwd(self):
         L = self.case.layer
         g = Guarded(L.N * L.Ho * L.Wo * L.F, self.tdt)
-        self.B.pc_conv_fwd(self.ctx, self.desc, self.pk, self.x, g.body)
+        self.B.pc_conv_fwd(self.ctx, self.desc, self.pk, self.x, g.ptr)
         _torch().cuda.synchronize()
         assert g.margins_intact()
         return from_dev_f32(g.body).reshape(L.N, L.Ho, L.Wo, L.F)
@@ -110,7 +112,7 @@ class GpuLayer:
     def bwd_data(self):
         L = self.case.layer
         g = Guarded(L.N * L.H * L.W * L.C, self.tdt)
-        self.B.pc_conv_bwd_data(self.ctx, self.desc, self.pk, self.dy, g.body)
+        self.B.pc_conv_bwd_data(self.ctx, self.desc, self.pk, self.dy, g.ptr)
         _torch().cuda.synchronize()
         assert g.margins_intact()
         return from_dev_f32(g.body).reshape(L.N, L.H, L.W, L.C)
@@ -118,7 +120,7 @@ class GpuLayer:
     def bwd_weight(self):
         torch = _torch()
         g = Guarded(self.nnzk * 4, torch.float32)
-        self.B.pc_conv_bwd_weight(self.ctx, self.desc, self.pk, self.x, self.dy, g.body)
+        self.B.pc_conv_bwd_weight(self.ctx, self.desc, self.pk, self.x, self.dy, g.ptr)
         torch.cuda.synchronize()
         assert g.margins_intact()
         return g.body.cpu().numpy().reshape(self.nnzk, 4), g
