@@ -179,8 +179,10 @@ static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
     };
     v->F = F;
     v->C = C;
-    v->Fp = (F + 31) / 32 * 32;
-    v->Cp = (C + 31) / 32 * 32;
+    v->Fp = (F + 127) / 128 * 128;
+    v->Cp = (C + 127) / 128 * 128;
+    v->Fk = (F + 31) / 32 * 32;
+    v->Ck = (C + 31) / 32 * 32;
     v->fm_rowptr = (int32_t *)take(sizeof(int32_t) * (F + 1));
     v->fm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)F * (PC_MAX_P + 1));
     v->fm_c = (uint16_t *)take(sizeof(uint16_t) * cap);
@@ -194,9 +196,8 @@ static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
     v->cm_slot = (int32_t *)take(sizeof(int32_t) * cap);
     v->cm_val = (float4 *)take(sizeof(float4) * cap);
     if (mfma) {
-        size_t tile = sizeof(uint16_t) * 9 * (size_t)v->Fp * v->Cp;
-        v->wz_fwd = (uint16_t *)take(tile);
-        v->wz_bwd = (uint16_t *)take(tile);
+        v->wz_fwd = (uint16_t *)take(sizeof(uint16_t) * 9 * (size_t)v->Fp * v->Ck);
+        v->wz_bwd = (uint16_t *)take(sizeof(uint16_t) * 9 * (size_t)v->Cp * v->Fk);
     } else {
         v->wz_fwd = v->wz_bwd = nullptr;
     }
