@@ -317,9 +317,182 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
     return PC_OK;
 }
 
+// ------------------------------------------------------------------ backward-weight
+// dW[t][f][c] = sum over output pixels of dy[pixel][f] * x[pixel shifted by tap t][c]: for every tap a
+// GEMM with M = filters, N = channels and the pixels as the reduction. Both operands need the pixels
+// contiguous per lane, while NHWC memory has the channels contiguous, so the staging transposes:
+// LDS holds dyT[filter][pixel] and xT[channel][row][column] (bf16). One workgroup owns a 64x64 tile of
+// (filter, channel) for all 9 taps (each wave 32x32x9: 144 accumulator registers) and walks pixel tiles
+// of R rows x TWp columns of one image. The three horizontal taps of a kernel row come from ONE aligned
+// LDS read plus its two neighbouring dwords, re-aligned in registers with v_alignbit. Pixel tiles are
+// split over blockIdx.z; every split writes only the kept taps, in compact slot order, to its own
+// partial buffer, and a second kernel adds the partials in a fixed order (no float atomics).
+#define WG_T 64                // filters and channels per workgroup
+#define WG_DY_PITCH 144        // bytes per filter row of dyT: 64 pixels of bf16 + 16 bytes of padding
+
+struct WgradMfmaArgs {
+    int32_t N, H, W, C, F, Ho, Wo;
+    int32_t TWp, R;            // pixel tile: R rows x TWp columns (TWp % 8 == 0, R*TWp % 16 == 0, <= 64)
+    int32_t xrow;              // elements per xT row: TWp + 16 (column index = halo column + 7)
+    int32_t xplane;            // bytes per xT channel plane
+    int32_t tiles_r, tiles_c, n_ktiles, ksplit;
+    int32_t nnzk;
+    uint8_t taps[PC_MAX_P][4];
+};
+
+__device__ __forceinline__ bf16x8 pc_as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    uint4 v = make_uint4(a, b, c, d);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+__global__ void __launch_bounds__(256)
+pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradMfmaArgs a, PackView v,
+                     float *__restrict__ partial)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    unsigned char *dyT = lds;
+    unsigned char *xT = lds + WG_T * WG_DY_PITCH;
+    __shared__ int8_t jmap[PC_MAX_P][9];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int fh = wave & 1, chh = wave >> 1;
+    const int c0 = blockIdx.x * WG_T, f0 = blockIdx.y * WG_T;
+    const int g = lane >> 5;
+
+    for (int e = threadIdx.x; e < v.P * 9; e += 256) (&jmap[0][0])[e] = -1;
+    __syncthreads();
+    for (int e = threadIdx.x; e < v.P * 4; e += 256) jmap[e >> 2][a.taps[e >> 2][e & 3]] = (int8_t)(e & 3);
+
+    f32x16 acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+    const int nks = (a.R * a.TWp) >> 4;
+    const int hw = a.TWp + 2;
+    const unsigned char *a_base = dyT + (fh * 32 + (lane & 31)) * WG_DY_PITCH + g * 16;
+    const unsigned char *b_base = xT + (chh * 32 + (lane & 31)) * a.xplane;
+
+    for (int kt = blockIdx.z; kt < a.n_ktiles; kt += a.ksplit) {
+        int q = kt;
+        const int tc = q % a.tiles_c; q /= a.tiles_c;
+        const int tr = q % a.tiles_r;
+        const int n = q / a.tiles_r;
+        const int oy0 = tr * a.R, ox0 = tc * a.TWp;
+        __syncthreads();
+        // dy tile, transposed to [filter][pixel]
+        for (int e = threadIdx.x; e < a.R * a.TWp * 8; e += 256) {
+            int fg = e & 7, p = e >> 3;
+            int prow = p / a.TWp, pcol = p - prow * a.TWp;
+            int oy = oy0 + prow, ox = ox0 + pcol, f = f0 + fg * 8;
+            uint4 val = make_uint4(0u, 0u, 0u, 0u);
+            if (oy < a.Ho && ox < a.Wo && f < a.F)
+                val = *reinterpret_cast<const uint4 *>(dy + (((int64_t)n * a.Ho + oy) * a.Wo + ox) * a.F + f);
+            uint16_t *dst = reinterpret_cast<uint16_t *>(dyT + (fg * 8) * WG_DY_PITCH) + p;
+            const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                dst[(2 * j) * (WG_DY_PITCH / 2)] = (uint16_t)(w[j] & 0xFFFFu);
+                dst[(2 * j + 1) * (WG_DY_PITCH / 2)] = (uint16_t)(w[j] >> 16);
+            }
+        }
+        // x halo tile, transposed to [channel][row][column + 7]
+        for (int e = threadIdx.x; e < (a.R + 2) * hw * 8; e += 256) {
+            int cg = e & 7, p = e >> 3;
+            int hy = p / hw, hx = p - hy * hw;
+            int yy = oy0 - 1 + hy, xx = ox0 - 1 + hx, c = c0 + cg * 8;
+            uint4 val = make_uint4(0u, 0u, 0u, 0u);
+            if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && c < a.C)
+                val = *reinterpret_cast<const uint4 *>(x + (((int64_t)n * a.H + yy) * a.W + xx) * a.C + c);
+            unsigned char *dstb = xT + (cg * 8) * a.xplane + (hy * a.xrow + hx + 7) * 2;
+            const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                *reinterpret_cast<uint16_t *>(dstb + (2 * j) * a.xplane) = (uint16_t)(w[j] & 0xFFFFu);
+                *reinterpret_cast<uint16_t *>(dstb + (2 * j + 1) * a.xplane) = (uint16_t)(w[j] >> 16);
+            }
+        }
+        __syncthreads();
+        for (int kk = 0; kk < nks; ++kk) {
+            const bf16x8 af = *reinterpret_cast<const bf16x8 *>(a_base + kk * 32);
+            const int p = kk * 16 + g * 8;
+            const int prow = p / a.TWp, pcol = p - prow * a.TWp;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const unsigned char *bp = b_base + ((prow + r) * a.xrow + pcol + 8) * 2;
+                const uint32_t dm = *reinterpret_cast<const uint32_t *>(bp - 4);
+                const uint4 d = *reinterpret_cast<const uint4 *>(bp);
+                const uint32_t dp = *reinterpret_cast<const uint32_t *>(bp + 16);
+                const uint32_t s01 = __builtin_amdgcn_alignbit(d.y, d.x, 16);
+                const uint32_t s12 = __builtin_amdgcn_alignbit(d.z, d.y, 16);
+                const uint32_t s23 = __builtin_amdgcn_alignbit(d.w, d.z, 16);
+                const bf16x8 b0 = pc_as_bf16x8(__builtin_amdgcn_alignbit(d.x, dm, 16), s01, s12, s23);
+                const bf16x8 b1 = pc_as_bf16x8(d.x, d.y, d.z, d.w);
+                const bf16x8 b2 = pc_as_bf16x8(s01, s12, s23, __builtin_amdgcn_alignbit(dp, d.w, 16));
+                acc[3 * r + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b0, acc[3 * r + 0], 0, 0, 0);
+                acc[3 * r + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b1, acc[3 * r + 1], 0, 0, 0);
+                acc[3 * r + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b2, acc[3 * r + 2], 0, 0, 0);
+            }
+        }
+    }
+    // kept taps only, compact slot order
+    const int c = c0 + chh * 32 + (lane & 31);
+    float *pout = partial + (int64_t)blockIdx.z * a.nnzk * 4;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int f = f0 + fh * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+        if (f < a.F && c < a.C) {
+            const int slot = v.slot_of[(int64_t)f * a.C + c];
+            if (slot >= 0) {
+                const int8_t *jm = jmap[v.fm_pid[slot]];
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const int j = jm[t];
+                    if (j >= 0) pout[(int64_t)slot * 4 + j] = acc[t][i];
+                }
+            }
+        }
+    }
+}
+
 pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
                              float *dw)
 {
-    // the pixel-reduction contraction is not built yet: the lane-per-kernel VALU kernel serves it
-    return pc_valu_bwd_weight(ctx, d, pk, x, dy, dw);
+    if (d->stride != 1) return pc_valu_bwd_weight(ctx, d, pk, x, dy, dw);   // stride-2 contraction not built yet
+    int64_t nnzk = 0;
+    pc_status s = pc_packed_info(ctx, pk, &nnzk, nullptr);
+    if (s != PC_OK) return s;
+    if (nnzk == 0) return PC_OK;
+    WgradMfmaArgs a;
+    memset(&a, 0, sizeof(a));
+    a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.F = d->F; a.Ho = d->H; a.Wo = d->W;
+    int ntc = (a.Wo + 31) / 32;
+    int tw = (a.Wo + ntc - 1) / ntc;
+    a.TWp = (tw + 7) / 8 * 8;
+    a.R = (64 / a.TWp) & ~1;
+    int ho2 = (a.Ho + 1) & ~1;
+    if (a.R > ho2) a.R = ho2;
+    a.xrow = a.TWp + 16;
+    a.xplane = (a.R + 2) * a.xrow * 2 + 16;
+    a.tiles_c = (a.Wo + a.TWp - 1) / a.TWp;
+    a.tiles_r = (a.Ho + a.R - 1) / a.R;
+    a.n_ktiles = d->N * a.tiles_r * a.tiles_c;
+    a.nnzk = (int32_t)nnzk;
+    memcpy(a.taps, pk->taps, sizeof(a.taps));
+    int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
+    int ks = (2 * ctx->num_cu + ft * ct - 1) / (ft * ct);
+    if (ks > a.n_ktiles) ks = a.n_ktiles;
+    if (ks < 1) ks = 1;
+    a.ksplit = ks;
+    void *scr = nullptr;
+    s = pc_scratch(ctx, sizeof(float) * 4 * (size_t)ks * (size_t)nnzk, &scr);
+    if (s != PC_OK) return s;
+    size_t lds = (size_t)WG_T * WG_DY_PITCH + (size_t)WG_T * a.xplane;
+    hipLaunchKernelGGL(pc_mfma_wgrad_kernel, dim3((unsigned)ct, (unsigned)ft, (unsigned)ks), dim3(256), lds, ctx->stream,
+                       (const uint16_t *)x, (const uint16_t *)dy, a, pk->v, (float *)scr);
+    s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight launch");
+    if (s != PC_OK) return s;
+    return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, pk, dw);
 }

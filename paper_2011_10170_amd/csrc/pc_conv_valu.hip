@@ -359,6 +359,16 @@ pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, PackView v, fl
     dw[slot] = s;
 }
 
+// dw[slot] = partial[0][slot] + partial[1][slot] + ... in that order (partial is [G][nnzk][4] float32)
+pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, const pc_packed *pk, float *dw)
+{
+    int64_t nnzk = pk->nnzk;
+    if (nnzk <= 0) return PC_OK;
+    hipLaunchKernelGGL(pc_wgrad_reduce_kernel, dim3((unsigned)((nnzk + 255) / 256)), dim3(256), 0, ctx->stream,
+                       (const float4 *)partial, G, pk->v, (float4 *)dw);
+    return pc_hip_check(ctx, hipGetLastError(), "bwd_weight reduce launch");
+}
+
 pc_status pc_valu_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
                              float *dw)
 {
@@ -396,7 +406,7 @@ pc_status pc_valu_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     else
         hipLaunchKernelGGL((pc_wgrad_valu_kernel<uint16_t>), grid, dim3(256), 0, ctx->stream, (const uint16_t *)x,
                            (const uint16_t *)dy, a, pk->v, (float4 *)scr);
-    hipLaunchKernelGGL(pc_wgrad_reduce_kernel, dim3((unsigned)bx), dim3(256), 0, ctx->stream, (const float4 *)scr, G,
-                       pk->v, (float4 *)dw);
-    return pc_hip_check(ctx, hipGetLastError(), "VALU bwd_weight launch");
+    s = pc_hip_check(ctx, hipGetLastError(), "VALU bwd_weight launch");
+    if (s != PC_OK) return s;
+    return pc_launch_wgrad_reduce(ctx, (const float *)scr, G, pk, dw);
 }

@@ -89,6 +89,8 @@ pc_status pc_valu_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
 pc_status pc_valu_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,
                              const void *dy, float *dw);
 
+pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, const pc_packed *pk, float *dw);
+
 bool pc_mfma_supports(int F, int C);
 pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W);
 pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y);
