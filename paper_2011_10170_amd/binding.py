@@ -21,7 +21,7 @@ PC_SCORE_RETAINED, PC_SCORE_KERNEL = 0, 1
 PC_VARIANT_AUTO, PC_VARIANT_VALU, PC_VARIANT_MFMA = 0, 1, 2
 
 EXPORTS = [
-    "pc_create", "pc_destroy", "pc_status_str", "pc_last_error", "pc_set_variant",
+    "pc_create", "pc_destroy", "pc_status_str", "pc_last_error", "pc_set_variant", "pc_set_plan_override",
     "pc_check_library", "pc_check_conv_desc", "pc_pattern_select", "pc_pack", "pc_update_values",
     "pc_packed_info", "pc_packed_free", "pc_scatter_dense", "pc_unpack_dense",
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
@@ -60,6 +60,7 @@ def load():
     lib.pc_last_error.argtypes = [vp]
     lib.pc_last_error.restype = ct.c_char_p
     lib.pc_set_variant.argtypes = [vp, ct.c_int]
+    lib.pc_set_plan_override.argtypes = [vp, i32, i32]
     lib.pc_check_library.argtypes = [vp, i32]
     lib.pc_check_conv_desc.argtypes = [ct.POINTER(pc_conv_desc)]
     lib.pc_pattern_select.argtypes = [vp, vp, vp, i32, i32, vp, i32, ct.c_int, i64, ct.c_int, vp, vp]
@@ -121,6 +122,10 @@ def pc_destroy(ctx) -> None:
 
 def pc_set_variant(ctx, variant: int) -> None:
     _check(ctx, load().pc_set_variant(ctx, int(variant)))
+
+
+def pc_set_plan_override(ctx, tile_cfg: int = -1, split_k: int = 0) -> None:
+    _check(ctx, load().pc_set_plan_override(ctx, int(tile_cfg), int(split_k)))
 
 
 def pc_check_library(masks: Sequence[int]) -> int:

@@ -93,6 +93,8 @@ extern "C" pc_status pc_create(pc_ctx **out, int device, void *hip_stream)
     ctx->device = device;
     ctx->stream = (hipStream_t)hip_stream;
     ctx->forced = PC_VARIANT_AUTO;
+    ctx->plan_cfg = -1;
+    ctx->plan_split = 0;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) { delete ctx; return PC_ERR_DEVICE; }
     ctx->num_cu = prop.multiProcessorCount;
@@ -120,6 +122,16 @@ extern "C" pc_status pc_set_variant(pc_ctx *ctx, pc_variant v)
     if (v != PC_VARIANT_AUTO && v != PC_VARIANT_VALU && v != PC_VARIANT_MFMA)
         return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_set_variant: unknown variant %d", (int)v);
     ctx->forced = v;
+    return PC_OK;
+}
+
+extern "C" pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t split_k)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (tile_cfg < -1 || tile_cfg > 5 || split_k < 0 || split_k > 64)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_set_plan_override: tile_cfg %d split_k %d out of range", tile_cfg, split_k);
+    ctx->plan_cfg = tile_cfg;
+    ctx->plan_split = split_k;
     return PC_OK;
 }
 

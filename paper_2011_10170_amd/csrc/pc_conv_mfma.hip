@@ -21,7 +21,6 @@
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-#define MF_PITCH 80          // LDS bytes per staged pixel: 32 channels of bf16 + 16 bytes of padding
 #define MF_LDS_MAX 65536
 
 bool pc_mfma_supports(int F, int C) { return F % 8 == 0 && C % 8 == 0; }
@@ -34,17 +33,27 @@ struct MfmaArgs {
     int32_t TI, TH, TW, IH, IW;
     int32_t tiles_y, tiles_x;
     int32_t KS;              // k-steps of 16 in the packed operand (padded reduction length / 16)
+    int32_t nchunks, cps;    // chunks of KC channels in total, and per split (blockIdx.z)
     int32_t tap_w[9];        // weight tap index of every list entry
     int32_t tap_off[9];      // LDS byte offset of every list entry
 };
 
-template <int A_T, int B_T, int WAVES_M, int WAVES_N, int NTAPS>
-__global__ void __launch_bounds__(256)
+// KC channels are staged per pass (LDS pixel pitch 2*KC + 16 bytes: conflict-free 16-byte reads).
+// A fragments are prefetched PF steps ahead from global memory, B fragments one step ahead from LDS.
+// With gridDim.z > 1 every split reduces its own range of channel chunks and writes float32 partial
+// sums [split][pixel][m] that pc_mfma_splitk_reduce_kernel adds in a fixed order.
+template <int A_T, int B_T, int WAVES_M, int WAVES_N, int NTAPS, int KC>
+__global__ void __launch_bounds__(256, 2)
 pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const uint16_t *__restrict__ wz,
-                    MfmaArgs g)
+                    float *__restrict__ partial, MfmaArgs g)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int BM = 32 * A_T * WAVES_M;
+    constexpr int KSC = KC / 16;
+    constexpr int NS = NTAPS * KSC;
+    constexpr int PF = (NS % 3 == 0) ? 3 : 2;
+    constexpr int PITCH = 2 * KC + 16;
+    constexpr int PARTS = KC / 8;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -58,6 +67,8 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
     const int m0 = blockIdx.y * BM + wm * (32 * A_T);
     const int mt0 = m0 >> 5;
     const int npix = g.TI * g.TH * g.TW;
+    const int ch0 = blockIdx.z * g.cps;
+    const int ch1 = min(ch0 + g.cps, g.nchunks);
 
     int base[B_T];
 #pragma unroll
@@ -67,7 +78,7 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
         int ti = q / (g.TH * g.TW);
         int rem = q - ti * g.TH * g.TW;
         int y = rem / g.TW, x = rem - y * g.TW;
-        base[j] = ((ti * g.IH + y * g.lstep) * g.IW + x * g.lstep) * MF_PITCH + (lane >> 5) * 16;
+        base[j] = ((ti * g.IH + y * g.lstep) * g.IW + x * g.lstep) * PITCH + (lane >> 5) * 16;
     }
 
     f32x16 acc[A_T][B_T];
@@ -78,40 +89,71 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    const uint16_t *wzl = wz + (int64_t)mt0 * 9 * g.KS * 512 + lane * 8;
+    // fragment of row tile i for step st of chunk ch (past the last chunk: re-read the last one, unused)
+    auto a_load = [&](int ch, int st, int i) -> bf16x8 {
+        const int t = st / KSC, ks = st % KSC;
+        const int chc = ch < ch1 ? ch : ch1 - 1;
+        return *reinterpret_cast<const bf16x8 *>(wzl + (int64_t)((i * 9 + g.tap_w[t]) * g.KS + chc * KSC + ks) * 512);
+    };
+    bf16x8 aring[PF][A_T];
+#pragma unroll
+    for (int d = 0; d < PF; ++d)
+#pragma unroll
+        for (int i = 0; i < A_T; ++i) aring[d][i] = a_load(ch0, d, i);
+
+    // element offset of every staged pixel in the input tensor (-1 = zero padding), computed once
     const int HP = g.TI * g.IH * g.IW;
-    const int nchunks = g.KS >> 1;
-    for (int ch = 0; ch < nchunks; ++ch) {
+    int64_t *pixoff = reinterpret_cast<int64_t *>(lds + (size_t)HP * PITCH);
+    for (int q = threadIdx.x; q < HP; q += 256) {
+        int ix = q % g.IW;
+        int t2 = q / g.IW;
+        int iy = t2 % g.IH;
+        int ti = t2 / g.IH;
+        int n = tn * g.TI + ti, y = in_y0 + iy, x = in_x0 + ix;
+        bool ok = n < g.N && y >= 0 && y < g.in_H && x >= 0 && x < g.in_W;
+        pixoff[q] = ok ? (((int64_t)n * g.in_H + y) * g.in_W + x) * g.in_CH : (int64_t)-1;
+    }
+    for (int ch = ch0; ch < ch1; ++ch) {
         __syncthreads();
-        for (int e = threadIdx.x; e < HP * 4; e += 256) {
-            int q = e >> 2, part = e & 3;
-            int ix = q % g.IW;
-            int t2 = q / g.IW;
-            int iy = t2 % g.IH;
-            int ti = t2 / g.IH;
-            int n = tn * g.TI + ti, y = in_y0 + iy, x = in_x0 + ix, c = ch * 32 + part * 8;
+        for (int e = threadIdx.x; e < HP * PARTS; e += 256) {
+            const int q = e / PARTS, part = e - q * PARTS;
+            const int c = ch * KC + part * 8;
+            const int64_t po = pixoff[q];
             uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (n < g.N && y >= 0 && y < g.in_H && x >= 0 && x < g.in_W && c < g.in_CH)
-                v = *reinterpret_cast<const uint4 *>(in + (((int64_t)n * g.in_H + y) * g.in_W + x) * g.in_CH + c);
-            *reinterpret_cast<uint4 *>(lds + q * MF_PITCH + part * 16) = v;
+            if (po >= 0 && c < g.in_CH) v = *reinterpret_cast<const uint4 *>(in + po + c);
+            *reinterpret_cast<uint4 *>(lds + q * PITCH + part * 16) = v;
         }
         __syncthreads();
+        bf16x8 bcur[B_T], bnxt[B_T];
 #pragma unroll
-        for (int t = 0; t < NTAPS; ++t) {
+        for (int j = 0; j < B_T; ++j) bcur[j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[0]);
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                bf16x8 af[A_T], bfr[B_T];
-#pragma unroll
-                for (int i = 0; i < A_T; ++i)
-                    af[i] = *reinterpret_cast<const bf16x8 *>(
-                        wz + ((((int64_t)(mt0 + i) * 9 + g.tap_w[t]) * g.KS + ch * 2 + ks) * 64 + lane) * 8);
+        for (int st = 0; st < NS; ++st) {
+            if (st + 1 < NS) {
+                const int t1 = (st + 1) / KSC, k1 = (st + 1) % KSC;
 #pragma unroll
                 for (int j = 0; j < B_T; ++j)
-                    bfr[j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[t] + ks * 32);
+                    bnxt[j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[t1] + k1 * 32);
+            }
+            bf16x8 anow[A_T];
 #pragma unroll
-                for (int i = 0; i < A_T; ++i)
+            for (int i = 0; i < A_T; ++i) anow[i] = aring[st % PF][i];
+            {
+                const int nst = st + PF;
+                const int nch = nst >= NS ? ch + 1 : ch;
+                const int nss = nst >= NS ? nst - NS : nst;
 #pragma unroll
-                    for (int j = 0; j < B_T; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < A_T; ++i) aring[st % PF][i] = a_load(nch, nss, i);
+            }
+#pragma unroll
+            for (int i = 0; i < A_T; ++i)
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(anow[i], bcur[j], acc[i][j], 0, 0, 0);
+            if (st + 1 < NS) {
+#pragma unroll
+                for (int j = 0; j < B_T; ++j) bcur[j] = bnxt[j];
             }
         }
     }
@@ -127,20 +169,52 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
         int n = tn * g.TI + ti, gy = gy0 + y, gx = gx0 + x;
         if (n >= g.N || gy >= g.GH || gx >= g.GW) continue;
         int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
-        uint16_t *op = out + (((int64_t)n * g.out_H + oy) * g.out_W + ox) * g.out_CH;
+        const int64_t opix = ((int64_t)n * g.out_H + oy) * g.out_W + ox;
+        if (gridDim.z == 1) {
+            uint16_t *op = out + opix * g.out_CH;
 #pragma unroll
-        for (int i = 0; i < A_T; ++i)
+            for (int i = 0; i < A_T; ++i)
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                int m = m0 + i * 32 + r4 * 8 + (lane >> 5) * 4;
-                if (m < g.out_CH) {
-                    uint2 pk;
-                    pk.x = (uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 0]) | ((uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 1]) << 16);
-                    pk.y = (uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 2]) | ((uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 3]) << 16);
-                    *reinterpret_cast<uint2 *>(op + m) = pk;
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    int m = m0 + i * 32 + r4 * 8 + (lane >> 5) * 4;
+                    if (m < g.out_CH) {
+                        uint2 pk;
+                        pk.x = (uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 0]) | ((uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 1]) << 16);
+                        pk.y = (uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 2]) | ((uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 3]) << 16);
+                        *reinterpret_cast<uint2 *>(op + m) = pk;
+                    }
                 }
-            }
+        } else {
+            const int64_t npx_all = (int64_t)g.N * g.out_H * g.out_W;
+            float *pp = partial + ((int64_t)blockIdx.z * npx_all + opix) * g.out_CH;
+#pragma unroll
+            for (int i = 0; i < A_T; ++i)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    int m = m0 + i * 32 + r4 * 8 + (lane >> 5) * 4;
+                    if (m < g.out_CH)
+                        *reinterpret_cast<float4 *>(pp + m) = make_float4(acc[i][j][r4 * 4 + 0], acc[i][j][r4 * 4 + 1],
+                                                                          acc[i][j][r4 * 4 + 2], acc[i][j][r4 * 4 + 3]);
+                }
+        }
     }
+}
+
+// out[e] = bf16(partial[0][e] + partial[1][e] + ...), 4 elements per thread
+__global__ void __launch_bounds__(256)
+pc_mfma_splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int splits, uint2 *__restrict__ out)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n4) return;
+    float4 s = partial[e];
+    for (int z = 1; z < splits; ++z) {
+        float4 p = partial[(int64_t)z * n4 + e];
+        s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    uint2 pk;
+    pk.x = (uint32_t)pc_f32_to_bf16(s.x) | ((uint32_t)pc_f32_to_bf16(s.y) << 16);
+    pk.y = (uint32_t)pc_f32_to_bf16(s.z) | ((uint32_t)pc_f32_to_bf16(s.w) << 16);
+    out[e] = pk;
 }
 
 // ------------------------------------------------------------------ operand tiles
@@ -198,8 +272,12 @@ pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W)
 }
 
 // ------------------------------------------------------------------ planning and launch
-struct MfmaCfg { int a, b, wm, wn; };
-static const MfmaCfg kCfgs[] = {{2, 4, 1, 4}, {2, 4, 2, 2}, {2, 2, 2, 2}, {1, 2, 2, 2}, {1, 1, 2, 2}};
+struct MfmaCfg { int a, b, wm, wn, kc; };
+static const MfmaCfg kCfgs[] = {
+    {2, 4, 1, 4, 32}, {2, 4, 2, 2, 32}, {2, 2, 2, 2, 32}, {2, 2, 2, 2, 64}, {1, 2, 2, 2, 64}, {1, 1, 2, 2, 64},
+};
+// automatic choice tries these in order and keeps the first that yields enough workgroups (else the last)
+static const int kAutoOrder[] = {4, 5};
 static const int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
 static void plan_mfma_tiles(MfmaArgs *g, int BN, int ext)
@@ -219,15 +297,15 @@ static void plan_mfma_tiles(MfmaArgs *g, int BN, int ext)
     g->tiles_x = (g->GW + g->TW - 1) / g->TW;
 }
 
-template <int A_T, int B_T, int WM, int WN>
+template <int A_T, int B_T, int WM, int WN, int KC>
 static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, int ntaps, const uint16_t *in, uint16_t *out,
-                       const uint16_t *wz, const MfmaArgs &g)
+                       const uint16_t *wz, float *partial, const MfmaArgs &g)
 {
     switch (ntaps) {
-    case 9: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 9>), grid, dim3(256), lds, st, in, out, wz, g); break;
-    case 4: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 4>), grid, dim3(256), lds, st, in, out, wz, g); break;
-    case 2: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 2>), grid, dim3(256), lds, st, in, out, wz, g); break;
-    default: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 1>), grid, dim3(256), lds, st, in, out, wz, g); break;
+    case 9: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 9, KC>), grid, dim3(256), lds, st, in, out, wz, partial, g); break;
+    case 4: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 4, KC>), grid, dim3(256), lds, st, in, out, wz, partial, g); break;
+    case 2: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 2, KC>), grid, dim3(256), lds, st, in, out, wz, partial, g); break;
+    default: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 1, KC>), grid, dim3(256), lds, st, in, out, wz, partial, g); break;
     }
 }
 
@@ -235,36 +313,65 @@ static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, int ntaps, const u
 static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, const int *tr, const int *tc,
                                const uint16_t *in, uint16_t *out, const uint16_t *wz)
 {
-    int pick = -1;
+    int pick = -1, pick_split = 1;
     MfmaArgs best = g;
-    for (int ci = 0; ci < kNumCfgs; ++ci) {
+    const int64_t want = 2 * (int64_t)ctx->num_cu;
+    const int n_try = ctx->plan_cfg >= 0 ? 1 : (int)(sizeof(kAutoOrder) / sizeof(kAutoOrder[0]));
+    for (int k = 0; k < n_try; ++k) {
+        const int ci = ctx->plan_cfg >= 0 ? ctx->plan_cfg : kAutoOrder[k];
         const MfmaCfg &c = kCfgs[ci];
         int BM = 32 * c.a * c.wm, BN = 32 * c.b * c.wn;
-        if (BM > 64 && g.out_CH <= 64) continue;
         MfmaArgs t = g;
         plan_mfma_tiles(&t, BN, ext);
-        size_t lds = (size_t)t.TI * t.IH * t.IW * MF_PITCH;
+        size_t lds = (size_t)t.TI * t.IH * t.IW * (2 * c.kc + 16 + 8);
         if (lds > MF_LDS_MAX) continue;
+        t.nchunks = (g.KS * 16 + c.kc - 1) / c.kc;
         int64_t blocks = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x * ((g.out_CH + BM - 1) / BM);
+        int split = 1;
+        if (ctx->plan_split > 0) split = ctx->plan_split;
+        else if (k == n_try - 1 && blocks < ctx->num_cu) {
+            split = (int)((ctx->num_cu + blocks - 1) / blocks);
+            if (split > 4) split = 4;
+        }
+        if (g.oscale != 1) split = 1;   // parity-class launches of one call share the output: no partial buffers
+        if (split > t.nchunks) split = t.nchunks;
+        t.cps = (t.nchunks + split - 1) / split;
+        split = (t.nchunks + t.cps - 1) / t.cps;
         pick = ci;
+        pick_split = split;
         best = t;
-        if (blocks >= 2 * (int64_t)ctx->num_cu) break;   // enough workgroups to fill the chip: keep the bigger tile
+        if (blocks >= want) break;   // enough workgroups to fill the chip: keep the bigger tile
     }
     if (pick < 0) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA conv: no tile configuration fits in LDS");
     g = best;
-    for (int t = 0; t < ntaps; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * MF_PITCH;
     const MfmaCfg &c = kCfgs[pick];
+    for (int t = 0; t < ntaps; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * (2 * c.kc + 16);
     int BM = 32 * c.a * c.wm;
-    dim3 grid((unsigned)(((g.N + g.TI - 1) / g.TI) * g.tiles_y * g.tiles_x), (unsigned)((g.out_CH + BM - 1) / BM));
-    size_t lds = (size_t)g.TI * g.IH * g.IW * MF_PITCH;
-    switch (pick) {
-    case 0: launch_cfg<2, 4, 1, 4>(ctx->stream, grid, lds, ntaps, in, out, wz, g); break;
-    case 1: launch_cfg<2, 4, 2, 2>(ctx->stream, grid, lds, ntaps, in, out, wz, g); break;
-    case 2: launch_cfg<2, 2, 2, 2>(ctx->stream, grid, lds, ntaps, in, out, wz, g); break;
-    case 3: launch_cfg<1, 2, 2, 2>(ctx->stream, grid, lds, ntaps, in, out, wz, g); break;
-    default: launch_cfg<1, 1, 2, 2>(ctx->stream, grid, lds, ntaps, in, out, wz, g); break;
+    dim3 grid((unsigned)(((g.N + g.TI - 1) / g.TI) * g.tiles_y * g.tiles_x), (unsigned)((g.out_CH + BM - 1) / BM),
+              (unsigned)pick_split);
+    size_t lds = (size_t)g.TI * g.IH * g.IW * (2 * c.kc + 16 + 8);
+    float *partial = nullptr;
+    const int64_t n_out = (int64_t)g.N * g.out_H * g.out_W * g.out_CH;
+    if (pick_split > 1) {
+        void *scr = nullptr;
+        pc_status s = pc_scratch(ctx, sizeof(float) * (size_t)pick_split * (size_t)n_out, &scr);
+        if (s != PC_OK) return s;
+        partial = (float *)scr;
     }
-    return pc_hip_check(ctx, hipGetLastError(), "MFMA conv launch");
+    switch (pick) {
+    case 0: launch_cfg<2, 4, 1, 4, 32>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    case 1: launch_cfg<2, 4, 2, 2, 32>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    case 2: launch_cfg<2, 2, 2, 2, 32>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    case 3: launch_cfg<2, 2, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    case 4: launch_cfg<1, 2, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    default: launch_cfg<1, 1, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    }
+    pc_status s = pc_hip_check(ctx, hipGetLastError(), "MFMA conv launch");
+    if (s != PC_OK || pick_split == 1) return s;
+    int64_t n4 = n_out / 4;
+    hipLaunchKernelGGL(pc_mfma_splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, ctx->stream,
+                       (const float4 *)partial, n4, pick_split, (uint2 *)out);
+    return pc_hip_check(ctx, hipGetLastError(), "split-K reduce launch");
 }
 
 pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y)
@@ -319,40 +426,68 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
 
 // ------------------------------------------------------------------ backward-weight
 // dW[t][f][c] = sum over output pixels of dy[pixel][f] * x[pixel shifted by tap t][c]: for every tap a
-// GEMM with M = filters, N = channels and the pixels as the reduction. Both operands need the pixels
-// contiguous per lane, while NHWC memory has the channels contiguous, so the staging transposes:
-// LDS holds dyT[filter][pixel] and xT[channel][row][column] (bf16). One workgroup owns a 64x64 tile of
-// (filter, channel) for all 9 taps (each wave 32x32x9: 144 accumulator registers) and walks pixel tiles
-// of R rows x TWp columns of one image. The three horizontal taps of a kernel row come from ONE aligned
-// LDS read plus its two neighbouring dwords, re-aligned in registers with v_alignbit. Pixel tiles are
-// split over blockIdx.z; every split writes only the kept taps, in compact slot order, to its own
-// partial buffer, and a second kernel adds the partials in a fixed order (no float atomics).
+// GEMM with M = filters, N = channels and the pixels as the reduction. Both MFMA operands need 8
+// reduction indices contiguous per lane, while NHWC memory has the channels contiguous. The reduction
+// is therefore ordered (spatial position, image) with the image index fastest in groups of 8: a lane's
+// 8 values are the same pixel and channel of 8 consecutive images, every tap is just another spatial
+// position (a different 16-byte slot, always aligned), and the zero padding is a zero slot.
+// LDS holds dyT[filter][slot][8 images] and xT[channel][slot][8 images] (bf16); the staging loads the
+// 8 images of a (position, 8 channels) task with eight 16-byte loads, transposes 8x8 in registers
+// (v_perm) and writes eight 16-byte rows. Slot indices are XOR-swizzled with the channel group so that
+// both the transposing writes and the fragment reads are free of bank conflicts.
+// One workgroup owns a 64x64 tile of (filter, channel) for all 9 taps (each wave 32x32x9: 144
+// accumulator registers) and walks pixel tiles; pixel tiles are split over blockIdx.z; every split
+// writes only the kept taps, in compact slot order, to its own partial buffer, and a second kernel adds
+// the partials in a fixed order (no float atomics).
 #define WG_T 64                // filters and channels per workgroup
-#define WG_DY_PITCH 144        // bytes per filter row of dyT: 64 pixels of bf16 + 16 bytes of padding
+#define WG_NSLOT 16            // dy slots per pixel tile (8 MFMA k-steps)
+#define WG_DY_PLANE (WG_NSLOT * 16 + 16)
 
 struct WgradMfmaArgs {
-    int32_t N, H, W, C, F, Ho, Wo;
-    int32_t TWp, R;            // pixel tile: R rows x TWp columns (TWp % 8 == 0, R*TWp % 16 == 0, <= 64)
-    int32_t xrow;              // elements per xT row: TWp + 16 (column index = halo column + 7)
+    int32_t N, H, W, C, F, Ho, Wo, stride;
+    int32_t TR, TC, npos, ng;  // pixel tile: ng groups of 8 images x (TR x TC output positions)
+    int32_t IR, IC, xs_per_g;  // x region per image group: IR x IC positions
+    int32_t xslots;            // ng * xs_per_g rounded up to a multiple of 8
     int32_t xplane;            // bytes per xT channel plane
-    int32_t tiles_r, tiles_c, n_ktiles, ksplit;
+    int32_t nks;               // MFMA k-steps per pixel tile: ceil(ng * npos / 2)
+    int32_t tiles_r, tiles_c, tiles_n, n_ktiles, ksplit;
     int32_t nnzk;
     uint8_t taps[PC_MAX_P][4];
 };
 
-__device__ __forceinline__ bf16x8 pc_as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+// 8 rows (images) of 8 bf16 (channels) -> 8 rows (channels) of 8 bf16 (images), row j stored at dst + j*pitch
+__device__ __forceinline__ void pc_transpose8x8_store(const uint4 (&r)[8], unsigned char *dst, int pitch)
 {
-    uint4 v = make_uint4(a, b, c, d);
-    return __builtin_bit_cast(bf16x8, v);
+    const uint32_t in[8][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
+                               {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w},
+                               {r[4].x, r[4].y, r[4].z, r[4].w}, {r[5].x, r[5].y, r[5].z, r[5].w},
+                               {r[6].x, r[6].y, r[6].z, r[6].w}, {r[7].x, r[7].y, r[7].z, r[7].w}};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint4 lo, hi;
+        lo.x = __builtin_amdgcn_perm(in[1][d], in[0][d], 0x05040100u);
+        lo.y = __builtin_amdgcn_perm(in[3][d], in[2][d], 0x05040100u);
+        lo.z = __builtin_amdgcn_perm(in[5][d], in[4][d], 0x05040100u);
+        lo.w = __builtin_amdgcn_perm(in[7][d], in[6][d], 0x05040100u);
+        *reinterpret_cast<uint4 *>(dst + (2 * d) * pitch) = lo;
+        hi.x = __builtin_amdgcn_perm(in[1][d], in[0][d], 0x07060302u);
+        hi.y = __builtin_amdgcn_perm(in[3][d], in[2][d], 0x07060302u);
+        hi.z = __builtin_amdgcn_perm(in[5][d], in[4][d], 0x07060302u);
+        hi.w = __builtin_amdgcn_perm(in[7][d], in[6][d], 0x07060302u);
+        *reinterpret_cast<uint4 *>(dst + (2 * d + 1) * pitch) = hi;
+    }
 }
 
-__global__ void __launch_bounds__(256)
+#ifndef WG_OCC
+#define WG_OCC 2
+#endif
+__global__ void __launch_bounds__(256, WG_OCC)
 pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradMfmaArgs a, PackView v,
                      float *__restrict__ partial)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *dyT = lds;
-    unsigned char *xT = lds + WG_T * WG_DY_PITCH;
+    unsigned char *xT = lds + WG_T * WG_DY_PLANE;
     __shared__ int8_t jmap[PC_MAX_P][9];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -370,88 +505,122 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
-    const int nks = (a.R * a.TWp) >> 4;
-    const int hw = a.TWp + 2;
-    const unsigned char *a_base = dyT + (fh * 32 + (lane & 31)) * WG_DY_PITCH + g * 16;
-    const unsigned char *b_base = xT + (chh * 32 + (lane & 31)) * a.xplane;
+    // per lane: LDS addresses of its A row and B column, and the x slot of each k-step's dy slot
+    const int fl = fh * 32 + (lane & 31), cl = chh * 32 + (lane & 31);
+    const unsigned char *a_row = dyT + fl * WG_DY_PLANE;
+    const unsigned char *b_col = xT + cl * a.xplane;
+    const int a_sw = (fl >> 3) & 7, b_sw = (cl >> 3) & 7;
+    int xb[WG_NSLOT / 2];
+#pragma unroll
+    for (int kk = 0; kk < WG_NSLOT / 2; ++kk) {
+        int slot = 2 * kk + g;
+        int ig = slot / a.npos, pos = slot - ig * a.npos;
+        int py = pos / a.TC, px = pos - py * a.TC;
+        xb[kk] = (ig < a.ng) ? ig * a.xs_per_g + (py * a.stride) * a.IC + px * a.stride : 0;
+    }
+    int toff[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) toff[t] = (t / 3) * a.IC + (t % 3);
+
+    // staging tasks of this thread: the (slot, channel group) of a task is the same for every pixel tile
+    const int tcg = threadIdx.x & 7;                      // group of 8 filters (dy) / channels (x)
+    const bool has_dy = threadIdx.x < WG_NSLOT * 8;
+    const int d_slot = threadIdx.x >> 3;
+    const int d_ig = d_slot / a.npos, d_pos = d_slot - d_ig * a.npos;
+    const int d_py = d_pos / a.TC, d_px = d_pos - d_py * a.TC;
+    bool has_x[2];
+    int x_slot[2], x_ig[2], x_iy[2], x_ix[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int e = threadIdx.x + 256 * k;
+        has_x[k] = e < a.xslots * 8;
+        x_slot[k] = e >> 3;
+        x_ig[k] = x_slot[k] / a.xs_per_g;
+        const int rem = x_slot[k] - x_ig[k] * a.xs_per_g;
+        x_iy[k] = rem / a.IC;
+        x_ix[k] = rem - x_iy[k] * a.IC;
+    }
+    const int64_t dy_img = (int64_t)a.Ho * a.Wo * a.F, x_img = (int64_t)a.H * a.W * a.C;
 
     for (int kt = blockIdx.z; kt < a.n_ktiles; kt += a.ksplit) {
         int q = kt;
         const int tc = q % a.tiles_c; q /= a.tiles_c;
         const int tr = q % a.tiles_r;
-        const int n = q / a.tiles_r;
-        const int oy0 = tr * a.R, ox0 = tc * a.TWp;
+        const int tn = q / a.tiles_r;
+        const int oy0 = tr * a.TR, ox0 = tc * a.TC, n0 = tn * a.ng * 8;
         __syncthreads();
-        // dy tile, transposed to [filter][pixel]
-        for (int e = threadIdx.x; e < a.R * a.TWp * 8; e += 256) {
-            int fg = e & 7, p = e >> 3;
-            int prow = p / a.TWp, pcol = p - prow * a.TWp;
-            int oy = oy0 + prow, ox = ox0 + pcol, f = f0 + fg * 8;
-            uint4 val = make_uint4(0u, 0u, 0u, 0u);
-            if (oy < a.Ho && ox < a.Wo && f < a.F)
-                val = *reinterpret_cast<const uint4 *>(dy + (((int64_t)n * a.Ho + oy) * a.Wo + ox) * a.F + f);
-            uint16_t *dst = reinterpret_cast<uint16_t *>(dyT + (fg * 8) * WG_DY_PITCH) + p;
-            const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+        if (has_dy) {
+            const int oy = oy0 + d_py, ox = ox0 + d_px, f = f0 + tcg * 8, nb = n0 + d_ig * 8;
+            const bool ok = d_ig < a.ng && oy < a.Ho && ox < a.Wo && f < a.F;
+            const uint16_t *src = dy + (int64_t)nb * dy_img + ((int64_t)oy * a.Wo + ox) * a.F + f;
+            uint4 r[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                dst[(2 * j) * (WG_DY_PITCH / 2)] = (uint16_t)(w[j] & 0xFFFFu);
-                dst[(2 * j + 1) * (WG_DY_PITCH / 2)] = (uint16_t)(w[j] >> 16);
+            for (int i = 0; i < 8; ++i) {
+                r[i] = make_uint4(0u, 0u, 0u, 0u);
+#ifndef EXP_NO_LOAD
+                if (ok && nb + i < a.N) r[i] = *reinterpret_cast<const uint4 *>(src + i * dy_img);
+#endif
+            }
+            pc_transpose8x8_store(r, dyT + (tcg * 8) * WG_DY_PLANE + ((d_slot ^ tcg) << 4), WG_DY_PLANE);
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (has_x[k]) {
+                const int yy = oy0 * a.stride - 1 + x_iy[k], xx = ox0 * a.stride - 1 + x_ix[k];
+                const int c = c0 + tcg * 8, nb = n0 + x_ig[k] * 8;
+                const bool ok = x_ig[k] < a.ng && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && c < a.C;
+                const uint16_t *src = x + (int64_t)nb * x_img + ((int64_t)yy * a.W + xx) * a.C + c;
+                uint4 r[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    r[i] = make_uint4(0u, 0u, 0u, 0u);
+#ifndef EXP_NO_LOAD
+                    if (ok && nb + i < a.N) r[i] = *reinterpret_cast<const uint4 *>(src + i * x_img);
+#endif
+                }
+                pc_transpose8x8_store(r, xT + (tcg * 8) * a.xplane + ((x_slot[k] ^ tcg) << 4), a.xplane);
             }
         }
-        // x halo tile, transposed to [channel][row][column + 7]
-        for (int e = threadIdx.x; e < (a.R + 2) * hw * 8; e += 256) {
-            int cg = e & 7, p = e >> 3;
-            int hy = p / hw, hx = p - hy * hw;
-            int yy = oy0 - 1 + hy, xx = ox0 - 1 + hx, c = c0 + cg * 8;
-            uint4 val = make_uint4(0u, 0u, 0u, 0u);
-            if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && c < a.C)
-                val = *reinterpret_cast<const uint4 *>(x + (((int64_t)n * a.H + yy) * a.W + xx) * a.C + c);
-            unsigned char *dstb = xT + (cg * 8) * a.xplane + (hy * a.xrow + hx + 7) * 2;
-            const uint32_t w[4] = {val.x, val.y, val.z, val.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                *reinterpret_cast<uint16_t *>(dstb + (2 * j) * a.xplane) = (uint16_t)(w[j] & 0xFFFFu);
-                *reinterpret_cast<uint16_t *>(dstb + (2 * j + 1) * a.xplane) = (uint16_t)(w[j] >> 16);
-            }
-        }
         __syncthreads();
-        for (int kk = 0; kk < nks; ++kk) {
-            const bf16x8 af = *reinterpret_cast<const bf16x8 *>(a_base + kk * 32);
-            const int p = kk * 16 + g * 8;
-            const int prow = p / a.TWp, pcol = p - prow * a.TWp;
 #pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                const unsigned char *bp = b_base + ((prow + r) * a.xrow + pcol + 8) * 2;
-                const uint32_t dm = *reinterpret_cast<const uint32_t *>(bp - 4);
-                const uint4 d = *reinterpret_cast<const uint4 *>(bp);
-                const uint32_t dp = *reinterpret_cast<const uint32_t *>(bp + 16);
-                const uint32_t s01 = __builtin_amdgcn_alignbit(d.y, d.x, 16);
-                const uint32_t s12 = __builtin_amdgcn_alignbit(d.z, d.y, 16);
-                const uint32_t s23 = __builtin_amdgcn_alignbit(d.w, d.z, 16);
-                const bf16x8 b0 = pc_as_bf16x8(__builtin_amdgcn_alignbit(d.x, dm, 16), s01, s12, s23);
-                const bf16x8 b1 = pc_as_bf16x8(d.x, d.y, d.z, d.w);
-                const bf16x8 b2 = pc_as_bf16x8(s01, s12, s23, __builtin_amdgcn_alignbit(dp, d.w, 16));
-                acc[3 * r + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b0, acc[3 * r + 0], 0, 0, 0);
-                acc[3 * r + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b1, acc[3 * r + 1], 0, 0, 0);
-                acc[3 * r + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b2, acc[3 * r + 2], 0, 0, 0);
+        for (int kk = 0; kk < WG_NSLOT / 2; ++kk) {
+            if (kk < a.nks) {
+                const bf16x8 af = *reinterpret_cast<const bf16x8 *>(a_row + (((2 * kk + g) ^ a_sw) << 4));
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const bf16x8 bf = *reinterpret_cast<const bf16x8 *>(b_col + (((xb[kk] + toff[t]) ^ b_sw) << 4));
+#ifndef EXP_NO_MFMA
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[t], 0, 0, 0);
+#else
+                    acc[t][0] += (float)bf[0] * (float)af[0];
+#endif
+                }
             }
         }
     }
-    // kept taps only, compact slot order
-    const int c = c0 + chh * 32 + (lane & 31);
+    // kept taps only, compact slot order; the table look-ups are issued together, then the stores
+    const int c = c0 + cl;
     float *pout = partial + (int64_t)blockIdx.z * a.nnzk * 4;
+    int slot[16], pidv[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int f = f0 + fh * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-        if (f < a.F && c < a.C) {
-            const int slot = v.slot_of[(int64_t)f * a.C + c];
-            if (slot >= 0) {
-                const int8_t *jm = jmap[v.fm_pid[slot]];
+        slot[i] = (f < a.F && c < a.C) ? v.slot_of[(int64_t)f * a.C + c] : -1;
+    }
 #pragma unroll
-                for (int t = 0; t < 9; ++t) {
-                    const int j = jm[t];
-                    if (j >= 0) pout[(int64_t)slot * 4 + j] = acc[t][i];
-                }
+    for (int i = 0; i < 16; ++i) pidv[i] = slot[i] >= 0 ? (int)v.fm_pid[slot[i]] : 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if (slot[i] >= 0) {
+            const int8_t *jm = jmap[pidv[i]];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const int j = jm[t];
+#ifndef EXP_NO_EPI
+                if (j >= 0) pout[(int64_t)slot[i] * 4 + j] = acc[t][i];
+#else
+                if (j >= 0 && acc[t][i] == 1.2345f) pout[(int64_t)slot[i] * 4 + j] = acc[t][i];
+#endif
             }
         }
     }
@@ -460,36 +629,62 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
                              float *dw)
 {
-    if (d->stride != 1) return pc_valu_bwd_weight(ctx, d, pk, x, dy, dw);   // stride-2 contraction not built yet
     int64_t nnzk = 0;
     pc_status s = pc_packed_info(ctx, pk, &nnzk, nullptr);
     if (s != PC_OK) return s;
     if (nnzk == 0) return PC_OK;
     WgradMfmaArgs a;
     memset(&a, 0, sizeof(a));
-    a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.F = d->F; a.Ho = d->H; a.Wo = d->W;
-    int ntc = (a.Wo + 31) / 32;
-    int tw = (a.Wo + ntc - 1) / ntc;
-    a.TWp = (tw + 7) / 8 * 8;
-    a.R = (64 / a.TWp) & ~1;
-    int ho2 = (a.Ho + 1) & ~1;
-    if (a.R > ho2) a.R = ho2;
-    a.xrow = a.TWp + 16;
-    a.xplane = (a.R + 2) * a.xrow * 2 + 16;
-    a.tiles_c = (a.Wo + a.TWp - 1) / a.TWp;
-    a.tiles_r = (a.Ho + a.R - 1) / a.R;
-    a.n_ktiles = d->N * a.tiles_r * a.tiles_c;
+    const int st = d->stride;
+    a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.F = d->F; a.stride = st;
+    a.Ho = (d->H - 1) / st + 1; a.Wo = (d->W - 1) / st + 1;
+    // output region per image group: up to 16 positions at stride 1, 8 at stride 2 (the x region grows 4x)
+    const int maxpos = st == 1 ? WG_NSLOT : WG_NSLOT / 2;
+    int best_tr = 1, best_tc = 1, best_ng = 1;
+    double best_eff = -1.0;
+    const int ngroups = (a.N + 7) / 8;
+    for (int tr = 1; tr <= maxpos; ++tr)
+        for (int tc = 1; tr * tc <= maxpos; ++tc) {
+            if (tr > a.Ho && tr > 1) continue;
+            if (tc > a.Wo && tc > 1) continue;
+            const int xs1 = ((tr - 1) * st + 3) * ((tc - 1) * st + 3);
+            int ngc = maxpos / (tr * tc);
+            if (ngc > ngroups) ngc = ngroups;
+            while (ngc > 1 && (size_t)WG_T * WG_DY_PLANE + (size_t)WG_T * (((ngc * xs1 + 7) / 8 * 8) * 16 + 16) > MF_LDS_MAX)
+                --ngc;
+            if ((size_t)WG_T * WG_DY_PLANE + (size_t)WG_T * (((ngc * xs1 + 7) / 8 * 8) * 16 + 16) > MF_LDS_MAX) continue;
+            int nr = (a.Ho + tr - 1) / tr, nc = (a.Wo + tc - 1) / tc;
+            double cover = (double)a.Ho * a.Wo / ((double)nr * tr * nc * tc);   // useful part of the tiles
+            double fill = (double)(ngc * tr * tc) / WG_NSLOT;                    // used dy slots
+            double halo = (double)(tr * tc) / xs1;                              // x reuse
+            double eff = cover * fill * (0.75 + 0.25 * halo);
+            if (eff > best_eff) { best_eff = eff; best_tr = tr; best_tc = tc; best_ng = ngc; }
+        }
+    if (best_eff < 0.0) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: no pixel tile fits in LDS");
+    a.TR = best_tr; a.TC = best_tc; a.npos = a.TR * a.TC;
+    a.ng = best_ng;
+    a.IR = (a.TR - 1) * st + 3; a.IC = (a.TC - 1) * st + 3;
+    a.xs_per_g = a.IR * a.IC;
+    a.xslots = (a.ng * a.xs_per_g + 7) / 8 * 8;
+    a.xplane = a.xslots * 16 + 16;
+    a.nks = (a.ng * a.npos + 1) / 2;
+    a.tiles_r = (a.Ho + a.TR - 1) / a.TR;
+    a.tiles_c = (a.Wo + a.TC - 1) / a.TC;
+    a.tiles_n = (ngroups + a.ng - 1) / a.ng;
+    a.n_ktiles = a.tiles_n * a.tiles_r * a.tiles_c;
     a.nnzk = (int32_t)nnzk;
     memcpy(a.taps, pk->taps, sizeof(a.taps));
+    size_t lds = (size_t)WG_T * WG_DY_PLANE + (size_t)WG_T * a.xplane;
+    if (lds > MF_LDS_MAX) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: tile does not fit in LDS");
     int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
-    int ks = (2 * ctx->num_cu + ft * ct - 1) / (ft * ct);
+    if (a.xslots * 8 > 512) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: x tile too large");
+    int ks = ctx->num_cu / (ft * ct);
     if (ks > a.n_ktiles) ks = a.n_ktiles;
     if (ks < 1) ks = 1;
     a.ksplit = ks;
     void *scr = nullptr;
     s = pc_scratch(ctx, sizeof(float) * 4 * (size_t)ks * (size_t)nnzk, &scr);
     if (s != PC_OK) return s;
-    size_t lds = (size_t)WG_T * WG_DY_PITCH + (size_t)WG_T * a.xplane;
     hipLaunchKernelGGL(pc_mfma_wgrad_kernel, dim3((unsigned)ct, (unsigned)ft, (unsigned)ks), dim3(256), lds, ctx->stream,
                        (const uint16_t *)x, (const uint16_t *)dy, a, pk->v, (float *)scr);
     s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight launch");

@@ -345,18 +345,32 @@ pc_wgrad_valu_kernel(const T *__restrict__ x, const T *__restrict__ dy, WgradArg
     if (live) partial[(int64_t)blockIdx.y * nnzk + slot] = make_float4(acc0, acc1, acc2, acc3);
 }
 
+// dw[slot] = sum over g of partial[g][slot] in a fixed order: 16 consecutive slots per workgroup,
+// 16 threads per slot each adding every 16th partial, then one thread adds the 16 sub-sums in order.
 __global__ void __launch_bounds__(256)
 pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, PackView v, float4 *__restrict__ dw)
 {
+    __shared__ float4 sub[16][16];
     const int nnzk = v.fm_rowptr[v.F];
-    int slot = blockIdx.x * blockDim.x + threadIdx.x;
-    if (slot >= nnzk) return;
+    const int q = threadIdx.x & 15, sg = threadIdx.x >> 4;
+    const int slot = blockIdx.x * 16 + q;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int gi = 0; gi < G; ++gi) {
-        float4 p = partial[(int64_t)gi * nnzk + slot];
-        s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    if (slot < nnzk) {
+        for (int gi = sg; gi < G; gi += 16) {
+            float4 p = partial[(int64_t)gi * nnzk + slot];
+            s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+        }
     }
-    dw[slot] = s;
+    sub[sg][q] = s;
+    __syncthreads();
+    if (sg == 0 && slot < nnzk) {
+        float4 t = sub[0][q];
+        for (int i = 1; i < 16; ++i) {
+            float4 p = sub[i][q];
+            t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+        }
+        dw[slot] = t;
+    }
 }
 
 // dw[slot] = partial[0][slot] + partial[1][slot] + ... in that order (partial is [G][nnzk][4] float32)
@@ -364,7 +378,7 @@ pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, const
 {
     int64_t nnzk = pk->nnzk;
     if (nnzk <= 0) return PC_OK;
-    hipLaunchKernelGGL(pc_wgrad_reduce_kernel, dim3((unsigned)((nnzk + 255) / 256)), dim3(256), 0, ctx->stream,
+    hipLaunchKernelGGL(pc_wgrad_reduce_kernel, dim3((unsigned)((nnzk + 15) / 16)), dim3(256), 0, ctx->stream,
                        (const float4 *)partial, G, pk->v, (float4 *)dw);
     return pc_hip_check(ctx, hipGetLastError(), "bwd_weight reduce launch");
 }

@@ -14,6 +14,8 @@ struct pc_ctx {
     int device;
     hipStream_t stream;
     pc_variant forced;
+    int plan_cfg;          // MFMA conv tile configuration override, -1 = automatic
+    int plan_split;        // MFMA conv split-K override, 0 = automatic
     int num_cu;
     char err[256];
     // scratch owned by the context (grown on demand, never shrunk)
