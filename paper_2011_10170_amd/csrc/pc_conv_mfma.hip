@@ -23,7 +23,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define MF_LDS_MAX 65536
 
-bool pc_mfma_supports(int F, int C) { return F % 8 == 0 && C % 8 == 0; }
+bool pc_mfma_supports(int F, int C) { (void)F; (void)C; return true; }
 
 struct MfmaArgs {
     int32_t N, in_H, in_W, in_CH;
@@ -121,7 +121,17 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
             const int c = ch * KC + part * 8;
             const int64_t po = pixoff[q];
             uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (po >= 0 && c < g.in_CH) v = *reinterpret_cast<const uint4 *>(in + po + c);
+            if (po >= 0 && c < g.in_CH) {
+                if ((g.in_CH & 7) == 0) {
+                    v = *reinterpret_cast<const uint4 *>(in + po + c);
+                } else {   // channel count not a multiple of 8: rows are not 16-byte aligned, load by element
+                    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (c + i < g.in_CH) w[i >> 1] |= (uint32_t)in[po + c + i] << ((i & 1) * 16);
+                    v = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
             *reinterpret_cast<uint4 *>(lds + q * PITCH + part * 16) = v;
         }
         __syncthreads();
@@ -177,11 +187,17 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     int m = m0 + i * 32 + r4 * 8 + (lane >> 5) * 4;
-                    if (m < g.out_CH) {
-                        uint2 pk;
-                        pk.x = (uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 0]) | ((uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 1]) << 16);
-                        pk.y = (uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 2]) | ((uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 3]) << 16);
-                        *reinterpret_cast<uint2 *>(op + m) = pk;
+                    if ((g.out_CH & 3) == 0) {
+                        if (m < g.out_CH) {
+                            uint2 pk;
+                            pk.x = (uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 0]) | ((uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 1]) << 16);
+                            pk.y = (uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 2]) | ((uint32_t)pc_f32_to_bf16(acc[i][j][r4 * 4 + 3]) << 16);
+                            *reinterpret_cast<uint2 *>(op + m) = pk;
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (m + e < g.out_CH) op[m + e] = pc_f32_to_bf16(acc[i][j][r4 * 4 + e]);
                     }
                 }
         } else {
@@ -192,9 +208,15 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     int m = m0 + i * 32 + r4 * 8 + (lane >> 5) * 4;
-                    if (m < g.out_CH)
-                        *reinterpret_cast<float4 *>(pp + m) = make_float4(acc[i][j][r4 * 4 + 0], acc[i][j][r4 * 4 + 1],
-                                                                          acc[i][j][r4 * 4 + 2], acc[i][j][r4 * 4 + 3]);
+                    if ((g.out_CH & 3) == 0) {
+                        if (m < g.out_CH)
+                            *reinterpret_cast<float4 *>(pp + m) = make_float4(acc[i][j][r4 * 4 + 0], acc[i][j][r4 * 4 + 1],
+                                                                              acc[i][j][r4 * 4 + 2], acc[i][j][r4 * 4 + 3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (m + e < g.out_CH) pp[m + e] = acc[i][j][r4 * 4 + e];
+                    }
                 }
         }
     }
@@ -275,6 +297,7 @@ pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W)
 struct MfmaCfg { int a, b, wm, wn, kc; };
 static const MfmaCfg kCfgs[] = {
     {2, 4, 1, 4, 32}, {2, 4, 2, 2, 32}, {2, 2, 2, 2, 32}, {2, 2, 2, 2, 64}, {1, 2, 2, 2, 64}, {1, 1, 2, 2, 64},
+    {1, 2, 2, 2, 16},
 };
 // automatic choice tries these in order and keeps the first that yields enough workgroups (else the last)
 static const int kAutoOrder[] = {4, 5};
@@ -318,14 +341,15 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
     const int64_t want = 2 * (int64_t)ctx->num_cu;
     const int n_try = ctx->plan_cfg >= 0 ? 1 : (int)(sizeof(kAutoOrder) / sizeof(kAutoOrder[0]));
     for (int k = 0; k < n_try; ++k) {
-        const int ci = ctx->plan_cfg >= 0 ? ctx->plan_cfg : kAutoOrder[k];
+        int ci = ctx->plan_cfg >= 0 ? ctx->plan_cfg : kAutoOrder[k];
+        if (ctx->plan_cfg < 0 && g.in_CH <= 16) ci = 6;   // a handful of input channels: one 16-channel k-step per tap
         const MfmaCfg &c = kCfgs[ci];
         int BM = 32 * c.a * c.wm, BN = 32 * c.b * c.wn;
         MfmaArgs t = g;
         plan_mfma_tiles(&t, BN, ext);
         size_t lds = (size_t)t.TI * t.IH * t.IW * (2 * c.kc + 16 + 8);
         if (lds > MF_LDS_MAX) continue;
-        t.nchunks = (g.KS * 16 + c.kc - 1) / c.kc;
+        t.nchunks = (g.in_CH + c.kc - 1) / c.kc;
         int64_t blocks = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x * ((g.out_CH + BM - 1) / BM);
         int split = 1;
         if (ctx->plan_split > 0) split = ctx->plan_split;
@@ -333,7 +357,7 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
             split = (int)((ctx->num_cu + blocks - 1) / blocks);
             if (split > 4) split = 4;
         }
-        if (g.oscale != 1) split = 1;   // parity-class launches of one call share the output: no partial buffers
+        if (g.oscale != 1 || (g.out_CH & 3)) split = 1;   // parity-class launches share the output; the reduce is 4-wide
         if (split > t.nchunks) split = t.nchunks;
         t.cps = (t.nchunks + split - 1) / split;
         split = (t.nchunks + t.cps - 1) / t.cps;
@@ -364,7 +388,8 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
     case 2: launch_cfg<2, 2, 2, 2, 32>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
     case 3: launch_cfg<2, 2, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
     case 4: launch_cfg<1, 2, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
-    default: launch_cfg<1, 1, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    case 5: launch_cfg<1, 1, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    default: launch_cfg<1, 2, 2, 2, 16>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
     }
     pc_status s = pc_hip_check(ctx, hipGetLastError(), "MFMA conv launch");
     if (s != PC_OK || pick_split == 1) return s;
@@ -440,8 +465,10 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
 // writes only the kept taps, in compact slot order, to its own partial buffer, and a second kernel adds
 // the partials in a fixed order (no float atomics).
 #define WG_T 64                // filters and channels per workgroup
-#define WG_NSLOT 16            // dy slots per pixel tile (8 MFMA k-steps)
+#define WG_NSLOT 32            // dy slots per pixel tile (16 MFMA k-steps)
+#define WG_XTASKS 3            // x staging tasks per thread at most (x slots <= 96)
 #define WG_DY_PLANE (WG_NSLOT * 16 + 16)
+#define WG_LDS_MAX (144 * 1024)
 
 struct WgradMfmaArgs {
     int32_t N, H, W, C, F, Ho, Wo, stride;
@@ -478,10 +505,22 @@ __device__ __forceinline__ void pc_transpose8x8_store(const uint4 (&r)[8], unsig
     }
 }
 
-#ifndef WG_OCC
-#define WG_OCC 2
-#endif
-__global__ void __launch_bounds__(256, WG_OCC)
+// 8 consecutive channels starting at channel c of a pixel row with nch channels; rows whose channel count
+// is not a multiple of 8 are not 16-byte aligned and are read by element (zero past the last channel).
+__device__ __forceinline__ uint4 pc_load8(const uint16_t *p, int nch, int c)
+{
+    if ((nch & 7) == 0) return *reinterpret_cast<const uint4 *>(p);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (c + i < nch) w[i >> 1] |= (uint32_t)p[i] << ((i & 1) * 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// One workgroup per CU (up to 512 registers per lane): the global loads of the NEXT pixel tile are in
+// flight in registers while the MFMAs of the current one run, and the fragments of the next k-step are
+// read from LDS while the 9 MFMAs of the current k-step issue.
+__global__ void __launch_bounds__(256, 1)
 pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradMfmaArgs a, PackView v,
                      float *__restrict__ partial)
 {
@@ -524,14 +563,13 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 
     // staging tasks of this thread: the (slot, channel group) of a task is the same for every pixel tile
     const int tcg = threadIdx.x & 7;                      // group of 8 filters (dy) / channels (x)
-    const bool has_dy = threadIdx.x < WG_NSLOT * 8;
-    const int d_slot = threadIdx.x >> 3;
+    const int d_slot = threadIdx.x >> 3;                  // WG_NSLOT * 8 == 256: one dy task per thread
     const int d_ig = d_slot / a.npos, d_pos = d_slot - d_ig * a.npos;
     const int d_py = d_pos / a.TC, d_px = d_pos - d_py * a.TC;
-    bool has_x[2];
-    int x_slot[2], x_ig[2], x_iy[2], x_ix[2];
+    bool has_x[WG_XTASKS];
+    int x_slot[WG_XTASKS], x_ig[WG_XTASKS], x_iy[WG_XTASKS], x_ix[WG_XTASKS];
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < WG_XTASKS; ++k) {
         const int e = threadIdx.x + 256 * k;
         has_x[k] = e < a.xslots * 8;
         x_slot[k] = e >> 3;
@@ -542,59 +580,76 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     }
     const int64_t dy_img = (int64_t)a.Ho * a.Wo * a.F, x_img = (int64_t)a.H * a.W * a.C;
 
-    for (int kt = blockIdx.z; kt < a.n_ktiles; kt += a.ksplit) {
+    uint4 rd[8], rx[WG_XTASKS][8];
+    auto issue = [&](int kt) {
         int q = kt;
         const int tc = q % a.tiles_c; q /= a.tiles_c;
         const int tr = q % a.tiles_r;
         const int tn = q / a.tiles_r;
         const int oy0 = tr * a.TR, ox0 = tc * a.TC, n0 = tn * a.ng * 8;
-        __syncthreads();
-        if (has_dy) {
+        {
             const int oy = oy0 + d_py, ox = ox0 + d_px, f = f0 + tcg * 8, nb = n0 + d_ig * 8;
             const bool ok = d_ig < a.ng && oy < a.Ho && ox < a.Wo && f < a.F;
             const uint16_t *src = dy + (int64_t)nb * dy_img + ((int64_t)oy * a.Wo + ox) * a.F + f;
-            uint4 r[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                r[i] = make_uint4(0u, 0u, 0u, 0u);
-#ifndef EXP_NO_LOAD
-                if (ok && nb + i < a.N) r[i] = *reinterpret_cast<const uint4 *>(src + i * dy_img);
-#endif
+                rd[i] = make_uint4(0u, 0u, 0u, 0u);
+                if (ok && nb + i < a.N) rd[i] = pc_load8(src + i * dy_img, a.F, f);
             }
-            pc_transpose8x8_store(r, dyT + (tcg * 8) * WG_DY_PLANE + ((d_slot ^ tcg) << 4), WG_DY_PLANE);
         }
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < WG_XTASKS; ++k) {
             if (has_x[k]) {
                 const int yy = oy0 * a.stride - 1 + x_iy[k], xx = ox0 * a.stride - 1 + x_ix[k];
                 const int c = c0 + tcg * 8, nb = n0 + x_ig[k] * 8;
                 const bool ok = x_ig[k] < a.ng && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && c < a.C;
                 const uint16_t *src = x + (int64_t)nb * x_img + ((int64_t)yy * a.W + xx) * a.C + c;
-                uint4 r[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    r[i] = make_uint4(0u, 0u, 0u, 0u);
-#ifndef EXP_NO_LOAD
-                    if (ok && nb + i < a.N) r[i] = *reinterpret_cast<const uint4 *>(src + i * x_img);
-#endif
+                    rx[k][i] = make_uint4(0u, 0u, 0u, 0u);
+                    if (ok && nb + i < a.N) rx[k][i] = pc_load8(src + i * x_img, a.C, c);
                 }
-                pc_transpose8x8_store(r, xT + (tcg * 8) * a.xplane + ((x_slot[k] ^ tcg) << 4), a.xplane);
             }
         }
+    };
+
+    int kt = blockIdx.z;
+    if (kt < a.n_ktiles) issue(kt);
+    for (; kt < a.n_ktiles; kt += a.ksplit) {
         __syncthreads();
+#ifndef EXP_NO_XPOSE
+        pc_transpose8x8_store(rd, dyT + (tcg * 8) * WG_DY_PLANE + ((d_slot ^ tcg) << 4), WG_DY_PLANE);
+#pragma unroll
+        for (int k = 0; k < WG_XTASKS; ++k)
+            if (has_x[k]) pc_transpose8x8_store(rx[k], xT + (tcg * 8) * a.xplane + ((x_slot[k] ^ tcg) << 4), a.xplane);
+#else
+        if (rd[0].x == 0x12345u && rx[0][0].x == 77u && rx[1][1].y == 5u && rx[2][2].z == 6u) dyT[threadIdx.x] = 1;
+#endif
+        __syncthreads();
+        if (kt + a.ksplit < a.n_ktiles) issue(kt + a.ksplit);
+
+        bf16x8 aq[2], bq[2][9];
+        aq[0] = *reinterpret_cast<const bf16x8 *>(a_row + ((g ^ a_sw) << 4));
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+            bq[0][t] = *reinterpret_cast<const bf16x8 *>(b_col + (((xb[0] + toff[t]) ^ b_sw) << 4));
 #pragma unroll
         for (int kk = 0; kk < WG_NSLOT / 2; ++kk) {
             if (kk < a.nks) {
-                const bf16x8 af = *reinterpret_cast<const bf16x8 *>(a_row + (((2 * kk + g) ^ a_sw) << 4));
+                if (kk + 1 < WG_NSLOT / 2 && kk + 1 < a.nks) {
+                    aq[(kk + 1) & 1] = *reinterpret_cast<const bf16x8 *>(a_row + (((2 * (kk + 1) + g) ^ a_sw) << 4));
 #pragma unroll
-                for (int t = 0; t < 9; ++t) {
-                    const bf16x8 bf = *reinterpret_cast<const bf16x8 *>(b_col + (((xb[kk] + toff[t]) ^ b_sw) << 4));
-#ifndef EXP_NO_MFMA
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[t], 0, 0, 0);
-#else
-                    acc[t][0] += (float)bf[0] * (float)af[0];
-#endif
+                    for (int t = 0; t < 9; ++t)
+                        bq[(kk + 1) & 1][t] = *reinterpret_cast<const bf16x8 *>(
+                            b_col + (((xb[(kk + 1) % (WG_NSLOT / 2)] + toff[t]) ^ b_sw) << 4));
                 }
+#pragma unroll
+                for (int t = 0; t < 9; ++t)
+#ifndef EXP_NO_MFMA
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[kk & 1], bq[kk & 1][t], acc[t], 0, 0, 0);
+#else
+                    acc[t][0] += (float)aq[kk & 1][0] * (float)bq[kk & 1][t][0];
+#endif
             }
         }
     }
@@ -616,11 +671,7 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 #pragma unroll
             for (int t = 0; t < 9; ++t) {
                 const int j = jm[t];
-#ifndef EXP_NO_EPI
                 if (j >= 0) pout[(int64_t)slot[i] * 4 + j] = acc[t][i];
-#else
-                if (j >= 0 && acc[t][i] == 1.2345f) pout[(int64_t)slot[i] * 4 + j] = acc[t][i];
-#endif
             }
         }
     }
@@ -639,7 +690,7 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.F = d->F; a.stride = st;
     a.Ho = (d->H - 1) / st + 1; a.Wo = (d->W - 1) / st + 1;
     // output region per image group: up to 16 positions at stride 1, 8 at stride 2 (the x region grows 4x)
-    const int maxpos = st == 1 ? WG_NSLOT : WG_NSLOT / 2;
+    const int maxpos = st == 1 ? WG_NSLOT / 2 : WG_NSLOT / 4;   // positions per image group
     int best_tr = 1, best_tc = 1, best_ng = 1;
     double best_eff = -1.0;
     const int ngroups = (a.N + 7) / 8;
@@ -648,11 +699,10 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
             if (tr > a.Ho && tr > 1) continue;
             if (tc > a.Wo && tc > 1) continue;
             const int xs1 = ((tr - 1) * st + 3) * ((tc - 1) * st + 3);
-            int ngc = maxpos / (tr * tc);
+            int ngc = WG_NSLOT / (tr * tc);
             if (ngc > ngroups) ngc = ngroups;
-            while (ngc > 1 && (size_t)WG_T * WG_DY_PLANE + (size_t)WG_T * (((ngc * xs1 + 7) / 8 * 8) * 16 + 16) > MF_LDS_MAX)
-                --ngc;
-            if ((size_t)WG_T * WG_DY_PLANE + (size_t)WG_T * (((ngc * xs1 + 7) / 8 * 8) * 16 + 16) > MF_LDS_MAX) continue;
+            while (ngc > 1 && ngc * xs1 > 32 * WG_XTASKS) --ngc;
+            if (ngc * xs1 > 32 * WG_XTASKS) continue;
             int nr = (a.Ho + tr - 1) / tr, nc = (a.Wo + tc - 1) / tc;
             double cover = (double)a.Ho * a.Wo / ((double)nr * tr * nc * tc);   // useful part of the tiles
             double fill = (double)(ngc * tr * tc) / WG_NSLOT;                    // used dy slots
@@ -675,9 +725,15 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     a.nnzk = (int32_t)nnzk;
     memcpy(a.taps, pk->taps, sizeof(a.taps));
     size_t lds = (size_t)WG_T * WG_DY_PLANE + (size_t)WG_T * a.xplane;
-    if (lds > MF_LDS_MAX) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: tile does not fit in LDS");
+    if (lds > WG_LDS_MAX) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: tile does not fit in LDS");
+    static bool lds_attr_set = false;
+    if (!lds_attr_set) {
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        WG_LDS_MAX));
+        lds_attr_set = true;
+    }
     int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
-    if (a.xslots * 8 > 512) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: x tile too large");
+    if (a.xslots > 32 * WG_XTASKS) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: x tile too large");
     int ks = ctx->num_cu / (ft * ct);
     if (ks > a.n_ktiles) ks = a.n_ktiles;
     if (ks < 1) ks = 1;

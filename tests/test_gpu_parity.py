@@ -110,6 +110,24 @@ def test_small_bf16_valu(B, ctx, oracle, shape):
     run_case(B, ctx, oracle, shape, "bf16", 8, 0.4, B.PC_VARIANT_VALU, "small")
 
 
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_bf16_auto(B, ctx, oracle, shape):
+    """The default kernel choice for bf16 (matrix-core kernels), on odd channel counts and ragged tiles."""
+    run_case(B, ctx, oracle, shape, "bf16", 8, 0.4, B.PC_VARIANT_AUTO, "small_auto")
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("split", [0, 3])
+def test_every_mfma_tile_configuration(B, ctx, oracle, cfg, split):
+    """Each built tile configuration of the forward/backward-data kernel, with and without split-K."""
+    B.pc_set_plan_override(ctx, cfg, split)
+    try:
+        for shape in [(3, 12, 20, 72, 96, 1), (2, 9, 9, 40, 24, 2)]:
+            run_case(B, ctx, oracle, shape, "bf16", 8, 0.3, B.PC_VARIANT_MFMA, ("cfg", cfg, split))
+    finally:
+        B.pc_set_plan_override(ctx, -1, 0)
+
+
 @pytest.mark.parametrize("shape", MEDIUM_BF16)
 def test_medium_bf16_valu(B, ctx, oracle, shape):
     run_case(B, ctx, oracle, shape, "bf16", 12, 0.3, B.PC_VARIANT_VALU, "medium")
