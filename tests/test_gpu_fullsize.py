@@ -1,0 +1,114 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times (default kernel choice). The oracle cannot run these layers in full, so selection is compared in
+full (bit-exact) and the three passes on sampled outputs the oracle computes one by one: random
+positions plus image corners and edges. Activations larger than inputs.PERIOD repeat cyclically
+(generation time); weights are always fully generated."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2011_10170_amd import inputs as I
+from tests._harness import Case, GpuLayer, oracle_masks, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+N_SAMPLES = 3000
+N_WSAMPLES = 192
+
+
+def _unique_layers():
+    out = []
+    for name in I.WORKLOAD_ORDER[1:]:
+        wl = I.WORKLOADS[name]
+        seen = set()
+        for li, L in enumerate(wl.layers):
+            if L in seen:
+                continue
+            seen.add(L)
+            out.append(pytest.param(name, li, id="%s-L%d-%dx%d-%dto%d-s%d" % (name, li, L.H, L.W, L.C, L.F, L.stride)))
+    return out
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2011_10170_amd import binding
+    binding.load()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(B):
+    import torch
+    c = B.pc_create(0, torch.cuda.current_stream().cuda_stream)
+    yield c
+    B.pc_destroy(c)
+
+
+def _border_pixels(N, H, W, CH, rng):
+    """Flat NHWC indices at corners and edge midpoints of a few images, a few channels each."""
+    ys = sorted({0, H // 2, H - 1})
+    xs = sorted({0, W // 2, W - 1})
+    out = []
+    for n in sorted({0, N // 2, N - 1}):
+        for y in ys:
+            for x in xs:
+                for ch in rng.integers(0, CH, size=3):
+                    out.append(((n * H + y) * W + x) * CH + int(ch))
+    return np.array(out, dtype=np.int64)
+
+
+@pytest.mark.parametrize("name,li", _unique_layers())
+def test_full_size_layer(B, ctx, oracle, name, li):
+    wl = I.WORKLOADS[name]
+    L = wl.layers[li]
+    print("full-size", name, li, L, flush=True)
+    sys.stdout.flush()
+    rng = np.random.default_rng(1000 + li)
+    case = Case(L, wl.dtype, wl.P, I.kept_per_filter(wl.keep, L.C), tag=("full", name, li))
+    pid, kp, M, Wm = oracle_masks(oracle, case)
+    g = GpuLayer(B, ctx, case)
+    try:
+        assert g.variant == B.PC_VARIANT_MFMA
+        gpid, gkeep = g.masks()
+        assert np.array_equal(gpid, pid) and np.array_equal(gkeep, kp)
+        assert g.nnzk == int(kp.sum()) == L.F * I.kept_per_filter(wl.keep, L.C)
+        assert np.array_equal(g.unpack(), Wm)
+
+        y = g.fwd().reshape(-1)
+        idx = np.concatenate([rng.integers(0, y.size, size=N_SAMPLES), _border_pixels(L.N, L.Ho, L.Wo, L.F, rng)])
+        ref = oracle.conv_fwd_at(case.x, Wm, L.stride, idx)
+        e = rel_l2(y[idx], ref)
+        print("  fwd sampled rel_l2", e, flush=True)
+        assert e <= 2e-2
+        del y
+
+        dx = g.bwd_data().reshape(-1)
+        idx = np.concatenate([rng.integers(0, dx.size, size=N_SAMPLES), _border_pixels(L.N, L.H, L.W, L.C, rng)])
+        ref = oracle.conv_bwd_data_at(case.dy, Wm, case.x.shape, L.stride, idx)
+        e = rel_l2(dx[idx], ref)
+        print("  bwd_data sampled rel_l2", e, flush=True)
+        assert e <= 2e-2
+        del dx
+
+        dw, guard = g.bwd_weight()
+        sf, sc = oracle.compact_order(pid, kp, wl.P)
+        slots = rng.integers(0, g.nnzk, size=N_WSAMPLES)
+        widx, got = [], []
+        for s in slots:
+            f, c = int(sf[s]), int(sc[s])
+            taps = [t for t in range(9) if (int(case.lib[pid[f, c]]) >> t) & 1]
+            j = int(rng.integers(0, 4))
+            widx.append((f * L.C + c) * 9 + taps[j])
+            got.append(dw[s, j])
+        ref = oracle.conv_bwd_weight_at(case.x, case.dy, L.F, L.stride, np.array(widx, dtype=np.int64))
+        e = rel_l2(np.array(got), ref)
+        print("  bwd_weight sampled rel_l2", e, flush=True)
+        assert e <= 1e-4
+        # nothing is written at pruned positions
+        dense = g.scatter(guard.body)
+        assert np.all(dense[M == 0] == 0.0)
+    finally:
+        g.close()
