@@ -39,7 +39,9 @@ def main() -> int:
     ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--no-graph", action="store_true", help="enqueue every step from the host instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
+    ap.add_argument("--cpu-sample-batch", type=int, default=128)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the batch would shard across GPUs with one "
@@ -204,9 +206,26 @@ def main() -> int:
     if t_hbm > t_unit:
         bound, unit, peak = "hbm", "GB/s", PEAK_HBM_GBS
         achieved = dv["bytes"] / dv["us"] / 1e3
+    # HBM bytes per launch of that kernel from the committed rocprofv3 counter summary (None when absent)
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", "%s_hbm_counters.md" % wl.name)
+    kname = {"mfma_bwd_weight": "pc_mfma_wgrad_kernel", "mfma_fwd": "pc_mfma_conv_kernel",
+             "mfma_bwd_data": "pc_mfma_conv_kernel", "valu_fwd": "pc_gather_conv_kernel",
+             "valu_bwd_data": "pc_gather_conv_kernel", "valu_bwd_weight": "pc_wgrad_valu_kernel"}.get(dk)
+    if kname and os.path.exists(prof):
+        tot_b, tot_n = 0.0, 0
+        for line in open(prof):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 5 and cells[1].startswith(kname):
+                n_disp = int(cells[2])
+                tot_b += float(cells[5].split("=")[-1]) * n_disp
+                tot_n += n_disp
+        if tot_n:
+            traffic = {"hbm_mib_per_launch": round(tot_b / tot_n, 2), "source": "profiles/%s_hbm_counters.md" % wl.name,
+                       "algorithmic_mib_per_launch": round(dv["bytes"] / dv["n"] / (1 << 20), 2)}
     roofline = {
         "kernel": dk, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-        "frac": round(achieved / peak, 4), "traffic": None,
+        "frac": round(achieved / peak, 4), "traffic": traffic,
         "launches_per_step": dv["n"], "avg_launch_us": round(dv["us"] / dv["n"], 2),
         "achieved_nonzero_tflops": round(dv["flops"] / dv["us"] / 1e6, 3),
         "algorithmic_gbs": round(dv["bytes"] / dv["us"] / 1e3, 1),
@@ -216,6 +235,15 @@ def main() -> int:
     for kname, kv in sorted(kinds.items()):
         log("kind %-18s launches %3d  total %9.1f us  nz %8.2f TF/s  dense %8.1f TF/s  alg %7.0f GB/s" % (
             kname, kv["n"], kv["us"], kv["flops"] / kv["us"] / 1e6, kv["dense"] / kv["us"] / 1e6, kv["bytes"] / kv["us"] / 1e3))
+
+    if args.calib_copy_mb > 0:
+        n = args.calib_copy_mb * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log("calibration copy: %d MiB read + %d MiB written" % (args.calib_copy_mb, args.calib_copy_mb))
 
     # ---- the CPU oracle on a bounded sample of the same workload (reported, not a target)
     cpu = None
