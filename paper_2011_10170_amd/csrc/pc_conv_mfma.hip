@@ -51,7 +51,7 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
     constexpr int BM = 32 * A_T * WAVES_M;
     constexpr int KSC = KC / 16;
     constexpr int NS = NTAPS * KSC;
-    constexpr int PF = (NS % 3 == 0) ? 3 : 2;
+    constexpr int PF = (NS % 3 == 0) ? 3 : ((NS % 2 == 0) ? 2 : 1);
     constexpr int PITCH = 2 * KC + 16;
     constexpr int PARTS = KC / 8;
     const int lane = threadIdx.x & 63;
@@ -347,16 +347,22 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
         int BM = 32 * c.a * c.wm, BN = 32 * c.b * c.wn;
         MfmaArgs t = g;
         plan_mfma_tiles(&t, BN, ext);
+        // too large for LDS (strided or tiny images): fewer images, then fewer rows per tile (idle lanes)
+        while ((size_t)t.TI * t.IH * t.IW * (2 * c.kc + 16 + 8) > MF_LDS_MAX) {
+            if (t.TI > 1) --t.TI;
+            else if (t.TH > 1) {
+                t.TH = (t.TH + 1) / 2;
+                t.IH = (t.TH - 1) * t.lstep + ext;
+                t.tiles_y = (t.GH + t.TH - 1) / t.TH;
+            } else break;
+        }
         size_t lds = (size_t)t.TI * t.IH * t.IW * (2 * c.kc + 16 + 8);
         if (lds > MF_LDS_MAX) continue;
         t.nchunks = (g.in_CH + c.kc - 1) / c.kc;
         int64_t blocks = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x * ((g.out_CH + BM - 1) / BM);
         int split = 1;
         if (ctx->plan_split > 0) split = ctx->plan_split;
-        else if (k == n_try - 1 && blocks < ctx->num_cu) {
-            split = (int)((ctx->num_cu + blocks - 1) / blocks);
-            if (split > 4) split = 4;
-        }
+        else if (k == n_try - 1 && blocks <= ctx->num_cu && t.nchunks >= 8) split = 4;
         if (g.oscale != 1 || (g.out_CH & 3)) split = 1;   // parity-class launches share the output; the reduce is 4-wide
         if (split > t.nchunks) split = t.nchunks;
         t.cps = (t.nchunks + split - 1) / split;
@@ -530,7 +536,12 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     __shared__ int8_t jmap[PC_MAX_P][9];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int fh = wave & 1, chh = wave >> 1;
+    // wave = (channel half, tap group). The 18 (filter half, tap) units of the 64x64x9 tile are split 9/9:
+    // tap group 0 holds taps 0..4 of filter half 0 and taps 0..3 of half 1; tap group 1 holds taps 8..4 of
+    // half 1 and taps 8..5 of half 0. In both groups unit u < 5 is ("first" half, tap slot u) and unit
+    // u >= 5 is ("second" half, tap slot u-5), so a wave reads 2 A and 5 B fragments for 9 MFMAs per k-step.
+    const int chh = wave & 1, tg = wave >> 1;
+    const int first_half = tg;                                    // filter half of units 0..4
     const int c0 = blockIdx.x * WG_T, f0 = blockIdx.y * WG_T;
     const int g = lane >> 5;
 
@@ -545,10 +556,10 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
     // per lane: LDS addresses of its A row and B column, and the x slot of each k-step's dy slot
-    const int fl = fh * 32 + (lane & 31), cl = chh * 32 + (lane & 31);
-    const unsigned char *a_row = dyT + fl * WG_DY_PLANE;
+    const int fl = lane & 31, cl = chh * 32 + (lane & 31);
+    const unsigned char *a_row = dyT + fl * WG_DY_PLANE;          // filter half 1 is 32 rows further
     const unsigned char *b_col = xT + cl * a.xplane;
-    const int a_sw = (fl >> 3) & 7, b_sw = (cl >> 3) & 7;
+    const int a_sw = (fl >> 3) & 7, b_sw = (cl >> 3) & 7;        // (fl + 32) >> 3 & 7 = a_sw ^ 4
     int xb[WG_NSLOT / 2];
 #pragma unroll
     for (int kk = 0; kk < WG_NSLOT / 2; ++kk) {
@@ -557,9 +568,15 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
         int py = pos / a.TC, px = pos - py * a.TC;
         xb[kk] = (ig < a.ng) ? ig * a.xs_per_g + (py * a.stride) * a.IC + px * a.stride : 0;
     }
-    int toff[9];
+    int toff[5];                                                  // x slot offset of this wave's 5 tap slots
 #pragma unroll
-    for (int t = 0; t < 9; ++t) toff[t] = (t / 3) * a.IC + (t % 3);
+    for (int b = 0; b < 5; ++b) {
+        const int tap = tg ? 8 - b : b;
+        toff[b] = (tap / 3) * a.IC + (tap % 3);
+    }
+    const unsigned char *a_row0 = a_row + (first_half ? 32 * WG_DY_PLANE : 0);          // rows of units 0..4
+    const unsigned char *a_row1 = a_row + (first_half ? 0 : 32 * WG_DY_PLANE);          // rows of units 5..8
+    const int a_sw0 = first_half ? (a_sw ^ 4) : a_sw, a_sw1 = first_half ? a_sw : (a_sw ^ 4);
 
     // staging tasks of this thread: the (slot, channel group) of a task is the same for every pixel tile
     const int tcg = threadIdx.x & 7;                      // group of 8 filters (dy) / channels (x)
@@ -628,50 +645,56 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
         __syncthreads();
         if (kt + a.ksplit < a.n_ktiles) issue(kt + a.ksplit);
 
-        bf16x8 aq[2], bq[2][9];
-        aq[0] = *reinterpret_cast<const bf16x8 *>(a_row + ((g ^ a_sw) << 4));
+        bf16x8 aq[2][2], bq[2][5];
+        aq[0][0] = *reinterpret_cast<const bf16x8 *>(a_row0 + ((g ^ a_sw0) << 4));
+        aq[0][1] = *reinterpret_cast<const bf16x8 *>(a_row1 + ((g ^ a_sw1) << 4));
 #pragma unroll
-        for (int t = 0; t < 9; ++t)
-            bq[0][t] = *reinterpret_cast<const bf16x8 *>(b_col + (((xb[0] + toff[t]) ^ b_sw) << 4));
+        for (int b = 0; b < 5; ++b)
+            bq[0][b] = *reinterpret_cast<const bf16x8 *>(b_col + (((xb[0] + toff[b]) ^ b_sw) << 4));
 #pragma unroll
         for (int kk = 0; kk < WG_NSLOT / 2; ++kk) {
             if (kk < a.nks) {
+                const int cur = kk & 1, nxt = cur ^ 1;
                 if (kk + 1 < WG_NSLOT / 2 && kk + 1 < a.nks) {
-                    aq[(kk + 1) & 1] = *reinterpret_cast<const bf16x8 *>(a_row + (((2 * (kk + 1) + g) ^ a_sw) << 4));
+                    const int s1 = 2 * (kk + 1) + g;
+                    aq[nxt][0] = *reinterpret_cast<const bf16x8 *>(a_row0 + ((s1 ^ a_sw0) << 4));
+                    aq[nxt][1] = *reinterpret_cast<const bf16x8 *>(a_row1 + ((s1 ^ a_sw1) << 4));
 #pragma unroll
-                    for (int t = 0; t < 9; ++t)
-                        bq[(kk + 1) & 1][t] = *reinterpret_cast<const bf16x8 *>(
-                            b_col + (((xb[(kk + 1) % (WG_NSLOT / 2)] + toff[t]) ^ b_sw) << 4));
+                    for (int b = 0; b < 5; ++b)
+                        bq[nxt][b] = *reinterpret_cast<const bf16x8 *>(
+                            b_col + (((xb[(kk + 1) % (WG_NSLOT / 2)] + toff[b]) ^ b_sw) << 4));
                 }
 #pragma unroll
-                for (int t = 0; t < 9; ++t)
-#ifndef EXP_NO_MFMA
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[kk & 1], bq[kk & 1][t], acc[t], 0, 0, 0);
-#else
-                    acc[t][0] += (float)aq[kk & 1][0] * (float)bq[kk & 1][t][0];
-#endif
+                for (int u = 0; u < 9; ++u)
+                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[cur][u < 5 ? 0 : 1], bq[cur][u < 5 ? u : u - 5],
+                                                                     acc[u], 0, 0, 0);
             }
         }
     }
     // kept taps only, compact slot order; the table look-ups are issued together, then the stores
     const int c = c0 + cl;
     float *pout = partial + (int64_t)blockIdx.z * a.nnzk * 4;
-    int slot[16], pidv[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int f = f0 + fh * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-        slot[i] = (f < a.F && c < a.C) ? v.slot_of[(int64_t)f * a.C + c] : -1;
-    }
+    for (int h = 0; h < 2; ++h) {                 // h = 0: units 0..4 ("first" half), h = 1: units 5..8
+        const int fh = h == 0 ? first_half : 1 - first_half;
+        int slot[16], pidv[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) pidv[i] = slot[i] >= 0 ? (int)v.fm_pid[slot[i]] : 0;
+        for (int i = 0; i < 16; ++i) {
+            const int f = f0 + fh * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+            slot[i] = (f < a.F && c < a.C) ? v.slot_of[(int64_t)f * a.C + c] : -1;
+        }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        if (slot[i] >= 0) {
-            const int8_t *jm = jmap[pidv[i]];
+        for (int i = 0; i < 16; ++i) pidv[i] = slot[i] >= 0 ? (int)v.fm_pid[slot[i]] : 0;
 #pragma unroll
-            for (int t = 0; t < 9; ++t) {
-                const int j = jm[t];
-                if (j >= 0) pout[(int64_t)slot[i] * 4 + j] = acc[t][i];
+        for (int i = 0; i < 16; ++i) {
+            if (slot[i] >= 0) {
+                const int8_t *jm = jmap[pidv[i]];
+#pragma unroll
+                for (int b = 0; b < (h == 0 ? 5 : 4); ++b) {
+                    const int tap = tg ? 8 - b : b;
+                    const int j = jm[tap];
+                    if (j >= 0) pout[(int64_t)slot[i] * 4 + j] = acc[h * 5 + b][i];
+                }
             }
         }
     }
