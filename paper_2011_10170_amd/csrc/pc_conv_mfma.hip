@@ -143,8 +143,12 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
             if (st + 1 < NS) {
                 const int t1 = (st + 1) / KSC, k1 = (st + 1) % KSC;
 #pragma unroll
+#ifndef EXP_NO_B
                 for (int j = 0; j < B_T; ++j)
                     bnxt[j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[t1] + k1 * 32);
+#else
+                for (int j = 0; j < B_T; ++j) { bnxt[j] = bcur[j]; bnxt[j][0] += (__bf16)1.0f; }
+#endif
             }
             bf16x8 anow[A_T];
 #pragma unroll
@@ -154,7 +158,11 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
                 const int nch = nst >= NS ? ch + 1 : ch;
                 const int nss = nst >= NS ? nst - NS : nst;
 #pragma unroll
+#ifndef EXP_NO_A
                 for (int i = 0; i < A_T; ++i) aring[st % PF][i] = a_load(nch, nss, i);
+#else
+                for (int i = 0; i < A_T; ++i) aring[st % PF][i][0] += (__bf16)1.0f;
+#endif
             }
 #pragma unroll
             for (int i = 0; i < A_T; ++i)
@@ -464,8 +472,9 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
 // position (a different 16-byte slot, always aligned), and the zero padding is a zero slot.
 // LDS holds dyT[filter][slot][8 images] and xT[channel][slot][8 images] (bf16); the staging loads the
 // 8 images of a (position, 8 channels) task with eight 16-byte loads, transposes 8x8 in registers
-// (v_perm) and writes eight 16-byte rows. Slot indices are XOR-swizzled with the channel group so that
-// both the transposing writes and the fragment reads are free of bank conflicts.
+// (v_perm) and writes eight 16-byte rows. Every group of 8 channel planes is shifted by 16 bytes so that
+// both the transposing writes and the fragment reads are free of bank conflicts while every fragment
+// address stays (per-lane base) + (wave-uniform offset).
 // One workgroup owns a 64x64 tile of (filter, channel) for all 9 taps (each wave 32x32x9: 144
 // accumulator registers) and walks pixel tiles; pixel tiles are split over blockIdx.z; every split
 // writes only the kept taps, in compact slot order, to its own partial buffer, and a second kernel adds
@@ -526,13 +535,14 @@ __device__ __forceinline__ uint4 pc_load8(const uint16_t *p, int nch, int c)
 // One workgroup per CU (up to 512 registers per lane): the global loads of the NEXT pixel tile are in
 // flight in registers while the MFMAs of the current one run, and the fragments of the next k-step are
 // read from LDS while the 9 MFMAs of the current k-step issue.
+template <int NKS>   // MFMA k-steps per pixel tile (dy slots / 2, rounded up to a multiple of 4; unused slots are zero)
 __global__ void __launch_bounds__(256, 1)
 pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradMfmaArgs a, PackView v,
                      float *__restrict__ partial)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *dyT = lds;
-    unsigned char *xT = lds + WG_T * WG_DY_PLANE;
+    unsigned char *xT = lds + WG_T * WG_DY_PLANE + 128;
     __shared__ int8_t jmap[PC_MAX_P][9];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -557,12 +567,11 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 
     // per lane: LDS addresses of its A row and B column, and the x slot of each k-step's dy slot
     const int fl = lane & 31, cl = chh * 32 + (lane & 31);
-    const unsigned char *a_row = dyT + fl * WG_DY_PLANE;          // filter half 1 is 32 rows further
-    const unsigned char *b_col = xT + cl * a.xplane;
-    const int a_sw = (fl >> 3) & 7, b_sw = (cl >> 3) & 7;        // (fl + 32) >> 3 & 7 = a_sw ^ 4
-    int xb[WG_NSLOT / 2];
+    // plane p (a filter of dyT, a channel of xT) starts at p * plane + (p >> 3) * 16
+    const unsigned char *b_col = xT + cl * a.xplane + (cl >> 3) * 16;
+    int xb[NKS];
 #pragma unroll
-    for (int kk = 0; kk < WG_NSLOT / 2; ++kk) {
+    for (int kk = 0; kk < NKS; ++kk) {
         int slot = 2 * kk + g;
         int ig = slot / a.npos, pos = slot - ig * a.npos;
         int py = pos / a.TC, px = pos - py * a.TC;
@@ -574,9 +583,9 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
         const int tap = tg ? 8 - b : b;
         toff[b] = (tap / 3) * a.IC + (tap % 3);
     }
-    const unsigned char *a_row0 = a_row + (first_half ? 32 * WG_DY_PLANE : 0);          // rows of units 0..4
-    const unsigned char *a_row1 = a_row + (first_half ? 0 : 32 * WG_DY_PLANE);          // rows of units 5..8
-    const int a_sw0 = first_half ? (a_sw ^ 4) : a_sw, a_sw1 = first_half ? a_sw : (a_sw ^ 4);
+    const int f_first = fl + (first_half ? 32 : 0), f_second = fl + (first_half ? 0 : 32);
+    const unsigned char *a_row0 = dyT + f_first * WG_DY_PLANE + (f_first >> 3) * 16;    // rows of units 0..4
+    const unsigned char *a_row1 = dyT + f_second * WG_DY_PLANE + (f_second >> 3) * 16;  // rows of units 5..8
 
     // staging tasks of this thread: the (slot, channel group) of a task is the same for every pixel tile
     const int tcg = threadIdx.x & 7;                      // group of 8 filters (dy) / channels (x)
@@ -635,40 +644,42 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     for (; kt < a.n_ktiles; kt += a.ksplit) {
         __syncthreads();
 #ifndef EXP_NO_XPOSE
-        pc_transpose8x8_store(rd, dyT + (tcg * 8) * WG_DY_PLANE + ((d_slot ^ tcg) << 4), WG_DY_PLANE);
+        pc_transpose8x8_store(rd, dyT + (tcg * 8) * WG_DY_PLANE + tcg * 16 + (d_slot << 4), WG_DY_PLANE);
 #pragma unroll
         for (int k = 0; k < WG_XTASKS; ++k)
-            if (has_x[k]) pc_transpose8x8_store(rx[k], xT + (tcg * 8) * a.xplane + ((x_slot[k] ^ tcg) << 4), a.xplane);
+            if (has_x[k]) pc_transpose8x8_store(rx[k], xT + (tcg * 8) * a.xplane + tcg * 16 + (x_slot[k] << 4), a.xplane);
 #else
         if (rd[0].x == 0x12345u && rx[0][0].x == 77u && rx[1][1].y == 5u && rx[2][2].z == 6u) dyT[threadIdx.x] = 1;
 #endif
         __syncthreads();
         if (kt + a.ksplit < a.n_ktiles) issue(kt + a.ksplit);
 
+        // fragment addresses are recomputed per pixel tile from two opaque per-lane bases: keeping all of
+        // them live across the loop would take more registers than the prefetched tile leaves
+        int o_a0 = (int)(a_row0 - lds) + g * 16, o_a1 = (int)(a_row1 - lds) + g * 16, o_b = (int)(b_col - lds);
+        asm volatile("" : "+v"(o_a0), "+v"(o_a1), "+v"(o_b));
+        const unsigned char *ar0 = lds + o_a0, *ar1 = lds + o_a1, *bc = lds + o_b;
         bf16x8 aq[2][2], bq[2][5];
-        aq[0][0] = *reinterpret_cast<const bf16x8 *>(a_row0 + ((g ^ a_sw0) << 4));
-        aq[0][1] = *reinterpret_cast<const bf16x8 *>(a_row1 + ((g ^ a_sw1) << 4));
+        aq[0][0] = *reinterpret_cast<const bf16x8 *>(ar0);
+        aq[0][1] = *reinterpret_cast<const bf16x8 *>(ar1);
 #pragma unroll
         for (int b = 0; b < 5; ++b)
-            bq[0][b] = *reinterpret_cast<const bf16x8 *>(b_col + (((xb[0] + toff[b]) ^ b_sw) << 4));
+            bq[0][b] = *reinterpret_cast<const bf16x8 *>(bc + ((xb[0] + toff[b]) << 4));
 #pragma unroll
-        for (int kk = 0; kk < WG_NSLOT / 2; ++kk) {
-            if (kk < a.nks) {
-                const int cur = kk & 1, nxt = cur ^ 1;
-                if (kk + 1 < WG_NSLOT / 2 && kk + 1 < a.nks) {
-                    const int s1 = 2 * (kk + 1) + g;
-                    aq[nxt][0] = *reinterpret_cast<const bf16x8 *>(a_row0 + ((s1 ^ a_sw0) << 4));
-                    aq[nxt][1] = *reinterpret_cast<const bf16x8 *>(a_row1 + ((s1 ^ a_sw1) << 4));
+        for (int kk = 0; kk < NKS; ++kk) {
+            const int cur = kk & 1, nxt = cur ^ 1;
+            if (kk + 1 < NKS) {
+                aq[nxt][0] = *reinterpret_cast<const bf16x8 *>(ar0 + (kk + 1) * 32);
+                aq[nxt][1] = *reinterpret_cast<const bf16x8 *>(ar1 + (kk + 1) * 32);
+                const unsigned char *bk = bc + (xb[kk + 1 < NKS ? kk + 1 : 0] << 4);
 #pragma unroll
-                    for (int b = 0; b < 5; ++b)
-                        bq[nxt][b] = *reinterpret_cast<const bf16x8 *>(
-                            b_col + (((xb[(kk + 1) % (WG_NSLOT / 2)] + toff[b]) ^ b_sw) << 4));
-                }
-#pragma unroll
-                for (int u = 0; u < 9; ++u)
-                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[cur][u < 5 ? 0 : 1], bq[cur][u < 5 ? u : u - 5],
-                                                                     acc[u], 0, 0, 0);
+                for (int b = 0; b < 5; ++b)
+                    bq[nxt][b] = *reinterpret_cast<const bf16x8 *>(bk + (toff[b] << 4));
             }
+#pragma unroll
+            for (int u = 0; u < 9; ++u)
+                acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[cur][u < 5 ? 0 : 1], bq[cur][u < 5 ? u : u - 5],
+                                                                 acc[u], 0, 0, 0);
         }
     }
     // kept taps only, compact slot order; the table look-ups are issued together, then the stores
@@ -747,12 +758,14 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     a.n_ktiles = a.tiles_n * a.tiles_r * a.tiles_c;
     a.nnzk = (int32_t)nnzk;
     memcpy(a.taps, pk->taps, sizeof(a.taps));
-    size_t lds = (size_t)WG_T * WG_DY_PLANE + (size_t)WG_T * a.xplane;
+    size_t lds = (size_t)WG_T * WG_DY_PLANE + 128 + (size_t)WG_T * a.xplane + 128;
     if (lds > WG_LDS_MAX) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: tile does not fit in LDS");
     static bool lds_attr_set = false;
     if (!lds_attr_set) {
-        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        WG_LDS_MAX));
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_MAX));
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_MAX));
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_kernel<12>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_MAX));
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_MAX));
         lds_attr_set = true;
     }
     int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
@@ -764,8 +777,12 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     void *scr = nullptr;
     s = pc_scratch(ctx, sizeof(float) * 4 * (size_t)ks * (size_t)nnzk, &scr);
     if (s != PC_OK) return s;
-    hipLaunchKernelGGL(pc_mfma_wgrad_kernel, dim3((unsigned)ct, (unsigned)ft, (unsigned)ks), dim3(256), lds, ctx->stream,
-                       (const uint16_t *)x, (const uint16_t *)dy, a, pk->v, (float *)scr);
+    const dim3 grid((unsigned)ct, (unsigned)ft, (unsigned)ks);
+    const uint16_t *xp = (const uint16_t *)x, *dyp = (const uint16_t *)dy;
+    if (a.nks <= 4) hipLaunchKernelGGL(pc_mfma_wgrad_kernel<4>, grid, dim3(256), lds, ctx->stream, xp, dyp, a, pk->v, (float *)scr);
+    else if (a.nks <= 8) hipLaunchKernelGGL(pc_mfma_wgrad_kernel<8>, grid, dim3(256), lds, ctx->stream, xp, dyp, a, pk->v, (float *)scr);
+    else if (a.nks <= 12) hipLaunchKernelGGL(pc_mfma_wgrad_kernel<12>, grid, dim3(256), lds, ctx->stream, xp, dyp, a, pk->v, (float *)scr);
+    else hipLaunchKernelGGL(pc_mfma_wgrad_kernel<16>, grid, dim3(256), lds, ctx->stream, xp, dyp, a, pk->v, (float *)scr);
     s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight launch");
     if (s != PC_OK) return s;
     return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, pk, dw);
