@@ -202,6 +202,7 @@ static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
     v->slot_f = (uint16_t *)take(sizeof(uint16_t) * cap);
     v->fm_val = (float4 *)take(sizeof(float4) * cap);
     v->slot_of = (int32_t *)take(sizeof(int32_t) * cap);
+    v->kinfo = (uint32_t *)take(sizeof(uint32_t) * cap);
     v->cm_rowptr = (int32_t *)take(sizeof(int32_t) * (C + 1));
     v->cm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)C * (PC_MAX_P + 1));
     v->cm_f = (uint16_t *)take(sizeof(uint16_t) * cap);

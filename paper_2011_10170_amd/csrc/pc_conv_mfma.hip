@@ -23,7 +23,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define MF_LDS_MAX 65536
 
-bool pc_mfma_supports(int F, int C) { (void)F; (void)C; return true; }
+bool pc_mfma_supports(int F, int C) { return (int64_t)F * C < (1 << 23); }   // kinfo packs the slot in 23 bits
 
 struct MfmaArgs {
     int32_t N, in_H, in_W, in_CH;
@@ -494,7 +494,10 @@ struct WgradMfmaArgs {
     int32_t nks;               // MFMA k-steps per pixel tile: ceil(ng * npos / 2)
     int32_t tiles_r, tiles_c, tiles_n, n_ktiles, ksplit;
     int32_t nnzk;
-    uint8_t taps[PC_MAX_P][4];
+    // decode tables built on the host (no integer divisions in the kernel); 0xFFFFFFFF = unused entry
+    int16_t xb_tab[WG_NSLOT];              // x slot read by dy slot s for tap (0,0)
+    uint32_t dy_tab[WG_NSLOT];             // dy slot -> (image group << 16) | (row << 8) | column of the output position
+    uint32_t x_tab[32 * WG_XTASKS];        // x slot  -> (image group << 16) | (row << 8) | column inside the x region
 };
 
 // 8 rows (images) of 8 bf16 (channels) -> 8 rows (channels) of 8 bf16 (images), row j stored at dst + j*pitch
@@ -535,6 +538,13 @@ __device__ __forceinline__ uint4 pc_load8(const uint16_t *p, int nch, int c)
 // One workgroup per CU (up to 512 registers per lane): the global loads of the NEXT pixel tile are in
 // flight in registers while the MFMAs of the current one run, and the fragments of the next k-step are
 // read from LDS while the 9 MFMAs of the current k-step issue.
+#ifdef EXP_TIMING
+__device__ long long pc_wgrad_dbg[32];
+extern "C" void pc_debug_read(long long *out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(pc_wgrad_dbg), sizeof(long long) * 32); }
+#define TSTAMP(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) pc_wgrad_dbg[i] = wall_clock64(); } while (0)
+#else
+#define TSTAMP(i)
+#endif
 template <int NKS>   // MFMA k-steps per pixel tile (dy slots / 2, rounded up to a multiple of 4; unused slots are zero)
 __global__ void __launch_bounds__(256, 1)
 pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradMfmaArgs a, PackView v,
@@ -543,7 +553,6 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *dyT = lds;
     unsigned char *xT = lds + WG_T * WG_DY_PLANE + 128;
-    __shared__ int8_t jmap[PC_MAX_P][9];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // wave = (channel half, tap group). The 18 (filter half, tap) units of the 64x64x9 tile are split 9/9:
@@ -551,13 +560,24 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     // half 1 and taps 8..5 of half 0. In both groups unit u < 5 is ("first" half, tap slot u) and unit
     // u >= 5 is ("second" half, tap slot u-5), so a wave reads 2 A and 5 B fragments for 9 MFMAs per k-step.
     const int chh = wave & 1, tg = wave >> 1;
-    const int first_half = tg;                                    // filter half of units 0..4
     const int c0 = blockIdx.x * WG_T, f0 = blockIdx.y * WG_T;
     const int g = lane >> 5;
 
-    for (int e = threadIdx.x; e < v.P * 9; e += 256) (&jmap[0][0])[e] = -1;
-    __syncthreads();
-    for (int e = threadIdx.x; e < v.P * 4; e += 256) jmap[e >> 2][a.taps[e >> 2][e & 3]] = (int8_t)(e & 3);
+    TSTAMP(0);
+    const int first_half = tg;                                    // filter half of units 0..4
+    const int fl = lane & 31, cl = chh * 32 + (lane & 31);
+    // (compact slot, pattern mask) of the 16 kernels this thread writes in the epilogue: loaded now so that
+    // the look-up latency hides behind the main loop
+    uint32_t kinf[2][8];
+#pragma unroll
+    for (int fh = 0; fh < 2; ++fh)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int p = threadIdx.x + 256 * k;
+            const int f = f0 + fh * 32 + (p >> 6), c = c0 + (p & 63);
+            kinf[fh][k] = (f < a.F && c < a.C) ? v.kinfo[(int64_t)f * a.C + c] : 0xFFFFFFFFu;
+        }
+    TSTAMP(1);
 
     f32x16 acc[9];
 #pragma unroll
@@ -565,18 +585,11 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
-    // per lane: LDS addresses of its A row and B column, and the x slot of each k-step's dy slot
-    const int fl = lane & 31, cl = chh * 32 + (lane & 31);
     // plane p (a filter of dyT, a channel of xT) starts at p * plane + (p >> 3) * 16
     const unsigned char *b_col = xT + cl * a.xplane + (cl >> 3) * 16;
     int xb[NKS];
 #pragma unroll
-    for (int kk = 0; kk < NKS; ++kk) {
-        int slot = 2 * kk + g;
-        int ig = slot / a.npos, pos = slot - ig * a.npos;
-        int py = pos / a.TC, px = pos - py * a.TC;
-        xb[kk] = (ig < a.ng) ? ig * a.xs_per_g + (py * a.stride) * a.IC + px * a.stride : 0;
-    }
+    for (int kk = 0; kk < NKS; ++kk) xb[kk] = a.xb_tab[2 * kk + g];
     int toff[5];                                                  // x slot offset of this wave's 5 tap slots
 #pragma unroll
     for (int b = 0; b < 5; ++b) {
@@ -590,19 +603,19 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     // staging tasks of this thread: the (slot, channel group) of a task is the same for every pixel tile
     const int tcg = threadIdx.x & 7;                      // group of 8 filters (dy) / channels (x)
     const int d_slot = threadIdx.x >> 3;                  // WG_NSLOT * 8 == 256: one dy task per thread
-    const int d_ig = d_slot / a.npos, d_pos = d_slot - d_ig * a.npos;
-    const int d_py = d_pos / a.TC, d_px = d_pos - d_py * a.TC;
-    bool has_x[WG_XTASKS];
+    const uint32_t d_tab = a.dy_tab[d_slot];
+    const bool d_ok = d_tab != 0xFFFFFFFFu;
+    const int d_ig = (int)(d_tab >> 16), d_py = (int)((d_tab >> 8) & 255), d_px = (int)(d_tab & 255);
+    bool has_x[WG_XTASKS], x_ok[WG_XTASKS];
     int x_slot[WG_XTASKS], x_ig[WG_XTASKS], x_iy[WG_XTASKS], x_ix[WG_XTASKS];
 #pragma unroll
     for (int k = 0; k < WG_XTASKS; ++k) {
         const int e = threadIdx.x + 256 * k;
         has_x[k] = e < a.xslots * 8;
         x_slot[k] = e >> 3;
-        x_ig[k] = x_slot[k] / a.xs_per_g;
-        const int rem = x_slot[k] - x_ig[k] * a.xs_per_g;
-        x_iy[k] = rem / a.IC;
-        x_ix[k] = rem - x_iy[k] * a.IC;
+        const uint32_t xt = has_x[k] ? a.x_tab[x_slot[k]] : 0xFFFFFFFFu;
+        x_ok[k] = xt != 0xFFFFFFFFu;
+        x_ig[k] = (int)(xt >> 16) & 255; x_iy[k] = (int)((xt >> 8) & 255); x_ix[k] = (int)(xt & 255);
     }
     const int64_t dy_img = (int64_t)a.Ho * a.Wo * a.F, x_img = (int64_t)a.H * a.W * a.C;
 
@@ -615,7 +628,7 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
         const int oy0 = tr * a.TR, ox0 = tc * a.TC, n0 = tn * a.ng * 8;
         {
             const int oy = oy0 + d_py, ox = ox0 + d_px, f = f0 + tcg * 8, nb = n0 + d_ig * 8;
-            const bool ok = d_ig < a.ng && oy < a.Ho && ox < a.Wo && f < a.F;
+            const bool ok = d_ok && oy < a.Ho && ox < a.Wo && f < a.F;
             const uint16_t *src = dy + (int64_t)nb * dy_img + ((int64_t)oy * a.Wo + ox) * a.F + f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -628,7 +641,7 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
             if (has_x[k]) {
                 const int yy = oy0 * a.stride - 1 + x_iy[k], xx = ox0 * a.stride - 1 + x_ix[k];
                 const int c = c0 + tcg * 8, nb = n0 + x_ig[k] * 8;
-                const bool ok = x_ig[k] < a.ng && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && c < a.C;
+                const bool ok = x_ok[k] && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && c < a.C;
                 const uint16_t *src = x + (int64_t)nb * x_img + ((int64_t)yy * a.W + xx) * a.C + c;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -640,9 +653,13 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     };
 
     int kt = blockIdx.z;
+    TSTAMP(2);
     if (kt < a.n_ktiles) issue(kt);
+    TSTAMP(3);
+    int tsi = 4;
     for (; kt < a.n_ktiles; kt += a.ksplit) {
         __syncthreads();
+        TSTAMP(tsi); tsi++;
 #ifndef EXP_NO_XPOSE
         pc_transpose8x8_store(rd, dyT + (tcg * 8) * WG_DY_PLANE + tcg * 16 + (d_slot << 4), WG_DY_PLANE);
 #pragma unroll
@@ -652,7 +669,9 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
         if (rd[0].x == 0x12345u && rx[0][0].x == 77u && rx[1][1].y == 5u && rx[2][2].z == 6u) dyT[threadIdx.x] = 1;
 #endif
         __syncthreads();
+        TSTAMP(tsi); tsi++;
         if (kt + a.ksplit < a.n_ktiles) issue(kt + a.ksplit);
+        TSTAMP(tsi); tsi++;
 
         // fragment addresses are recomputed per pixel tile from two opaque per-lane bases: keeping all of
         // them live across the loop would take more registers than the prefetched tile leaves
@@ -682,33 +701,53 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
                                                                  acc[u], 0, 0, 0);
         }
     }
-    // kept taps only, compact slot order; the table look-ups are issued together, then the stores
-    const int c = c0 + cl;
+    TSTAMP(20);
+    // Epilogue, one filter half (32 filters) at a time: the waves park their tiles of that half in LDS as
+    // out[tap][filter][channel] (float32, 72 KiB), then every thread walks 8 kernels (f, c) of the half and,
+    // for the kept ones, gathers the 4 kept taps and writes them as one 16-byte entry in compact slot order.
     float *pout = partial + (int64_t)blockIdx.z * a.nnzk * 4;
+    float *ot = reinterpret_cast<float *>(lds);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {                 // h = 0: units 0..4 ("first" half), h = 1: units 5..8
-        const int fh = h == 0 ? first_half : 1 - first_half;
-        int slot[16], pidv[16];
+    for (int fh = 0; fh < 2; ++fh) {
+        __syncthreads();
+        const int h = fh == first_half ? 0 : 1;   // this wave's unit range holding filter half fh
+        TSTAMP(22 + fh * 3);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int f = f0 + fh * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-            slot[i] = (f < a.F && c < a.C) ? v.slot_of[(int64_t)f * a.C + c] : -1;
-        }
+        for (int b = 0; b < 5; ++b) {
+            if (h == 0 || b < 4) {
+                const int tap = tg ? 8 - b : b;
+                float *tp = ot + (tap * 32) * WG_T + cl;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) pidv[i] = slot[i] >= 0 ? (int)v.fm_pid[slot[i]] : 0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            if (slot[i] >= 0) {
-                const int8_t *jm = jmap[pidv[i]];
-#pragma unroll
-                for (int b = 0; b < (h == 0 ? 5 : 4); ++b) {
-                    const int tap = tg ? 8 - b : b;
-                    const int j = jm[tap];
-                    if (j >= 0) pout[(int64_t)slot[i] * 4 + j] = acc[h * 5 + b][i];
+                for (int i = 0; i < 16; ++i) {
+                    const int fr = 8 * (i >> 2) + 4 * g + (i & 3);
+                    // units 0..4 and 5..8 are distinct registers: select without dynamic indexing
+                    tp[fr * WG_T] = h == 0 ? acc[b][i] : acc[5 + (b < 4 ? b : 0)][i];
                 }
             }
         }
+        __syncthreads();
+        TSTAMP(23 + fh * 3);
+        const uint32_t (&info)[8] = kinf[fh];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int p = threadIdx.x + 256 * k;
+            const int fr = p >> 6, cc = p & 63;
+            // entry j of a slot is the j-th set bit of the pattern mask: peel the 4 set bits and read those taps
+            if (info[k] != 0xFFFFFFFFu) {
+                uint32_t m = info[k] & 0x1FFu;
+                const float *ob = ot + fr * WG_T + cc;
+                float o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int t = __builtin_ctz(m);
+                    m &= m - 1u;
+                    o[j] = ob[t * (32 * WG_T)];
+                }
+                *reinterpret_cast<float4 *>(pout + (int64_t)(info[k] >> 9) * 4) = make_float4(o[0], o[1], o[2], o[3]);
+            }
+        }
     }
+    TSTAMP(21);
 }
 
 pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
@@ -757,9 +796,19 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     a.tiles_n = (ngroups + a.ng - 1) / a.ng;
     a.n_ktiles = a.tiles_n * a.tiles_r * a.tiles_c;
     a.nnzk = (int32_t)nnzk;
-    memcpy(a.taps, pk->taps, sizeof(a.taps));
+    for (int sl = 0; sl < WG_NSLOT; ++sl) {
+        int ig = sl / a.npos, pos = sl % a.npos, py = pos / a.TC, px = pos % a.TC;
+        bool ok = ig < a.ng;
+        a.dy_tab[sl] = ok ? ((uint32_t)ig << 16) | ((uint32_t)py << 8) | (uint32_t)px : 0xFFFFFFFFu;
+        a.xb_tab[sl] = ok ? (int16_t)(ig * a.xs_per_g + py * st * a.IC + px * st) : (int16_t)0;
+    }
+    for (int xs = 0; xs < 32 * WG_XTASKS; ++xs) {
+        int ig = xs / a.xs_per_g, rem = xs % a.xs_per_g;
+        a.x_tab[xs] = (ig < a.ng) ? ((uint32_t)ig << 16) | ((uint32_t)(rem / a.IC) << 8) | (uint32_t)(rem % a.IC) : 0xFFFFFFFFu;
+    }
     size_t lds = (size_t)WG_T * WG_DY_PLANE + 128 + (size_t)WG_T * a.xplane + 128;
     if (lds > WG_LDS_MAX) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: tile does not fit in LDS");
+    if (lds < (size_t)9 * 32 * WG_T * sizeof(float)) lds = (size_t)9 * 32 * WG_T * sizeof(float);   // the epilogue parks one filter half
     static bool lds_attr_set = false;
     if (!lds_attr_set) {
         PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_MAX));

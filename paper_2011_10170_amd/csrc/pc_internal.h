@@ -35,6 +35,7 @@ struct PackView {
     uint16_t *slot_f;     // [cap]   filter of the slot
     float4 *fm_val;       // [cap]   the 4 kept weights, ascending tap index
     int32_t *slot_of;     // [F][C]  slot of kernel (f,c), -1 when pruned
+    uint32_t *kinfo;      // [F][C]  (slot << 9) | 9-bit pattern mask, 0xFFFFFFFF when pruned (needs F*C < 2^23)
     // channel-major table for backward-data: rows = channels, kernels ordered (pattern id, filter)
     int32_t *cm_rowptr;   // [C+1]
     int32_t *cm_grp;      // [C][P+1]

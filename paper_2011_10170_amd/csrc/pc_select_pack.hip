@@ -204,6 +204,7 @@ pc_pack_place_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pi
                     v.slot_f[slot] = (uint16_t)row;
                     v.fm_val[slot] = val;
                     v.slot_of[k] = slot;
+                    v.kinfo[k] = ((uint32_t)slot << 9) | la.mask[p];
                 } else {
                     v.cm_f[slot] = (uint16_t)e;
                     v.cm_slot[slot] = v.slot_of[k];
@@ -216,7 +217,7 @@ pc_pack_place_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pi
     if (filter_major) {
         for (int e = threadIdx.x; e < len; e += blockDim.x) {
             int64_t k = row * row_stride + e * elem_stride;
-            if (!keep[k]) v.slot_of[k] = -1;
+            if (!keep[k]) { v.slot_of[k] = -1; v.kinfo[k] = 0xFFFFFFFFu; }
         }
     }
 }
