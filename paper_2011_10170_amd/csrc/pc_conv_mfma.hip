@@ -23,6 +23,13 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define MF_LDS_MAX 65536
 
+#ifdef EXP_TIMING
+__device__ long long pc_wgrad_dbg[32];
+extern "C" void pc_debug_read(long long *out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(pc_wgrad_dbg), sizeof(long long) * 32); }
+#define TSTAMP(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) pc_wgrad_dbg[i] = wall_clock64(); } while (0)
+#else
+#define TSTAMP(i)
+#endif
 bool pc_mfma_supports(int F, int C) { return (int64_t)F * C < (1 << 23); }   // kinfo packs the slot in 23 bits
 
 struct MfmaArgs {
@@ -38,6 +45,17 @@ struct MfmaArgs {
     int32_t tap_off[9];      // LDS byte offset of every list entry
 };
 
+// Depth of the A-fragment prefetch ring: the smallest divisor of the steps per chunk that keeps the loads
+// about 1000 cycles (an L2 round trip) ahead of their MFMAs; small tiles prefetch a whole chunk ahead.
+constexpr int pc_prefetch_depth(int ns, int step_cycles)
+{
+    int want = (1024 + step_cycles - 1) / step_cycles;
+    if (want > ns) want = ns;
+    for (int d = want; d <= ns; ++d)
+        if (ns % d == 0) return d;
+    return ns;
+}
+
 // KC channels are staged per pass (LDS pixel pitch 2*KC + 16 bytes: conflict-free 16-byte reads).
 // A fragments are prefetched PF steps ahead from global memory, B fragments one step ahead from LDS.
 // With gridDim.z > 1 every split reduces its own range of channel chunks and writes float32 partial
@@ -51,7 +69,7 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
     constexpr int BM = 32 * A_T * WAVES_M;
     constexpr int KSC = KC / 16;
     constexpr int NS = NTAPS * KSC;
-    constexpr int PF = (NS % 3 == 0) ? 3 : ((NS % 2 == 0) ? 2 : 1);
+    constexpr int PF = pc_prefetch_depth(NS, A_T * B_T * 32);
     constexpr int PITCH = 2 * KC + 16;
     constexpr int PARTS = KC / 8;
     const int lane = threadIdx.x & 63;
@@ -102,6 +120,12 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
 #pragma unroll
         for (int i = 0; i < A_T; ++i) aring[d][i] = a_load(ch0, d, i);
 
+#ifdef EXP_TIMING_CONV
+#define CSTAMP(i) TSTAMP(i)
+#else
+#define CSTAMP(i)
+#endif
+    CSTAMP(0);
     // element offset of every staged pixel in the input tensor (-1 = zero padding), computed once
     const int HP = g.TI * g.IH * g.IW;
     int64_t *pixoff = reinterpret_cast<int64_t *>(lds + (size_t)HP * PITCH);
@@ -114,8 +138,11 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
         bool ok = n < g.N && y >= 0 && y < g.in_H && x >= 0 && x < g.in_W;
         pixoff[q] = ok ? (((int64_t)n * g.in_H + y) * g.in_W + x) * g.in_CH : (int64_t)-1;
     }
+    int csi = 2;
+    CSTAMP(1);
     for (int ch = ch0; ch < ch1; ++ch) {
         __syncthreads();
+        CSTAMP(csi); csi++;
         for (int e = threadIdx.x; e < HP * PARTS; e += 256) {
             const int q = e / PARTS, part = e - q * PARTS;
             const int c = ch * KC + part * 8;
@@ -134,21 +161,28 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
             }
             *reinterpret_cast<uint4 *>(lds + q * PITCH + part * 16) = v;
         }
+        CSTAMP(csi); csi++;
         __syncthreads();
-        bf16x8 bcur[B_T], bnxt[B_T];
+        CSTAMP(csi); csi++;
+        // B fragments are read DB steps ahead of their MFMAs (LDS latency is longer than one small step);
+        // scheduling barriers keep the compiler from sinking the loads back next to their uses
+        constexpr int DB = (A_T * B_T >= 4) ? 1 : (NS >= 4 ? 4 : NS);
+        constexpr int RB = DB + 1;
+        bf16x8 bring[RB][B_T];
 #pragma unroll
-        for (int j = 0; j < B_T; ++j) bcur[j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[0]);
+        for (int d = 0; d < DB; ++d) {
+            const int t1 = d / KSC, k1 = d % KSC;
+#pragma unroll
+            for (int j = 0; j < B_T; ++j)
+                bring[d % RB][j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[t1] + k1 * 32);
+        }
 #pragma unroll
         for (int st = 0; st < NS; ++st) {
-            if (st + 1 < NS) {
-                const int t1 = (st + 1) / KSC, k1 = (st + 1) % KSC;
+            if (st + DB < NS) {
+                const int t1 = (st + DB) / KSC, k1 = (st + DB) % KSC;
 #pragma unroll
-#ifndef EXP_NO_B
                 for (int j = 0; j < B_T; ++j)
-                    bnxt[j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[t1] + k1 * 32);
-#else
-                for (int j = 0; j < B_T; ++j) { bnxt[j] = bcur[j]; bnxt[j][0] += (__bf16)1.0f; }
-#endif
+                    bring[(st + DB) % RB][j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[t1] + k1 * 32);
             }
             bf16x8 anow[A_T];
 #pragma unroll
@@ -158,24 +192,19 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
                 const int nch = nst >= NS ? ch + 1 : ch;
                 const int nss = nst >= NS ? nst - NS : nst;
 #pragma unroll
-#ifndef EXP_NO_A
                 for (int i = 0; i < A_T; ++i) aring[st % PF][i] = a_load(nch, nss, i);
-#else
-                for (int i = 0; i < A_T; ++i) aring[st % PF][i][0] += (__bf16)1.0f;
-#endif
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < A_T; ++i)
 #pragma unroll
                 for (int j = 0; j < B_T; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(anow[i], bcur[j], acc[i][j], 0, 0, 0);
-            if (st + 1 < NS) {
-#pragma unroll
-                for (int j = 0; j < B_T; ++j) bcur[j] = bnxt[j];
-            }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(anow[i], bring[st % RB][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
+    CSTAMP(30);
     // epilogue: lane holds, for its pixel, 4 consecutive output channels per accumulator quad
 #pragma unroll
     for (int j = 0; j < B_T; ++j) {
@@ -228,6 +257,7 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
                 }
         }
     }
+    CSTAMP(31);
 }
 
 // out[e] = bf16(partial[0][e] + partial[1][e] + ...), 4 elements per thread
@@ -538,13 +568,6 @@ __device__ __forceinline__ uint4 pc_load8(const uint16_t *p, int nch, int c)
 // One workgroup per CU (up to 512 registers per lane): the global loads of the NEXT pixel tile are in
 // flight in registers while the MFMAs of the current one run, and the fragments of the next k-step are
 // read from LDS while the 9 MFMAs of the current k-step issue.
-#ifdef EXP_TIMING
-__device__ long long pc_wgrad_dbg[32];
-extern "C" void pc_debug_read(long long *out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(pc_wgrad_dbg), sizeof(long long) * 32); }
-#define TSTAMP(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) pc_wgrad_dbg[i] = wall_clock64(); } while (0)
-#else
-#define TSTAMP(i)
-#endif
 template <int NKS>   // MFMA k-steps per pixel tile (dy slots / 2, rounded up to a multiple of 4; unused slots are zero)
 __global__ void __launch_bounds__(256, 1)
 pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradMfmaArgs a, PackView v,
@@ -620,6 +643,19 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     const int64_t dy_img = (int64_t)a.Ho * a.Wo * a.F, x_img = (int64_t)a.H * a.W * a.C;
 
     uint4 rd[8], rx[WG_XTASKS][8];
+    // 8 images of one (position, 8 channels) task: one branch per task, not per load, in the common case
+    auto load_task = [&](uint4 (&r)[8], const uint16_t *src, int64_t img, int nch, int ch, bool ok, int nb) {
+        if (ok && nb + 8 <= a.N && (nch & 7) == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r[i] = *reinterpret_cast<const uint4 *>(src + i * img);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                r[i] = make_uint4(0u, 0u, 0u, 0u);
+                if (ok && nb + i < a.N) r[i] = pc_load8(src + i * img, nch, ch);
+            }
+        }
+    };
     auto issue = [&](int kt) {
         int q = kt;
         const int tc = q % a.tiles_c; q /= a.tiles_c;
@@ -629,12 +665,7 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
         {
             const int oy = oy0 + d_py, ox = ox0 + d_px, f = f0 + tcg * 8, nb = n0 + d_ig * 8;
             const bool ok = d_ok && oy < a.Ho && ox < a.Wo && f < a.F;
-            const uint16_t *src = dy + (int64_t)nb * dy_img + ((int64_t)oy * a.Wo + ox) * a.F + f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                rd[i] = make_uint4(0u, 0u, 0u, 0u);
-                if (ok && nb + i < a.N) rd[i] = pc_load8(src + i * dy_img, a.F, f);
-            }
+            load_task(rd, dy + (int64_t)nb * dy_img + ((int64_t)oy * a.Wo + ox) * a.F + f, dy_img, a.F, f, ok, nb);
         }
 #pragma unroll
         for (int k = 0; k < WG_XTASKS; ++k) {
@@ -642,12 +673,7 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
                 const int yy = oy0 * a.stride - 1 + x_iy[k], xx = ox0 * a.stride - 1 + x_ix[k];
                 const int c = c0 + tcg * 8, nb = n0 + x_ig[k] * 8;
                 const bool ok = x_ok[k] && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W && c < a.C;
-                const uint16_t *src = x + (int64_t)nb * x_img + ((int64_t)yy * a.W + xx) * a.C + c;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    rx[k][i] = make_uint4(0u, 0u, 0u, 0u);
-                    if (ok && nb + i < a.N) rx[k][i] = pc_load8(src + i * x_img, a.C, c);
-                }
+                load_task(rx[k], x + (int64_t)nb * x_img + ((int64_t)yy * a.W + xx) * a.C + c, x_img, a.C, c, ok, nb);
             }
         }
     };
