@@ -85,9 +85,11 @@ const char *pc_last_error(const pc_ctx *ctx);
 pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
 
 /* Tuning aid for the MFMA forward/backward-data kernels: tile_cfg selects one of the built tile
- * configurations (0..6) instead of the automatic choice (-1); split_k > 0 forces that many splits of
- * the reduction (0 = automatic). A configuration that does not fit a layer makes the conv call return
- * PC_ERR_UNSUPPORTED. Results do not depend on the choice beyond float32 summation order. */
+ * configurations instead of the automatic choice (-1): 0..6 are tile shapes of the cooperative kernel,
+ * 7..9 the persistent wave-specialised kernel with pixel tiles of 128, 64 and 32 pixels (it takes
+ * 9-tap launches only; the tap subsets of a strided backward-data pass then use the automatic choice).
+ * split_k > 0 forces that many splits of the reduction in the cooperative kernel (0 = automatic).
+ * A configuration that does not fit a layer makes the conv call return PC_ERR_UNSUPPORTED. Results do not depend on the choice beyond float32 summation order. */
 pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t split_k);
 
 /* Host-only argument checks (usable without a GPU). */

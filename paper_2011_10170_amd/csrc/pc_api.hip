@@ -128,7 +128,7 @@ extern "C" pc_status pc_set_variant(pc_ctx *ctx, pc_variant v)
 extern "C" pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t split_k)
 {
     if (!ctx) return PC_ERR_INVALID_ARG;
-    if (tile_cfg < -1 || tile_cfg > 6 || split_k < 0 || split_k > 64)
+    if (tile_cfg < -1 || tile_cfg > 9 || split_k < 0 || split_k > 64)
         return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_set_plan_override: tile_cfg %d split_k %d out of range", tile_cfg, split_k);
     ctx->plan_cfg = tile_cfg;
     ctx->plan_split = split_k;
@@ -193,8 +193,8 @@ static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
     v->C = C;
     v->Fp = (F + 127) / 128 * 128;
     v->Cp = (C + 127) / 128 * 128;
-    v->Fk = (F + 31) / 32 * 32;
-    v->Ck = (C + 31) / 32 * 32;
+    v->Fk = (F + 63) / 64 * 64;
+    v->Ck = (C + 63) / 64 * 64;
     v->fm_rowptr = (int32_t *)take(sizeof(int32_t) * (F + 1));
     v->fm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)F * (PC_MAX_P + 1));
     v->fm_c = (uint16_t *)take(sizeof(uint16_t) * cap);

@@ -20,6 +20,7 @@
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t v4u32 __attribute__((ext_vector_type(4)));
 
 #define MF_LDS_MAX 65536
 
@@ -43,6 +44,12 @@ struct MfmaArgs {
     int32_t nchunks, cps;    // chunks of KC channels in total, and per split (blockIdx.z)
     int32_t tap_w[9];        // weight tap index of every list entry
     int32_t tap_off[9];      // LDS byte offset of every list entry
+    // used by the wave-specialised kernel only
+    int32_t m_tiles, total_tiles;   // row tiles of the output channels; all tiles (row tile fastest)
+    int32_t xbuf, red_off, nelem;   // bytes per staged input buffer, LDS offset of the reduction area, 16-byte elements per buffer
+    uint32_t in_bytes;              // size of the input tensor (bound of the buffer loads)
+    // divisions by these run as a multiply-high with floor(2^32 / d) + 1 (exact while dividend * d < 2^32)
+    uint32_t mg_IW, mg_IH, mg_TW, mg_THTW, mg_mt, mg_tx, mg_ty;
 };
 
 // Depth of the A-fragment prefetch ring: the smallest divisor of the steps per chunk that keeps the loads
@@ -277,6 +284,367 @@ pc_mfma_splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int
     out[e] = pk;
 }
 
+
+// ------------------------------------------------------------------ wave-specialised kernel
+// Eight wavefronts per workgroup, one workgroup per CU, walking tiles of 32*A_T output channels x
+// 32*B_T pixels (row tile fastest, so workgroups running side by side share the input tile in L2).
+//   wavefronts 4..7 (loaders) stage the input halo tile of the NEXT item (tile, 64-channel chunk) into
+//     one of two LDS buffers; their global loads are issued KS_DEPTH items ahead into registers, so an
+//     HBM round trip is hidden behind several items of MFMA work and never stalls an MFMA wavefront
+//     (a wavefront's outstanding loads retire in order: mixing long bulk loads with the short
+//     operand loads in one wavefront makes every operand wait for the bulk);
+//   wavefronts 0..3 (MFMA) all own the WHOLE tile and split the reduction: wavefront w takes the k-step
+//     of channels 16w..16w+15 of every tap of every chunk. A wavefront tile of 64x128 needs half the
+//     operand bytes per MFMA of the 32x64 tile an output split would leave at this workgroup size,
+//     which keeps both operand paths (A fragments from L2 through the 64 B/clk vector cache, B
+//     fragments from LDS) well under their limits. At the end of a tile the four partial sums are
+//     added in a fixed order (wavefront 0..3) through LDS, every wavefront finishing and storing a
+//     quarter of the tile.
+// Both roles execute the same sequence of workgroup barriers: one after the first staged item, one
+// per item, and 2*ROUNDS-1 per finished tile.
+#ifdef EXP_TIMING_KS
+#define KSTAMP(i) do { if (blockIdx.x == 0 && (threadIdx.x & 255) == 0) pc_wgrad_dbg[i] = wall_clock64(); } while (0)
+#else
+#define KSTAMP(i)
+#endif
+#define KS_NV 8          // 16-byte elements staged per loader thread and item (256 loader threads)
+#define KS_DEPTH 3       // items in flight in the loader's registers
+
+// q / d with mg = floor(2^32 / d) + 1 from the host (exact while q * d < 2^32); mg == 0 stands for d == 1
+__device__ __forceinline__ uint32_t pc_udiv(uint32_t q, uint32_t mg) { return mg ? __umulhi(q, mg) : q; }
+
+constexpr int pc_ring_depth(int nf)
+{
+    int best = 1;
+    for (int d = 1; d <= 10; ++d)
+        if (nf % d == 0) best = d;
+    return best;
+}
+
+template <int A_T, int B_T, int NTAPS, int KC>
+__global__ void __launch_bounds__(512, 1)
+pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const uint16_t *__restrict__ wz, MfmaArgs g)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int KSC = KC / 16;          // k-steps per chunk
+    constexpr int KSW = KC / 64;          // k-steps per chunk, tap and MFMA wavefront
+    constexpr int S = NTAPS * KSW;        // steps per item and wavefront
+    constexpr int NF = S * A_T;           // A fragments per item and wavefront
+    constexpr int PFD = pc_ring_depth(NF);
+    constexpr int PITCH = 2 * KC + 16;
+    constexpr int PARTS = KC / 8;
+    constexpr int NT = A_T * B_T;
+    constexpr int ROUNDS = NT >= 4 ? NT / 4 : 1;
+    constexpr int NOWN = NT >= 4 ? 4 : NT;
+    constexpr int DB = B_T >= 4 ? 1 : (B_T == 2 ? 2 : 4);   // B fragments are read this many steps ahead
+    constexpr int DBS = DB < S ? DB : S;
+    constexpr int RB = DBS + 1;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = wave & 3;
+    const int G = gridDim.x;
+    int vb = blockIdx.x;
+    if ((G & 7) == 0) vb = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);   // neighbours in the tile order share an XCD
+    const int ntile_blk = (g.total_tiles - vb + G - 1) / G;
+    const int nch = g.nchunks;
+    const int I = ntile_blk * nch;
+    const int TEB = 2 * ROUNDS - 1;       // barriers of the end-of-tile reduction
+
+    if (wave >= 4) {
+        // ------------------------------------------------------------ loaders
+        KSTAMP(16);
+        const int tl = threadIdx.x - 256;
+        const int part = tl % PARTS;
+        // The input is read with buffer loads: an offset past the end of the tensor returns zeros, which
+        // serves every element that is not a real input value (zero padding around the image, images
+        // past the batch, channels past the last one, unused loader slots) without a branch. Loads and
+        // LDS writes stay unconditional, so the compiler can count the loads in flight and wait for
+        // exactly the oldest register set.
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(in), 0, g.in_bytes, 0x00020000);
+        constexpr uint32_t OOB = 0x80000000u;   // past any tensor this kernel accepts, and no wrap-around with the chunk offset
+        const bool part_in_last = (nch - 1) * KC + part * 8 < g.in_CH;   // this thread's channels exist in the last chunk
+        int pk[KS_NV], loff[KS_NV];
+#pragma unroll
+        for (int v = 0; v < KS_NV; ++v) {
+            const int e = tl + 256 * v;
+            const uint32_t q = (uint32_t)e / PARTS;
+            const uint32_t t2 = pc_udiv(q, g.mg_IW);
+            const int ix = (int)(q - t2 * g.IW);
+            const uint32_t ti = pc_udiv(t2, g.mg_IH);
+            const int iy = (int)(t2 - ti * g.IH);
+            pk[v] = e < g.nelem ? (int)((ti << 20) | (iy << 10) | ix) : -1;
+            loff[v] = e < g.nelem ? (int)q * PITCH + part * 16 : g.xbuf - 16;
+        }
+        int lk = 0, lch = 0;              // cursor of the next item to load
+        uint32_t voff[KS_NV];             // byte offset of every element's pixel (+ its 16-byte part) in the tensor
+        auto tile_offsets = [&](int k) {
+            uint32_t pt = pc_udiv((uint32_t)(vb + k * G), g.mg_mt);
+            const uint32_t u = pc_udiv(pt, g.mg_tx);
+            const int tx = (int)(pt - u * g.tiles_x);
+            const uint32_t tnn = pc_udiv(u, g.mg_ty);
+            const int ty = (int)(u - tnn * g.tiles_y);
+            const int ltn = (int)tnn * g.TI;
+            const int ly0 = ty * g.TH * g.iscale + g.ioff_y;
+            const int lx0 = tx * g.TW * g.iscale + g.ioff_x;
+#pragma unroll
+            for (int v = 0; v < KS_NV; ++v) {
+                const int n = ltn + (pk[v] >> 20), y = ly0 + ((pk[v] >> 10) & 1023), x = lx0 + (pk[v] & 1023);
+                const bool ok = pk[v] >= 0 && n < g.N && (unsigned)y < (unsigned)g.in_H && (unsigned)x < (unsigned)g.in_W;
+                voff[v] = ok ? (uint32_t)((n * g.in_H + y) * g.in_W + x) * (uint32_t)(g.in_CH * 2) + part * 16 : OOB;
+            }
+        };
+        tile_offsets(0);
+        auto issue = [&](uint4 (&R)[KS_NV]) {
+            const int so = lch * (KC * 2);
+            const bool cut = (lch == nch - 1 && !part_in_last) || lk >= ntile_blk;
+#pragma unroll
+            for (int v = 0; v < KS_NV; ++v) {
+                const v4u32 val = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(cut ? OOB : voff[v]), so, 0);
+                R[v] = make_uint4(val.x, val.y, val.z, val.w);
+            }
+            if (lk < ntile_blk && ++lch == nch) {
+                lch = 0;
+                if (++lk < ntile_blk) tile_offsets(lk);
+            }
+        };
+        auto put = [&](const uint4 (&R)[KS_NV], int bufoff) {
+#pragma unroll
+            for (int v = 0; v < KS_NV; ++v) *reinterpret_cast<uint4 *>(lds + bufoff + loff[v]) = R[v];
+        };
+        uint4 R0[KS_NV], R1[KS_NV], R2[KS_NV];
+        KSTAMP(17);
+        issue(R0); issue(R1);
+        KSTAMP(18);
+        put(R0, 0);
+        KSTAMP(19);
+        __syncthreads();
+        KSTAMP(20);
+        issue(R2); issue(R0);
+        int chc = 0;                      // chunk index of item i inside its tile
+        // item i: while the MFMA wavefronts work on buffer i&1, write item i+1 (register set (i+1)%3) to the
+        // other buffer (past the last item: zeros, never read) and refill that set with item i+4
+        auto lstep = [&](int i, uint4 (&R)[KS_NV]) {
+#ifndef EXP_KS_NO_LOADER
+            put(R, ((i + 1) & 1) * g.xbuf);
+#endif
+            if (i < 4) KSTAMP(21 + 2 * i);
+#ifndef EXP_KS_NO_LOADER
+            issue(R);
+#endif
+            __syncthreads();
+            if (i < 4) KSTAMP(22 + 2 * i);
+            if (++chc == nch) {
+                chc = 0;
+                for (int b = 0; b < TEB; ++b) __syncthreads();
+            }
+        };
+        int i = 0;
+        for (; i + 3 <= I; i += 3) {
+            lstep(i, R1);
+            lstep(i + 1, R2);
+            lstep(i + 2, R0);
+        }
+        if (i < I) {
+            lstep(i, R1);
+            if (i + 1 < I) lstep(i + 1, R2);
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------- MFMA wavefronts
+    KSTAMP(0);
+    const int npix = g.TI * g.TH * g.TW;
+    int base[B_T];
+#pragma unroll
+    for (int j = 0; j < B_T; ++j) {
+        int q = j * 32 + (lane & 31);
+        if (q >= npix) q = npix - 1;
+        const int ti = (int)pc_udiv((uint32_t)q, g.mg_THTW);
+        const int rem = q - ti * g.TH * g.TW;
+        const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
+        base[j] = ((ti * g.IH + y * g.lstep) * g.IW + x * g.lstep) * PITCH + (lane >> 5) * 16 + w * (KSW * 32);
+    }
+    // the pixel sub-tile this wavefront finishes and stores
+    const int jo = w % B_T;
+    const int qo = jo * 32 + (lane & 31);
+    const int o_ti = (int)pc_udiv((uint32_t)qo, g.mg_THTW);
+    const int o_y = (int)pc_udiv((uint32_t)(qo - o_ti * g.TH * g.TW), g.mg_TW);
+    const int o_x = qo - o_ti * g.TH * g.TW - o_y * g.TW;
+
+    int fo[NF];                           // element offset of A fragment phi inside an item
+#pragma unroll
+    for (int ph = 0; ph < NF; ++ph) {
+        const int st = ph / A_T, ii = ph % A_T;
+        fo[ph] = ((ii * 9 + g.tap_w[st / KSW]) * g.KS + st % KSW) * 512;
+    }
+    int mt = 0, tn = 0, gy0 = 0, gx0 = 0;
+    auto tile_of = [&](int k, int &mt_, int &tn_, int &gy0_, int &gx0_) {
+        const uint32_t t = (uint32_t)(vb + k * G);
+        const uint32_t pt = pc_udiv(t, g.mg_mt);
+        mt_ = (int)(t - pt * g.m_tiles);
+        const uint32_t u = pc_udiv(pt, g.mg_tx);
+        const int tx = (int)(pt - u * g.tiles_x);
+        const uint32_t tnn = pc_udiv(u, g.mg_ty);
+        const int ty = (int)(u - tnn * g.tiles_y);
+        tn_ = (int)tnn * g.TI;
+        gy0_ = ty * g.TH;
+        gx0_ = tx * g.TW;
+    };
+    auto a_base = [&](int mt_, int ch_) -> const uint16_t * {
+        return wz + ((int64_t)(mt_ * A_T * 9) * g.KS + ch_ * KSC + w * KSW) * 512 + lane * 8;
+    };
+    tile_of(0, mt, tn, gy0, gx0);
+    int k = 0, ch = 0;
+    const uint16_t *ab = a_base(mt, 0);
+
+    f32x16 acc[A_T][B_T];
+#pragma unroll
+    for (int i = 0; i < A_T; ++i)
+#pragma unroll
+        for (int j = 0; j < B_T; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 aring[PFD];
+#pragma unroll
+    for (int ph = 0; ph < PFD; ++ph) aring[ph] = *reinterpret_cast<const bf16x8 *>(ab + fo[ph]);
+
+    KSTAMP(1);
+    __syncthreads();
+    KSTAMP(2);
+    for (int i = 0; i < I; ++i) {
+        // the item after this one (for the A prefetch); past the end: this one again, unused
+        int nk = k, nchk = ch + 1, nmt = mt, ntn = tn, ngy0 = gy0, ngx0 = gx0;
+        if (nchk == nch) {
+            nchk = 0;
+            nk = k + 1;
+            if (nk < ntile_blk) tile_of(nk, nmt, ntn, ngy0, ngx0);
+            else nchk = ch;
+        }
+        const uint16_t *abn = a_base(nmt, nchk);
+        const unsigned char *xb = lds + (i & 1) * g.xbuf;
+
+        bf16x8 bring[RB][B_T];
+#pragma unroll
+        for (int d = 0; d < DBS; ++d)
+#pragma unroll
+            for (int j = 0; j < B_T; ++j)
+                bring[d % RB][j] = *reinterpret_cast<const bf16x8 *>(xb + base[j] + g.tap_off[d / KSW] + (d % KSW) * 32);
+#pragma unroll
+        for (int st = 0; st < S; ++st) {
+#ifndef EXP_KS_NO_B
+            if (st + DBS < S) {
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+                    bring[(st + DBS) % RB][j] =
+                        *reinterpret_cast<const bf16x8 *>(xb + base[j] + g.tap_off[(st + DBS) / KSW] + ((st + DBS) % KSW) * 32);
+            }
+#else
+            if (st + DBS < S) {
+#pragma unroll
+                for (int j = 0; j < B_T; ++j) bring[(st + DBS) % RB][j] = bring[st % RB][j];
+            }
+#endif
+            bf16x8 anow[A_T];
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii) {
+                const int ph = st * A_T + ii;
+                anow[ii] = aring[ph % PFD];
+                const int nph = ph + PFD;
+#ifndef EXP_KS_NO_A
+                aring[ph % PFD] = nph < NF ? *reinterpret_cast<const bf16x8 *>(ab + fo[nph < NF ? nph : 0])
+                                           : *reinterpret_cast<const bf16x8 *>(abn + fo[nph < NF ? 0 : nph - NF]);
+#endif
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+                    acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(anow[ii], bring[st % RB][j], acc[ii][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (i < 4) KSTAMP(3 + 2 * i);
+        __syncthreads();
+        if (i < 4) KSTAMP(4 + 2 * i);
+
+        if (ch == nch - 1) {
+            // sum the four partial tiles in the order of the wavefronts; wavefront o finishes tile r*4+o
+            float *red = reinterpret_cast<float *>(lds + g.red_off);
+            const int n = tn + o_ti, gy = gy0 + o_y, gx = gx0 + o_x;
+            const bool pix_ok = qo < npix && n < g.N && gy < g.GH && gx < g.GW;
+            const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
+            uint16_t *op = out + (((int64_t)n * g.out_H + oy) * g.out_W + ox) * g.out_CH;
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
+#pragma unroll
+                for (int o = 0; o < NOWN; ++o) {
+                    if (o == w) continue;
+                    const int tau = r * 4 + o;
+                    const int wi = w < o ? w : w - 1;
+                    float *dst = red + ((o * 3 + wi) * 4) * 256 + lane * 4;
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4)
+                        *reinterpret_cast<float4 *>(dst + q4 * 256) =
+                            make_float4(acc[tau / B_T][tau % B_T][q4 * 4 + 0], acc[tau / B_T][tau % B_T][q4 * 4 + 1],
+                                        acc[tau / B_T][tau % B_T][q4 * 4 + 2], acc[tau / B_T][tau % B_T][q4 * 4 + 3]);
+                }
+                __syncthreads();
+#pragma unroll
+                for (int o = 0; o < NOWN; ++o) {
+                    if (o != w) continue;
+                    const int tau = r * 4 + o;
+                    const int ti_ = tau / B_T;
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                        for (int ws = 0; ws < 4; ++ws) {
+                            float4 p;
+                            if (ws == o)
+                                p = make_float4(acc[tau / B_T][tau % B_T][q4 * 4 + 0], acc[tau / B_T][tau % B_T][q4 * 4 + 1],
+                                                acc[tau / B_T][tau % B_T][q4 * 4 + 2], acc[tau / B_T][tau % B_T][q4 * 4 + 3]);
+                            else
+                                p = *reinterpret_cast<const float4 *>(red + ((o * 3 + (ws < o ? ws : ws - 1)) * 4 + q4) * 256 + lane * 4);
+                            if (ws == 0) s = p;
+                            else { s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w; }
+                        }
+                        const int m = (mt * A_T + ti_) * 32 + q4 * 8 + (lane >> 5) * 4;
+                        if (pix_ok) {
+                            if ((g.out_CH & 3) == 0) {
+                                if (m < g.out_CH) {
+                                    uint2 pkd;
+                                    pkd.x = (uint32_t)pc_f32_to_bf16(s.x) | ((uint32_t)pc_f32_to_bf16(s.y) << 16);
+                                    pkd.y = (uint32_t)pc_f32_to_bf16(s.z) | ((uint32_t)pc_f32_to_bf16(s.w) << 16);
+                                    *reinterpret_cast<uint2 *>(op + m) = pkd;
+                                }
+                            } else {
+                                const float sv[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (m + e < g.out_CH) op[m + e] = pc_f32_to_bf16(sv[e]);
+                            }
+                        }
+                    }
+                }
+                if (r + 1 < ROUNDS) __syncthreads();
+            }
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[ii][j][r] = 0.0f;
+            if (k == 0) KSTAMP(12);
+        }
+        if (i == I - 1) KSTAMP(13);
+        k = nk; ch = nchk; mt = nmt; tn = ntn; gy0 = ngy0; gx0 = ngx0;
+        ab = abn;
+    }
+}
+
 // ------------------------------------------------------------------ operand tiles
 // wz_fwd[mt][tap][ks][lane][8]: mt = filter/32, ks = channel/16; element i of lane l is
 // w[f = 32*mt + l%32][c = 16*ks + 8*(l/32) + i][tap], zero when pruned or padded.
@@ -370,17 +738,122 @@ static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, int ntaps, const u
     }
 }
 
+
+// ---- wave-specialised kernel: plan and launch (9-tap launches whose channel count is a multiple of 8)
+#define KS_LDS_MAX (160 * 1024)
+
+template <int B_T>
+static hipError_t launch_ks(hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out, const uint16_t *wz,
+                            const MfmaArgs &g)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<2, B_T, 9, 64>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, KS_LDS_MAX);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<2, B_T, 9, 64>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
+    return hipGetLastError();
+}
+
+// Fills the tile plan for pixel tiles of 32*bt pixels; false when the staged tile does not fit.
+static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *lds_bytes, double *est, int num_cu)
+{
+    MfmaArgs t = g;
+    plan_mfma_tiles(&t, 32 * bt, ext);
+    const int cap = 256 * KS_NV / 8;      // staged pixels: 8 16-byte parts per pixel and 64-channel chunk
+    while (t.TI * t.IH * t.IW > cap) {
+        if (t.TI > 1) --t.TI;
+        else if (t.TH > 1) {
+            t.TH = (t.TH + 1) / 2;
+            t.IH = (t.TH - 1) * t.lstep + ext;
+            t.tiles_y = (t.GH + t.TH - 1) / t.TH;
+        } else return false;
+    }
+    const int HP = t.TI * t.IH * t.IW;
+    t.nelem = HP * 8;
+    t.xbuf = HP * 144 + 16;   // one spare 16-byte slot for the loader threads without an element
+    t.red_off = 2 * t.xbuf;
+    const int nt = 2 * bt, nown = nt >= 4 ? 4 : nt;
+    *lds_bytes = (size_t)t.red_off + (size_t)nown * 12288;
+    if (*lds_bytes > KS_LDS_MAX) return false;
+    t.m_tiles = (g.out_CH + 63) / 64;
+    const int64_t p_tiles = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x;
+    const int64_t total = p_tiles * t.m_tiles;
+    if (total > (1 << 30)) return false;
+    t.total_tiles = (int)total;
+    int64_t dmax = t.m_tiles > t.tiles_x ? t.m_tiles : t.tiles_x;
+    if (t.tiles_y > dmax) dmax = t.tiles_y;
+    if (total * dmax >= ((int64_t)1 << 32)) return false;   // the multiply-high divisions of the tile index stay exact
+    const int64_t in_bytes = (int64_t)g.N * g.in_H * g.in_W * g.in_CH * 2;
+    if (in_bytes >= ((int64_t)1 << 31)) return false;   // 32-bit buffer offsets, with 2^31 as the out-of-range marker
+    t.in_bytes = (uint32_t)in_bytes;
+    auto magic = [](int d) { return d == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint64_t)d) + 1); };
+    t.mg_IW = magic(t.IW); t.mg_IH = magic(t.IH); t.mg_TW = magic(t.TW); t.mg_THTW = magic(t.TH * t.TW);
+    t.mg_mt = magic(t.m_tiles); t.mg_tx = magic(t.tiles_x); t.mg_ty = magic(t.tiles_y);
+    t.nchunks = (g.in_CH + 63) / 64;
+    t.cps = t.nchunks;
+    const int64_t rounds = (total + num_cu - 1) / num_cu;
+    *est = (double)rounds * ((double)t.nchunks * 576.0 * bt + 2500.0);
+    *out = t;
+    return true;
+}
+
+// PC_OK: launched. PC_ERR_UNSUPPORTED without a message: not applicable, the caller uses the other kernel.
+static pc_status run_mfma_conv_ks(pc_ctx *ctx, const MfmaArgs &g0, int ext, const int *tr, const int *tc, const uint16_t *in,
+                                  uint16_t *out, const uint16_t *wz, bool *launched)
+{
+    *launched = false;
+    static const int kBt[3] = {4, 2, 1};
+    MfmaArgs best;
+    size_t best_lds = 0;
+    double best_est = 0.0;
+    int best_bt = 0;
+    for (int k = 0; k < 3; ++k) {
+        if (ctx->plan_cfg >= 7 && ctx->plan_cfg - 7 != k) continue;
+        MfmaArgs t;
+        size_t lds;
+        double est;
+        if (!plan_ks(g0, ext, kBt[k], &t, &lds, &est, ctx->num_cu)) continue;
+        if (!best_bt || est < best_est) { best = t; best_lds = lds; best_est = est; best_bt = kBt[k]; }
+    }
+    if (!best_bt) return PC_OK;
+    MfmaArgs g = best;
+    for (int t = 0; t < 9; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * 144;
+    const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;
+    hipError_t e;
+    switch (best_bt) {
+    case 4: e = launch_ks<4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 2: e = launch_ks<2>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    }
+    *launched = true;
+    return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");
+}
+
 // g holds everything but the tile plan; ext = reach of the tap offsets (3 or 2); tap rows/cols in tr/tc.
 static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, const int *tr, const int *tc,
                                const uint16_t *in, uint16_t *out, const uint16_t *wz)
 {
+    if (ntaps == 9 && (g.in_CH & 7) == 0 && g.in_CH >= 32 && (ctx->plan_cfg < 0 || ctx->plan_cfg >= 7) &&
+        ctx->plan_split == 0) {
+        bool launched = false;
+        pc_status s = run_mfma_conv_ks(ctx, g, ext, tr, tc, in, out, wz, &launched);
+        if (launched || s != PC_OK) return s;
+    }
+    int plan_cfg = ctx->plan_cfg;
+    if (plan_cfg >= 7) {   // forced wave-specialised kernel: launches it cannot take (tap subsets) use the automatic choice
+        if (ntaps == 9) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA conv: the wave-specialised kernel does not fit this launch");
+        plan_cfg = -1;
+    }
     int pick = -1, pick_split = 1;
     MfmaArgs best = g;
     const int64_t want = 2 * (int64_t)ctx->num_cu;
-    const int n_try = ctx->plan_cfg >= 0 ? 1 : (int)(sizeof(kAutoOrder) / sizeof(kAutoOrder[0]));
+    const int n_try = plan_cfg >= 0 ? 1 : (int)(sizeof(kAutoOrder) / sizeof(kAutoOrder[0]));
     for (int k = 0; k < n_try; ++k) {
-        int ci = ctx->plan_cfg >= 0 ? ctx->plan_cfg : kAutoOrder[k];
-        if (ctx->plan_cfg < 0 && g.in_CH <= 16) ci = 6;   // a handful of input channels: one 16-channel k-step per tap
+        int ci = plan_cfg >= 0 ? plan_cfg : kAutoOrder[k];
+        if (plan_cfg < 0 && g.in_CH <= 16) ci = 6;   // a handful of input channels: one 16-channel k-step per tap
         const MfmaCfg &c = kCfgs[ci];
         int BM = 32 * c.a * c.wm, BN = 32 * c.b * c.wn;
         MfmaArgs t = g;

@@ -46,7 +46,7 @@ struct PackView {
     uint16_t *wz_fwd;     // A operand of the forward pass
     uint16_t *wz_bwd;     // A operand of the backward-data pass
     int32_t Fp, Cp;       // F and C rounded up to 128 (row extent of the operand tiles)
-    int32_t Fk, Ck;       // F and C rounded up to 32 (reduction extent of the operand tiles)
+    int32_t Fk, Ck;       // F and C rounded up to 64, the largest channel chunk a kernel walks (reduction extent of the operand tiles)
 };
 
 struct pc_packed {

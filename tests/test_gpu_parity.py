@@ -128,6 +128,29 @@ def test_every_mfma_tile_configuration(B, ctx, oracle, cfg, split):
         B.pc_set_plan_override(ctx, -1, 0)
 
 
+# Shapes for the wave-specialised forward/backward-data kernel (channel counts that are multiples of 8): a
+# partial last channel chunk, tiny images, a strided layer, and more tiles than workgroups.
+WAVE_SPEC = [
+    (3, 12, 20, 72, 96, 1),
+    (2, 9, 9, 40, 24, 2),
+    (20, 2, 2, 128, 64, 1),
+    (5, 4, 4, 192, 80, 1),
+    (12, 32, 32, 64, 128, 1),
+]
+
+
+@pytest.mark.parametrize("cfg", [7, 8, 9])
+@pytest.mark.parametrize("shape", WAVE_SPEC)
+def test_wave_specialised_kernel(B, ctx, oracle, cfg, shape):
+    """The persistent kernel with loader wavefronts and a reduction split over four MFMA wavefronts, for
+    each of its pixel-tile widths (128, 64 and 32 pixels)."""
+    B.pc_set_plan_override(ctx, cfg, 0)
+    try:
+        run_case(B, ctx, oracle, shape, "bf16", 8, 0.3, B.PC_VARIANT_MFMA, ("wave_spec", cfg))
+    finally:
+        B.pc_set_plan_override(ctx, -1, 0)
+
+
 @pytest.mark.parametrize("shape", MEDIUM_BF16)
 def test_medium_bf16_valu(B, ctx, oracle, shape):
     run_case(B, ctx, oracle, shape, "bf16", 12, 0.3, B.PC_VARIANT_VALU, "medium")
