@@ -21,6 +21,7 @@
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t v4u32 __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u32 __attribute__((ext_vector_type(2)));
 
 #define MF_LDS_MAX 65536
 
@@ -47,7 +48,7 @@ struct MfmaArgs {
     // used by the wave-specialised kernel only
     int32_t m_tiles, total_tiles;   // row tiles of the output channels; all tiles (row tile fastest)
     int32_t xbuf, red_off, nelem;   // bytes per staged input buffer, LDS offset of the reduction area, 16-byte elements per buffer
-    uint32_t in_bytes;              // size of the input tensor (bound of the buffer loads)
+    uint32_t in_bytes, out_bytes;   // sizes of the input and output tensors (bounds of the buffer loads and stores)
     // divisions by these run as a multiply-high with floor(2^32 / d) + 1 (exact while dividend * d < 2^32)
     uint32_t mg_IW, mg_IH, mg_TW, mg_THTW, mg_mt, mg_tx, mg_ty;
 };
@@ -473,6 +474,8 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     const int o_y = (int)pc_udiv((uint32_t)(qo - o_ti * g.TH * g.TW), g.mg_TW);
     const int o_x = qo - o_ti * g.TH * g.TW - o_y * g.TW;
 
+    const __amdgpu_buffer_rsrc_t osrc = __builtin_amdgcn_make_buffer_rsrc(out, 0, g.out_bytes, 0x00020000);
+    constexpr uint32_t OOB_OUT = 0x80000000u;
     int fo[NF];                           // element offset of A fragment phi inside an item
 #pragma unroll
     for (int ph = 0; ph < NF; ++ph) {
@@ -558,12 +561,21 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                                            : *reinterpret_cast<const bf16x8 *>(abn + fo[nph < NF ? 0 : nph - NF]);
 #endif
             }
-            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int ii = 0; ii < A_T; ++ii)
 #pragma unroll
                 for (int j = 0; j < B_T; ++j)
                     acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(anow[ii], bring[st % RB][j], acc[ii][j], 0, 0, 0);
+            // One wavefront per SIMD issues everything in program order: the loads of the later steps and their
+            // address arithmetic go one or two at a time into the shadow of each MFMA instead of in a bunch
+            // between two steps, where they would leave the matrix pipe idle.
+#pragma unroll
+            for (int m = 0; m < A_T * B_T; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);       // address arithmetic
+                if (m < B_T) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              // one LDS read
+                else if (m < B_T + A_T) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         if (i < 4) KSTAMP(3 + 2 * i);
@@ -576,7 +588,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
             const int n = tn + o_ti, gy = gy0 + o_y, gx = gx0 + o_x;
             const bool pix_ok = qo < npix && n < g.N && gy < g.GH && gx < g.GW;
             const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
-            uint16_t *op = out + (((int64_t)n * g.out_H + oy) * g.out_W + ox) * g.out_CH;
+            const uint32_t opix_off = pix_ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) : OOB_OUT;
 #pragma unroll
             for (int r = 0; r < ROUNDS; ++r) {
 #pragma unroll
@@ -611,22 +623,13 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                             if (ws == 0) s = p;
                             else { s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w; }
                         }
+                        // a store past the end of the buffer is dropped: pixels and channels outside the output need no branch
                         const int m = (mt * A_T + ti_) * 32 + q4 * 8 + (lane >> 5) * 4;
-                        if (pix_ok) {
-                            if ((g.out_CH & 3) == 0) {
-                                if (m < g.out_CH) {
-                                    uint2 pkd;
-                                    pkd.x = (uint32_t)pc_f32_to_bf16(s.x) | ((uint32_t)pc_f32_to_bf16(s.y) << 16);
-                                    pkd.y = (uint32_t)pc_f32_to_bf16(s.z) | ((uint32_t)pc_f32_to_bf16(s.w) << 16);
-                                    *reinterpret_cast<uint2 *>(op + m) = pkd;
-                                }
-                            } else {
-                                const float sv[4] = {s.x, s.y, s.z, s.w};
-#pragma unroll
-                                for (int e = 0; e < 4; ++e)
-                                    if (m + e < g.out_CH) op[m + e] = pc_f32_to_bf16(sv[e]);
-                            }
-                        }
+                        uint2 pkd;
+                        pkd.x = pc_pack_bf16x2(s.x, s.y);
+                        pkd.y = pc_pack_bf16x2(s.z, s.w);
+                        const v2u32 pv = {pkd.x, pkd.y};
+                        __builtin_amdgcn_raw_buffer_store_b64(pv, osrc, (int)((m < g.out_CH ? opix_off : OOB_OUT) + (uint32_t)(m * 2)), 0, 0);
                     }
                 }
                 if (r + 1 < ROUNDS) __syncthreads();
@@ -789,6 +792,9 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *l
     const int64_t in_bytes = (int64_t)g.N * g.in_H * g.in_W * g.in_CH * 2;
     if (in_bytes >= ((int64_t)1 << 31)) return false;   // 32-bit buffer offsets, with 2^31 as the out-of-range marker
     t.in_bytes = (uint32_t)in_bytes;
+    const int64_t out_bytes = (int64_t)g.N * g.out_H * g.out_W * g.out_CH * 2;
+    if (out_bytes >= ((int64_t)1 << 31) || (g.out_CH & 3)) return false;   // 8-byte buffer stores of 4 channels
+    t.out_bytes = (uint32_t)out_bytes;
     auto magic = [](int d) { return d == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint64_t)d) + 1); };
     t.mg_IW = magic(t.IW); t.mg_IH = magic(t.IH); t.mg_TW = magic(t.TW); t.mg_THTW = magic(t.TH * t.TW);
     t.mg_mt = magic(t.m_tiles); t.mg_tx = magic(t.tiles_x); t.mg_ty = magic(t.tiles_y);
@@ -819,6 +825,9 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, const MfmaArgs &g0, int ext, cons
         if (!best_bt || est < best_est) { best = t; best_lds = lds; best_est = est; best_bt = kBt[k]; }
     }
     if (!best_bt) return PC_OK;
+    // The end-of-tile reduction costs about as much as one 64-channel chunk of MFMA work: with one or two
+    // chunks per tile the cooperative kernel's output split is faster, unless every workgroup has a single tile.
+    if (ctx->plan_cfg < 0 && (best.nchunks < 2 || (best.nchunks == 2 && best.total_tiles > ctx->num_cu))) return PC_OK;
     MfmaArgs g = best;
     for (int t = 0; t < 9; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * 144;
     const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;

@@ -110,6 +110,15 @@ __device__ __forceinline__ uint16_t pc_f32_to_bf16(float f)
     u += 0x7FFFu + ((u >> 16) & 1u);   // round to nearest, ties to even (finite inputs)
     return (uint16_t)(u >> 16);
 }
+// two floats -> two bf16 (round to nearest even, v_cvt_pk_bf16_f32), the first in the low half
+__device__ __forceinline__ uint32_t pc_pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const f2 v = {lo, hi};
+    const bf2 b = __builtin_convertvector(v, bf2);
+    return *reinterpret_cast<const uint32_t *>(&b);
+}
 template <typename T> __device__ __forceinline__ float pc_load(const T *p);
 template <> __device__ __forceinline__ float pc_load<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float pc_load<uint16_t>(const uint16_t *p) { return pc_bf16_to_f32(*p); }
