@@ -807,7 +807,7 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *l
 }
 
 // PC_OK: launched. PC_ERR_UNSUPPORTED without a message: not applicable, the caller uses the other kernel.
-static pc_status run_mfma_conv_ks(pc_ctx *ctx, const MfmaArgs &g0, int ext, const int *tr, const int *tc, const uint16_t *in,
+static pc_status run_mfma_conv_ks(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext, const int *tr, const int *tc, const uint16_t *in,
                                   uint16_t *out, const uint16_t *wz, bool *launched)
 {
     *launched = false;
@@ -817,7 +817,7 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, const MfmaArgs &g0, int ext, cons
     double best_est = 0.0;
     int best_bt = 0;
     for (int k = 0; k < 3; ++k) {
-        if (ctx->plan_cfg >= 7 && ctx->plan_cfg - 7 != k) continue;
+        if (pcfg >= 7 && pcfg - 7 != k) continue;
         MfmaArgs t;
         size_t lds;
         double est;
@@ -827,7 +827,7 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, const MfmaArgs &g0, int ext, cons
     if (!best_bt) return PC_OK;
     // The end-of-tile reduction costs about as much as one 64-channel chunk of MFMA work: with one or two
     // chunks per tile the cooperative kernel's output split is faster, unless every workgroup has a single tile.
-    if (ctx->plan_cfg < 0 && (best.nchunks < 2 || (best.nchunks == 2 && best.total_tiles > ctx->num_cu))) return PC_OK;
+    if (pcfg < 0 && (best.nchunks < 2 || (best.nchunks == 2 && best.total_tiles > ctx->num_cu))) return PC_OK;
     MfmaArgs g = best;
     for (int t = 0; t < 9; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * 144;
     const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;
@@ -845,13 +845,12 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, const MfmaArgs &g0, int ext, cons
 static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, const int *tr, const int *tc,
                                const uint16_t *in, uint16_t *out, const uint16_t *wz)
 {
-    if (ntaps == 9 && (g.in_CH & 7) == 0 && g.in_CH >= 32 && (ctx->plan_cfg < 0 || ctx->plan_cfg >= 7) &&
-        ctx->plan_split == 0) {
+    int plan_cfg = ctx->plan_cfg >= 10 ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
+    if (ntaps == 9 && (g.in_CH & 7) == 0 && g.in_CH >= 32 && (plan_cfg < 0 || plan_cfg >= 7) && ctx->plan_split == 0) {
         bool launched = false;
-        pc_status s = run_mfma_conv_ks(ctx, g, ext, tr, tc, in, out, wz, &launched);
+        pc_status s = run_mfma_conv_ks(ctx, plan_cfg, g, ext, tr, tc, in, out, wz, &launched);
         if (launched || s != PC_OK) return s;
     }
-    int plan_cfg = ctx->plan_cfg;
     if (plan_cfg >= 7) {   // forced wave-specialised kernel: launches it cannot take (tap subsets) use the automatic choice
         if (ntaps == 9) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA conv: the wave-specialised kernel does not fit this launch");
         plan_cfg = -1;
@@ -1258,6 +1257,342 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     TSTAMP(21);
 }
 
+
+// ------------------------------------------------------------------ backward-weight, wave-specialised
+// Same arithmetic and LDS planes as the kernel above, re-organised like the forward kernel: wavefronts
+// 4..7 load, transpose and write the NEXT pixel tile (16 dy slots: 8 MFMA k-steps) into the other of two
+// LDS buffers while wavefronts 0..3 issue the 72 MFMAs of the current one; the loaders' global loads are
+// two pixel tiles ahead in registers. All loads are buffer loads whose offset is out of range for
+// everything that must read as zero (padding, tile edges, unused slots), so the loader has no branches.
+// Every split writes its partial sums in compact slot order; pc_wgrad_reduce_kernel adds them in split
+// order. (Letting the last workgroup of a tile add them inside this kernel was slower: data crossing
+// the XCDs within a kernel needs device-scope write-through stores and read-through loads, and one
+// workgroup waits for those round trips in series.)
+#define WS_NSLOT 16
+#define WS_NKS (WS_NSLOT / 2)
+#define WS_XSLOTS 48
+#define WS_DY_PLANE (WS_NSLOT * 16 + 16)
+#define WS_LDS_MAX (160 * 1024 - 256)   // dynamic part; the kernel has a few bytes of static LDS too
+
+struct WgradWsArgs {
+    int32_t N, H, W, C, F, Ho, Wo, stride;
+    int32_t TR, TC, npos, ng, IR, IC, xs_per_g, xslots, xplane;
+    int32_t tiles_r, tiles_c, n_ktiles, ksplit, nnzk;
+    int32_t buf_bytes;                     // one LDS buffer: dyT planes, then xT planes
+    uint32_t x_bytes, dy_bytes;            // tensor sizes (bounds of the buffer loads)
+    uint32_t mg_tc, mg_tr;                 // multiply-high constants of the divisions by tiles_c and tiles_r
+    int16_t xb_tab[WS_NSLOT];              // x slot read by dy slot s for tap (0,0)
+    uint32_t dy_tab[WS_NSLOT];             // dy slot -> (image group << 16) | (row << 8) | column; 0xFFFFFFFF = unused
+    uint32_t x_tab[WS_XSLOTS];             // x slot  -> (image group << 16) | (row << 8) | column inside the x region
+};
+
+__global__ void __launch_bounds__(512, 1)
+pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradWsArgs a, PackView v,
+                        float *__restrict__ partial, float *__restrict__ dw)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int XT_OFF = WG_T * WS_DY_PLANE + 128;   // xT planes inside a buffer
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c0 = blockIdx.x * WG_T, f0 = blockIdx.y * WG_T;
+    const int nt = (a.n_ktiles - (int)blockIdx.z + a.ksplit - 1) / a.ksplit;   // pixel tiles of this workgroup
+
+    // (compact slot, pattern mask) of the 8 kernels this thread writes in the epilogue
+    uint32_t kinf[2][4];
+#pragma unroll
+    for (int fh = 0; fh < 2; ++fh)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int p = threadIdx.x + 512 * k;
+            const int f = f0 + fh * 32 + (p >> 6), c = c0 + (p & 63);
+            kinf[fh][k] = (f < a.F && c < a.C) ? v.kinfo[(int64_t)f * a.C + c] : 0xFFFFFFFFu;
+        }
+    float *pout = a.ksplit > 1 ? partial + (int64_t)blockIdx.z * a.nnzk * 4 : dw;
+    const float *ot = reinterpret_cast<const float *>(lds);
+    // gathers the 4 kept taps of every kept kernel of filter half fh from the parked tile
+    auto gather = [&](int fh) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int p = threadIdx.x + 512 * k;
+            const uint32_t info = kinf[fh][k];
+            if (info != 0xFFFFFFFFu) {
+                uint32_t m = info & 0x1FFu;
+                const float *ob = ot + (p >> 6) * WG_T + (p & 63);
+                float o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int t = __builtin_ctz(m);
+                    m &= m - 1u;
+                    o[j] = ob[t * (32 * WG_T)];
+                }
+                *reinterpret_cast<float4 *>(pout + (int64_t)(info >> 9) * 4) = make_float4(o[0], o[1], o[2], o[3]);
+            }
+        }
+    };
+
+    if (wave >= 4) {
+        // ------------------------------------------------------------ loaders
+        const int tl = threadIdx.x - 256;
+        const int cg = tl & 7;
+        const bool dy0 = wave < 6;                      // task 0 of wavefronts 4,5 is a dy task, of 6,7 an x task
+        constexpr uint32_t OOB = 0x80000000u;
+        const __amdgpu_buffer_rsrc_t xsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(x), 0, a.x_bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t src0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(dy0 ? dy : x), 0,
+                                                                               dy0 ? a.dy_bytes : a.x_bytes, 0x00020000);
+        const int dy_img = a.Ho * a.Wo * a.F * 2, x_img = a.H * a.W * a.C * 2;   // bytes per image
+        // task 0: slot tl>>3 (dy) or (tl-128)>>3 (x slots 0..15); task 1: x slot 16 + tl>>3 (x slots 16..47)
+        const int slot0 = dy0 ? tl >> 3 : (tl - 128) >> 3;
+        const int slot1 = 16 + (tl >> 3);
+        const uint32_t tab0 = dy0 ? a.dy_tab[slot0] : (slot0 < a.xslots ? a.x_tab[slot0] : 0xFFFFFFFFu);
+        const uint32_t tab1 = slot1 < a.xslots ? a.x_tab[slot1] : 0xFFFFFFFFu;
+        const int ig0 = (int)(tab0 >> 16) & 255, r0 = (int)(tab0 >> 8) & 255, q0 = (int)tab0 & 255;
+        const int ig1 = (int)(tab1 >> 16) & 255, r1 = (int)(tab1 >> 8) & 255, q1 = (int)tab1 & 255;
+        const bool chan0 = dy0 ? f0 + cg * 8 < a.F : c0 + cg * 8 < a.C;
+        const bool use0 = tab0 != 0xFFFFFFFFu && chan0;
+        const bool use1 = tab1 != 0xFFFFFFFFu && c0 + cg * 8 < a.C;
+        // byte offset of the task's first image relative to the pixel tile's origin
+        const int rel0 = dy0 ? ig0 * 8 * dy_img + ((r0 * a.Wo + q0) * a.F + f0 + cg * 8) * 2
+                             : ig0 * 8 * x_img + ((r0 * a.W + q0) * a.C + c0 + cg * 8) * 2;
+        const int rel1 = ig1 * 8 * x_img + ((r1 * a.W + q1) * a.C + c0 + cg * 8) * 2;
+        const int img0 = dy0 ? dy_img : x_img;
+        const int pitch0 = dy0 ? WS_DY_PLANE : a.xplane;
+        const int dst0 = (dy0 ? 0 : XT_OFF) + (cg * 8) * pitch0 + cg * 16 + (slot0 << 4);
+        const int dst1 = XT_OFF + (cg * 8) * a.xplane + cg * 16 + (slot1 << 4);
+
+        int kt = blockIdx.z;                             // next pixel tile to request
+        auto issue = [&](uint4 (&A)[8], uint4 (&B)[8]) {
+            const bool live = kt < a.n_ktiles;
+            const uint32_t u = pc_udiv((uint32_t)kt, a.mg_tc);
+            const int tc = kt - (int)u * a.tiles_c;
+            const uint32_t tn = pc_udiv(u, a.mg_tr);
+            const int tr = (int)u - (int)tn * a.tiles_r;
+            const int oy0 = tr * a.TR, ox0 = tc * a.TC, n0 = (int)tn * a.ng * 8;
+            const int xy0 = oy0 * a.stride - 1, xx0 = ox0 * a.stride - 1;
+            const int org_d = n0 * dy_img + (oy0 * a.Wo + ox0) * a.F * 2;
+            const int org_x = n0 * x_img + (xy0 * a.W + xx0) * a.C * 2;
+            bool ok0, ok1;
+            if (dy0) ok0 = oy0 + r0 < a.Ho && ox0 + q0 < a.Wo;
+            else ok0 = (unsigned)(xy0 + r0) < (unsigned)a.H && (unsigned)(xx0 + q0) < (unsigned)a.W;
+            ok0 = ok0 && live && use0 && n0 + ig0 * 8 < a.N;
+            ok1 = (unsigned)(xy0 + r1) < (unsigned)a.H && (unsigned)(xx0 + q1) < (unsigned)a.W && live && use1 &&
+                  n0 + ig1 * 8 < a.N;
+            const uint32_t vo0 = ok0 ? (uint32_t)(rel0 + (dy0 ? org_d : org_x)) : OOB;
+            const uint32_t vo1 = ok1 ? (uint32_t)(rel1 + org_x) : OOB;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const v4u32 t0 = __builtin_amdgcn_raw_buffer_load_b128(src0, (int)vo0, i * img0, 0);
+                A[i] = make_uint4(t0.x, t0.y, t0.z, t0.w);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const v4u32 t1 = __builtin_amdgcn_raw_buffer_load_b128(xsrc, (int)vo1, i * x_img, 0);
+                B[i] = make_uint4(t1.x, t1.y, t1.z, t1.w);
+            }
+            kt += a.ksplit;
+        };
+        // a task whose slot lies past the x planes has nowhere to write (every slot inside them is written,
+        // with zeros where nothing is loaded)
+        const bool in0 = dy0 || slot0 < a.xslots, in1 = slot1 < a.xslots;
+        auto put = [&](const uint4 (&A)[8], const uint4 (&B)[8], int bufoff) {
+            if (in0) pc_transpose8x8_store(A, lds + bufoff + dst0, pitch0);
+            if (in1) pc_transpose8x8_store(B, lds + bufoff + dst1, a.xplane);
+        };
+        uint4 A0[8], B0[8], A1[8], B1[8];
+        issue(A0, B0); issue(A1, B1);
+        put(A0, B0, 0);
+        __syncthreads();
+        issue(A0, B0);
+        // tile i: write tile i+1 (register set (i+1)&1) into buffer (i+1)&1, refill the set with tile i+3
+        int i = 0;
+        // (the scheduling barriers keep the transposes of the next tile, and with them the wait for its data,
+        // from being hoisted in front of the workgroup barrier)
+        auto sync = [&]() {
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        for (; i + 2 <= nt; i += 2) {
+            put(A1, B1, a.buf_bytes); issue(A1, B1); sync();
+            put(A0, B0, 0);           issue(A0, B0); sync();
+        }
+        if (i < nt) { put(A1, B1, a.buf_bytes); issue(A1, B1); sync(); }
+#pragma unroll
+        for (int fh = 0; fh < 2; ++fh) {
+            __syncthreads();
+            __syncthreads();
+            gather(fh);
+        }
+    } else {
+        // ------------------------------------------------------------ MFMA wavefronts
+        // wave = (channel half, tap group); the 18 (filter half, tap) units are split 9/9 as in the kernel above
+        const int chh = wave & 1, tg = wave >> 1;
+        const int g = lane >> 5;
+        const int first_half = tg;
+        const int fl = lane & 31, cl = chh * 32 + (lane & 31);
+        f32x16 acc[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+        int xb[WS_NKS];
+#pragma unroll
+        for (int kk = 0; kk < WS_NKS; ++kk) xb[kk] = a.xb_tab[2 * kk + g];
+        int toff[5];
+#pragma unroll
+        for (int b = 0; b < 5; ++b) {
+            const int tap = tg ? 8 - b : b;
+            toff[b] = (tap / 3) * a.IC + (tap % 3);
+        }
+        const int f_first = fl + (first_half ? 32 : 0), f_second = fl + (first_half ? 0 : 32);
+        const int o_a0 = f_first * WS_DY_PLANE + (f_first >> 3) * 16 + g * 16;
+        const int o_a1 = f_second * WS_DY_PLANE + (f_second >> 3) * 16 + g * 16;
+        const int o_b = XT_OFF + cl * a.xplane + (cl >> 3) * 16;
+
+        __syncthreads();
+        for (int i = 0; i < nt; ++i) {
+            const unsigned char *bufp = lds + (i & 1) * a.buf_bytes;
+            const unsigned char *ar0 = bufp + o_a0, *ar1 = bufp + o_a1, *bc = bufp + o_b;
+            bf16x8 aq[2][2], bq[2][5];
+            aq[0][0] = *reinterpret_cast<const bf16x8 *>(ar0);
+            aq[0][1] = *reinterpret_cast<const bf16x8 *>(ar1);
+#pragma unroll
+            for (int b = 0; b < 5; ++b) bq[0][b] = *reinterpret_cast<const bf16x8 *>(bc + ((xb[0] + toff[b]) << 4));
+#pragma unroll
+            for (int kk = 0; kk < WS_NKS; ++kk) {
+                const int cur = kk & 1, nxt = cur ^ 1;
+                if (kk + 1 < WS_NKS) {
+                    aq[nxt][0] = *reinterpret_cast<const bf16x8 *>(ar0 + (kk + 1) * 32);
+                    aq[nxt][1] = *reinterpret_cast<const bf16x8 *>(ar1 + (kk + 1) * 32);
+                    const unsigned char *bk = bc + (xb[kk + 1 < WS_NKS ? kk + 1 : 0] << 4);
+#pragma unroll
+                    for (int b = 0; b < 5; ++b) bq[nxt][b] = *reinterpret_cast<const bf16x8 *>(bk + (toff[b] << 4));
+                }
+#pragma unroll
+                for (int u = 0; u < 9; ++u)
+                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[cur][u < 5 ? 0 : 1], bq[cur][u < 5 ? u : u - 5], acc[u], 0, 0, 0);
+                // the 7 fragment reads of the next k-step go one by one into the shadow of the MFMAs
+#pragma unroll
+                for (int u = 0; u < 9; ++u) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                    if (u < 7) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();
+        }
+        // epilogue, one filter half at a time: park the half's tiles as out[tap][filter][channel] (72 KiB)
+        float *otw = reinterpret_cast<float *>(lds);
+#pragma unroll
+        for (int fh = 0; fh < 2; ++fh) {
+            __syncthreads();
+            const int h = fh == first_half ? 0 : 1;
+#pragma unroll
+            for (int b = 0; b < 5; ++b) {
+                if (h == 0 || b < 4) {
+                    const int tap = tg ? 8 - b : b;
+                    float *tp = otw + (tap * 32) * WG_T + cl;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int fr = 8 * (i >> 2) + 4 * g + (i & 3);
+                        tp[fr * WG_T] = h == 0 ? acc[b][i] : acc[5 + (b < 4 ? b : 0)][i];
+                    }
+                }
+            }
+            __syncthreads();
+            gather(fh);
+        }
+    }
+
+}
+
+// Wave-specialised backward-weight: plan and launch. *launched stays false when the layer is outside what
+// that kernel takes (the caller then uses the cooperative kernel).
+static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
+                                       float *dw, int64_t nnzk, bool *launched)
+{
+    *launched = false;
+    WgradWsArgs a;
+    memset(&a, 0, sizeof(a));
+    const int st = d->stride;
+    a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.F = d->F; a.stride = st;
+    a.Ho = (d->H - 1) / st + 1; a.Wo = (d->W - 1) / st + 1;
+    // 16-byte aligned buffer loads of 8 channels, whole groups of 8 images, 31-bit byte offsets
+    if ((a.N & 7) || (a.C & 7) || (a.F & 7)) return PC_OK;
+    const int64_t xb = (int64_t)a.N * a.H * a.W * a.C * 2, db = (int64_t)a.N * a.Ho * a.Wo * a.F * 2;
+    if (xb >= ((int64_t)1 << 31) || db >= ((int64_t)1 << 31)) return PC_OK;
+    const int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
+    a.x_bytes = (uint32_t)xb; a.dy_bytes = (uint32_t)db;
+    int best_tr = 0, best_tc = 0, best_ng = 0;
+    double best_eff = -1.0;
+    const int ngroups = a.N / 8;
+    for (int tr = 1; tr <= WS_NSLOT; ++tr)
+        for (int tc = 1; tr * tc <= WS_NSLOT; ++tc) {
+            if ((tr > a.Ho && tr > 1) || (tc > a.Wo && tc > 1)) continue;
+            const int xs1 = ((tr - 1) * st + 3) * ((tc - 1) * st + 3);
+            int ngc = WS_NSLOT / (tr * tc);
+            if (ngc > ngroups) ngc = ngroups;
+            while (ngc > 1 && ngc * xs1 > WS_XSLOTS) --ngc;
+            if (ngc * xs1 > WS_XSLOTS) continue;
+            const int nr = (a.Ho + tr - 1) / tr, nc = (a.Wo + tc - 1) / tc;
+            const double cover = (double)a.Ho * a.Wo / ((double)nr * tr * nc * tc);
+            const double fill = (double)(ngc * tr * tc) / WS_NSLOT;
+            const double halo = (double)(tr * tc) / xs1;
+            const double eff = cover * fill * (0.75 + 0.25 * halo);
+            if (eff > best_eff) { best_eff = eff; best_tr = tr; best_tc = tc; best_ng = ngc; }
+        }
+    if (best_eff < 0.0) return PC_OK;
+    a.TR = best_tr; a.TC = best_tc; a.npos = a.TR * a.TC; a.ng = best_ng;
+    a.IR = (a.TR - 1) * st + 3; a.IC = (a.TC - 1) * st + 3;
+    a.xs_per_g = a.IR * a.IC;
+    a.xslots = (a.ng * a.xs_per_g + 7) / 8 * 8;
+    if (a.xslots > WS_XSLOTS) return PC_OK;
+    a.xplane = a.xslots * 16 + 16;
+    a.tiles_r = (a.Ho + a.TR - 1) / a.TR;
+    a.tiles_c = (a.Wo + a.TC - 1) / a.TC;
+    const int tiles_n = (ngroups + a.ng - 1) / a.ng;
+    const int64_t nkt = (int64_t)tiles_n * a.tiles_r * a.tiles_c;
+    if (nkt * (a.tiles_r > a.tiles_c ? a.tiles_r : a.tiles_c) >= ((int64_t)1 << 31)) return PC_OK;
+    a.n_ktiles = (int)nkt;
+    a.nnzk = (int32_t)nnzk;
+    auto magic = [](int dd) { return dd == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint64_t)dd) + 1); };
+    a.mg_tc = magic(a.tiles_c); a.mg_tr = magic(a.tiles_r);
+    for (int sl = 0; sl < WS_NSLOT; ++sl) {
+        const int ig = sl / a.npos, pos = sl % a.npos, py = pos / a.TC, px = pos % a.TC;
+        const bool ok = ig < a.ng;
+        a.dy_tab[sl] = ok ? ((uint32_t)ig << 16) | ((uint32_t)py << 8) | (uint32_t)px : 0xFFFFFFFFu;
+        a.xb_tab[sl] = ok ? (int16_t)(ig * a.xs_per_g + py * st * a.IC + px * st) : (int16_t)0;
+    }
+    for (int xs = 0; xs < WS_XSLOTS; ++xs) {
+        const int ig = xs / a.xs_per_g, rem = xs % a.xs_per_g;
+        a.x_tab[xs] = (ig < a.ng) ? ((uint32_t)ig << 16) | ((uint32_t)(rem / a.IC) << 8) | (uint32_t)(rem % a.IC) : 0xFFFFFFFFu;
+    }
+    a.buf_bytes = (WG_T * WS_DY_PLANE + 128 + WG_T * a.xplane + 128 + 255) / 256 * 256;
+    size_t lds = 2 * (size_t)a.buf_bytes;
+    if (lds < (size_t)9 * 32 * WG_T * sizeof(float)) lds = (size_t)9 * 32 * WG_T * sizeof(float);   // the epilogue parks one filter half
+    if (lds > WS_LDS_MAX) return PC_OK;
+    int ks = ctx->num_cu / (ft * ct);
+    if (ks > a.n_ktiles) ks = a.n_ktiles;
+    if (ks < 1) ks = 1;
+    a.ksplit = ks;
+    void *scr = nullptr;
+    if (ks > 1) {
+        pc_status s = pc_scratch(ctx, sizeof(float) * 4 * (size_t)ks * (size_t)nnzk, &scr);
+        if (s != PC_OK) return s;
+    }
+    static bool attr_done = false;
+    if (!attr_done) {
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS_MAX));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(pc_mfma_wgrad_ws_kernel, dim3((unsigned)ct, (unsigned)ft, (unsigned)ks), dim3(512), lds, ctx->stream,
+                       (const uint16_t *)x, (const uint16_t *)dy, a, pk->v, (float *)scr, dw);
+    *launched = true;
+    pc_status s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight (wave-specialised) launch");
+    if (s != PC_OK || ks == 1) return s;
+    return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, pk, dw);
+}
+
 pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
                              float *dw)
 {
@@ -1265,6 +1600,13 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     pc_status s = pc_packed_info(ctx, pk, &nnzk, nullptr);
     if (s != PC_OK) return s;
     if (nnzk == 0) return PC_OK;
+    if (ctx->plan_cfg != 10) {   // 10 forces the cooperative kernel
+        bool launched = false;
+        s = pc_mfma_bwd_weight_ws(ctx, d, pk, x, dy, dw, nnzk, &launched);
+        if (launched || s != PC_OK) return s;
+        if (ctx->plan_cfg == 11)
+            return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: the wave-specialised kernel does not take this layer");
+    }
     WgradMfmaArgs a;
     memset(&a, 0, sizeof(a));
     const int st = d->stride;

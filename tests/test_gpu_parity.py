@@ -151,6 +151,28 @@ def test_wave_specialised_kernel(B, ctx, oracle, cfg, shape):
         B.pc_set_plan_override(ctx, -1, 0)
 
 
+# Batches that are multiples of 8 (whole image groups), several pixel tiles per workgroup, strided and
+# tiny-image layers, partial channel tiles: both backward-weight kernels (10 = cooperative, 11 = wave-specialised).
+WGRAD_SHAPES = [
+    (8, 12, 20, 72, 96, 1),
+    (16, 9, 9, 40, 24, 2),
+    (24, 2, 2, 128, 64, 1),
+    (8, 4, 4, 192, 80, 1),
+    (16, 32, 32, 64, 128, 1),
+    (32, 8, 8, 64, 64, 1),
+]
+
+
+@pytest.mark.parametrize("cfg", [10, 11])
+@pytest.mark.parametrize("shape", WGRAD_SHAPES)
+def test_backward_weight_kernels(B, ctx, oracle, cfg, shape):
+    B.pc_set_plan_override(ctx, cfg, 0)
+    try:
+        run_case(B, ctx, oracle, shape, "bf16", 8, 0.3, B.PC_VARIANT_MFMA, ("wgrad", cfg))
+    finally:
+        B.pc_set_plan_override(ctx, -1, 0)
+
+
 @pytest.mark.parametrize("shape", MEDIUM_BF16)
 def test_medium_bf16_valu(B, ctx, oracle, shape):
     run_case(B, ctx, oracle, shape, "bf16", 12, 0.3, B.PC_VARIANT_VALU, "medium")
