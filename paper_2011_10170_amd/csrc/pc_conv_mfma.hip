@@ -46,11 +46,12 @@ struct MfmaArgs {
     int32_t tap_w[9];        // weight tap index of every list entry
     int32_t tap_off[9];      // LDS byte offset of every list entry
     // used by the wave-specialised kernel only
-    int32_t m_tiles, total_tiles;   // row tiles of the output channels; all tiles (row tile fastest)
+    int32_t m_tiles, total_tiles;   // row tiles of the output channels; all tiles
+    int32_t m_fast, fdiv;           // tile index = slow * fdiv + fast; m_fast: the row tile is the fast index (fdiv = m_tiles), else the pixel tile
     int32_t xbuf, red_off, nelem;   // bytes per staged input buffer, LDS offset of the reduction area, 16-byte elements per buffer
     uint32_t in_bytes, out_bytes;   // sizes of the input and output tensors (bounds of the buffer loads and stores)
     // divisions by these run as a multiply-high with floor(2^32 / d) + 1 (exact while dividend * d < 2^32)
-    uint32_t mg_IW, mg_IH, mg_TW, mg_THTW, mg_mt, mg_tx, mg_ty;
+    uint32_t mg_IW, mg_IH, mg_TW, mg_THTW, mg_fd, mg_tx, mg_ty;
 };
 
 // Depth of the A-fragment prefetch ring: the smallest divisor of the steps per chunk that keeps the loads
@@ -314,10 +315,11 @@ pc_mfma_splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int
 // q / d with mg = floor(2^32 / d) + 1 from the host (exact while q * d < 2^32); mg == 0 stands for d == 1
 __device__ __forceinline__ uint32_t pc_udiv(uint32_t q, uint32_t mg) { return mg ? __umulhi(q, mg) : q; }
 
-constexpr int pc_ring_depth(int nf)
+// Depth of the A-fragment ring: the largest divisor of the fragments per item that does not exceed cap
+constexpr int pc_ring_depth(int nf, int cap)
 {
     int best = 1;
-    for (int d = 1; d <= 10; ++d)
+    for (int d = 1; d <= cap; ++d)
         if (nf % d == 0) best = d;
     return best;
 }
@@ -331,7 +333,9 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     constexpr int KSW = KC / 64;          // k-steps per chunk, tap and MFMA wavefront
     constexpr int S = NTAPS * KSW;        // steps per item and wavefront
     constexpr int NF = S * A_T;           // A fragments per item and wavefront
-    constexpr int PFD = pc_ring_depth(NF);
+    // the ring has to cover an L2 round trip in MFMA time: narrow pixel tiles issue fewer MFMAs per fragment
+    // and have the registers for a whole item of fragments
+    constexpr int PFD = pc_ring_depth(NF, B_T >= 4 ? 10 : 18);
     constexpr int PITCH = 2 * KC + 16;
     constexpr int PARTS = KC / 8;
     constexpr int NT = A_T * B_T;
@@ -381,7 +385,8 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         int lk = 0, lch = 0;              // cursor of the next item to load
         uint32_t voff[KS_NV];             // byte offset of every element's pixel (+ its 16-byte part) in the tensor
         auto tile_offsets = [&](int k) {
-            uint32_t pt = pc_udiv((uint32_t)(vb + k * G), g.mg_mt);
+            const uint32_t tq = pc_udiv((uint32_t)(vb + k * G), g.mg_fd);
+            const uint32_t pt = g.m_fast ? tq : (uint32_t)(vb + k * G) - tq * g.fdiv;
             const uint32_t u = pc_udiv(pt, g.mg_tx);
             const int tx = (int)(pt - u * g.tiles_x);
             const uint32_t tnn = pc_udiv(u, g.mg_ty);
@@ -485,8 +490,9 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     int mt = 0, tn = 0, gy0 = 0, gx0 = 0;
     auto tile_of = [&](int k, int &mt_, int &tn_, int &gy0_, int &gx0_) {
         const uint32_t t = (uint32_t)(vb + k * G);
-        const uint32_t pt = pc_udiv(t, g.mg_mt);
-        mt_ = (int)(t - pt * g.m_tiles);
+        const uint32_t tq = pc_udiv(t, g.mg_fd), trm = t - tq * g.fdiv;
+        const uint32_t pt = g.m_fast ? tq : trm;
+        mt_ = (int)(g.m_fast ? trm : tq);
         const uint32_t u = pc_udiv(pt, g.mg_tx);
         const int tx = (int)(pt - u * g.tiles_x);
         const uint32_t tnn = pc_udiv(u, g.mg_ty);
@@ -786,7 +792,13 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *l
     const int64_t total = p_tiles * t.m_tiles;
     if (total > (1 << 30)) return false;
     t.total_tiles = (int)total;
-    int64_t dmax = t.m_tiles > t.tiles_x ? t.m_tiles : t.tiles_x;
+    // Tiles that follow each other run side by side, mostly on one XCD, and share what their common index
+    // reads through that XCD's L2: the input tile when the row tile runs fastest, the weights of a row
+    // tile when the pixel tile does. The bigger of the two operands is the one to share.
+    const int64_t w_bytes = (int64_t)g.out_CH * g.in_CH * 18, x_bytes = (int64_t)g.N * g.in_H * g.in_W * g.in_CH * 2;
+    t.m_fast = x_bytes >= w_bytes;
+    t.fdiv = t.m_fast ? t.m_tiles : (int)p_tiles;
+    int64_t dmax = t.fdiv > t.tiles_x ? t.fdiv : t.tiles_x;
     if (t.tiles_y > dmax) dmax = t.tiles_y;
     if (total * dmax >= ((int64_t)1 << 32)) return false;   // the multiply-high divisions of the tile index stay exact
     const int64_t in_bytes = (int64_t)g.N * g.in_H * g.in_W * g.in_CH * 2;
@@ -797,7 +809,7 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *l
     t.out_bytes = (uint32_t)out_bytes;
     auto magic = [](int d) { return d == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint64_t)d) + 1); };
     t.mg_IW = magic(t.IW); t.mg_IH = magic(t.IH); t.mg_TW = magic(t.TW); t.mg_THTW = magic(t.TH * t.TW);
-    t.mg_mt = magic(t.m_tiles); t.mg_tx = magic(t.tiles_x); t.mg_ty = magic(t.tiles_y);
+    t.mg_fd = magic(t.fdiv); t.mg_tx = magic(t.tiles_x); t.mg_ty = magic(t.tiles_y);
     t.nchunks = (g.in_CH + 63) / 64;
     t.cps = t.nchunks;
     const int64_t rounds = (total + num_cu - 1) / num_cu;
@@ -1268,6 +1280,11 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 // order. (Letting the last workgroup of a tile add them inside this kernel was slower: data crossing
 // the XCDs within a kernel needs device-scope write-through stores and read-through loads, and one
 // workgroup waits for those round trips in series.)
+#ifdef EXP_TIMING_WS
+#define WSTAMP(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && (threadIdx.x & 255) == 0) pc_wgrad_dbg[i] = wall_clock64(); } while (0)
+#else
+#define WSTAMP(i)
+#endif
 #define WS_NSLOT 16
 #define WS_NKS (WS_NSLOT / 2)
 #define WS_XSLOTS 48
@@ -1296,6 +1313,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c0 = blockIdx.x * WG_T, f0 = blockIdx.y * WG_T;
     const int nt = (a.n_ktiles - (int)blockIdx.z + a.ksplit - 1) / a.ksplit;   // pixel tiles of this workgroup
+    WSTAMP(0);
 
     // (compact slot, pattern mask) of the 8 kernels this thread writes in the epilogue
     uint32_t kinf[2][4];
@@ -1332,6 +1350,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 
     if (wave >= 4) {
         // ------------------------------------------------------------ loaders
+        WSTAMP(16);
         const int tl = threadIdx.x - 256;
         const int cg = tl & 7;
         const bool dy0 = wave < 6;                      // task 0 of wavefronts 4,5 is a dy task, of 6,7 an x task
@@ -1398,9 +1417,13 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             if (in1) pc_transpose8x8_store(B, lds + bufoff + dst1, a.xplane);
         };
         uint4 A0[8], B0[8], A1[8], B1[8];
+        WSTAMP(17);
         issue(A0, B0); issue(A1, B1);
+        WSTAMP(18);
         put(A0, B0, 0);
+        WSTAMP(19);
         __syncthreads();
+        WSTAMP(20);
         issue(A0, B0);
         // tile i: write tile i+1 (register set (i+1)&1) into buffer (i+1)&1, refill the set with tile i+3
         int i = 0;
@@ -1412,8 +1435,8 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             __builtin_amdgcn_sched_barrier(0);
         };
         for (; i + 2 <= nt; i += 2) {
-            put(A1, B1, a.buf_bytes); issue(A1, B1); sync();
-            put(A0, B0, 0);           issue(A0, B0); sync();
+            put(A1, B1, a.buf_bytes); if (i == 0) WSTAMP(21); issue(A1, B1); if (i == 0) WSTAMP(22); sync(); if (i == 0) WSTAMP(23);
+            put(A0, B0, 0);           if (i == 0) WSTAMP(24); issue(A0, B0); sync(); if (i == 0) WSTAMP(25);
         }
         if (i < nt) { put(A1, B1, a.buf_bytes); issue(A1, B1); sync(); }
 #pragma unroll
@@ -1448,7 +1471,9 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
         const int o_a1 = f_second * WS_DY_PLANE + (f_second >> 3) * 16 + g * 16;
         const int o_b = XT_OFF + cl * a.xplane + (cl >> 3) * 16;
 
+        WSTAMP(1);
         __syncthreads();
+        WSTAMP(2);
         for (int i = 0; i < nt; ++i) {
             const unsigned char *bufp = lds + (i & 1) * a.buf_bytes;
             const unsigned char *ar0 = bufp + o_a0, *ar1 = bufp + o_a1, *bc = bufp + o_b;
@@ -1479,7 +1504,9 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (i < 4) WSTAMP(3 + 2 * i);
             __syncthreads();
+            if (i < 4) WSTAMP(4 + 2 * i);
         }
         // epilogue, one filter half at a time: park the half's tiles as out[tap][filter][channel] (72 KiB)
         float *otw = reinterpret_cast<float *>(lds);
