@@ -302,8 +302,8 @@ pc_mfma_splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int
 //     fragments from LDS) well under their limits. At the end of a tile the four partial sums are
 //     added in a fixed order (wavefront 0..3) through LDS, every wavefront finishing and storing a
 //     quarter of the tile.
-// Both roles execute the same sequence of workgroup barriers: one after the first staged item, one
-// per item, and 2*ROUNDS-1 per finished tile.
+// Both roles execute the same sequence of workgroup barriers: one after the first staged item and one
+// per item.
 #ifdef EXP_TIMING_KS
 #define KSTAMP(i) do { if (blockIdx.x == 0 && (threadIdx.x & 255) == 0) pc_wgrad_dbg[i] = wall_clock64(); } while (0)
 #else
@@ -354,7 +354,6 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     const int ntile_blk = (g.total_tiles - vb + G - 1) / G;
     const int nch = g.nchunks;
     const int I = ntile_blk * nch;
-    const int TEB = 2 * ROUNDS - 1;       // barriers of the end-of-tile reduction
 
     if (wave >= 4) {
         // ------------------------------------------------------------ loaders
@@ -428,7 +427,6 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         __syncthreads();
         KSTAMP(20);
         issue(R2); issue(R0);
-        int chc = 0;                      // chunk index of item i inside its tile
         // item i: while the MFMA wavefronts work on buffer i&1, write item i+1 (register set (i+1)%3) to the
         // other buffer (past the last item: zeros, never read) and refill that set with item i+4
         auto lstep = [&](int i, uint4 (&R)[KS_NV]) {
@@ -441,10 +439,6 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 #endif
             __syncthreads();
             if (i < 4) KSTAMP(22 + 2 * i);
-            if (++chc == nch) {
-                chc = 0;
-                for (int b = 0; b < TEB; ++b) __syncthreads();
-            }
         };
         int i = 0;
         for (; i + 3 <= I; i += 3) {
@@ -584,32 +578,37 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (i < 4) KSTAMP(3 + 2 * i);
-        __syncthreads();
-        if (i < 4) KSTAMP(4 + 2 * i);
-
+        // End of a tile: every wavefront leaves the partial tiles it does not own in LDS before the item's
+        // barrier (the reduction area is separate from the input buffers and was last read a barrier ago),
+        // then adds the four partial sums of the tiles it owns, in the order of the wavefronts, and stores them.
+        float *red = reinterpret_cast<float *>(lds + g.red_off);
         if (ch == nch - 1) {
-            // sum the four partial tiles in the order of the wavefronts; wavefront o finishes tile r*4+o
-            float *red = reinterpret_cast<float *>(lds + g.red_off);
-            const int n = tn + o_ti, gy = gy0 + o_y, gx = gx0 + o_x;
-            const bool pix_ok = qo < npix && n < g.N && gy < g.GH && gx < g.GW;
-            const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
-            const uint32_t opix_off = pix_ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) : OOB_OUT;
 #pragma unroll
-            for (int r = 0; r < ROUNDS; ++r) {
+            for (int r = 0; r < ROUNDS; ++r)
 #pragma unroll
                 for (int o = 0; o < NOWN; ++o) {
                     if (o == w) continue;
                     const int tau = r * 4 + o;
                     const int wi = w < o ? w : w - 1;
-                    float *dst = red + ((o * 3 + wi) * 4) * 256 + lane * 4;
+                    float *dst = red + (((r * NOWN + o) * 3 + wi) * 4) * 256 + lane * 4;
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4)
                         *reinterpret_cast<float4 *>(dst + q4 * 256) =
                             make_float4(acc[tau / B_T][tau % B_T][q4 * 4 + 0], acc[tau / B_T][tau % B_T][q4 * 4 + 1],
                                         acc[tau / B_T][tau % B_T][q4 * 4 + 2], acc[tau / B_T][tau % B_T][q4 * 4 + 3]);
                 }
-                __syncthreads();
+        }
+        if (i < 4) KSTAMP(3 + 2 * i);
+        __syncthreads();
+        if (i < 4) KSTAMP(4 + 2 * i);
+
+        if (ch == nch - 1) {
+            const int n = tn + o_ti, gy = gy0 + o_y, gx = gx0 + o_x;
+            const bool pix_ok = qo < npix && n < g.N && gy < g.GH && gx < g.GW;
+            const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
+            const uint32_t opix_off = pix_ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) : OOB_OUT;
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
 #pragma unroll
                 for (int o = 0; o < NOWN; ++o) {
                     if (o != w) continue;
@@ -625,7 +624,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                                 p = make_float4(acc[tau / B_T][tau % B_T][q4 * 4 + 0], acc[tau / B_T][tau % B_T][q4 * 4 + 1],
                                                 acc[tau / B_T][tau % B_T][q4 * 4 + 2], acc[tau / B_T][tau % B_T][q4 * 4 + 3]);
                             else
-                                p = *reinterpret_cast<const float4 *>(red + ((o * 3 + (ws < o ? ws : ws - 1)) * 4 + q4) * 256 + lane * 4);
+                                p = *reinterpret_cast<const float4 *>(red + (((r * NOWN + o) * 3 + (ws < o ? ws : ws - 1)) * 4 + q4) * 256 + lane * 4);
                             if (ws == 0) s = p;
                             else { s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w; }
                         }
@@ -638,7 +637,6 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                         __builtin_amdgcn_raw_buffer_store_b64(pv, osrc, (int)((m < g.out_CH ? opix_off : OOB_OUT) + (uint32_t)(m * 2)), 0, 0);
                     }
                 }
-                if (r + 1 < ROUNDS) __syncthreads();
             }
 #pragma unroll
             for (int ii = 0; ii < A_T; ++ii)
@@ -771,7 +769,11 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *l
 {
     MfmaArgs t = g;
     plan_mfma_tiles(&t, 32 * bt, ext);
-    const int cap = 256 * KS_NV / 8;      // staged pixels: 8 16-byte parts per pixel and 64-channel chunk
+    const int nt = 2 * bt, nown = nt >= 4 ? 4 : nt;
+    const int red_bytes = (nt >= 4 ? nt / 4 : 1) * nown * 12288;
+    // staged pixels: 8 16-byte parts per pixel and 64-channel chunk, within the loader's registers and within LDS
+    int cap = 256 * KS_NV / 8;
+    if (cap > (KS_LDS_MAX - red_bytes - 32) / (2 * 144)) cap = (KS_LDS_MAX - red_bytes - 32) / (2 * 144);
     while (t.TI * t.IH * t.IW > cap) {
         if (t.TI > 1) --t.TI;
         else if (t.TH > 1) {
@@ -784,8 +786,7 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *l
     t.nelem = HP * 8;
     t.xbuf = HP * 144 + 16;   // one spare 16-byte slot for the loader threads without an element
     t.red_off = 2 * t.xbuf;
-    const int nt = 2 * bt, nown = nt >= 4 ? 4 : nt;
-    *lds_bytes = (size_t)t.red_off + (size_t)nown * 12288;
+    *lds_bytes = (size_t)t.red_off + (size_t)red_bytes;
     if (*lds_bytes > KS_LDS_MAX) return false;
     t.m_tiles = (g.out_CH + 63) / 64;
     const int64_t p_tiles = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x;
