@@ -1398,14 +1398,16 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
                   n0 + ig1 * 8 < a.N;
             const uint32_t vo0 = ok0 ? (uint32_t)(rel0 + (dy0 ? org_d : org_x)) : OOB;
             const uint32_t vo1 = ok1 ? (uint32_t)(rel1 + org_x) : OOB;
+            // images of the task's group that exist (the last group of a batch that is no multiple of 8 is short)
+            const int nv0 = a.N - (n0 + ig0 * 8), nv1 = a.N - (n0 + ig1 * 8);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const v4u32 t0 = __builtin_amdgcn_raw_buffer_load_b128(src0, (int)vo0, i * img0, 0);
+                const v4u32 t0 = __builtin_amdgcn_raw_buffer_load_b128(src0, (int)(i < nv0 ? vo0 : OOB), i * img0, 0);
                 A[i] = make_uint4(t0.x, t0.y, t0.z, t0.w);
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const v4u32 t1 = __builtin_amdgcn_raw_buffer_load_b128(xsrc, (int)vo1, i * x_img, 0);
+                const v4u32 t1 = __builtin_amdgcn_raw_buffer_load_b128(xsrc, (int)(i < nv1 ? vo1 : OOB), i * x_img, 0);
                 B[i] = make_uint4(t1.x, t1.y, t1.z, t1.w);
             }
             kt += a.ksplit;
@@ -1545,15 +1547,16 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     const int st = d->stride;
     a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.F = d->F; a.stride = st;
     a.Ho = (d->H - 1) / st + 1; a.Wo = (d->W - 1) / st + 1;
-    // 16-byte aligned buffer loads of 8 channels, whole groups of 8 images, 31-bit byte offsets
-    if ((a.N & 7) || (a.C & 7) || (a.F & 7)) return PC_OK;
+    // 16-byte buffer loads of 8 channels: channel counts that are no multiple of 8 would make the last group of
+    // the tensor's last pixel reach past its end (the cooperative kernel reads those layers by element)
+    if ((a.C & 7) || (a.F & 7)) return PC_OK;
     const int64_t xb = (int64_t)a.N * a.H * a.W * a.C * 2, db = (int64_t)a.N * a.Ho * a.Wo * a.F * 2;
     if (xb >= ((int64_t)1 << 31) || db >= ((int64_t)1 << 31)) return PC_OK;
     const int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
     a.x_bytes = (uint32_t)xb; a.dy_bytes = (uint32_t)db;
     int best_tr = 0, best_tc = 0, best_ng = 0;
     double best_eff = -1.0;
-    const int ngroups = a.N / 8;
+    const int ngroups = (a.N + 7) / 8;
     for (int tr = 1; tr <= WS_NSLOT; ++tr)
         for (int tc = 1; tr * tc <= WS_NSLOT; ++tc) {
             if ((tr > a.Ho && tr > 1) || (tc > a.Wo && tc > 1)) continue;

@@ -151,8 +151,9 @@ def test_wave_specialised_kernel(B, ctx, oracle, cfg, shape):
         B.pc_set_plan_override(ctx, -1, 0)
 
 
-# Batches that are multiples of 8 (whole image groups), several pixel tiles per workgroup, strided and
-# tiny-image layers, partial channel tiles: both backward-weight kernels (10 = cooperative, 11 = wave-specialised).
+# Channel counts that are multiples of 8 (what the wave-specialised kernel takes): several pixel tiles per
+# workgroup, strided and tiny-image layers, partial channel tiles, short image groups; both backward-weight
+# kernels (10 = cooperative, 11 = wave-specialised).
 WGRAD_SHAPES = [
     (8, 12, 20, 72, 96, 1),
     (16, 9, 9, 40, 24, 2),
@@ -160,6 +161,8 @@ WGRAD_SHAPES = [
     (8, 4, 4, 192, 80, 1),
     (16, 32, 32, 64, 128, 1),
     (32, 8, 8, 64, 64, 1),
+    (12, 6, 10, 16, 24, 1),     # the last image group is short
+    (3, 5, 5, 8, 8, 2),
 ]
 
 
