@@ -209,17 +209,22 @@ def main() -> int:
     # HBM bytes per launch of that kernel from the committed rocprofv3 counter summary (None when absent)
     traffic = None
     prof = os.path.join(ROOT, "profiles", "%s_hbm_counters.md" % wl.name)
-    kname = {"mfma_bwd_weight": "pc_mfma_wgrad_kernel", "mfma_fwd": "pc_mfma_conv_kernel",
-             "mfma_bwd_data": "pc_mfma_conv_kernel", "valu_fwd": "pc_gather_conv_kernel",
-             "valu_bwd_data": "pc_gather_conv_kernel", "valu_bwd_weight": "pc_wgrad_valu_kernel"}.get(dk)
-    if kname and os.path.exists(prof):
+    # kernels one library call of that kind launches: the first entry is the kernel that does the work (its
+    # dispatches count the calls), the others are helpers whose bytes belong to the same call
+    knames = {"mfma_bwd_weight": ("pc_mfma_wgrad", "pc_wgrad_reduce_kernel"),
+              "mfma_fwd": ("pc_mfma_conv", "pc_mfma_splitk_reduce_kernel"),
+              "mfma_bwd_data": ("pc_mfma_conv", "pc_mfma_splitk_reduce_kernel"),
+              "valu_fwd": ("pc_gather_conv_kernel",), "valu_bwd_data": ("pc_gather_conv_kernel",),
+              "valu_bwd_weight": ("pc_wgrad_valu_kernel", "pc_wgrad_reduce_kernel")}.get(dk)
+    if knames and os.path.exists(prof):
         tot_b, tot_n = 0.0, 0
         for line in open(prof):
             cells = [c.strip() for c in line.split("|")]
-            if len(cells) > 5 and cells[1].startswith(kname):
+            if len(cells) > 5 and any(cells[1].startswith(k) for k in knames):
                 n_disp = int(cells[2])
                 tot_b += float(cells[5].split("=")[-1]) * n_disp
-                tot_n += n_disp
+                if cells[1].startswith(knames[0]):
+                    tot_n += n_disp
         if tot_n:
             traffic = {"hbm_mib_per_launch": round(tot_b / tot_n, 2), "source": "profiles/%s_hbm_counters.md" % wl.name,
                        "algorithmic_mib_per_launch": round(dv["bytes"] / dv["n"] / (1 << 20), 2)}
