@@ -1312,8 +1312,26 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     constexpr int XT_OFF = WG_T * WS_DY_PLANE + 128;   // xT planes inside a buffer
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c0 = blockIdx.x * WG_T, f0 = blockIdx.y * WG_T;
-    const int nt = (a.n_ktiles - (int)blockIdx.z + a.ksplit - 1) / a.ksplit;   // pixel tiles of this workgroup
+    // Workgroups go to the XCDs round-robin by their linear index. The index is re-read so that the workgroups of
+    // one XCD share as few pixel splits as possible: each XCD's L2 then fetches its own slice of x and dy once,
+    // instead of every XCD fetching all of both.
+    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    {
+        const int T = gridDim.x * gridDim.y, ks = a.ksplit;
+        const int lin = bx + gridDim.x * (by + gridDim.y * bz);
+        const int xcd = lin & 7, r = lin >> 3;
+        int tile = -1;
+        if ((ks & 7) == 0) {                           // an XCD owns ks/8 splits, all tiles of each
+            tile = r % T;
+            bz = (r / T) * 8 + xcd;
+        } else if (ks < 8 && (8 % ks) == 0 && (T % (8 / ks)) == 0) {   // 8/ks XCDs share a split
+            bz = xcd % ks;
+            tile = r * (8 / ks) + xcd / ks;
+        }
+        if (tile >= 0) { bx = tile % (int)gridDim.x; by = tile / (int)gridDim.x; }
+    }
+    const int c0 = bx * WG_T, f0 = by * WG_T;
+    const int nt = (a.n_ktiles - bz + a.ksplit - 1) / a.ksplit;   // pixel tiles of this workgroup
     WSTAMP(0);
 
     // (compact slot, pattern mask) of the 8 kernels this thread writes in the epilogue
@@ -1326,7 +1344,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             const int f = f0 + fh * 32 + (p >> 6), c = c0 + (p & 63);
             kinf[fh][k] = (f < a.F && c < a.C) ? v.kinfo[(int64_t)f * a.C + c] : 0xFFFFFFFFu;
         }
-    float *pout = a.ksplit > 1 ? partial + (int64_t)blockIdx.z * a.nnzk * 4 : dw;
+    float *pout = a.ksplit > 1 ? partial + (int64_t)bz * a.nnzk * 4 : dw;
     const float *ot = reinterpret_cast<const float *>(lds);
     // gathers the 4 kept taps of every kept kernel of filter half fh from the parked tile
     auto gather = [&](int fh) {
@@ -1379,7 +1397,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
         const int dst0 = (dy0 ? 0 : XT_OFF) + (cg * 8) * pitch0 + cg * 16 + (slot0 << 4);
         const int dst1 = XT_OFF + (cg * 8) * a.xplane + cg * 16 + (slot1 << 4);
 
-        int kt = blockIdx.z;                             // next pixel tile to request
+        int kt = bz;                                     // next pixel tile to request
         auto issue = [&](uint4 (&A)[8], uint4 (&B)[8]) {
             const bool live = kt < a.n_ktiles;
             const uint32_t u = pc_udiv((uint32_t)kt, a.mg_tc);
