@@ -309,7 +309,8 @@ pc_mfma_splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int
 #else
 #define KSTAMP(i)
 #endif
-#define KS_NV 8          // 16-byte elements staged per loader thread and item (256 loader threads)
+#define KS_NV 8          // 16-byte elements staged per loader thread and item (256 loader threads), reduction split
+#define KS_NV1 12        // the same without the reduction split (512-pixel tiles of 32 channels)
 #define KS_DEPTH 3       // items in flight in the loader's registers
 
 // q / d with mg = floor(2^32 / d) + 1 from the host (exact while q * d < 2^32); mg == 0 stands for d == 1
@@ -324,13 +325,15 @@ constexpr int pc_ring_depth(int nf, int cap)
     return best;
 }
 
-template <int A_T, int B_T, int NTAPS, int KC>
+template <int A_T, int B_T, int NTAPS, int KC, int KSP>
 __global__ void __launch_bounds__(512, 1)
 pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const uint16_t *__restrict__ wz, MfmaArgs g)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int KSC = KC / 16;          // k-steps per chunk
-    constexpr int KSW = KC / 64;          // k-steps per chunk, tap and MFMA wavefront
+    static_assert(KSP == 4 || KSP == 1, "the MFMA wavefronts split the reduction four ways or not at all");
+    constexpr int KSW = KC / (16 * KSP);  // k-steps per chunk, tap and MFMA wavefront
+    constexpr int NV = KSP == 4 ? KS_NV : KS_NV1;   // 16-byte elements staged per loader thread and item
     constexpr int S = NTAPS * KSW;        // steps per item and wavefront
     constexpr int NF = S * A_T;           // A fragments per item and wavefront
     // the ring has to cover an L2 round trip in MFMA time: narrow pixel tiles issue fewer MFMAs per fragment
@@ -369,9 +372,9 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(in), 0, g.in_bytes, 0x00020000);
         constexpr uint32_t OOB = 0x80000000u;   // past any tensor this kernel accepts, and no wrap-around with the chunk offset
         const bool part_in_last = (nch - 1) * KC + part * 8 < g.in_CH;   // this thread's channels exist in the last chunk
-        int pk[KS_NV], loff[KS_NV];
+        int pk[NV], loff[NV];
 #pragma unroll
-        for (int v = 0; v < KS_NV; ++v) {
+        for (int v = 0; v < NV; ++v) {
             const int e = tl + 256 * v;
             const uint32_t q = (uint32_t)e / PARTS;
             const uint32_t t2 = pc_udiv(q, g.mg_IW);
@@ -382,7 +385,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
             loff[v] = e < g.nelem ? (int)q * PITCH + part * 16 : g.xbuf - 16;
         }
         int lk = 0, lch = 0;              // cursor of the next item to load
-        uint32_t voff[KS_NV];             // byte offset of every element's pixel (+ its 16-byte part) in the tensor
+        uint32_t voff[NV];             // byte offset of every element's pixel (+ its 16-byte part) in the tensor
         auto tile_offsets = [&](int k) {
             const uint32_t tq = pc_udiv((uint32_t)(vb + k * G), g.mg_fd);
             const uint32_t pt = g.m_fast ? tq : (uint32_t)(vb + k * G) - tq * g.fdiv;
@@ -394,18 +397,18 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
             const int ly0 = ty * g.TH * g.iscale + g.ioff_y;
             const int lx0 = tx * g.TW * g.iscale + g.ioff_x;
 #pragma unroll
-            for (int v = 0; v < KS_NV; ++v) {
+            for (int v = 0; v < NV; ++v) {
                 const int n = ltn + (pk[v] >> 20), y = ly0 + ((pk[v] >> 10) & 1023), x = lx0 + (pk[v] & 1023);
                 const bool ok = pk[v] >= 0 && n < g.N && (unsigned)y < (unsigned)g.in_H && (unsigned)x < (unsigned)g.in_W;
                 voff[v] = ok ? (uint32_t)((n * g.in_H + y) * g.in_W + x) * (uint32_t)(g.in_CH * 2) + part * 16 : OOB;
             }
         };
         tile_offsets(0);
-        auto issue = [&](uint4 (&R)[KS_NV]) {
+        auto issue = [&](uint4 (&R)[NV]) {
             const int so = lch * (KC * 2);
             const bool cut = (lch == nch - 1 && !part_in_last) || lk >= ntile_blk;
 #pragma unroll
-            for (int v = 0; v < KS_NV; ++v) {
+            for (int v = 0; v < NV; ++v) {
                 const v4u32 val = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(cut ? OOB : voff[v]), so, 0);
                 R[v] = make_uint4(val.x, val.y, val.z, val.w);
             }
@@ -414,11 +417,11 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                 if (++lk < ntile_blk) tile_offsets(lk);
             }
         };
-        auto put = [&](const uint4 (&R)[KS_NV], int bufoff) {
+        auto put = [&](const uint4 (&R)[NV], int bufoff) {
 #pragma unroll
-            for (int v = 0; v < KS_NV; ++v) *reinterpret_cast<uint4 *>(lds + bufoff + loff[v]) = R[v];
+            for (int v = 0; v < NV; ++v) *reinterpret_cast<uint4 *>(lds + bufoff + loff[v]) = R[v];
         };
-        uint4 R0[KS_NV], R1[KS_NV], R2[KS_NV];
+        uint4 R0[NV], R1[NV], R2[NV];
         KSTAMP(17);
         issue(R0); issue(R1);
         KSTAMP(18);
@@ -429,7 +432,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         issue(R2); issue(R0);
         // item i: while the MFMA wavefronts work on buffer i&1, write item i+1 (register set (i+1)%3) to the
         // other buffer (past the last item: zeros, never read) and refill that set with item i+4
-        auto lstep = [&](int i, uint4 (&R)[KS_NV]) {
+        auto lstep = [&](int i, uint4 (&R)[NV]) {
 #ifndef EXP_KS_NO_LOADER
             put(R, ((i + 1) & 1) * g.xbuf);
 #endif
@@ -459,12 +462,14 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     int base[B_T];
 #pragma unroll
     for (int j = 0; j < B_T; ++j) {
-        int q = j * 32 + (lane & 31);
+        // reduction split: every wavefront covers all pixels and its own k-steps; otherwise its own pixels
+        int q = ((KSP == 1 ? w * B_T : 0) + j) * 32 + (lane & 31);
         if (q >= npix) q = npix - 1;
         const int ti = (int)pc_udiv((uint32_t)q, g.mg_THTW);
         const int rem = q - ti * g.TH * g.TW;
         const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
-        base[j] = ((ti * g.IH + y * g.lstep) * g.IW + x * g.lstep) * PITCH + (lane >> 5) * 16 + w * (KSW * 32);
+        base[j] = ((ti * g.IH + y * g.lstep) * g.IW + x * g.lstep) * PITCH + (lane >> 5) * 16 +
+                  (KSP == 4 ? w * (KSW * 32) : 0);
     }
     // the pixel sub-tile this wavefront finishes and stores
     const int jo = w % B_T;
@@ -496,7 +501,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         gx0_ = tx * g.TW;
     };
     auto a_base = [&](int mt_, int ch_) -> const uint16_t * {
-        return wz + ((int64_t)(mt_ * A_T * 9) * g.KS + ch_ * KSC + w * KSW) * 512 + lane * 8;
+        return wz + ((int64_t)(mt_ * A_T * 9) * g.KS + ch_ * KSC + (KSP == 4 ? w * KSW : 0)) * 512 + lane * 8;
     };
     tile_of(0, mt, tn, gy0, gx0);
     int k = 0, ch = 0;
@@ -582,7 +587,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         // barrier (the reduction area is separate from the input buffers and was last read a barrier ago),
         // then adds the four partial sums of the tiles it owns, in the order of the wavefronts, and stores them.
         float *red = reinterpret_cast<float *>(lds + g.red_off);
-        if (ch == nch - 1) {
+        if (KSP == 4 && ch == nch - 1) {
 #pragma unroll
             for (int r = 0; r < ROUNDS; ++r)
 #pragma unroll
@@ -602,7 +607,44 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         __syncthreads();
         if (i < 4) KSTAMP(4 + 2 * i);
 
-        if (ch == nch - 1) {
+        if (KSP == 1 && ch == nch - 1) {
+            // Every wavefront stores its own 32*B_T pixels, 64 at a time through a private LDS area (pixel-major
+            // bf16 rows): read back, 8 consecutive lanes hold the 128 contiguous bytes of one pixel's 64 channels
+            // and the stores are whole 16-byte pieces of full lines instead of scattered 8-byte ones.
+            unsigned char *stg = lds + g.red_off + w * (64 * 144);
+#pragma unroll
+            for (int half = 0; half < B_T / 2; ++half) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const int j = half * 2 + jj;
+                            uint2 pkd;
+                            pkd.x = pc_pack_bf16x2(acc[ii][j][q4 * 4 + 0], acc[ii][j][q4 * 4 + 1]);
+                            pkd.y = pc_pack_bf16x2(acc[ii][j][q4 * 4 + 2], acc[ii][j][q4 * 4 + 3]);
+                            *reinterpret_cast<uint2 *>(stg + (jj * 32 + (lane & 31)) * 144 + (ii * 32 + q4 * 8 + (lane >> 5) * 4) * 2) = pkd;
+                        }
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    const int px = it * 8 + (lane >> 3), c16 = lane & 7;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + px * 144 + c16 * 16);
+                    const int q = (w * B_T + half * 2) * 32 + px;
+                    const int ti = (int)pc_udiv((uint32_t)q, g.mg_THTW);
+                    const int rem = q - ti * g.TH * g.TW;
+                    const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
+                    const int n = tn + ti, gy = gy0 + y, gx = gx0 + x;
+                    const int m = mt * (32 * A_T) + c16 * 8;
+                    const bool ok = q < npix && n < g.N && gy < g.GH && gx < g.GW && m < g.out_CH;
+                    const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
+                    const uint32_t off = ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) + (uint32_t)(m * 2) : OOB_OUT;
+                    const v4u32 pv = {v.x, v.y, v.z, v.w};
+                    __builtin_amdgcn_raw_buffer_store_b128(pv, osrc, (int)off, 0, 0);
+                }
+            }
+        }
+        if (KSP == 4 && ch == nch - 1) {
             const int n = tn + o_ti, gy = gy0 + o_y, gx = gx0 + o_x;
             const bool pix_ok = qo < npix && n < g.N && gy < g.GH && gx < g.GW;
             const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
@@ -638,6 +680,8 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                     }
                 }
             }
+        }
+        if (ch == nch - 1) {
 #pragma unroll
             for (int ii = 0; ii < A_T; ++ii)
 #pragma unroll
@@ -749,31 +793,34 @@ static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, int ntaps, const u
 // ---- wave-specialised kernel: plan and launch (9-tap launches whose channel count is a multiple of 8)
 #define KS_LDS_MAX (160 * 1024)
 
-template <int B_T>
+template <int B_T, int KC, int KSP>
 static hipError_t launch_ks(hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out, const uint16_t *wz,
                             const MfmaArgs &g)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<2, B_T, 9, 64>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<2, B_T, 9, KC, KSP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, KS_LDS_MAX);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<2, B_T, 9, 64>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
+    hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<2, B_T, 9, KC, KSP>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
     return hipGetLastError();
 }
 
-// Fills the tile plan for pixel tiles of 32*bt pixels; false when the staged tile does not fit.
-static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *lds_bytes, double *est, int num_cu)
+// Fills the tile plan; false when the staged tile does not fit. ksp = 4: the MFMA wavefronts split the
+// reduction of a tile of 32*bt pixels (64-channel chunks); ksp = 1: they split a tile of 128*bt pixels
+// (32-channel chunks, no reduction across wavefronts).
+static bool plan_ks(const MfmaArgs &g, int ext, int bt, int ksp, MfmaArgs *out, size_t *lds_bytes, double *est, int num_cu)
 {
+    const int kc = ksp == 4 ? 64 : 32, pitch = 2 * kc + 16, parts = kc / 8, nv = ksp == 4 ? KS_NV : KS_NV1;
     MfmaArgs t = g;
-    plan_mfma_tiles(&t, 32 * bt, ext);
+    plan_mfma_tiles(&t, (ksp == 4 ? 32 : 128) * bt, ext);
     const int nt = 2 * bt, nown = nt >= 4 ? 4 : nt;
-    const int red_bytes = (nt >= 4 ? nt / 4 : 1) * nown * 12288;
-    // staged pixels: 8 16-byte parts per pixel and 64-channel chunk, within the loader's registers and within LDS
-    int cap = 256 * KS_NV / 8;
-    if (cap > (KS_LDS_MAX - red_bytes - 32) / (2 * 144)) cap = (KS_LDS_MAX - red_bytes - 32) / (2 * 144);
+    const int red_bytes = ksp == 4 ? (nt >= 4 ? nt / 4 : 1) * nown * 12288 : 4 * 64 * 144;   // reduction area / store staging
+    // staged pixels: within the loader's registers (nv 16-byte elements per thread) and within LDS
+    int cap = 256 * nv / parts;
+    if (cap > (KS_LDS_MAX - red_bytes - 32) / (2 * pitch)) cap = (KS_LDS_MAX - red_bytes - 32) / (2 * pitch);
     while (t.TI * t.IH * t.IW > cap) {
         if (t.TI > 1) --t.TI;
         else if (t.TH > 1) {
@@ -783,8 +830,8 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *l
         } else return false;
     }
     const int HP = t.TI * t.IH * t.IW;
-    t.nelem = HP * 8;
-    t.xbuf = HP * 144 + 16;   // one spare 16-byte slot for the loader threads without an element
+    t.nelem = HP * parts;
+    t.xbuf = HP * pitch + 16;   // one spare 16-byte slot for the loader threads without an element
     t.red_off = 2 * t.xbuf;
     *lds_bytes = (size_t)t.red_off + (size_t)red_bytes;
     if (*lds_bytes > KS_LDS_MAX) return false;
@@ -806,15 +853,18 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, MfmaArgs *out, size_t *l
     if (in_bytes >= ((int64_t)1 << 31)) return false;   // 32-bit buffer offsets, with 2^31 as the out-of-range marker
     t.in_bytes = (uint32_t)in_bytes;
     const int64_t out_bytes = (int64_t)g.N * g.out_H * g.out_W * g.out_CH * 2;
-    if (out_bytes >= ((int64_t)1 << 31) || (g.out_CH & 3)) return false;   // 8-byte buffer stores of 4 channels
+    if (out_bytes >= ((int64_t)1 << 31) || (g.out_CH & (ksp == 4 ? 3 : 7))) return false;   // 8- or 16-byte buffer stores
     t.out_bytes = (uint32_t)out_bytes;
     auto magic = [](int d) { return d == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint64_t)d) + 1); };
     t.mg_IW = magic(t.IW); t.mg_IH = magic(t.IH); t.mg_TW = magic(t.TW); t.mg_THTW = magic(t.TH * t.TW);
     t.mg_fd = magic(t.fdiv); t.mg_tx = magic(t.tiles_x); t.mg_ty = magic(t.tiles_y);
-    t.nchunks = (g.in_CH + 63) / 64;
+    t.nchunks = (g.in_CH + kc - 1) / kc;
     t.cps = t.nchunks;
+    // cycles of one workgroup: tiles per workgroup x (MFMAs of a tile at 32 cycles each per wavefront + the tile's
+    // fixed cost: the reduction across wavefronts, or just the store)
     const int64_t rounds = (total + num_cu - 1) / num_cu;
-    *est = (double)rounds * ((double)t.nchunks * 576.0 * bt + 2500.0);
+    if (ksp == 4) *est = (double)rounds * ((double)t.nchunks * 576.0 * bt + 2500.0);
+    else *est = (double)rounds * ((double)t.nchunks * 1152.0 * bt + 1200.0);
     *out = t;
     return true;
 }
@@ -824,31 +874,34 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int
                                   uint16_t *out, const uint16_t *wz, bool *launched)
 {
     *launched = false;
-    static const int kBt[3] = {4, 2, 1};
+    // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
+    static const int kBt[4] = {4, 2, 1, 4}, kKsp[4] = {4, 4, 4, 1}, kCode[4] = {7, 8, 9, 13};
     MfmaArgs best;
     size_t best_lds = 0;
     double best_est = 0.0;
-    int best_bt = 0;
-    for (int k = 0; k < 3; ++k) {
-        if (pcfg >= 7 && pcfg - 7 != k) continue;
+    int best_k = -1;
+    for (int k = 0; k < 4; ++k) {
+        if (pcfg >= 7 && pcfg != kCode[k]) continue;
         MfmaArgs t;
         size_t lds;
         double est;
-        if (!plan_ks(g0, ext, kBt[k], &t, &lds, &est, ctx->num_cu)) continue;
-        if (!best_bt || est < best_est) { best = t; best_lds = lds; best_est = est; best_bt = kBt[k]; }
+        if (!plan_ks(g0, ext, kBt[k], kKsp[k], &t, &lds, &est, ctx->num_cu)) continue;
+        if (best_k < 0 || est < best_est) { best = t; best_lds = lds; best_est = est; best_k = k; }
     }
-    if (!best_bt) return PC_OK;
+    if (best_k < 0) return PC_OK;
     // The end-of-tile reduction costs about as much as one 64-channel chunk of MFMA work: with one or two
     // chunks per tile the cooperative kernel's output split is faster, unless every workgroup has a single tile.
-    if (pcfg < 0 && (best.nchunks < 2 || (best.nchunks == 2 && best.total_tiles > ctx->num_cu))) return PC_OK;
+    if (pcfg < 0 && kKsp[best_k] == 4 && (best.nchunks < 2 || (best.nchunks == 2 && best.total_tiles > ctx->num_cu))) return PC_OK;
     MfmaArgs g = best;
-    for (int t = 0; t < 9; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * 144;
+    const int pitch = kKsp[best_k] == 4 ? 144 : 80;
+    for (int t = 0; t < 9; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * pitch;
     const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;
     hipError_t e;
-    switch (best_bt) {
-    case 4: e = launch_ks<4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 2: e = launch_ks<2>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    default: e = launch_ks<1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    switch (best_k) {
+    case 0: e = launch_ks<4, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 1: e = launch_ks<2, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 2: e = launch_ks<1, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
     }
     *launched = true;
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");
@@ -858,7 +911,7 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int
 static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, const int *tr, const int *tc,
                                const uint16_t *in, uint16_t *out, const uint16_t *wz)
 {
-    int plan_cfg = ctx->plan_cfg >= 10 ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
+    int plan_cfg = (ctx->plan_cfg >= 10 && ctx->plan_cfg != 13) ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
     if (ntaps == 9 && (g.in_CH & 7) == 0 && g.in_CH >= 32 && (plan_cfg < 0 || plan_cfg >= 7) && ctx->plan_split == 0) {
         bool launched = false;
         pc_status s = run_mfma_conv_ks(ctx, plan_cfg, g, ext, tr, tc, in, out, wz, &launched);

@@ -139,11 +139,11 @@ WAVE_SPEC = [
 ]
 
 
-@pytest.mark.parametrize("cfg", [7, 8, 9])
+@pytest.mark.parametrize("cfg", [7, 8, 9, 13])
 @pytest.mark.parametrize("shape", WAVE_SPEC)
 def test_wave_specialised_kernel(B, ctx, oracle, cfg, shape):
-    """The persistent kernel with loader wavefronts and a reduction split over four MFMA wavefronts, for
-    each of its pixel-tile widths (128, 64 and 32 pixels)."""
+    """The persistent kernel with loader wavefronts: the reduction split over four MFMA wavefronts for each of
+    its pixel-tile widths (7, 8, 9: 128, 64 and 32 pixels), and the pixel split (13: 512-pixel tiles)."""
     B.pc_set_plan_override(ctx, cfg, 0)
     try:
         run_case(B, ctx, oracle, shape, "bf16", 8, 0.3, B.PC_VARIANT_MFMA, ("wave_spec", cfg))
