@@ -1346,7 +1346,8 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 #define WS_LDS_MAX (160 * 1024 - 256)   // dynamic part; the kernel has a few bytes of static LDS too
 
 struct WgradWsArgs {
-    int32_t N, H, W, C, F, Ho, Wo, stride;
+    int32_t N, H, W, C, F, Ho, Wo, stride;   // C: channels of the x tensor the kernel reads (padded to a multiple of 8)
+    int32_t Creal;                           // channels of the layer (row length of the kinfo table)
     int32_t TR, TC, npos, ng, IR, IC, xs_per_g, xslots, xplane;
     int32_t tiles_r, tiles_c, n_ktiles, ksplit, nnzk;
     int32_t buf_bytes;                     // one LDS buffer: dyT planes, then xT planes
@@ -1395,7 +1396,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
         for (int k = 0; k < 4; ++k) {
             const int p = threadIdx.x + 512 * k;
             const int f = f0 + fh * 32 + (p >> 6), c = c0 + (p & 63);
-            kinf[fh][k] = (f < a.F && c < a.C) ? v.kinfo[(int64_t)f * a.C + c] : 0xFFFFFFFFu;
+            kinf[fh][k] = (f < a.F && c < a.Creal) ? v.kinfo[(int64_t)f * a.Creal + c] : 0xFFFFFFFFu;
         }
     float *pout = a.ksplit > 1 ? partial + (int64_t)bz * a.nnzk * 4 : dw;
     const float *ot = reinterpret_cast<const float *>(lds);
@@ -1607,6 +1608,22 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 
 }
 
+// xp[pixel][0..Cp) = x[pixel][0..C), zero above: a copy whose pixel rows are 16-byte aligned groups of 8 channels
+__global__ void __launch_bounds__(256)
+pc_pad_channels_kernel(const uint16_t *__restrict__ x, uint4 *__restrict__ xp, int64_t npix, int C, int Cp)
+{
+    const int gpp = Cp / 8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= npix * gpp) return;
+    const int64_t p = i / gpp;
+    const int c0 = (int)(i - p * gpp) * 8;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (c0 + e < C) w[e >> 1] |= (uint32_t)x[p * C + c0 + e] << ((e & 1) * 16);
+    xp[i] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 // Wave-specialised backward-weight: plan and launch. *launched stays false when the layer is outside what
 // that kernel takes (the caller then uses the cooperative kernel).
 static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
@@ -1616,11 +1633,13 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     WgradWsArgs a;
     memset(&a, 0, sizeof(a));
     const int st = d->stride;
-    a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.F = d->F; a.stride = st;
+    a.N = d->N; a.H = d->H; a.W = d->W; a.C = (d->C + 7) / 8 * 8; a.Creal = d->C; a.F = d->F; a.stride = st;
     a.Ho = (d->H - 1) / st + 1; a.Wo = (d->W - 1) / st + 1;
-    // 16-byte buffer loads of 8 channels: channel counts that are no multiple of 8 would make the last group of
-    // the tensor's last pixel reach past its end (the cooperative kernel reads those layers by element)
-    if ((a.C & 7) || (a.F & 7)) return PC_OK;
+    // 16-byte buffer loads of 8 channels. An input whose channel count is no multiple of 8 (the first layer's 3)
+    // is first copied to rows padded to 8 channels; an output-gradient with such a filter count is left to the
+    // cooperative kernel, which reads by element.
+    if (a.F & 7) return PC_OK;
+    const bool pad_x = a.C != a.Creal;
     const int64_t xb = (int64_t)a.N * a.H * a.W * a.C * 2, db = (int64_t)a.N * a.Ho * a.Wo * a.F * 2;
     if (xb >= ((int64_t)1 << 31) || db >= ((int64_t)1 << 31)) return PC_OK;
     const int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
@@ -1678,9 +1697,17 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     if (ks < 1) ks = 1;
     a.ksplit = ks;
     void *scr = nullptr;
-    if (ks > 1) {
-        pc_status s = pc_scratch(ctx, sizeof(float) * 4 * (size_t)ks * (size_t)nnzk, &scr);
+    const size_t part_bytes = ks > 1 ? (sizeof(float) * 4 * (size_t)ks * (size_t)nnzk + 255) / 256 * 256 : 0;
+    if (part_bytes || pad_x) {
+        pc_status s = pc_scratch(ctx, part_bytes + (pad_x ? (size_t)xb : 0), &scr);
         if (s != PC_OK) return s;
+    }
+    if (pad_x) {
+        uint4 *xp = reinterpret_cast<uint4 *>(static_cast<unsigned char *>(scr) + part_bytes);
+        const int64_t npix = (int64_t)a.N * a.H * a.W, n16 = npix * (a.C / 8);
+        hipLaunchKernelGGL(pc_pad_channels_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, ctx->stream,
+                           (const uint16_t *)x, xp, npix, a.Creal, a.C);
+        x = xp;
     }
     static bool attr_done = false;
     if (!attr_done) {

@@ -151,7 +151,7 @@ def test_wave_specialised_kernel(B, ctx, oracle, cfg, shape):
         B.pc_set_plan_override(ctx, -1, 0)
 
 
-# Channel counts that are multiples of 8 (what the wave-specialised kernel takes): several pixel tiles per
+# Filter counts that are multiples of 8 (what the wave-specialised kernel takes): several pixel tiles per
 # workgroup, strided and tiny-image layers, partial channel tiles, short image groups; both backward-weight
 # kernels (10 = cooperative, 11 = wave-specialised).
 WGRAD_SHAPES = [
@@ -163,6 +163,8 @@ WGRAD_SHAPES = [
     (32, 8, 8, 64, 64, 1),
     (12, 6, 10, 16, 24, 1),     # the last image group is short
     (3, 5, 5, 8, 8, 2),
+    (16, 16, 16, 3, 64, 1),     # first-layer shape: the input is copied to 8-channel rows
+    (8, 7, 9, 12, 24, 1),
 ]
 
 
