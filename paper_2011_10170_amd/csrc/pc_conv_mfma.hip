@@ -793,30 +793,30 @@ static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, int ntaps, const u
 // ---- wave-specialised kernel: plan and launch (9-tap launches whose channel count is a multiple of 8)
 #define KS_LDS_MAX (160 * 1024)
 
-template <int B_T, int KC, int KSP>
+template <int A_T, int B_T, int KC, int KSP>
 static hipError_t launch_ks(hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out, const uint16_t *wz,
                             const MfmaArgs &g)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<2, B_T, 9, KC, KSP>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, KS_LDS_MAX);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<2, B_T, 9, KC, KSP>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
+    hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
     return hipGetLastError();
 }
 
 // Fills the tile plan; false when the staged tile does not fit. ksp = 4: the MFMA wavefronts split the
 // reduction of a tile of 32*bt pixels (64-channel chunks); ksp = 1: they split a tile of 128*bt pixels
 // (32-channel chunks, no reduction across wavefronts).
-static bool plan_ks(const MfmaArgs &g, int ext, int bt, int ksp, MfmaArgs *out, size_t *lds_bytes, double *est, int num_cu)
+static bool plan_ks(const MfmaArgs &g, int ext, int at, int bt, int ksp, int kc, MfmaArgs *out, size_t *lds_bytes, double *est, int num_cu)
 {
-    const int kc = ksp == 4 ? 64 : 32, pitch = 2 * kc + 16, parts = kc / 8, nv = ksp == 4 ? KS_NV : KS_NV1;
+    const int pitch = 2 * kc + 16, parts = kc / 8, nv = ksp == 4 ? KS_NV : KS_NV1;
     MfmaArgs t = g;
     plan_mfma_tiles(&t, (ksp == 4 ? 32 : 128) * bt, ext);
-    const int nt = 2 * bt, nown = nt >= 4 ? 4 : nt;
+    const int nt = at * bt, nown = nt >= 4 ? 4 : nt;
     const int red_bytes = ksp == 4 ? (nt >= 4 ? nt / 4 : 1) * nown * 12288 : 4 * 64 * 144;   // reduction area / store staging
     // staged pixels: within the loader's registers (nv 16-byte elements per thread) and within LDS
     int cap = 256 * nv / parts;
@@ -835,7 +835,7 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, int ksp, MfmaArgs *out, 
     t.red_off = 2 * t.xbuf;
     *lds_bytes = (size_t)t.red_off + (size_t)red_bytes;
     if (*lds_bytes > KS_LDS_MAX) return false;
-    t.m_tiles = (g.out_CH + 63) / 64;
+    t.m_tiles = (g.out_CH + 32 * at - 1) / (32 * at);
     const int64_t p_tiles = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x;
     const int64_t total = p_tiles * t.m_tiles;
     if (total > (1 << 30)) return false;
@@ -863,8 +863,9 @@ static bool plan_ks(const MfmaArgs &g, int ext, int bt, int ksp, MfmaArgs *out, 
     // cycles of one workgroup: tiles per workgroup x (MFMAs of a tile at 32 cycles each per wavefront + the tile's
     // fixed cost: the reduction across wavefronts, or just the store)
     const int64_t rounds = (total + num_cu - 1) / num_cu;
-    if (ksp == 4) *est = (double)rounds * ((double)t.nchunks * 576.0 * bt + 2500.0);
-    else *est = (double)rounds * ((double)t.nchunks * 1152.0 * bt + 1200.0);
+    // (an item also costs a barrier and the refill of the fragment pipelines: about 450 cycles)
+    if (ksp == 4) *est = (double)rounds * ((double)t.nchunks * (288.0 * at * bt * kc / 64 + 450.0) + 2500.0);
+    else *est = (double)rounds * ((double)t.nchunks * (1152.0 * bt + 450.0) + 1200.0);
     *out = t;
     return true;
 }
@@ -875,33 +876,37 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int
 {
     *launched = false;
     // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
-    static const int kBt[4] = {4, 2, 1, 4}, kKsp[4] = {4, 4, 4, 1}, kCode[4] = {7, 8, 9, 13};
+    enum { NCAND = 6 };
+    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1}, kBt[NCAND] = {4, 2, 1, 4, 1, 1}, kKsp[NCAND] = {4, 4, 4, 1, 4, 4},
+                     kKc[NCAND] = {64, 64, 64, 32, 128, 128}, kCode[NCAND] = {7, 8, 9, 13, 14, 15};
     MfmaArgs best;
     size_t best_lds = 0;
     double best_est = 0.0;
     int best_k = -1;
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < NCAND; ++k) {
         if (pcfg >= 7 && pcfg != kCode[k]) continue;
         MfmaArgs t;
         size_t lds;
         double est;
-        if (!plan_ks(g0, ext, kBt[k], kKsp[k], &t, &lds, &est, ctx->num_cu)) continue;
+        if (!plan_ks(g0, ext, kAt[k], kBt[k], kKsp[k], kKc[k], &t, &lds, &est, ctx->num_cu)) continue;
         if (best_k < 0 || est < best_est) { best = t; best_lds = lds; best_est = est; best_k = k; }
     }
     if (best_k < 0) return PC_OK;
-    // The end-of-tile reduction costs about as much as one 64-channel chunk of MFMA work: with one or two
-    // chunks per tile the cooperative kernel's output split is faster, unless every workgroup has a single tile.
-    if (pcfg < 0 && kKsp[best_k] == 4 && (best.nchunks < 2 || (best.nchunks == 2 && best.total_tiles > ctx->num_cu))) return PC_OK;
+    // The end-of-tile reduction costs about as much as 64 channels of MFMA work: up to 128 reduction channels
+    // the cooperative kernel's output split is faster, unless every workgroup has a single tile.
+    if (pcfg < 0 && kKsp[best_k] == 4 && (g0.in_CH <= 64 || (g0.in_CH <= 128 && best.total_tiles > ctx->num_cu))) return PC_OK;
     MfmaArgs g = best;
-    const int pitch = kKsp[best_k] == 4 ? 144 : 80;
+    const int pitch = 2 * kKc[best_k] + 16;
     for (int t = 0; t < 9; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * pitch;
     const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;
     hipError_t e;
     switch (best_k) {
-    case 0: e = launch_ks<4, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 1: e = launch_ks<2, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 2: e = launch_ks<1, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    default: e = launch_ks<4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 0: e = launch_ks<2, 4, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 1: e = launch_ks<2, 2, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 2: e = launch_ks<2, 1, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 3: e = launch_ks<2, 4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 4: e = launch_ks<2, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<1, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
     }
     *launched = true;
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");
@@ -911,7 +916,7 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int
 static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, const int *tr, const int *tc,
                                const uint16_t *in, uint16_t *out, const uint16_t *wz)
 {
-    int plan_cfg = (ctx->plan_cfg >= 10 && ctx->plan_cfg != 13) ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
+    int plan_cfg = (ctx->plan_cfg >= 10 && ctx->plan_cfg < 13) ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
     if (ntaps == 9 && (g.in_CH & 7) == 0 && g.in_CH >= 32 && (plan_cfg < 0 || plan_cfg >= 7) && ctx->plan_split == 0) {
         bool launched = false;
         pc_status s = run_mfma_conv_ks(ctx, plan_cfg, g, ext, tr, tc, in, out, wz, &launched);
