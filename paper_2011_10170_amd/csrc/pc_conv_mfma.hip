@@ -701,11 +701,14 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 // w[f = 32*mt + l%32][c = 16*ks + 8*(l/32) + i][tap], zero when pruned or padded.
 // wz_bwd has the roles of filter and channel exchanged (rows = channels, k = filters).
 __global__ void __launch_bounds__(256)
-pc_pack_tiles_kernel(const float *__restrict__ W, LibArg la, PackView v, int bwd)
+pc_pack_tiles_kernel(const float *__restrict__ W, LibArg la, PackView v, int64_t total_fwd)
 {
+    // one launch fills both operands: the first total_fwd threads wz_fwd, the others wz_bwd
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int bwd = idx >= total_fwd;
+    if (bwd) idx -= total_fwd;
     const int Mp = bwd ? v.Cp : v.Fp;          // padded row count (multiple of 128)
     const int KS = (bwd ? v.Fk : v.Ck) / 16;   // padded reduction length / 16
-    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = (int64_t)(Mp / 32) * 9 * KS * 64;
     if (idx >= total) return;
     int lane = (int)(idx & 63);
@@ -741,12 +744,9 @@ pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W)
     PackView v = pk->v;
     LibArg la;
     pc_fill_lib(&la, pk->lib, v.P);
-    for (int bwd = 0; bwd < 2; ++bwd) {
-        int Mp = bwd ? v.Cp : v.Fp, KS = (bwd ? v.Fk : v.Ck) / 16;
-        int64_t total = (int64_t)(Mp / 32) * 9 * KS * 64;
-        hipLaunchKernelGGL(pc_pack_tiles_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, ctx->stream, W, la,
-                           v, bwd);
-    }
+    const int64_t total_fwd = (int64_t)(v.Fp / 32) * 9 * (v.Ck / 16) * 64, total_bwd = (int64_t)(v.Cp / 32) * 9 * (v.Fk / 16) * 64;
+    hipLaunchKernelGGL(pc_pack_tiles_kernel, dim3((unsigned)((total_fwd + total_bwd + 255) / 256)), dim3(256), 0, ctx->stream,
+                       W, la, v, total_fwd);
     return pc_hip_check(ctx, hipGetLastError(), "pack tiles launch");
 }
 

@@ -135,17 +135,15 @@ __global__ void __launch_bounds__(1024) pc_pack_scan_kernel(int32_t *rowptr, int
     for (int i = lo; i < hi; ++i) sum += rowptr[i];
     part[threadIdx.x] = sum;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int i = 0; i < 1024; ++i) {
-            int v = part[i];
-            part[i] = run;
-            run += v;
-        }
-        rowptr[rows] = run;
+    // inclusive prefix over the 1024 partial sums (integers: any order gives the same result)
+    for (int d = 1; d < 1024; d <<= 1) {
+        int add = threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
     }
-    __syncthreads();
-    int run = part[threadIdx.x];
+    if (threadIdx.x == 1023) rowptr[rows] = part[1023];
+    int run = part[threadIdx.x] - sum;
     for (int i = lo; i < hi; ++i) {
         int v = rowptr[i];
         rowptr[i] = run;
@@ -253,12 +251,14 @@ pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8
     hipLaunchKernelGGL(pc_pack_scan_kernel, dim3(1), dim3(1024), 0, st, v.fm_rowptr, v.F);
     hipLaunchKernelGGL(pc_pack_place_kernel, dim3(v.F), dim3(256), 0, st, W, pid, keep, v.F, v.C, (int64_t)v.C,
                        (int64_t)1, la, bf16, 1, v);
-    // channel-major
-    hipLaunchKernelGGL(pc_pack_count_kernel, dim3(v.C), dim3(256), 0, st, pid, keep, v.C, v.F, (int64_t)1,
-                       (int64_t)v.C, v.P, v.cm_grp, v.cm_rowptr);
-    hipLaunchKernelGGL(pc_pack_scan_kernel, dim3(1), dim3(1024), 0, st, v.cm_rowptr, v.C);
-    hipLaunchKernelGGL(pc_pack_place_kernel, dim3(v.C), dim3(256), 0, st, W, pid, keep, v.C, v.F, (int64_t)1,
-                       (int64_t)v.C, la, bf16, 0, v);
+    // channel-major: the table of the gather kernels' backward-data pass (the matrix-core kernels read operand tiles)
+    if (pk->variant != PC_VARIANT_MFMA) {
+        hipLaunchKernelGGL(pc_pack_count_kernel, dim3(v.C), dim3(256), 0, st, pid, keep, v.C, v.F, (int64_t)1,
+                           (int64_t)v.C, v.P, v.cm_grp, v.cm_rowptr);
+        hipLaunchKernelGGL(pc_pack_scan_kernel, dim3(1), dim3(1024), 0, st, v.cm_rowptr, v.C);
+        hipLaunchKernelGGL(pc_pack_place_kernel, dim3(v.C), dim3(256), 0, st, W, pid, keep, v.C, v.F, (int64_t)1,
+                           (int64_t)v.C, la, bf16, 0, v);
+    }
     pc_status s = pc_hip_check(ctx, hipGetLastError(), "pack launch");
     if (s == PC_OK && pk->variant == PC_VARIANT_MFMA) s = pc_launch_pack_tiles(ctx, pk, W);
     return s;
@@ -273,7 +273,8 @@ pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W)
     int64_t nk = (int64_t)v.F * v.C;
     unsigned blocks = (unsigned)((nk + 255) / 256);
     hipLaunchKernelGGL(pc_pack_regather_fm_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, la, bf16, v);
-    hipLaunchKernelGGL(pc_pack_regather_cm_kernel, dim3(blocks), dim3(256), 0, ctx->stream, v);
+    if (pk->variant != PC_VARIANT_MFMA)
+        hipLaunchKernelGGL(pc_pack_regather_cm_kernel, dim3(blocks), dim3(256), 0, ctx->stream, v);
     pc_status s = pc_hip_check(ctx, hipGetLastError(), "update_values launch");
     if (s == PC_OK && pk->variant == PC_VARIANT_MFMA) s = pc_launch_pack_tiles(ctx, pk, W);
     return s;
