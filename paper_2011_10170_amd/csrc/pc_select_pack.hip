@@ -81,6 +81,82 @@ pc_select_rank_kernel(const float *__restrict__ R, int64_t L, int64_t n_keep, ui
     if (live) keep[(int64_t)blockIdx.y * L + i] = before < n_keep ? 1 : 0;
 }
 
+// Exact top-n_keep of every row of R (n rows of length L, L <= PC_TOPN_MAX) in the order (score descending,
+// index ascending), one workgroup per row: a 4-pass radix select over order-preserving 32-bit keys finds the
+// score of the n_keep-th kernel and how many kernels with exactly that score are kept; those are the ones
+// with the lowest indices. Counts are integers: the result does not depend on the order of the atomics.
+#define PC_TOPN_MAX 8192
+__device__ __forceinline__ uint32_t pc_order_key(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);   // a > b as floats  <=>  key(a) > key(b) as unsigned
+}
+
+__global__ void __launch_bounds__(256)
+pc_select_topn_row_kernel(const float *__restrict__ R, int L, int n_keep, uint8_t *__restrict__ keep)
+{
+    extern __shared__ uint32_t keys[];          // L keys
+    __shared__ int hist[256], above[256];
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_remaining, s_wave_cnt[4], s_base;
+    const float *seg = R + (int64_t)blockIdx.x * L;
+    uint8_t *out = keep + (int64_t)blockIdx.x * L;
+    if (n_keep <= 0 || n_keep >= L) {
+        for (int i = threadIdx.x; i < L; i += 256) out[i] = n_keep > 0 ? 1 : 0;
+        return;
+    }
+    for (int i = threadIdx.x; i < L; i += 256) keys[i] = pc_order_key(seg[i]);
+    if (threadIdx.x == 0) { s_prefix = 0u; s_remaining = n_keep; }
+    __syncthreads();
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[threadIdx.x] = 0;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        const uint32_t himask = shift == 24 ? 0u : 0xFFFFFFFFu << (shift + 8);
+        for (int i = threadIdx.x; i < L; i += 256) {
+            const uint32_t k = keys[i];
+            if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        // above[d] = number of candidates whose digit is larger than d (suffix sum, exclusive)
+        above[threadIdx.x] = hist[threadIdx.x];
+        __syncthreads();
+        for (int d = 1; d < 256; d <<= 1) {
+            const int add = threadIdx.x + d < 256 ? above[threadIdx.x + d] : 0;
+            __syncthreads();
+            above[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int incl = above[threadIdx.x], excl = incl - hist[threadIdx.x];
+        const int rem = s_remaining;
+        __syncthreads();
+        if (excl < rem && rem <= incl) {        // exactly one digit holds the rem-th largest candidate
+            s_prefix = prefix | ((uint32_t)threadIdx.x << shift);
+            s_remaining = rem - excl;
+        }
+        __syncthreads();
+    }
+    const uint32_t T = s_prefix;
+    const int take_equal = s_remaining;         // kernels with key == T that are kept: the first ones by index
+    if (threadIdx.x == 0) s_base = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i0 = 0; i0 < L; i0 += 256) {
+        const int i = i0 + threadIdx.x;
+        const uint32_t k = i < L ? keys[i] : 0u;
+        const bool eq = i < L && k == T;
+        const unsigned long long b = __ballot(eq);
+        if (lane == 0) s_wave_cnt[wave] = __popcll(b);
+        __syncthreads();
+        int before = s_base + __popcll(b & ((1ull << lane) - 1ull));
+        for (int w2 = 0; w2 < wave; ++w2) before += s_wave_cnt[w2];
+        if (i < L) out[i] = (k > T || (eq && before < take_equal)) ? 1 : 0;
+        __syncthreads();
+        if (threadIdx.x == 0) s_base += s_wave_cnt[0] + s_wave_cnt[1] + s_wave_cnt[2] + s_wave_cnt[3];
+        __syncthreads();
+    }
+}
+
 pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, int C, const LibArg &la,
                            pc_keep_mode km, int64_t n_keep, pc_score_mode sm, uint8_t *pid, uint8_t *keep)
 {
@@ -93,8 +169,13 @@ pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, i
     hipLaunchKernelGGL(pc_select_score_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, G, nk, la, (int)sm, pid, R);
     int64_t L = (km == PC_KEEP_PER_FILTER) ? C : nk;
     unsigned nseg = (km == PC_KEEP_PER_FILTER) ? (unsigned)F : 1u;
-    dim3 grid((unsigned)((L + 255) / 256), nseg);
-    hipLaunchKernelGGL(pc_select_rank_kernel, grid, dim3(256), 0, ctx->stream, R, L, n_keep, keep);
+    if (L <= PC_TOPN_MAX) {
+        hipLaunchKernelGGL(pc_select_topn_row_kernel, dim3(nseg), dim3(256), sizeof(uint32_t) * (size_t)L, ctx->stream, R, (int)L,
+                           (int)(n_keep < L ? n_keep : L), keep);
+    } else {
+        dim3 grid((unsigned)((L + 255) / 256), nseg);
+        hipLaunchKernelGGL(pc_select_rank_kernel, grid, dim3(256), 0, ctx->stream, R, L, n_keep, keep);
+    }
     return pc_hip_check(ctx, hipGetLastError(), "select launch");
 }
 
