@@ -84,12 +84,19 @@ const char *pc_last_error(const pc_ctx *ctx);
  * PC_VARIANT_MFMA on a layer it cannot serve makes pc_pack return PC_ERR_UNSUPPORTED. */
 pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
 
-/* Tuning aid for the MFMA forward/backward-data kernels: tile_cfg selects one of the built tile
- * configurations instead of the automatic choice (-1): 0..6 are tile shapes of the cooperative kernel,
- * 7..9 the persistent wave-specialised kernel with pixel tiles of 128, 64 and 32 pixels (it takes
- * 9-tap launches only; the tap subsets of a strided backward-data pass then use the automatic choice).
- * split_k > 0 forces that many splits of the reduction in the cooperative kernel (0 = automatic).
- * A configuration that does not fit a layer makes the conv call return PC_ERR_UNSUPPORTED. Results do not depend on the choice beyond float32 summation order. */
+/* Tuning aid for tests and sweeps: forces a kernel of the matrix-core family instead of the automatic
+ * choice (tile_cfg = -1) for later calls on this context.
+ *   0..6   forward/backward-data: a tile shape of the cooperative kernel
+ *   7..9   forward/backward-data: the persistent wave-specialised kernel, reduction split over its MFMA
+ *          wavefronts, tiles of 64 output channels x 128, 64, 32 pixels
+ *   13     the same kernel with the pixels split over the wavefronts (64 x 512 tiles, 32-channel chunks)
+ *   14, 15 as 9 with 128-channel chunks, and with tiles of 32 output channels x 32 pixels
+ *   10, 11 backward-weight: the cooperative / the wave-specialised kernel (the other passes stay automatic)
+ * The wave-specialised forward/backward-data kernel takes 9-tap launches only: the tap subsets of a strided
+ * backward-data pass use the automatic choice. split_k > 0 forces that many splits of the reduction in the
+ * cooperative forward/backward-data kernel (0 = automatic). A configuration that does not fit a layer makes
+ * the conv call return PC_ERR_UNSUPPORTED. Results do not depend on the choice beyond float32 summation
+ * order. Returns PC_ERR_INVALID_ARG for values outside these ranges. */
 pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t split_k);
 
 /* Host-only argument checks (usable without a GPU). */
