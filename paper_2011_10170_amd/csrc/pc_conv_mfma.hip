@@ -1393,16 +1393,19 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int nt = (a.n_ktiles - bz + a.ksplit - 1) / a.ksplit;   // pixel tiles of this workgroup
     WSTAMP(0);
 
-    // (compact slot, pattern mask) of the 8 kernels this thread writes in the epilogue
+    // (compact slot, pattern mask) of the 8 kernels this thread writes in the epilogue; requested early (the loaders
+    // first request their pixel tiles) so that the look-up latency hides behind the main loop
     uint32_t kinf[2][4];
+    auto load_kinfo = [&]() {
 #pragma unroll
-    for (int fh = 0; fh < 2; ++fh)
+        for (int fh = 0; fh < 2; ++fh)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int p = threadIdx.x + 512 * k;
-            const int f = f0 + fh * 32 + (p >> 6), c = c0 + (p & 63);
-            kinf[fh][k] = (f < a.F && c < a.Creal) ? v.kinfo[(int64_t)f * a.Creal + c] : 0xFFFFFFFFu;
-        }
+            for (int k = 0; k < 4; ++k) {
+                const int p = threadIdx.x + 512 * k;
+                const int f = f0 + fh * 32 + (p >> 6), c = c0 + (p & 63);
+                kinf[fh][k] = (f < a.F && c < a.Creal) ? v.kinfo[(int64_t)f * a.Creal + c] : 0xFFFFFFFFu;
+            }
+    };
     float *pout = a.ksplit > 1 ? partial + (int64_t)bz * a.nnzk * 4 : dw;
     const float *ot = reinterpret_cast<const float *>(lds);
     // gathers the 4 kept taps of every kept kernel of filter half fh from the parked tile
@@ -1499,6 +1502,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
         uint4 A0[8], B0[8], A1[8], B1[8];
         WSTAMP(17);
         issue(A0, B0); issue(A1, B1);
+        load_kinfo();
         WSTAMP(18);
         put(A0, B0, 0);
         WSTAMP(19);
@@ -1528,6 +1532,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     } else {
         // ------------------------------------------------------------ MFMA wavefronts
         // wave = (channel half, tap group); the 18 (filter half, tap) units are split 9/9 as in the kernel above
+        load_kinfo();
         const int chh = wave & 1, tg = wave >> 1;
         const int g = lane >> 5;
         const int first_half = tg;
