@@ -49,7 +49,8 @@ struct MfmaArgs {
     int32_t m_tiles, total_tiles;   // row tiles of the output channels; all tiles
     int32_t m_fast, fdiv;           // tile index = slow * fdiv + fast; m_fast: the row tile is the fast index (fdiv = m_tiles), else the pixel tile
     int32_t xbuf, red_off, nelem;   // bytes per staged input buffer, LDS offset of the reduction area, 16-byte elements per buffer
-    uint32_t in_bytes, out_bytes;   // sizes of the input and output tensors (bounds of the buffer loads and stores)
+    uint32_t in_bytes, out_bytes, wz_bytes;   // sizes of the input, output and operand-tile buffers (bounds of the buffer accesses)
+    int32_t tap_o0, tap_dr, tap_ds; // LDS byte offset of tap 3r+s = tap_o0 + r*tap_dr + s*tap_ds
     // divisions by these run as a multiply-high with floor(2^32 / d) + 1 (exact while dividend * d < 2^32)
     uint32_t mg_IW, mg_IH, mg_TW, mg_THTW, mg_fd, mg_tx, mg_ty;
 };
@@ -480,12 +481,22 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 
     const __amdgpu_buffer_rsrc_t osrc = __builtin_amdgcn_make_buffer_rsrc(out, 0, g.out_bytes, 0x00020000);
     constexpr uint32_t OOB_OUT = 0x80000000u;
-    int fo[NF];                           // element offset of A fragment phi inside an item
-#pragma unroll
-    for (int ph = 0; ph < NF; ++ph) {
+    // A fragments: buffer loads with the lane's 16 bytes as the vector offset and everything else in the scalar
+    // offset. This kernel only runs the full 3x3 tap list in tap order (weight tap t at list position t), so
+    // fragment (row tile ii, tap t, k-step kk) of an item lies at (ii*9 + t) * KS + kk fragments of 1 KiB past
+    // the item's first one, and the LDS offset of tap t = 3r + s is tap_o0 + r*tap_dr + s*tap_ds: a handful of
+    // scalars instead of per-fragment tables that would not fit the scalar registers.
+    const __amdgpu_buffer_rsrc_t wsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(wz), 0, g.wz_bytes, 0x00020000);
+    const int a_voff = lane * 16;
+    const int ksb = g.KS * 1024;          // bytes between the fragments of two taps
+    auto a_frag = [&](int item_base, int ph) -> bf16x8 {   // ph: compile-time fragment index inside the item
         const int st = ph / A_T, ii = ph % A_T;
-        fo[ph] = ((ii * 9 + g.tap_w[st / KSW]) * g.KS + st % KSW) * 512;
-    }
+        const v4u32 r = __builtin_amdgcn_raw_buffer_load_b128(wsrc, a_voff, item_base + (ii * 9 + st / KSW) * ksb + (st % KSW) * 1024, 0);
+        bf16x8 o;
+        __builtin_memcpy(&o, &r, 16);
+        return o;
+    };
+    auto tap_off = [&](int t) -> int { return g.tap_o0 + (t / 3) * g.tap_dr + (t % 3) * g.tap_ds; };
     int mt = 0, tn = 0, gy0 = 0, gx0 = 0;
     auto tile_of = [&](int k, int &mt_, int &tn_, int &gy0_, int &gx0_) {
         const uint32_t t = (uint32_t)(vb + k * G);
@@ -500,12 +511,12 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         gy0_ = ty * g.TH;
         gx0_ = tx * g.TW;
     };
-    auto a_base = [&](int mt_, int ch_) -> const uint16_t * {
-        return wz + ((int64_t)(mt_ * A_T * 9) * g.KS + ch_ * KSC + (KSP == 4 ? w * KSW : 0)) * 512 + lane * 8;
+    auto a_base = [&](int mt_, int ch_) -> int {   // byte offset of the item's first fragment for this wavefront
+        return ((mt_ * A_T * 9) * g.KS + ch_ * KSC + (KSP == 4 ? w * KSW : 0)) * 1024;
     };
     tile_of(0, mt, tn, gy0, gx0);
     int k = 0, ch = 0;
-    const uint16_t *ab = a_base(mt, 0);
+    int ab = a_base(mt, 0);
 
     f32x16 acc[A_T][B_T];
 #pragma unroll
@@ -517,7 +528,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 
     bf16x8 aring[PFD];
 #pragma unroll
-    for (int ph = 0; ph < PFD; ++ph) aring[ph] = *reinterpret_cast<const bf16x8 *>(ab + fo[ph]);
+    for (int ph = 0; ph < PFD; ++ph) aring[ph] = a_frag(ab, ph);
 
     KSTAMP(1);
     __syncthreads();
@@ -531,7 +542,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
             if (nk < ntile_blk) tile_of(nk, nmt, ntn, ngy0, ngx0);
             else nchk = ch;
         }
-        const uint16_t *abn = a_base(nmt, nchk);
+        const int abn = a_base(nmt, nchk);
         const unsigned char *xb = lds + (i & 1) * g.xbuf;
 
         bf16x8 bring[RB][B_T];
@@ -539,7 +550,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         for (int d = 0; d < DBS; ++d)
 #pragma unroll
             for (int j = 0; j < B_T; ++j)
-                bring[d % RB][j] = *reinterpret_cast<const bf16x8 *>(xb + base[j] + g.tap_off[d / KSW] + (d % KSW) * 32);
+                bring[d % RB][j] = *reinterpret_cast<const bf16x8 *>(xb + base[j] + tap_off(d / KSW) + (d % KSW) * 32);
 #pragma unroll
         for (int st = 0; st < S; ++st) {
 #ifndef EXP_KS_NO_B
@@ -547,7 +558,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 #pragma unroll
                 for (int j = 0; j < B_T; ++j)
                     bring[(st + DBS) % RB][j] =
-                        *reinterpret_cast<const bf16x8 *>(xb + base[j] + g.tap_off[(st + DBS) / KSW] + ((st + DBS) % KSW) * 32);
+                        *reinterpret_cast<const bf16x8 *>(xb + base[j] + tap_off((st + DBS) / KSW) + ((st + DBS) % KSW) * 32);
             }
 #else
             if (st + DBS < S) {
@@ -562,8 +573,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                 anow[ii] = aring[ph % PFD];
                 const int nph = ph + PFD;
 #ifndef EXP_KS_NO_A
-                aring[ph % PFD] = nph < NF ? *reinterpret_cast<const bf16x8 *>(ab + fo[nph < NF ? nph : 0])
-                                           : *reinterpret_cast<const bf16x8 *>(abn + fo[nph < NF ? 0 : nph - NF]);
+                aring[ph % PFD] = nph < NF ? a_frag(ab, nph < NF ? nph : 0) : a_frag(abn, nph < NF ? 0 : nph - NF);
 #endif
             }
 #pragma unroll
@@ -897,7 +907,13 @@ static pc_status run_mfma_conv_ks(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int
     if (pcfg < 0 && kKsp[best_k] == 4 && (g0.in_CH <= 64 || (g0.in_CH <= 128 && best.total_tiles > ctx->num_cu))) return PC_OK;
     MfmaArgs g = best;
     const int pitch = 2 * kKc[best_k] + 16;
-    for (int t = 0; t < 9; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * pitch;
+    // the tap list is the full 3x3 in tap order, forward (offset (r, s)) or rotated (offset (2-r, 2-s))
+    for (int t = 0; t < 9; ++t)
+        if (g.tap_w[t] != t || tr[t] != (tr[0] ? 2 - t / 3 : t / 3) || tc[t] != (tc[0] ? 2 - t % 3 : t % 3)) return PC_OK;
+    g.tap_dr = (tr[0] ? -1 : 1) * g.IW * pitch;
+    g.tap_ds = (tc[0] ? -1 : 1) * pitch;
+    g.tap_o0 = (tr[0] * g.IW + tc[0]) * pitch;
+    g.wz_bytes = (uint32_t)((size_t)((g.out_CH + 127) / 128 * 4) * 9 * g.KS * 1024);
     const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;
     hipError_t e;
     switch (best_k) {
