@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpatconv.so")
-SOURCES = ["pc_api.hip", "pc_select_pack.hip", "pc_conv_valu.hip", "pc_conv_mfma.hip"]
+SOURCES = ["pc_api.hip", "pc_select_pack.hip", "pc_conv_valu.hip", "pc_conv_mfma.hip", "pc_conv_mfma_ws.hip",
+           "pc_wgrad_mfma.hip"]
 
 # Contraction is off so that the selection arithmetic keeps its written order; the conv kernels
 # call fmaf explicitly. Packed fp32 instructions are disabled for the device pass.

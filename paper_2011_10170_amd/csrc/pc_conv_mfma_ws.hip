@@ -1,0 +1,514 @@
+// Forward / backward-data on the matrix cores, persistent wave-specialised kernel (see pc_conv_mfma.hip for the
+// implicit-GEMM formulation, the operand tiles and the MFMA register layout).
+#include "pc_mfma.h"
+
+// ------------------------------------------------------------------ wave-specialised kernel
+// Eight wavefronts per workgroup, one workgroup per CU, walking tiles of 32*A_T output channels x
+// 32*B_T pixels (row tile fastest, so workgroups running side by side share the input tile in L2).
+//   wavefronts 4..7 (loaders) stage the input halo tile of the NEXT item (tile, 64-channel chunk) into
+//     one of two LDS buffers; their global loads are issued KS_DEPTH items ahead into registers, so an
+//     HBM round trip is hidden behind several items of MFMA work and never stalls an MFMA wavefront
+//     (a wavefront's outstanding loads retire in order: mixing long bulk loads with the short
+//     operand loads in one wavefront makes every operand wait for the bulk);
+//   wavefronts 0..3 (MFMA) all own the WHOLE tile and split the reduction: wavefront w takes the k-step
+//     of channels 16w..16w+15 of every tap of every chunk. A wavefront tile of 64x128 needs half the
+//     operand bytes per MFMA of the 32x64 tile an output split would leave at this workgroup size,
+//     which keeps both operand paths (A fragments from L2 through the 64 B/clk vector cache, B
+//     fragments from LDS) well under their limits. At the end of a tile the four partial sums are
+//     added in a fixed order (wavefront 0..3) through LDS, every wavefront finishing and storing a
+//     quarter of the tile.
+// Both roles execute the same sequence of workgroup barriers: one after the first staged item and one
+// per item.
+#define KS_NV 8          // 16-byte elements staged per loader thread and item (256 loader threads), reduction split
+#define KS_NV1 12        // the same without the reduction split (512-pixel tiles of 32 channels)
+#define KS_DEPTH 3       // items in flight in the loader's registers
+
+// Depth of the A-fragment ring: the largest divisor of the fragments per item that does not exceed cap
+constexpr int pc_ring_depth(int nf, int cap)
+{
+    int best = 1;
+    for (int d = 1; d <= cap; ++d)
+        if (nf % d == 0) best = d;
+    return best;
+}
+
+template <int A_T, int B_T, int NTAPS, int KC, int KSP>
+__global__ void __launch_bounds__(512, 1)
+pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const uint16_t *__restrict__ wz, MfmaArgs g)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int KSC = KC / 16;          // k-steps per chunk
+    static_assert(KSP == 4 || KSP == 1, "the MFMA wavefronts split the reduction four ways or not at all");
+    constexpr int KSW = KC / (16 * KSP);  // k-steps per chunk, tap and MFMA wavefront
+    constexpr int NV = KSP == 4 ? KS_NV : KS_NV1;   // 16-byte elements staged per loader thread and item
+    constexpr int S = NTAPS * KSW;        // steps per item and wavefront
+    constexpr int NF = S * A_T;           // A fragments per item and wavefront
+    // the ring has to cover an L2 round trip in MFMA time: narrow pixel tiles issue fewer MFMAs per fragment
+    // and have the registers for a whole item of fragments
+    constexpr int PFD = pc_ring_depth(NF, B_T >= 4 ? 10 : 18);
+    constexpr int PITCH = 2 * KC + 16;
+    constexpr int PARTS = KC / 8;
+    constexpr int NT = A_T * B_T;
+    constexpr int ROUNDS = NT >= 4 ? NT / 4 : 1;
+    constexpr int NOWN = NT >= 4 ? 4 : NT;
+    constexpr int DB = B_T >= 4 ? 1 : (B_T == 2 ? 2 : 4);   // B fragments are read this many steps ahead
+    constexpr int DBS = DB < S ? DB : S;
+    constexpr int RB = DBS + 1;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = wave & 3;
+    const int G = gridDim.x;
+    int vb = blockIdx.x;
+    if ((G & 7) == 0) vb = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);   // neighbours in the tile order share an XCD
+    const int ntile_blk = (g.total_tiles - vb + G - 1) / G;
+    const int nch = g.nchunks;
+    const int I = ntile_blk * nch;
+
+    if (wave >= 4) {
+        // ------------------------------------------------------------ loaders
+        const int tl = threadIdx.x - 256;
+        const int part = tl % PARTS;
+        // The input is read with buffer loads: an offset past the end of the tensor returns zeros, which
+        // serves every element that is not a real input value (zero padding around the image, images
+        // past the batch, channels past the last one, unused loader slots) without a branch. Loads and
+        // LDS writes stay unconditional, so the compiler can count the loads in flight and wait for
+        // exactly the oldest register set.
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(in), 0, g.in_bytes, 0x00020000);
+        constexpr uint32_t OOB = 0x80000000u;   // past any tensor this kernel accepts, and no wrap-around with the chunk offset
+        const bool part_in_last = (nch - 1) * KC + part * 8 < g.in_CH;   // this thread's channels exist in the last chunk
+        int pk[NV], loff[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int e = tl + 256 * v;
+            const uint32_t q = (uint32_t)e / PARTS;
+            const uint32_t t2 = pc_udiv(q, g.mg_IW);
+            const int ix = (int)(q - t2 * g.IW);
+            const uint32_t ti = pc_udiv(t2, g.mg_IH);
+            const int iy = (int)(t2 - ti * g.IH);
+            pk[v] = e < g.nelem ? (int)((ti << 20) | (iy << 10) | ix) : -1;
+            loff[v] = e < g.nelem ? (int)q * PITCH + part * 16 : g.xbuf - 16;
+        }
+        int lk = 0, lch = 0;              // cursor of the next item to load
+        uint32_t voff[NV];             // byte offset of every element's pixel (+ its 16-byte part) in the tensor
+        auto tile_offsets = [&](int k) {
+            const uint32_t tq = pc_udiv((uint32_t)(vb + k * G), g.mg_fd);
+            const uint32_t pt = g.m_fast ? tq : (uint32_t)(vb + k * G) - tq * g.fdiv;
+            const uint32_t u = pc_udiv(pt, g.mg_tx);
+            const int tx = (int)(pt - u * g.tiles_x);
+            const uint32_t tnn = pc_udiv(u, g.mg_ty);
+            const int ty = (int)(u - tnn * g.tiles_y);
+            const int ltn = (int)tnn * g.TI;
+            const int ly0 = ty * g.TH * g.iscale + g.ioff_y;
+            const int lx0 = tx * g.TW * g.iscale + g.ioff_x;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int n = ltn + (pk[v] >> 20), y = ly0 + ((pk[v] >> 10) & 1023), x = lx0 + (pk[v] & 1023);
+                const bool ok = pk[v] >= 0 && n < g.N && (unsigned)y < (unsigned)g.in_H && (unsigned)x < (unsigned)g.in_W;
+                voff[v] = ok ? (uint32_t)((n * g.in_H + y) * g.in_W + x) * (uint32_t)(g.in_CH * 2) + part * 16 : OOB;
+            }
+        };
+        tile_offsets(0);
+        auto issue = [&](uint4 (&R)[NV]) {
+            const int so = lch * (KC * 2);
+            const bool cut = (lch == nch - 1 && !part_in_last) || lk >= ntile_blk;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const v4u32 val = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(cut ? OOB : voff[v]), so, 0);
+                R[v] = make_uint4(val.x, val.y, val.z, val.w);
+            }
+            if (lk < ntile_blk && ++lch == nch) {
+                lch = 0;
+                if (++lk < ntile_blk) tile_offsets(lk);
+            }
+        };
+        auto put = [&](const uint4 (&R)[NV], int bufoff) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) *reinterpret_cast<uint4 *>(lds + bufoff + loff[v]) = R[v];
+        };
+        uint4 R0[NV], R1[NV], R2[NV];
+        issue(R0); issue(R1);
+        put(R0, 0);
+        __syncthreads();
+        issue(R2); issue(R0);
+        // item i: while the MFMA wavefronts work on buffer i&1, write item i+1 (register set (i+1)%3) to the
+        // other buffer (past the last item: zeros, never read) and refill that set with item i+4
+        auto lstep = [&](int i, uint4 (&R)[NV]) {
+            put(R, ((i + 1) & 1) * g.xbuf);
+            issue(R);
+            __syncthreads();
+        };
+        int i = 0;
+        for (; i + 3 <= I; i += 3) {
+            lstep(i, R1);
+            lstep(i + 1, R2);
+            lstep(i + 2, R0);
+        }
+        if (i < I) {
+            lstep(i, R1);
+            if (i + 1 < I) lstep(i + 1, R2);
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------- MFMA wavefronts
+    const int npix = g.TI * g.TH * g.TW;
+    int base[B_T];
+#pragma unroll
+    for (int j = 0; j < B_T; ++j) {
+        // reduction split: every wavefront covers all pixels and its own k-steps; otherwise its own pixels
+        int q = ((KSP == 1 ? w * B_T : 0) + j) * 32 + (lane & 31);
+        if (q >= npix) q = npix - 1;
+        const int ti = (int)pc_udiv((uint32_t)q, g.mg_THTW);
+        const int rem = q - ti * g.TH * g.TW;
+        const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
+        base[j] = ((ti * g.IH + y * g.lstep) * g.IW + x * g.lstep) * PITCH + (lane >> 5) * 16 +
+                  (KSP == 4 ? w * (KSW * 32) : 0);
+    }
+    // the pixel sub-tile this wavefront finishes and stores
+    const int jo = w % B_T;
+    const int qo = jo * 32 + (lane & 31);
+    const int o_ti = (int)pc_udiv((uint32_t)qo, g.mg_THTW);
+    const int o_y = (int)pc_udiv((uint32_t)(qo - o_ti * g.TH * g.TW), g.mg_TW);
+    const int o_x = qo - o_ti * g.TH * g.TW - o_y * g.TW;
+
+    const __amdgpu_buffer_rsrc_t osrc = __builtin_amdgcn_make_buffer_rsrc(out, 0, g.out_bytes, 0x00020000);
+    constexpr uint32_t OOB_OUT = 0x80000000u;
+    // A fragments: buffer loads with the lane's 16 bytes as the vector offset and everything else in the scalar
+    // offset. This kernel only runs the full 3x3 tap list in tap order (weight tap t at list position t), so
+    // fragment (row tile ii, tap t, k-step kk) of an item lies at (ii*9 + t) * KS + kk fragments of 1 KiB past
+    // the item's first one, and the LDS offset of tap t = 3r + s is tap_o0 + r*tap_dr + s*tap_ds: a handful of
+    // scalars instead of per-fragment tables that would not fit the scalar registers.
+    const __amdgpu_buffer_rsrc_t wsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(wz), 0, g.wz_bytes, 0x00020000);
+    const int a_voff = lane * 16;
+    const int ksb = g.KS * 1024;          // bytes between the fragments of two taps
+    auto a_frag = [&](int item_base, int ph) -> bf16x8 {   // ph: compile-time fragment index inside the item
+        const int st = ph / A_T, ii = ph % A_T;
+        const v4u32 r = __builtin_amdgcn_raw_buffer_load_b128(wsrc, a_voff, item_base + (ii * 9 + st / KSW) * ksb + (st % KSW) * 1024, 0);
+        bf16x8 o;
+        __builtin_memcpy(&o, &r, 16);
+        return o;
+    };
+    auto tap_off = [&](int t) -> int { return g.tap_o0 + (t / 3) * g.tap_dr + (t % 3) * g.tap_ds; };
+    int mt = 0, tn = 0, gy0 = 0, gx0 = 0;
+    auto tile_of = [&](int k, int &mt_, int &tn_, int &gy0_, int &gx0_) {
+        const uint32_t t = (uint32_t)(vb + k * G);
+        const uint32_t tq = pc_udiv(t, g.mg_fd), trm = t - tq * g.fdiv;
+        const uint32_t pt = g.m_fast ? tq : trm;
+        mt_ = (int)(g.m_fast ? trm : tq);
+        const uint32_t u = pc_udiv(pt, g.mg_tx);
+        const int tx = (int)(pt - u * g.tiles_x);
+        const uint32_t tnn = pc_udiv(u, g.mg_ty);
+        const int ty = (int)(u - tnn * g.tiles_y);
+        tn_ = (int)tnn * g.TI;
+        gy0_ = ty * g.TH;
+        gx0_ = tx * g.TW;
+    };
+    auto a_base = [&](int mt_, int ch_) -> int {   // byte offset of the item's first fragment for this wavefront
+        return ((mt_ * A_T * 9) * g.KS + ch_ * KSC + (KSP == 4 ? w * KSW : 0)) * 1024;
+    };
+    tile_of(0, mt, tn, gy0, gx0);
+    int k = 0, ch = 0;
+    int ab = a_base(mt, 0);
+
+    f32x16 acc[A_T][B_T];
+#pragma unroll
+    for (int i = 0; i < A_T; ++i)
+#pragma unroll
+        for (int j = 0; j < B_T; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 aring[PFD];
+#pragma unroll
+    for (int ph = 0; ph < PFD; ++ph) aring[ph] = a_frag(ab, ph);
+
+    __syncthreads();
+    for (int i = 0; i < I; ++i) {
+        // the item after this one (for the A prefetch); past the end: this one again, unused
+        int nk = k, nchk = ch + 1, nmt = mt, ntn = tn, ngy0 = gy0, ngx0 = gx0;
+        if (nchk == nch) {
+            nchk = 0;
+            nk = k + 1;
+            if (nk < ntile_blk) tile_of(nk, nmt, ntn, ngy0, ngx0);
+            else nchk = ch;
+        }
+        const int abn = a_base(nmt, nchk);
+        const unsigned char *xb = lds + (i & 1) * g.xbuf;
+
+        bf16x8 bring[RB][B_T];
+#pragma unroll
+        for (int d = 0; d < DBS; ++d)
+#pragma unroll
+            for (int j = 0; j < B_T; ++j)
+                bring[d % RB][j] = *reinterpret_cast<const bf16x8 *>(xb + base[j] + tap_off(d / KSW) + (d % KSW) * 32);
+#pragma unroll
+        for (int st = 0; st < S; ++st) {
+            if (st + DBS < S) {
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+                    bring[(st + DBS) % RB][j] =
+                        *reinterpret_cast<const bf16x8 *>(xb + base[j] + tap_off((st + DBS) / KSW) + ((st + DBS) % KSW) * 32);
+            }
+            bf16x8 anow[A_T];
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii) {
+                const int ph = st * A_T + ii;
+                anow[ii] = aring[ph % PFD];
+                const int nph = ph + PFD;
+                aring[ph % PFD] = nph < NF ? a_frag(ab, nph < NF ? nph : 0) : a_frag(abn, nph < NF ? 0 : nph - NF);
+            }
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+                    acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(anow[ii], bring[st % RB][j], acc[ii][j], 0, 0, 0);
+            // One wavefront per SIMD issues everything in program order: the loads of the later steps and their
+            // address arithmetic go one or two at a time into the shadow of each MFMA instead of in a bunch
+            // between two steps, where they would leave the matrix pipe idle.
+#pragma unroll
+            for (int m = 0; m < A_T * B_T; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);       // address arithmetic
+                if (m < B_T) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              // one LDS read
+                else if (m < B_T + A_T) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // End of a tile: every wavefront leaves the partial tiles it does not own in LDS before the item's
+        // barrier (the reduction area is separate from the input buffers and was last read a barrier ago),
+        // then adds the four partial sums of the tiles it owns, in the order of the wavefronts, and stores them.
+        float *red = reinterpret_cast<float *>(lds + g.red_off);
+        if (KSP == 4 && ch == nch - 1) {
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r)
+#pragma unroll
+                for (int o = 0; o < NOWN; ++o) {
+                    if (o == w) continue;
+                    const int tau = r * 4 + o;
+                    const int wi = w < o ? w : w - 1;
+                    float *dst = red + (((r * NOWN + o) * 3 + wi) * 4) * 256 + lane * 4;
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4)
+                        *reinterpret_cast<float4 *>(dst + q4 * 256) =
+                            make_float4(acc[tau / B_T][tau % B_T][q4 * 4 + 0], acc[tau / B_T][tau % B_T][q4 * 4 + 1],
+                                        acc[tau / B_T][tau % B_T][q4 * 4 + 2], acc[tau / B_T][tau % B_T][q4 * 4 + 3]);
+                }
+        }
+        __syncthreads();
+
+        if (KSP == 1 && ch == nch - 1) {
+            // Every wavefront stores its own 32*B_T pixels, 64 at a time through a private LDS area (pixel-major
+            // bf16 rows): read back, 8 consecutive lanes hold the 128 contiguous bytes of one pixel's 64 channels
+            // and the stores are whole 16-byte pieces of full lines instead of scattered 8-byte ones.
+            unsigned char *stg = lds + g.red_off + w * (64 * 144);
+#pragma unroll
+            for (int half = 0; half < B_T / 2; ++half) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const int j = half * 2 + jj;
+                            uint2 pkd;
+                            pkd.x = pc_pack_bf16x2(acc[ii][j][q4 * 4 + 0], acc[ii][j][q4 * 4 + 1]);
+                            pkd.y = pc_pack_bf16x2(acc[ii][j][q4 * 4 + 2], acc[ii][j][q4 * 4 + 3]);
+                            *reinterpret_cast<uint2 *>(stg + (jj * 32 + (lane & 31)) * 144 + (ii * 32 + q4 * 8 + (lane >> 5) * 4) * 2) = pkd;
+                        }
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    const int px = it * 8 + (lane >> 3), c16 = lane & 7;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + px * 144 + c16 * 16);
+                    const int q = (w * B_T + half * 2) * 32 + px;
+                    const int ti = (int)pc_udiv((uint32_t)q, g.mg_THTW);
+                    const int rem = q - ti * g.TH * g.TW;
+                    const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
+                    const int n = tn + ti, gy = gy0 + y, gx = gx0 + x;
+                    const int m = mt * (32 * A_T) + c16 * 8;
+                    const bool ok = q < npix && n < g.N && gy < g.GH && gx < g.GW && m < g.out_CH;
+                    const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
+                    const uint32_t off = ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) + (uint32_t)(m * 2) : OOB_OUT;
+                    const v4u32 pv = {v.x, v.y, v.z, v.w};
+                    __builtin_amdgcn_raw_buffer_store_b128(pv, osrc, (int)off, 0, 0);
+                }
+            }
+        }
+        if (KSP == 4 && ch == nch - 1) {
+            const int n = tn + o_ti, gy = gy0 + o_y, gx = gx0 + o_x;
+            const bool pix_ok = qo < npix && n < g.N && gy < g.GH && gx < g.GW;
+            const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
+            const uint32_t opix_off = pix_ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) : OOB_OUT;
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
+#pragma unroll
+                for (int o = 0; o < NOWN; ++o) {
+                    if (o != w) continue;
+                    const int tau = r * 4 + o;
+                    const int ti_ = tau / B_T;
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                        for (int ws = 0; ws < 4; ++ws) {
+                            float4 p;
+                            if (ws == o)
+                                p = make_float4(acc[tau / B_T][tau % B_T][q4 * 4 + 0], acc[tau / B_T][tau % B_T][q4 * 4 + 1],
+                                                acc[tau / B_T][tau % B_T][q4 * 4 + 2], acc[tau / B_T][tau % B_T][q4 * 4 + 3]);
+                            else
+                                p = *reinterpret_cast<const float4 *>(red + (((r * NOWN + o) * 3 + (ws < o ? ws : ws - 1)) * 4 + q4) * 256 + lane * 4);
+                            if (ws == 0) s = p;
+                            else { s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w; }
+                        }
+                        // a store past the end of the buffer is dropped: pixels and channels outside the output need no branch
+                        const int m = (mt * A_T + ti_) * 32 + q4 * 8 + (lane >> 5) * 4;
+                        uint2 pkd;
+                        pkd.x = pc_pack_bf16x2(s.x, s.y);
+                        pkd.y = pc_pack_bf16x2(s.z, s.w);
+                        const v2u32 pv = {pkd.x, pkd.y};
+                        __builtin_amdgcn_raw_buffer_store_b64(pv, osrc, (int)((m < g.out_CH ? opix_off : OOB_OUT) + (uint32_t)(m * 2)), 0, 0);
+                    }
+                }
+            }
+        }
+        if (ch == nch - 1) {
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[ii][j][r] = 0.0f;
+        }
+        k = nk; ch = nchk; mt = nmt; tn = ntn; gy0 = ngy0; gx0 = ngx0;
+        ab = abn;
+    }
+}
+
+// ---- wave-specialised kernel: plan and launch (9-tap launches whose channel count is a multiple of 8)
+#define KS_LDS_MAX (160 * 1024)
+
+template <int A_T, int B_T, int KC, int KSP>
+static hipError_t launch_ks(hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out, const uint16_t *wz,
+                            const MfmaArgs &g)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, KS_LDS_MAX);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
+    return hipGetLastError();
+}
+
+// Fills the tile plan; false when the staged tile does not fit. ksp = 4: the MFMA wavefronts split the
+// reduction of a tile of 32*bt pixels (64-channel chunks); ksp = 1: they split a tile of 128*bt pixels
+// (32-channel chunks, no reduction across wavefronts).
+static bool plan_ks(const MfmaArgs &g, int ext, int at, int bt, int ksp, int kc, MfmaArgs *out, size_t *lds_bytes, double *est, int num_cu)
+{
+    const int pitch = 2 * kc + 16, parts = kc / 8, nv = ksp == 4 ? KS_NV : KS_NV1;
+    MfmaArgs t = g;
+    pc_plan_mfma_tiles(&t, (ksp == 4 ? 32 : 128) * bt, ext);
+    const int nt = at * bt, nown = nt >= 4 ? 4 : nt;
+    const int red_bytes = ksp == 4 ? (nt >= 4 ? nt / 4 : 1) * nown * 12288 : 4 * 64 * 144;   // reduction area / store staging
+    // staged pixels: within the loader's registers (nv 16-byte elements per thread) and within LDS
+    int cap = 256 * nv / parts;
+    if (cap > (KS_LDS_MAX - red_bytes - 32) / (2 * pitch)) cap = (KS_LDS_MAX - red_bytes - 32) / (2 * pitch);
+    while (t.TI * t.IH * t.IW > cap) {
+        if (t.TI > 1) --t.TI;
+        else if (t.TH > 1) {
+            t.TH = (t.TH + 1) / 2;
+            t.IH = (t.TH - 1) * t.lstep + ext;
+            t.tiles_y = (t.GH + t.TH - 1) / t.TH;
+        } else return false;
+    }
+    const int HP = t.TI * t.IH * t.IW;
+    t.nelem = HP * parts;
+    t.xbuf = HP * pitch + 16;   // one spare 16-byte slot for the loader threads without an element
+    t.red_off = 2 * t.xbuf;
+    *lds_bytes = (size_t)t.red_off + (size_t)red_bytes;
+    if (*lds_bytes > KS_LDS_MAX) return false;
+    t.m_tiles = (g.out_CH + 32 * at - 1) / (32 * at);
+    const int64_t p_tiles = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x;
+    const int64_t total = p_tiles * t.m_tiles;
+    if (total > (1 << 30)) return false;
+    t.total_tiles = (int)total;
+    // Tiles that follow each other run side by side, mostly on one XCD, and share what their common index
+    // reads through that XCD's L2: the input tile when the row tile runs fastest, the weights of a row
+    // tile when the pixel tile does. The bigger of the two operands is the one to share.
+    const int64_t w_bytes = (int64_t)g.out_CH * g.in_CH * 18, x_bytes = (int64_t)g.N * g.in_H * g.in_W * g.in_CH * 2;
+    t.m_fast = x_bytes >= w_bytes;
+    t.fdiv = t.m_fast ? t.m_tiles : (int)p_tiles;
+    int64_t dmax = t.fdiv > t.tiles_x ? t.fdiv : t.tiles_x;
+    if (t.tiles_y > dmax) dmax = t.tiles_y;
+    if (total * dmax >= ((int64_t)1 << 32)) return false;   // the multiply-high divisions of the tile index stay exact
+    const int64_t in_bytes = (int64_t)g.N * g.in_H * g.in_W * g.in_CH * 2;
+    if (in_bytes >= ((int64_t)1 << 31)) return false;   // 32-bit buffer offsets, with 2^31 as the out-of-range marker
+    t.in_bytes = (uint32_t)in_bytes;
+    const int64_t out_bytes = (int64_t)g.N * g.out_H * g.out_W * g.out_CH * 2;
+    if (out_bytes >= ((int64_t)1 << 31) || (g.out_CH & (ksp == 4 ? 3 : 7))) return false;   // 8- or 16-byte buffer stores
+    t.out_bytes = (uint32_t)out_bytes;
+    auto magic = [](int d) { return pc_udiv_magic(d); };
+    t.mg_IW = magic(t.IW); t.mg_IH = magic(t.IH); t.mg_TW = magic(t.TW); t.mg_THTW = magic(t.TH * t.TW);
+    t.mg_fd = magic(t.fdiv); t.mg_tx = magic(t.tiles_x); t.mg_ty = magic(t.tiles_y);
+    t.nchunks = (g.in_CH + kc - 1) / kc;
+    t.cps = t.nchunks;
+    // cycles of one workgroup: tiles per workgroup x (MFMAs of a tile at 32 cycles each per wavefront + the tile's
+    // fixed cost: the reduction across wavefronts, or just the store)
+    const int64_t rounds = (total + num_cu - 1) / num_cu;
+    // (an item also costs a barrier and the refill of the fragment pipelines: about 450 cycles)
+    if (ksp == 4) *est = (double)rounds * ((double)t.nchunks * (288.0 * at * bt * kc / 64 + 450.0) + 2500.0);
+    else *est = (double)rounds * ((double)t.nchunks * (1152.0 * bt + 450.0) + 1200.0);
+    *out = t;
+    return true;
+}
+
+// PC_OK: launched. PC_ERR_UNSUPPORTED without a message: not applicable, the caller uses the other kernel.
+pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext, const int *tr, const int *tc,
+                              const uint16_t *in, uint16_t *out, const uint16_t *wz, bool *launched)
+{
+    *launched = false;
+    // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
+    enum { NCAND = 6 };
+    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1}, kBt[NCAND] = {4, 2, 1, 4, 1, 1}, kKsp[NCAND] = {4, 4, 4, 1, 4, 4},
+                     kKc[NCAND] = {64, 64, 64, 32, 128, 128}, kCode[NCAND] = {7, 8, 9, 13, 14, 15};
+    MfmaArgs best;
+    size_t best_lds = 0;
+    double best_est = 0.0;
+    int best_k = -1;
+    for (int k = 0; k < NCAND; ++k) {
+        if (pcfg >= 7 && pcfg != kCode[k]) continue;
+        MfmaArgs t;
+        size_t lds;
+        double est;
+        if (!plan_ks(g0, ext, kAt[k], kBt[k], kKsp[k], kKc[k], &t, &lds, &est, ctx->num_cu)) continue;
+        if (best_k < 0 || est < best_est) { best = t; best_lds = lds; best_est = est; best_k = k; }
+    }
+    if (best_k < 0) return PC_OK;
+    // The end-of-tile reduction costs about as much as 64 channels of MFMA work: up to 128 reduction channels
+    // the cooperative kernel's output split is faster, unless every workgroup has a single tile.
+    if (pcfg < 0 && kKsp[best_k] == 4 && (g0.in_CH <= 64 || (g0.in_CH <= 128 && best.total_tiles > ctx->num_cu))) return PC_OK;
+    MfmaArgs g = best;
+    const int pitch = 2 * kKc[best_k] + 16;
+    // the tap list is the full 3x3 in tap order, forward (offset (r, s)) or rotated (offset (2-r, 2-s))
+    for (int t = 0; t < 9; ++t)
+        if (g.tap_w[t] != t || tr[t] != (tr[0] ? 2 - t / 3 : t / 3) || tc[t] != (tc[0] ? 2 - t % 3 : t % 3)) return PC_OK;
+    g.tap_dr = (tr[0] ? -1 : 1) * g.IW * pitch;
+    g.tap_ds = (tc[0] ? -1 : 1) * pitch;
+    g.tap_o0 = (tr[0] * g.IW + tc[0]) * pitch;
+    g.wz_bytes = (uint32_t)((size_t)((g.out_CH + 127) / 128 * 4) * 9 * g.KS * 1024);
+    const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;
+    hipError_t e;
+    switch (best_k) {
+    case 0: e = launch_ks<2, 4, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 1: e = launch_ks<2, 2, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 2: e = launch_ks<2, 1, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 3: e = launch_ks<2, 4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 4: e = launch_ks<2, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<1, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    }
+    *launched = true;
+    return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");
+}
