@@ -89,7 +89,8 @@ pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
  *   0..6   forward/backward-data: a tile shape of the cooperative kernel
  *   7..9   forward/backward-data: the persistent wave-specialised kernel, reduction split over its MFMA
  *          wavefronts, tiles of 64 output channels x 128, 64, 32 pixels
- *   13     the same kernel with the pixels split over the wavefronts (64 x 512 tiles, 32-channel chunks)
+ *   13, 16 the same kernel with the pixels split over the wavefronts (64 x 512 and 64 x 256 tiles,
+ *          32-channel chunks)
  *   14, 15 as 9 with 128-channel chunks, and with tiles of 32 output channels x 32 pixels
  *   10, 11 backward-weight: the cooperative / the wave-specialised kernel (the other passes stay automatic)
  * The wave-specialised forward/backward-data kernel takes 9-tap launches only: the tap subsets of a strided

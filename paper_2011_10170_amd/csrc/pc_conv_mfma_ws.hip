@@ -471,9 +471,9 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
 {
     *launched = false;
     // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
-    enum { NCAND = 6 };
-    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1}, kBt[NCAND] = {4, 2, 1, 4, 1, 1}, kKsp[NCAND] = {4, 4, 4, 1, 4, 4},
-                     kKc[NCAND] = {64, 64, 64, 32, 128, 128}, kCode[NCAND] = {7, 8, 9, 13, 14, 15};
+    enum { NCAND = 7 };
+    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1, 2}, kBt[NCAND] = {4, 2, 1, 4, 1, 1, 2}, kKsp[NCAND] = {4, 4, 4, 1, 4, 4, 1},
+                     kKc[NCAND] = {64, 64, 64, 32, 128, 128, 32}, kCode[NCAND] = {7, 8, 9, 13, 14, 15, 16};
     MfmaArgs best;
     size_t best_lds = 0;
     double best_est = 0.0;
@@ -507,7 +507,8 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
     case 2: e = launch_ks<2, 1, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
     case 3: e = launch_ks<2, 4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
     case 4: e = launch_ks<2, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    default: e = launch_ks<1, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 5: e = launch_ks<1, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<2, 2, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
     }
     *launched = true;
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");
