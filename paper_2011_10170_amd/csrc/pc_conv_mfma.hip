@@ -299,6 +299,48 @@ pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W)
     return pc_hip_check(ctx, hipGetLastError(), "pack tiles launch");
 }
 
+// xp[pixel][0..Cp) = x[pixel][0..C), zero above: a copy whose pixel rows are 16-byte aligned groups of 8 channels
+__global__ void __launch_bounds__(256)
+pc_pad_channels_kernel(const uint16_t *__restrict__ x, uint4 *__restrict__ xp, int64_t npix, int C, int Cp)
+{
+    const int gpp = Cp / 8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= npix * gpp) return;
+    const int64_t p = i / gpp;
+    const int c0 = (int)(i - p * gpp) * 8;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (c0 + e < C) w[e >> 1] |= (uint32_t)x[p * C + c0 + e] << ((e & 1) * 16);
+    xp[i] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+void pc_launch_pad_channels(pc_ctx *ctx, const uint16_t *x, void *xp, int64_t npix, int C, int Cp)
+{
+    const int64_t n16 = npix * (Cp / 8);
+    hipLaunchKernelGGL(pc_pad_channels_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, ctx->stream, x,
+                       reinterpret_cast<uint4 *>(xp), npix, C, Cp);
+}
+
+// y[pixel][0..C) = yp[pixel][0..C) for rows of Cp = 8 channels (C < 8): the inverse of the copy above
+__global__ void __launch_bounds__(256)
+pc_unpad_channels_kernel(const uint4 *__restrict__ yp, uint16_t *__restrict__ y, int64_t npix, int C)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= npix) return;
+    const uint4 v = yp[p];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (e < C) y[p * C + e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+}
+
+void pc_launch_unpad_channels(pc_ctx *ctx, const void *yp, uint16_t *y, int64_t npix, int C)
+{
+    hipLaunchKernelGGL(pc_unpad_channels_kernel, dim3((unsigned)((npix + 255) / 256)), dim3(256), 0, ctx->stream,
+                       reinterpret_cast<const uint4 *>(yp), y, npix, C);
+}
+
 // ------------------------------------------------------------------ planning and launch
 struct MfmaCfg { int a, b, wm, wn, kc; };
 static const MfmaCfg kCfgs[] = {
@@ -344,10 +386,39 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
                                const uint16_t *in, uint16_t *out, const uint16_t *wz)
 {
     int plan_cfg = (ctx->plan_cfg >= 10 && ctx->plan_cfg < 13) ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
-    if (ntaps == 9 && (g.in_CH & 7) == 0 && g.in_CH >= 32 && (plan_cfg < 0 || plan_cfg >= 7) && ctx->plan_split == 0) {
-        bool launched = false;
-        pc_status s = pc_run_mfma_conv_ws(ctx, plan_cfg, g, ext, tr, tc, in, out, wz, &launched);
-        if (launched || s != PC_OK) return s;
+    if (ntaps == 9 && (plan_cfg < 0 || plan_cfg >= 7) && ctx->plan_split == 0) {
+        // The wave-specialised kernel reads and writes whole groups of 8 channels. The first layer's few channels
+        // (input of the forward pass, output of the backward-data pass) go through a copy with 8-channel rows.
+        MfmaArgs gw = g;
+        const uint16_t *inw = in;
+        uint16_t *outw = out;
+        const int64_t in_pix = (int64_t)g.N * g.in_H * g.in_W, out_pix = (int64_t)g.N * g.out_H * g.out_W;
+        // (for the input the copy pays off on large images only: on 32x32 inputs the cooperative kernel's element-wise
+        // staging of 3 channels is as fast as copy + kernel)
+        const bool pad_in = g.in_CH < 8 && (in_pix >= 300000 || plan_cfg >= 7), pad_out = g.out_CH < 8 && g.oscale == 1;
+        if (pad_in || pad_out) {
+            void *scr = nullptr;
+            pc_status s = pc_scratch(ctx, (size_t)16 * (size_t)((pad_in ? in_pix : 0) + (pad_out ? out_pix : 0)), &scr);
+            if (s != PC_OK) return s;
+            if (pad_in) {
+                pc_launch_pad_channels(ctx, in, scr, in_pix, g.in_CH, 8);
+                inw = static_cast<const uint16_t *>(scr);
+                gw.in_CH = 8;
+            }
+            if (pad_out) {
+                outw = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(scr) + (pad_in ? 16 * in_pix : 0));
+                gw.out_CH = 8;
+            }
+        }
+        if ((gw.in_CH & 7) == 0 && (gw.in_CH >= 32 || pad_in)) {
+            bool launched = false;
+            pc_status s = pc_run_mfma_conv_ws(ctx, plan_cfg, gw, ext, tr, tc, inw, outw, wz, &launched);
+            if (s != PC_OK) return s;
+            if (launched) {
+                if (pad_out) pc_launch_unpad_channels(ctx, outw, out, out_pix, g.out_CH);
+                return pc_hip_check(ctx, hipGetLastError(), "channel copy launch");
+            }
+        }
     }
     if (plan_cfg >= 7) {   // forced wave-specialised kernel: launches it cannot take (tap subsets) use the automatic choice
         if (ntaps == 9) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA conv: the wave-specialised kernel does not fit this launch");

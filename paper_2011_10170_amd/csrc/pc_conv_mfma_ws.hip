@@ -327,7 +327,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                     const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
                     const int n = tn + ti, gy = gy0 + y, gx = gx0 + x;
                     const int m = mt * (32 * A_T) + c16 * 8;
-                    const bool ok = q < npix && n < g.N && gy < g.GH && gx < g.GW && m < g.out_CH;
+                    const bool ok = q < npix && n < g.N && gy < g.GH && gx < g.GW && m < g.out_CH && c16 < 4 * A_T;
                     const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
                     const uint32_t off = ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) + (uint32_t)(m * 2) : OOB_OUT;
                     const v4u32 pv = {v.x, v.y, v.z, v.w};
@@ -460,7 +460,7 @@ static bool plan_ks(const MfmaArgs &g, int ext, int at, int bt, int ksp, int kc,
     const int64_t rounds = (total + num_cu - 1) / num_cu;
     // (an item also costs a barrier and the refill of the fragment pipelines: about 450 cycles)
     if (ksp == 4) *est = (double)rounds * ((double)t.nchunks * (288.0 * at * bt * kc / 64 + 450.0) + 2500.0);
-    else *est = (double)rounds * ((double)t.nchunks * (1152.0 * bt + 450.0) + 1200.0);
+    else *est = (double)rounds * ((double)t.nchunks * (18.0 * kc * at * bt + 450.0) + 1200.0);
     *out = t;
     return true;
 }
@@ -471,15 +471,18 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
 {
     *launched = false;
     // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
-    enum { NCAND = 7 };
-    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1, 2}, kBt[NCAND] = {4, 2, 1, 4, 1, 1, 2}, kKsp[NCAND] = {4, 4, 4, 1, 4, 4, 1},
-                     kKc[NCAND] = {64, 64, 64, 32, 128, 128, 32}, kCode[NCAND] = {7, 8, 9, 13, 14, 15, 16};
+    enum { NCAND = 10 };
+    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1, 2, 2, 2, 1}, kBt[NCAND] = {4, 2, 1, 4, 1, 1, 2, 4, 2, 4},
+                     kKsp[NCAND] = {4, 4, 4, 1, 4, 4, 1, 1, 1, 1}, kKc[NCAND] = {64, 64, 64, 32, 128, 128, 32, 16, 16, 32},
+                     kCode[NCAND] = {7, 8, 9, 13, 14, 15, 16, 17, 18, 19};
     MfmaArgs best;
     size_t best_lds = 0;
     double best_est = 0.0;
     int best_k = -1;
     for (int k = 0; k < NCAND; ++k) {
         if (pcfg >= 7 && pcfg != kCode[k]) continue;
+        // 16-channel chunks are for the few input channels of a first layer, 32-row tiles for its few output channels
+        if (pcfg < 0 && ((kKc[k] == 16) != (g0.in_CH <= 16) || (kAt[k] == 1 && kKsp[k] == 1) != (g0.out_CH <= 32))) continue;
         MfmaArgs t;
         size_t lds;
         double est;
@@ -508,7 +511,10 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
     case 3: e = launch_ks<2, 4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
     case 4: e = launch_ks<2, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
     case 5: e = launch_ks<1, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    default: e = launch_ks<2, 2, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 6: e = launch_ks<2, 2, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 7: e = launch_ks<2, 4, 16, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 8: e = launch_ks<2, 2, 16, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<1, 4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
     }
     *launched = true;
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");

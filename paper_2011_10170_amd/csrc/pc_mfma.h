@@ -41,4 +41,8 @@ void pc_plan_mfma_tiles(MfmaArgs *g, int BN, int ext);
 // wins, >= 7 = the forced variant. *launched stays false when the launch is left to the cooperative kernel.
 pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext, const int *tr, const int *tc,
                               const uint16_t *in, uint16_t *out, const uint16_t *wz, bool *launched);
+
+// Copies between a tensor with C < 8 channels per pixel and one with 8-channel (16-byte) pixel rows.
+void pc_launch_pad_channels(pc_ctx *ctx, const uint16_t *x, void *xp, int64_t npix, int C, int Cp);
+void pc_launch_unpad_channels(pc_ctx *ctx, const void *yp, uint16_t *y, int64_t npix, int C);
 #endif

@@ -544,22 +544,6 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 
 }
 
-// xp[pixel][0..Cp) = x[pixel][0..C), zero above: a copy whose pixel rows are 16-byte aligned groups of 8 channels
-__global__ void __launch_bounds__(256)
-pc_pad_channels_kernel(const uint16_t *__restrict__ x, uint4 *__restrict__ xp, int64_t npix, int C, int Cp)
-{
-    const int gpp = Cp / 8;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= npix * gpp) return;
-    const int64_t p = i / gpp;
-    const int c0 = (int)(i - p * gpp) * 8;
-    uint32_t w[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-        if (c0 + e < C) w[e >> 1] |= (uint32_t)x[p * C + c0 + e] << ((e & 1) * 16);
-    xp[i] = make_uint4(w[0], w[1], w[2], w[3]);
-}
-
 // Wave-specialised backward-weight: plan and launch. *launched stays false when the layer is outside what
 // that kernel takes (the caller then uses the cooperative kernel).
 static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
@@ -639,10 +623,8 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
         if (s != PC_OK) return s;
     }
     if (pad_x) {
-        uint4 *xp = reinterpret_cast<uint4 *>(static_cast<unsigned char *>(scr) + part_bytes);
-        const int64_t npix = (int64_t)a.N * a.H * a.W, n16 = npix * (a.C / 8);
-        hipLaunchKernelGGL(pc_pad_channels_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, ctx->stream,
-                           (const uint16_t *)x, xp, npix, a.Creal, a.C);
+        void *xp = static_cast<unsigned char *>(scr) + part_bytes;
+        pc_launch_pad_channels(ctx, (const uint16_t *)x, xp, (int64_t)a.N * a.H * a.W, a.Creal, a.C);
         x = xp;
     }
     static bool attr_done = false;
