@@ -130,8 +130,8 @@ def main() -> int:
                     events.append((li, which, e0, e1))
 
     # The step is launch-bound on the host (dozens of short kernels), so it is captured once into a HIP graph
-    # and replayed; steps with re-selection read the kept-kernel count back and cannot be captured.
-    use_graph = not args.no_graph and not wl.with_select
+    # and replayed; no call of the step reads anything back to the host, re-selection and re-packing included.
+    use_graph = not args.no_graph
     for _ in range(max(1, args.warmup if not use_graph else 1)):
         step()
     torch.cuda.synchronize()

@@ -197,6 +197,7 @@ static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
     v->Ck = (C + 63) / 64 * 64;
     v->fm_rowptr = (int32_t *)take(sizeof(int32_t) * (F + 1));
     v->fm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)F * (PC_MAX_P + 1));
+    v->fm_rowtot = (int32_t *)take(sizeof(int32_t) * F);
     v->fm_c = (uint16_t *)take(sizeof(uint16_t) * cap);
     v->fm_pid = (uint8_t *)take(cap);
     v->slot_f = (uint16_t *)take(sizeof(uint16_t) * cap);
@@ -205,6 +206,7 @@ static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
     v->kinfo = (uint32_t *)take(sizeof(uint32_t) * cap);
     v->cm_rowptr = (int32_t *)take(sizeof(int32_t) * (C + 1));
     v->cm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)C * (PC_MAX_P + 1));
+    v->cm_rowtot = (int32_t *)take(sizeof(int32_t) * C);
     v->cm_f = (uint16_t *)take(sizeof(uint16_t) * cap);
     v->cm_slot = (int32_t *)take(sizeof(int32_t) * cap);
     v->cm_val = (float4 *)take(sizeof(float4) * cap);
@@ -287,7 +289,18 @@ extern "C" pc_status pc_pack(pc_ctx *ctx, const float *W, const uint8_t *pid, co
     pc_fill_lib(&la, lib, P);
     memcpy(pk->taps, la.taps, sizeof(pk->taps));
     s = pc_launch_pack(ctx, pk, W, pid, keep);
-    if (s == PC_OK) s = pc_hip_check(ctx, hipEventRecord(pk->packed_evt, ctx->stream), "hipEventRecord");
+    // An event recorded while the stream is being captured into a graph cannot be waited on afterwards, so a
+    // captured pack records none; pc_packed_info then waits for the context's stream instead.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(ctx->stream, &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        cap = hipStreamCaptureStatusNone;
+    }
+    pk->evt_recorded = false;
+    if (s == PC_OK && cap == hipStreamCaptureStatusNone) {
+        s = pc_hip_check(ctx, hipEventRecord(pk->packed_evt, ctx->stream), "hipEventRecord");
+        pk->evt_recorded = s == PC_OK;
+    }
     if (s != PC_OK) {
         if (!*out) pc_packed_free(pk);
         return s;
@@ -313,7 +326,8 @@ extern "C" pc_status pc_packed_info(pc_ctx *ctx, const pc_packed *pk, int64_t *n
         pc_packed *m = const_cast<pc_packed *>(pk);
         if (m->nnzk < 0) {
             PC_HIP(ctx, hipSetDevice(ctx->device));
-            PC_HIP(ctx, hipEventSynchronize(pk->packed_evt));
+            if (pk->evt_recorded) PC_HIP(ctx, hipEventSynchronize(pk->packed_evt));
+            else PC_HIP(ctx, hipStreamSynchronize(ctx->stream));
             int32_t n = 0;
             PC_HIP(ctx, hipMemcpy(&n, pk->v.fm_rowptr + pk->v.F, sizeof(int32_t), hipMemcpyDeviceToHost));
             m->nnzk = n;

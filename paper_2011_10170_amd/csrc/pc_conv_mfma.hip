@@ -245,60 +245,7 @@ pc_mfma_splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int
 }
 
 
-// ------------------------------------------------------------------ operand tiles
-// wz_fwd[mt][tap][ks][lane][8]: mt = filter/32, ks = channel/16; element i of lane l is
-// w[f = 32*mt + l%32][c = 16*ks + 8*(l/32) + i][tap], zero when pruned or padded.
-// wz_bwd has the roles of filter and channel exchanged (rows = channels, k = filters).
-__global__ void __launch_bounds__(256)
-pc_pack_tiles_kernel(const float *__restrict__ W, LibArg la, PackView v, int64_t total_fwd)
-{
-    // one launch fills both operands: the first total_fwd threads wz_fwd, the others wz_bwd
-    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int bwd = idx >= total_fwd;
-    if (bwd) idx -= total_fwd;
-    const int Mp = bwd ? v.Cp : v.Fp;          // padded row count (multiple of 128)
-    const int KS = (bwd ? v.Fk : v.Ck) / 16;   // padded reduction length / 16
-    int64_t total = (int64_t)(Mp / 32) * 9 * KS * 64;
-    if (idx >= total) return;
-    int lane = (int)(idx & 63);
-    int64_t r = idx >> 6;
-    int ks = (int)(r % KS); r /= KS;
-    int tap = (int)(r % 9);
-    int mt = (int)(r / 9);
-    int m = mt * 32 + (lane & 31);
-    int k0 = ks * 16 + (lane >> 5) * 8;
-    uint16_t o[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int k = k0 + i;
-        int f = bwd ? k : m, c = bwd ? m : k;
-        uint16_t val = 0;
-        if (f < v.F && c < v.C) {
-            int slot = v.slot_of[(int64_t)f * v.C + c];
-            if (slot >= 0 && (la.mask[v.fm_pid[slot]] >> tap) & 1u)
-                val = pc_f32_to_bf16(W[((int64_t)f * v.C + c) * 9 + tap]);
-        }
-        o[i] = val;
-    }
-    uint4 pk;
-    pk.x = o[0] | ((uint32_t)o[1] << 16);
-    pk.y = o[2] | ((uint32_t)o[3] << 16);
-    pk.z = o[4] | ((uint32_t)o[5] << 16);
-    pk.w = o[6] | ((uint32_t)o[7] << 16);
-    reinterpret_cast<uint4 *>(bwd ? v.wz_bwd : v.wz_fwd)[idx] = pk;
-}
-
-pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W)
-{
-    PackView v = pk->v;
-    LibArg la;
-    pc_fill_lib(&la, pk->lib, v.P);
-    const int64_t total_fwd = (int64_t)(v.Fp / 32) * 9 * (v.Ck / 16) * 64, total_bwd = (int64_t)(v.Cp / 32) * 9 * (v.Fk / 16) * 64;
-    hipLaunchKernelGGL(pc_pack_tiles_kernel, dim3((unsigned)((total_fwd + total_bwd + 255) / 256)), dim3(256), 0, ctx->stream,
-                       W, la, v, total_fwd);
-    return pc_hip_check(ctx, hipGetLastError(), "pack tiles launch");
-}
-
+// ------------------------------------------------------------------ channel padding copies
 // xp[pixel][0..Cp) = x[pixel][0..C), zero above: a copy whose pixel rows are 16-byte aligned groups of 8 channels
 __global__ void __launch_bounds__(256)
 pc_pad_channels_kernel(const uint16_t *__restrict__ x, uint4 *__restrict__ xp, int64_t npix, int C, int Cp)

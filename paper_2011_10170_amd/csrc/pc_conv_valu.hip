@@ -345,27 +345,34 @@ pc_wgrad_valu_kernel(const T *__restrict__ x, const T *__restrict__ dy, WgradArg
     if (live) partial[(int64_t)blockIdx.y * nnzk + slot] = make_float4(acc0, acc1, acc2, acc3);
 }
 
-// dw[slot] = sum over g of partial[g][slot] in a fixed order: 16 consecutive slots per workgroup,
-// 16 threads per slot each adding every 16th partial, then one thread adds the 16 sub-sums in order.
+// dw[slot] = sum over g of partial[g][slot] in a fixed order: TPS threads per slot each add every TPS-th
+// partial (ascending), then one thread adds the TPS sub-sums in order. 256 / TPS consecutive slots per workgroup.
+// partial is [G][pstride] float4; the number of live slots is read on the device.
+template <int TPS>
 __global__ void __launch_bounds__(256)
-pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, PackView v, float4 *__restrict__ dw)
+pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, int64_t pstride, PackView v, float4 *__restrict__ dw)
 {
-    __shared__ float4 sub[16][16];
+    constexpr int SPB = 256 / TPS;
+    __shared__ float4 sub[TPS > 1 ? TPS : 1][TPS > 1 ? SPB : 1];
     const int nnzk = v.fm_rowptr[v.F];
-    const int q = threadIdx.x & 15, sg = threadIdx.x >> 4;
-    const int slot = blockIdx.x * 16 + q;
+    const int q = threadIdx.x % SPB, sg = threadIdx.x / SPB;
+    const int64_t slot = (int64_t)blockIdx.x * SPB + q;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     if (slot < nnzk) {
-        for (int gi = sg; gi < G; gi += 16) {
-            float4 p = partial[(int64_t)gi * nnzk + slot];
+        for (int gi = sg; gi < G; gi += TPS) {
+            float4 p = partial[(int64_t)gi * pstride + slot];
             s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
         }
+    }
+    if (TPS == 1) {
+        if (slot < nnzk) dw[slot] = s;
+        return;
     }
     sub[sg][q] = s;
     __syncthreads();
     if (sg == 0 && slot < nnzk) {
         float4 t = sub[0][q];
-        for (int i = 1; i < 16; ++i) {
+        for (int i = 1; i < TPS; ++i) {
             float4 p = sub[i][q];
             t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
         }
@@ -373,13 +380,22 @@ pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, PackView v, fl
     }
 }
 
-// dw[slot] = partial[0][slot] + partial[1][slot] + ... in that order (partial is [G][nnzk][4] float32)
-pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, const pc_packed *pk, float *dw)
+// nslots bounds the live slots from above (the exact count when the host knows it, else the pack's capacity)
+pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, int64_t pstride, int64_t nslots,
+                                 const pc_packed *pk, float *dw)
 {
-    int64_t nnzk = pk->nnzk;
-    if (nnzk <= 0) return PC_OK;
-    hipLaunchKernelGGL(pc_wgrad_reduce_kernel, dim3((unsigned)((nnzk + 15) / 16)), dim3(256), 0, ctx->stream,
-                       (const float4 *)partial, G, pk->v, (float4 *)dw);
+    if (nslots <= 0) return PC_OK;
+    const float4 *pp = (const float4 *)partial;
+    float4 *out = (float4 *)dw;
+    if (G >= 32)
+        hipLaunchKernelGGL(pc_wgrad_reduce_kernel<16>, dim3((unsigned)((nslots + 15) / 16)), dim3(256), 0, ctx->stream, pp, G,
+                           pstride, pk->v, out);
+    else if (G >= 8)
+        hipLaunchKernelGGL(pc_wgrad_reduce_kernel<4>, dim3((unsigned)((nslots + 63) / 64)), dim3(256), 0, ctx->stream, pp, G,
+                           pstride, pk->v, out);
+    else
+        hipLaunchKernelGGL(pc_wgrad_reduce_kernel<1>, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, ctx->stream, pp, G,
+                           pstride, pk->v, out);
     return pc_hip_check(ctx, hipGetLastError(), "bwd_weight reduce launch");
 }
 
@@ -422,5 +438,5 @@ pc_status pc_valu_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
                            (const uint16_t *)dy, a, pk->v, (float4 *)scr);
     s = pc_hip_check(ctx, hipGetLastError(), "VALU bwd_weight launch");
     if (s != PC_OK) return s;
-    return pc_launch_wgrad_reduce(ctx, (const float *)scr, G, pk, dw);
+    return pc_launch_wgrad_reduce(ctx, (const float *)scr, G, nnzk, nnzk, pk, dw);
 }

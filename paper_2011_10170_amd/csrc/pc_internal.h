@@ -30,6 +30,7 @@ struct PackView {
     // filter-major table: rows = filters, kernels ordered (pattern id, channel)
     int32_t *fm_rowptr;   // [F+1]   slot range of filter f
     int32_t *fm_grp;      // [F][P+1] first slot of pattern group p in filter f; [P] = row end
+    int32_t *fm_rowtot;   // [F]     kept kernels of filter f (pack-time intermediate)
     uint16_t *fm_c;       // [cap]   input channel of the slot
     uint8_t *fm_pid;      // [cap]   pattern id of the slot
     uint16_t *slot_f;     // [cap]   filter of the slot
@@ -39,6 +40,7 @@ struct PackView {
     // channel-major table for backward-data: rows = channels, kernels ordered (pattern id, filter)
     int32_t *cm_rowptr;   // [C+1]
     int32_t *cm_grp;      // [C][P+1]
+    int32_t *cm_rowtot;   // [C]     kept kernels of channel c (pack-time intermediate)
     uint16_t *cm_f;       // [cap]
     int32_t *cm_slot;     // [cap]   filter-major slot of the entry
     float4 *cm_val;       // [cap]
@@ -59,6 +61,7 @@ struct pc_packed {
     size_t slab_bytes;
     PackView v;
     hipEvent_t packed_evt;       // recorded after the last pack on this handle
+    bool evt_recorded;           // false when that pack was enqueued under stream capture (no event then)
     int64_t nnzk;                // -1 until read back
 };
 
@@ -92,7 +95,8 @@ pc_status pc_valu_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
 pc_status pc_valu_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,
                              const void *dy, float *dw);
 
-pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, const pc_packed *pk, float *dw);
+pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, int64_t pstride, int64_t nslots,
+                                 const pc_packed *pk, float *dw);
 
 bool pc_mfma_supports(int F, int C);
 pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W);

@@ -5,6 +5,37 @@
 #include "pc_internal.h"
 
 // ------------------------------------------------------------------ selection
+// Tap importances of one kernel -> best pattern of the pool and the ranking score. Every sum is taken in
+// ascending tap order, one rounded float32 addition at a time. The importances are squares, so none is below +0
+// and adding +0 for a tap outside the pattern changes no bit: the 9 unconditional additions below give exactly
+// ((s_a + s_b) + s_c) + s_d of the pattern's taps a < b < c < d. masks may point to kernel arguments or LDS.
+__device__ __forceinline__ void pc_score_taps(const float (&s)[9], const uint16_t *masks, int P, int score_mode,
+                                              int *pid_out, float *rank_out)
+{
+    int best = 0;
+    float best_score = 0.0f;
+#pragma unroll 2
+    for (int p = 0; p < P; ++p) {
+        const unsigned m = masks[p];
+        float acc = 0.0f;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc = acc + (((m >> t) & 1u) ? s[t] : 0.0f);
+        if (p == 0 || acc > best_score) {
+            best_score = acc;
+            best = p;
+        }
+    }
+    *pid_out = best;
+    if (score_mode == PC_SCORE_KERNEL) {
+        float acc = s[0];
+#pragma unroll
+        for (int t = 1; t < 9; ++t) acc = acc + s[t];
+        *rank_out = acc;
+    } else {
+        *rank_out = best_score;
+    }
+}
+
 // One thread per kernel (f,c): 9 tap importances, the best pattern of the pool, the ranking score.
 __global__ void __launch_bounds__(256)
 pc_select_score_kernel(const float *__restrict__ W, const float *__restrict__ G, int64_t nk, LibArg la,
@@ -23,33 +54,11 @@ pc_select_score_kernel(const float *__restrict__ W, const float *__restrict__ G,
             s[t] = w * w;
         }
     }
-    int best = 0;
-    float best_score = 0.0f;
-    for (int p = 0; p < la.P; ++p) {
-        unsigned m = la.mask[p];
-        float acc = 0.0f;
-        bool first = true;
-#pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            if (m & (1u << t)) {
-                acc = first ? s[t] : acc + s[t];
-                first = false;
-            }
-        }
-        if (p == 0 || acc > best_score) {
-            best_score = acc;
-            best = p;
-        }
-    }
+    int best;
+    float r;
+    pc_score_taps(s, la.mask, la.P, score_mode, &best, &r);
     pid[k] = (uint8_t)best;
-    if (score_mode == PC_SCORE_KERNEL) {
-        float acc = s[0];
-#pragma unroll
-        for (int t = 1; t < 9; ++t) acc = acc + s[t];
-        R[k] = acc;
-    } else {
-        R[k] = best_score;
-    }
+    R[k] = r;
 }
 
 // Exact rank inside a segment of length L: element i is kept iff fewer than n_keep elements
@@ -157,10 +166,142 @@ pc_select_topn_row_kernel(const float *__restrict__ R, int L, int n_keep, uint8_
     }
 }
 
+// Selection of one filter row in one workgroup (rows of up to PC_TOPN_MAX kernels): scores as in the kernel
+// above, then the top n_keep of the row by the same radix select, without the round trip of the scores through
+// memory. W and G reach the lanes through LDS so that the global loads are contiguous.
+__global__ void __launch_bounds__(512)
+pc_select_row_kernel(const float *__restrict__ W, const float *__restrict__ G, int C, LibArg la, int score_mode,
+                     int n_keep, uint8_t *__restrict__ pid, uint8_t *__restrict__ keep)
+{
+    extern __shared__ uint32_t dyn[];           // C keys, then blockDim.x * 9 floats of W, then as many of G
+    __shared__ int hist[256];
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_remaining, s_wave_cnt[16], s_base;
+    __shared__ uint16_t s_mask[PC_MAX_P + 2];
+    const int T = blockDim.x, tid = threadIdx.x;
+    if (tid < la.P) s_mask[tid] = la.mask[tid];   // visible after the first barrier of the loop below
+    uint32_t *keys = dyn;
+    float *sw = reinterpret_cast<float *>(dyn + C);
+    float *sg = sw + (size_t)T * 9;
+    const int64_t row0 = (int64_t)blockIdx.x * C;
+    for (int c0 = 0; c0 < C; c0 += T) {
+        const int n = C - c0 < T ? C - c0 : T;
+        const float *wsrc = W + (row0 + c0) * 9;
+        const float *gsrc = G ? G + (row0 + c0) * 9 : nullptr;
+        if (c0) __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+            const int i = j * T + tid;
+            if (i < n * 9) {
+                sw[i] = wsrc[i];
+                if (gsrc) sg[i] = gsrc[i];
+            }
+        }
+        __syncthreads();
+        if (tid < n) {
+            float s[9];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const float w = sw[tid * 9 + t];
+                if (gsrc) {
+                    const float gw = sg[tid * 9 + t] * w;
+                    s[t] = gw * gw;
+                } else {
+                    s[t] = w * w;
+                }
+            }
+            int best;
+            float r;
+            pc_score_taps(s, s_mask, la.P, score_mode, &best, &r);
+            pid[row0 + c0 + tid] = (uint8_t)best;
+            keys[c0 + tid] = pc_order_key(r);
+        }
+    }
+    uint8_t *out = keep + row0;
+    if (n_keep <= 0 || n_keep >= C) {
+        for (int i = tid; i < C; i += T) out[i] = n_keep > 0 ? 1 : 0;
+        return;
+    }
+    if (tid == 0) { s_prefix = 0u; s_remaining = n_keep; }
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();                        // also orders the keys / s_prefix writes before their readers
+        const uint32_t prefix = s_prefix;
+        const uint32_t himask = shift == 24 ? 0u : 0xFFFFFFFFu << (shift + 8);
+        for (int i = tid; i < C; i += T) {
+            const uint32_t k = keys[i];
+            if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // lane l owns digits 4l..4l+3; hi = candidates with a digit above the lane's four
+            const int h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+            const int mine = h0 + h1 + h2 + h3;
+            int incl = mine;
+            for (int off = 1; off < 64; off <<= 1) {
+                const int t = __shfl_down(incl, off);
+                if (lane + off < 64) incl += t;
+            }
+            const int rem = s_remaining;
+            const int hi = incl - mine;
+            // exactly one digit d has (candidates above d) < rem <= (candidates above d) + hist[d]
+            const int e3 = hi, e2 = e3 + h3, e1 = e2 + h2, e0 = e1 + h1;
+            int d = -1, ex = 0;
+            if (e3 < rem && rem <= e3 + h3) { d = 3; ex = e3; }
+            else if (e2 < rem && rem <= e2 + h2) { d = 2; ex = e2; }
+            else if (e1 < rem && rem <= e1 + h1) { d = 1; ex = e1; }
+            else if (e0 < rem && rem <= e0 + h0) { d = 0; ex = e0; }
+            if (d >= 0) {
+                s_prefix = prefix | ((uint32_t)(4 * lane + d) << shift);
+                s_remaining = rem - ex;
+            }
+        }
+        __syncthreads();
+    }
+    const uint32_t Tk = s_prefix;
+    const int take_equal = s_remaining;         // kernels with key == Tk that are kept: the first ones by index
+    const int nwaves = T >> 6;
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < C; i0 += T) {
+        const int i = i0 + tid;
+        const uint32_t k = i < C ? keys[i] : 0u;
+        const bool eq = i < C && k == Tk;
+        const unsigned long long b = __ballot(eq);
+        if (lane == 0) s_wave_cnt[wave] = __popcll(b);
+        __syncthreads();
+        int before = s_base + __popcll(b & ((1ull << lane) - 1ull));
+        for (int w2 = 0; w2 < wave; ++w2) before += s_wave_cnt[w2];
+        if (i < C) out[i] = (k > Tk || (eq && before < take_equal)) ? 1 : 0;
+        __syncthreads();
+        if (tid == 0) {
+            int add = 0;
+            for (int w2 = 0; w2 < nwaves; ++w2) add += s_wave_cnt[w2];
+            s_base += add;
+        }
+        __syncthreads();
+    }
+}
+
 pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, int C, const LibArg &la,
                            pc_keep_mode km, int64_t n_keep, pc_score_mode sm, uint8_t *pid, uint8_t *keep)
 {
     int64_t nk = (int64_t)F * C;
+    if (km == PC_KEEP_PER_FILTER && C <= PC_TOPN_MAX) {
+        const int T = C <= 256 ? 256 : 512;
+        const size_t lds = sizeof(uint32_t) * (size_t)C + 2 * sizeof(float) * 9 * (size_t)T;   // at most 68 KiB
+        static bool attr_done = false;
+        if (!attr_done) {
+            PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_select_row_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)(sizeof(uint32_t) * PC_TOPN_MAX + 2 * sizeof(float) * 9 * 512)));
+            attr_done = true;
+        }
+        const int nk_row = (int)(n_keep < C ? n_keep : C);
+        hipLaunchKernelGGL(pc_select_row_kernel, dim3((unsigned)F), dim3((unsigned)T), lds, ctx->stream, W, G, C, la, (int)sm,
+                           nk_row, pid, keep);
+        return pc_hip_check(ctx, hipGetLastError(), "select launch");
+    }
     void *scr = nullptr;
     pc_status s = pc_scratch(ctx, sizeof(float) * (size_t)nk, &scr);
     if (s != PC_OK) return s;
@@ -182,15 +323,17 @@ pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, i
 // ------------------------------------------------------------------ packing
 // Table rows are filters (row stride C, element stride 1 in the [F][C] maps) for the
 // filter-major table, channels (row stride 1, element stride C) for the channel-major one.
+//
+// A pack is two launches. The first counts the kept kernels of every table row per pattern id and, for the
+// matrix-core variant, writes the operand tiles (they depend on W and the masks only). The second places the
+// kernels: every workgroup adds up the totals of the rows before its own, so no separate scan is needed.
 
-// Kept kernels of every row, per pattern id.
-__global__ void __launch_bounds__(256)
-pc_pack_count_kernel(const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep, int rows, int len,
-                     int64_t row_stride, int64_t elem_stride, int P, int32_t *__restrict__ grp,
-                     int32_t *__restrict__ rowptr)
+// Kept kernels of one row, per pattern id, and their total.
+__device__ __forceinline__ void pc_pack_count_row(const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep, int row,
+                                                  int len, int64_t row_stride, int64_t elem_stride, int P,
+                                                  int32_t *__restrict__ grp, int32_t *__restrict__ rowtot)
 {
     __shared__ int hist[PC_MAX_P + 1];
-    int row = blockIdx.x;
     for (int p = threadIdx.x; p <= PC_MAX_P; p += blockDim.x) hist[p] = 0;
     __syncthreads();
     for (int e = threadIdx.x; e < len; e += blockDim.x) {
@@ -199,105 +342,226 @@ pc_pack_count_kernel(const uint8_t *__restrict__ pid, const uint8_t *__restrict_
     }
     __syncthreads();
     for (int p = threadIdx.x; p < P; p += blockDim.x) grp[(int64_t)row * (PC_MAX_P + 1) + p] = hist[p];
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < 64) {
         int tot = 0;
-        for (int p = 0; p < P; ++p) tot += hist[p];
-        rowptr[row] = tot;
+        for (int p = threadIdx.x; p < P; p += 64) tot += hist[p];
+        for (int off = 32; off > 0; off >>= 1) tot += __shfl_down(tot, off);
+        if (threadIdx.x == 0) rowtot[row] = tot;
     }
 }
 
-// In-place exclusive scan of rowptr[0..rows) with the total written to rowptr[rows]. One block.
-__global__ void __launch_bounds__(1024) pc_pack_scan_kernel(int32_t *rowptr, int rows)
+// Operand tiles of one 32-filter x 32-channel block, all 9 taps.
+// wz_fwd[mt][tap][ks][lane][8]: mt = filter/32, ks = channel/16; element i of lane l is
+// w[f = 32*mt + l%32][c = 16*ks + 8*(l/32) + i][tap] as bf16, zero when pruned or padded.
+// wz_bwd has the roles of filter and channel exchanged (rows = channels, k = filters).
+// The pattern mask of a kernel comes from pid/keep, or (FROM_KINFO) from the kinfo table of an earlier pack.
+#define PC_TILE_PITCH 40   // bf16 elements per LDS row: 32 + 8 keeps 16-byte alignment and spreads the banks
+template <bool FROM_KINFO>
+__device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, const uint8_t *__restrict__ pid,
+                                                   const uint8_t *__restrict__ keep, const LibArg &la, const PackView &v,
+                                                   int fb, int cb)
 {
-    __shared__ int part[1024];
-    int per = (rows + 1023) / 1024;
-    int lo = threadIdx.x * per, hi = lo + per < rows ? lo + per : rows;
-    int sum = 0;
-    for (int i = lo; i < hi; ++i) sum += rowptr[i];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    // inclusive prefix over the 1024 partial sums (integers: any order gives the same result)
-    for (int d = 1; d < 1024; d <<= 1) {
-        int add = threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+    __shared__ __align__(16) uint16_t tA[9][32][PC_TILE_PITCH];   // [tap][filter][channel]
+    __shared__ __align__(16) uint16_t tB[9][32][PC_TILE_PITCH];   // [tap][channel][filter]
+    __shared__ uint16_t tm[32][32];                               // pattern mask of kernel (f,c), 0 = pruned / outside
+    __shared__ uint16_t lm[PC_MAX_P + 2];                         // the pool's masks
+    const int tid = threadIdx.x, f0 = fb * 32, c0 = cb * 32;
+    if (!FROM_KINFO) {
+        if (tid < la.P) lm[tid] = la.mask[tid];
+        uint8_t kp[4], pd[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = j * 256 + tid, f = f0 + (i >> 5), c = c0 + (i & 31);
+            const bool in = f < v.F && c < v.C;
+            const int64_t k = in ? (int64_t)f * v.C + c : 0;
+            kp[j] = in ? keep[k] : (uint8_t)0;
+            pd[j] = pid[k];
+        }
         __syncthreads();
-        part[threadIdx.x] += add;
-        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = j * 256 + tid;
+            tm[i >> 5][i & 31] = (kp[j] && pd[j] < la.P) ? lm[pd[j]] : (uint16_t)0;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = j * 256 + tid, f = f0 + (i >> 5), c = c0 + (i & 31);
+            uint32_t u = 0xFFFFFFFFu;
+            if (f < v.F && c < v.C) u = v.kinfo[(int64_t)f * v.C + c];
+            tm[i >> 5][i & 31] = u == 0xFFFFFFFFu ? (uint16_t)0 : (uint16_t)(u & 511u);
+        }
     }
-    if (threadIdx.x == 1023) rowptr[rows] = part[1023];
-    int run = part[threadIdx.x] - sum;
-    for (int i = lo; i < hi; ++i) {
-        int v = rowptr[i];
-        rowptr[i] = run;
-        run += v;
+    __syncthreads();
+    const int ncols = v.C - c0 < 32 ? (v.C - c0 > 0 ? v.C - c0 : 0) : 32;
+    if ((v.C & 3) == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0) {
+        // a filter row of the block is ncols*9 contiguous floats starting on a 16-byte boundary
+        const int nq = ncols * 9 / 4;
+#pragma unroll
+        for (int it = 0; it < 9; ++it) {
+            const int q = it * 256 + tid;            // 32 rows x 72 quads
+            const int r = q / 72, jq = q - r * 72;
+            float4 w4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (f0 + r < v.F && jq < nq)
+                w4 = *reinterpret_cast<const float4 *>(W + ((int64_t)(f0 + r) * v.C + c0) * 9 + jq * 4);
+            const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = jq * 4 + e, cl = j / 9, tap = j - cl * 9;
+                const uint16_t val = ((tm[r][cl] >> tap) & 1u) ? pc_f32_to_bf16(wv[e]) : (uint16_t)0;
+                tA[tap][r][cl] = val;
+                tB[tap][cl][r] = val;
+            }
+        }
+    } else {
+        for (int idx = tid; idx < 32 * 288; idx += 256) {
+            const int r = idx / 288, j = idx - r * 288, cl = j / 9, tap = j - cl * 9;
+            uint16_t val = 0;
+            if (f0 + r < v.F && cl < ncols && ((tm[r][cl] >> tap) & 1u))
+                val = pc_f32_to_bf16(W[((int64_t)(f0 + r) * v.C + c0 + cl) * 9 + tap]);
+            tA[tap][r][cl] = val;
+            tB[tap][cl][r] = val;
+        }
+    }
+    __syncthreads();
+    const int KSf = v.Ck / 16, KSb = v.Fk / 16;
+    uint4 *of = reinterpret_cast<uint4 *>(v.wz_fwd), *ob = reinterpret_cast<uint4 *>(v.wz_bwd);
+    for (int o = tid; o < 9 * 2 * 64; o += 256) {
+        const int lane = o & 63, q = o >> 6, tap = q >> 1, sl = q & 1;
+        const int row = lane & 31, col = 16 * sl + 8 * (lane >> 5);
+        if (2 * cb + sl < KSf)
+            of[((int64_t)(fb * 9 + tap) * KSf + 2 * cb + sl) * 64 + lane] = *reinterpret_cast<const uint4 *>(&tA[tap][row][col]);
+        if (2 * fb + sl < KSb)
+            ob[((int64_t)(cb * 9 + tap) * KSb + 2 * fb + sl) * 64 + lane] = *reinterpret_cast<const uint4 *>(&tB[tap][row][col]);
     }
 }
 
-__device__ __forceinline__ float4 pc_gather_taps(const float *__restrict__ W, int64_t k, const uint8_t *tp, bool bf16)
+// First launch of a pack: workgroups [0, F) count the filter rows, [F, F + ncm) the channel rows (ncm = C for the
+// gather variant, else 0), the rest write the operand tiles (matrix-core variant), one 32 x 32 block each.
+__global__ void __launch_bounds__(256)
+pc_pack_stage1_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep,
+                      LibArg la, PackView v, int ncm, int tiles_c)
+{
+    int b = blockIdx.x;
+    if (b < v.F) {
+        pc_pack_count_row(pid, keep, b, v.C, (int64_t)v.C, 1, v.P, v.fm_grp, v.fm_rowtot);
+        return;
+    }
+    b -= v.F;
+    if (b < ncm) {
+        pc_pack_count_row(pid, keep, b, v.F, 1, (int64_t)v.C, v.P, v.cm_grp, v.cm_rowtot);
+        return;
+    }
+    b -= ncm;
+    pc_pack_tile_block<false>(W, pid, keep, la, v, b / tiles_c, b % tiles_c);
+}
+
+// Operand tiles again from new weights, masks from the kinfo table (values change, tables do not).
+__global__ void __launch_bounds__(256)
+pc_pack_retile_kernel(const float *__restrict__ W, LibArg la, PackView v, int tiles_c)
+{
+    pc_pack_tile_block<true>(W, nullptr, nullptr, la, v, blockIdx.x / tiles_c, blockIdx.x % tiles_c);
+}
+
+// The 4 kept weights of kernel k; taps holds the 4 tap indices, one per byte, ascending from the low byte.
+__device__ __forceinline__ float4 pc_gather_taps(const float *__restrict__ W, int64_t k, uint32_t taps, bool bf16)
 {
     float v[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        float w = W[k * 9 + tp[j]];
+        float w = W[k * 9 + ((taps >> (8 * j)) & 255u)];
         v[j] = bf16 ? pc_bf16_to_f32(pc_f32_to_bf16(w)) : w;
     }
     return make_float4(v[0], v[1], v[2], v[3]);
 }
 
-// Places the kept kernels of one row at rowptr[row] + (pattern group start) + (rank inside the group).
-// Each wave takes patterns wave, wave+4, ... and walks the row 64 elements at a time; the rank of
-// an element is the number of earlier group members, so the order inside a group is ascending.
+__device__ __forceinline__ uint32_t pc_taps_word(const LibArg &la, int p)
+{
+    return (uint32_t)la.taps[p][0] | ((uint32_t)la.taps[p][1] << 8) | ((uint32_t)la.taps[p][2] << 16) | ((uint32_t)la.taps[p][3] << 24);
+}
+
+// Places the kept kernels of one row at (kept kernels of the rows before) + (pattern group start) + (rank inside
+// the group); the rank of an element is the number of earlier members of its group in the row, so the order
+// inside a group is ascending. The row is walked 256 elements at a time: every wave ballots each pattern id,
+// the per-wave counts go through LDS. All counts are integers, so no result depends on an execution order.
+template <bool FM>
 __global__ void __launch_bounds__(256)
 pc_pack_place_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep,
-                     int rows, int len, int64_t row_stride, int64_t elem_stride, LibArg la, int bf16,
-                     int filter_major, PackView v)
+                     int rows, int len, int64_t row_stride, int64_t elem_stride, LibArg la, int bf16, PackView v)
 {
-    __shared__ int start[PC_MAX_P + 1];
-    int row = blockIdx.x;
-    int32_t *grp = (filter_major ? v.fm_grp : v.cm_grp) + (int64_t)row * (PC_MAX_P + 1);
-    const int32_t *rowptr = filter_major ? v.fm_rowptr : v.cm_rowptr;
-    if (threadIdx.x == 0) {
-        int run = rowptr[row];
-        for (int p = 0; p < la.P; ++p) {
-            int cnt = grp[p];
+    __shared__ int start[PC_MAX_P + 1];          // next free slot of every pattern group
+    __shared__ int wcnt[4][PC_MAX_P + 2];        // members of every group in the current 256 elements, per wave
+    __shared__ int red[4];
+    __shared__ uint32_t ltaps[PC_MAX_P + 2];      // tap lists and masks of the pool
+    __shared__ uint16_t lmask[PC_MAX_P + 2];
+    const int row = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int P = la.P;
+    if (tid < P) { ltaps[tid] = pc_taps_word(la, tid); lmask[tid] = la.mask[tid]; }
+    int32_t *grp = (FM ? v.fm_grp : v.cm_grp) + (int64_t)row * (PC_MAX_P + 1);
+    int32_t *rowptr = FM ? v.fm_rowptr : v.cm_rowptr;
+    const int32_t *rowtot = FM ? v.fm_rowtot : v.cm_rowtot;
+    // kept kernels in the rows before this one
+    int part = 0;
+    for (int i = tid; i < row; i += 256) part += rowtot[i];
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off);
+    if (lane == 0) red[wave] = part;
+    if (tid < P) start[tid] = grp[tid];          // counts for now
+    __syncthreads();
+    const int base = red[0] + red[1] + red[2] + red[3];
+    if (tid == 0) {
+        rowptr[row] = base;
+        if (row == rows - 1) rowptr[rows] = base + rowtot[row];
+        int run = base;
+        for (int p = 0; p < P; ++p) {
+            const int cnt = start[p];
             start[p] = run;
-            grp[p] = run;
             run += cnt;
         }
-        grp[la.P] = run;
+        start[P] = run;
     }
     __syncthreads();
-    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int p = wave; p < la.P; p += 4) {
-        int run = start[p];
-        for (int e0 = 0; e0 < len; e0 += 64) {
-            int e = e0 + lane;
-            int64_t k = row * row_stride + e * elem_stride;
-            bool hit = e < len && keep[k] && pid[k] == p;
-            unsigned long long b = __ballot(hit);
-            if (hit) {
-                int slot = run + __popcll(b & ((1ull << lane) - 1ull));
-                float4 val = pc_gather_taps(W, k, la.taps[p], bf16 != 0);
-                if (filter_major) {
-                    v.fm_c[slot] = (uint16_t)e;
-                    v.fm_pid[slot] = (uint8_t)p;
-                    v.slot_f[slot] = (uint16_t)row;
-                    v.fm_val[slot] = val;
-                    v.slot_of[k] = slot;
-                    v.kinfo[k] = ((uint32_t)slot << 9) | la.mask[p];
-                } else {
-                    v.cm_f[slot] = (uint16_t)e;
-                    v.cm_slot[slot] = v.slot_of[k];
-                    v.cm_val[slot] = val;
-                }
+    if (tid <= P) grp[tid] = start[tid];         // group starts, [P] = row end
+    for (int e0 = 0; e0 < len; e0 += 256) {
+        const int e = e0 + tid;
+        const int64_t k = row * row_stride + e * elem_stride;
+        int code = 255;
+        if (e < len) {
+            const int kp = keep[k], pd = pid[k];
+            if (kp && pd < P) code = pd;
+        }
+        int my_rank = 0, c0 = 0, c1 = 0;
+        for (int p = 0; p < P; ++p) {
+            const unsigned long long b = __ballot(code == p);
+            if (code == p) my_rank = __popcll(b & ((1ull << lane) - 1ull));
+            const int n = __popcll(b);
+            if (lane == (p & 63)) { if (p < 64) c0 = n; else c1 = n; }
+        }
+        if (lane < P) wcnt[wave][lane] = c0;
+        if (lane + 64 < P) wcnt[wave][lane + 64] = c1;
+        __syncthreads();
+        if (code != 255) {
+            int slot = start[code] + my_rank;
+            for (int w2 = 0; w2 < wave; ++w2) slot += wcnt[w2][code];
+            const float4 val = pc_gather_taps(W, k, ltaps[code], bf16 != 0);
+            if (FM) {
+                v.fm_c[slot] = (uint16_t)e;
+                v.fm_pid[slot] = (uint8_t)code;
+                v.slot_f[slot] = (uint16_t)row;
+                v.fm_val[slot] = val;
+                v.slot_of[k] = slot;
+                v.kinfo[k] = ((uint32_t)slot << 9) | lmask[code];
+            } else {
+                v.cm_f[slot] = (uint16_t)e;
+                v.cm_slot[slot] = v.slot_of[k];
+                v.cm_val[slot] = val;
             }
-            run += __popcll(b);
+        } else if (FM && e < len) {
+            v.slot_of[k] = -1;
+            v.kinfo[k] = 0xFFFFFFFFu;
         }
-    }
-    if (filter_major) {
-        for (int e = threadIdx.x; e < len; e += blockDim.x) {
-            int64_t k = row * row_stride + e * elem_stride;
-            if (!keep[k]) { v.slot_of[k] = -1; v.kinfo[k] = 0xFFFFFFFFu; }
-        }
+        __syncthreads();
+        if (tid < P) start[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
+        __syncthreads();
     }
 }
 
@@ -309,7 +573,7 @@ pc_pack_regather_fm_kernel(const float *__restrict__ W, LibArg la, int bf16, Pac
     if (k >= (int64_t)v.F * v.C) return;
     int slot = v.slot_of[k];
     if (slot < 0) return;
-    v.fm_val[slot] = pc_gather_taps(W, k, la.taps[v.fm_pid[slot]], bf16 != 0);
+    v.fm_val[slot] = pc_gather_taps(W, k, pc_taps_word(la, v.fm_pid[slot]), bf16 != 0);
 }
 
 __global__ void __launch_bounds__(256) pc_pack_regather_cm_kernel(PackView v)
@@ -326,23 +590,28 @@ pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8
     pc_fill_lib(&la, pk->lib, v.P);
     int bf16 = pk->dtype == PC_BF16;
     hipStream_t st = ctx->stream;
-    // filter-major
-    hipLaunchKernelGGL(pc_pack_count_kernel, dim3(v.F), dim3(256), 0, st, pid, keep, v.F, v.C, (int64_t)v.C,
-                       (int64_t)1, v.P, v.fm_grp, v.fm_rowptr);
-    hipLaunchKernelGGL(pc_pack_scan_kernel, dim3(1), dim3(1024), 0, st, v.fm_rowptr, v.F);
-    hipLaunchKernelGGL(pc_pack_place_kernel, dim3(v.F), dim3(256), 0, st, W, pid, keep, v.F, v.C, (int64_t)v.C,
-                       (int64_t)1, la, bf16, 1, v);
-    // channel-major: the table of the gather kernels' backward-data pass (the matrix-core kernels read operand tiles)
-    if (pk->variant != PC_VARIANT_MFMA) {
-        hipLaunchKernelGGL(pc_pack_count_kernel, dim3(v.C), dim3(256), 0, st, pid, keep, v.C, v.F, (int64_t)1,
-                           (int64_t)v.C, v.P, v.cm_grp, v.cm_rowptr);
-        hipLaunchKernelGGL(pc_pack_scan_kernel, dim3(1), dim3(1024), 0, st, v.cm_rowptr, v.C);
-        hipLaunchKernelGGL(pc_pack_place_kernel, dim3(v.C), dim3(256), 0, st, W, pid, keep, v.C, v.F, (int64_t)1,
-                           (int64_t)v.C, la, bf16, 0, v);
-    }
-    pc_status s = pc_hip_check(ctx, hipGetLastError(), "pack launch");
-    if (s == PC_OK && pk->variant == PC_VARIANT_MFMA) s = pc_launch_pack_tiles(ctx, pk, W);
-    return s;
+    const bool mfma = pk->variant == PC_VARIANT_MFMA;
+    // the channel-major table serves the gather kernels' backward-data pass (the matrix-core kernels read operand tiles)
+    const int ncm = mfma ? 0 : v.C;
+    const int tiles_c = v.Cp / 32, ntiles = mfma ? (v.Fp / 32) * tiles_c : 0;
+    hipLaunchKernelGGL(pc_pack_stage1_kernel, dim3((unsigned)(v.F + ncm + ntiles)), dim3(256), 0, st, W, pid, keep, la, v, ncm,
+                       tiles_c);
+    hipLaunchKernelGGL(pc_pack_place_kernel<true>, dim3(v.F), dim3(256), 0, st, W, pid, keep, v.F, v.C, (int64_t)v.C,
+                       (int64_t)1, la, bf16, v);
+    if (!mfma)
+        hipLaunchKernelGGL(pc_pack_place_kernel<false>, dim3(v.C), dim3(256), 0, st, W, pid, keep, v.C, v.F, (int64_t)1,
+                           (int64_t)v.C, la, bf16, v);
+    return pc_hip_check(ctx, hipGetLastError(), "pack launch");
+}
+
+pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W)
+{
+    PackView v = pk->v;
+    LibArg la;
+    pc_fill_lib(&la, pk->lib, v.P);
+    const int tiles_c = v.Cp / 32;
+    hipLaunchKernelGGL(pc_pack_retile_kernel, dim3((unsigned)((v.Fp / 32) * tiles_c)), dim3(256), 0, ctx->stream, W, la, v, tiles_c);
+    return pc_hip_check(ctx, hipGetLastError(), "pack tiles launch");
 }
 
 pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W)

@@ -32,7 +32,7 @@ struct WgradMfmaArgs {
     int32_t xplane;            // bytes per xT channel plane
     int32_t nks;               // MFMA k-steps per pixel tile: ceil(ng * npos / 2)
     int32_t tiles_r, tiles_c, tiles_n, n_ktiles, ksplit;
-    int32_t nnzk;
+    int32_t pstride;       // slots per partial plane
     // decode tables built on the host (no integer divisions in the kernel); 0xFFFFFFFF = unused entry
     int16_t xb_tab[WG_NSLOT];              // x slot read by dy slot s for tap (0,0)
     uint32_t dy_tab[WG_NSLOT];             // dy slot -> (image group << 16) | (row << 8) | column of the output position
@@ -227,7 +227,7 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
     // Epilogue, one filter half (32 filters) at a time: the waves park their tiles of that half in LDS as
     // out[tap][filter][channel] (float32, 72 KiB), then every thread walks 8 kernels (f, c) of the half and,
     // for the kept ones, gathers the 4 kept taps and writes them as one 16-byte entry in compact slot order.
-    float *pout = partial + (int64_t)blockIdx.z * a.nnzk * 4;
+    float *pout = partial + (int64_t)blockIdx.z * a.pstride * 4;
     float *ot = reinterpret_cast<float *>(lds);
 #pragma unroll
     for (int fh = 0; fh < 2; ++fh) {
@@ -290,7 +290,7 @@ struct WgradWsArgs {
     int32_t N, H, W, C, F, Ho, Wo, stride;   // C: channels of the x tensor the kernel reads (padded to a multiple of 8)
     int32_t Creal;                           // channels of the layer (row length of the kinfo table)
     int32_t TR, TC, npos, ng, IR, IC, xs_per_g, xslots, xplane;
-    int32_t tiles_r, tiles_c, n_ktiles, ksplit, nnzk;
+    int32_t tiles_r, tiles_c, n_ktiles, ksplit, pstride;
     int32_t buf_bytes;                     // one LDS buffer: dyT planes, then xT planes
     uint32_t x_bytes, dy_bytes;            // tensor sizes (bounds of the buffer loads)
     uint32_t mg_tc, mg_tr;                 // multiply-high constants of the divisions by tiles_c and tiles_r
@@ -341,7 +341,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
                 kinf[fh][k] = (f < a.F && c < a.Creal) ? v.kinfo[(int64_t)f * a.Creal + c] : 0xFFFFFFFFu;
             }
     };
-    float *pout = a.ksplit > 1 ? partial + (int64_t)bz * a.nnzk * 4 : dw;
+    float *pout = a.ksplit > 1 ? partial + (int64_t)bz * a.pstride * 4 : dw;
     const float *ot = reinterpret_cast<const float *>(lds);
     // gathers the 4 kept taps of every kept kernel of filter half fh from the parked tile
     auto gather = [&](int fh) {
@@ -547,7 +547,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 // Wave-specialised backward-weight: plan and launch. *launched stays false when the layer is outside what
 // that kernel takes (the caller then uses the cooperative kernel).
 static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
-                                       float *dw, int64_t nnzk, bool *launched)
+                                       float *dw, int64_t nslots, bool *launched)
 {
     *launched = false;
     WgradWsArgs a;
@@ -595,7 +595,7 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     const int64_t nkt = (int64_t)tiles_n * a.tiles_r * a.tiles_c;
     if (nkt * (a.tiles_r > a.tiles_c ? a.tiles_r : a.tiles_c) >= ((int64_t)1 << 31)) return PC_OK;
     a.n_ktiles = (int)nkt;
-    a.nnzk = (int32_t)nnzk;
+    a.pstride = (int32_t)nslots;
     auto magic = [](int dd) { return pc_udiv_magic(dd); };
     a.mg_tc = magic(a.tiles_c); a.mg_tr = magic(a.tiles_r);
     for (int sl = 0; sl < WS_NSLOT; ++sl) {
@@ -617,7 +617,7 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     if (ks < 1) ks = 1;
     a.ksplit = ks;
     void *scr = nullptr;
-    const size_t part_bytes = ks > 1 ? (sizeof(float) * 4 * (size_t)ks * (size_t)nnzk + 255) / 256 * 256 : 0;
+    const size_t part_bytes = ks > 1 ? (sizeof(float) * 4 * (size_t)ks * (size_t)nslots + 255) / 256 * 256 : 0;
     if (part_bytes || pad_x) {
         pc_status s = pc_scratch(ctx, part_bytes + (pad_x ? (size_t)xb : 0), &scr);
         if (s != PC_OK) return s;
@@ -637,19 +637,22 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     *launched = true;
     pc_status s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight (wave-specialised) launch");
     if (s != PC_OK || ks == 1) return s;
-    return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, pk, dw);
+    return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, nslots, nslots, pk, dw);
 }
 
 pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
                              float *dw)
 {
-    int64_t nnzk = 0;
-    pc_status s = pc_packed_info(ctx, pk, &nnzk, nullptr);
-    if (s != PC_OK) return s;
-    if (nnzk == 0) return PC_OK;
+    // The kernels find the kept kernels and their slots on the device; the host only needs an upper bound of
+    // the slot count to size and stride the partial planes: the exact count when a read-back has already
+    // happened, else the capacity of the pack. No read-back is forced here, so a step that re-packs stays
+    // asynchronous.
+    const int64_t nslots = pk->nnzk >= 0 ? pk->nnzk : (int64_t)pk->v.F * pk->v.C;
+    if (nslots == 0) return PC_OK;
+    pc_status s = PC_OK;
     if (ctx->plan_cfg != 10) {   // 10 forces the cooperative kernel
         bool launched = false;
-        s = pc_mfma_bwd_weight_ws(ctx, d, pk, x, dy, dw, nnzk, &launched);
+        s = pc_mfma_bwd_weight_ws(ctx, d, pk, x, dy, dw, nslots, &launched);
         if (launched || s != PC_OK) return s;
         if (ctx->plan_cfg == 11)
             return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA bwd_weight: the wave-specialised kernel does not take this layer");
@@ -692,7 +695,7 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     a.tiles_c = (a.Wo + a.TC - 1) / a.TC;
     a.tiles_n = (ngroups + a.ng - 1) / a.ng;
     a.n_ktiles = a.tiles_n * a.tiles_r * a.tiles_c;
-    a.nnzk = (int32_t)nnzk;
+    a.pstride = (int32_t)nslots;
     for (int sl = 0; sl < WG_NSLOT; ++sl) {
         int ig = sl / a.npos, pos = sl % a.npos, py = pos / a.TC, px = pos % a.TC;
         bool ok = ig < a.ng;
@@ -721,7 +724,7 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     if (ks < 1) ks = 1;
     a.ksplit = ks;
     void *scr = nullptr;
-    s = pc_scratch(ctx, sizeof(float) * 4 * (size_t)ks * (size_t)nnzk, &scr);
+    s = pc_scratch(ctx, sizeof(float) * 4 * (size_t)ks * (size_t)nslots, &scr);
     if (s != PC_OK) return s;
     const dim3 grid((unsigned)ct, (unsigned)ft, (unsigned)ks);
     const uint16_t *xp = (const uint16_t *)x, *dyp = (const uint16_t *)dy;
@@ -731,5 +734,5 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     else hipLaunchKernelGGL(pc_mfma_wgrad_kernel<16>, grid, dim3(256), lds, ctx->stream, xp, dyp, a, pk->v, (float *)scr);
     s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight launch");
     if (s != PC_OK) return s;
-    return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, pk, dw);
+    return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, nslots, nslots, pk, dw);
 }

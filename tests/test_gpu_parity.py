@@ -315,6 +315,108 @@ def test_update_values_and_repack(B, ctx, oracle):
         g.close()
 
 
+def test_select_long_rows_with_partial_ties(B, ctx, oracle):
+    """Rows longer than one workgroup pass, scores from a small discrete set: the cut falls inside a run of equal
+    scores in most rows, so the lowest channels of the run must win (per-filter and per-layer modes)."""
+    import torch
+    rng = np.random.default_rng(7)
+    lib = I.make_library(12)
+    for F, C, n_keep in ((5, 700, 123), (3, 1300, 1), (4, 513, 512), (2, 8192, 3000), (2, 9000, 77)):
+        Wn = rng.integers(-3, 4, size=(F, C, 9)).astype(np.float32) * 0.25
+        Gn = rng.integers(-2, 3, size=(F, C, 9)).astype(np.float32)
+        Wd, Gd = to_dev(Wn), to_dev(Gn)
+        for sm in (0, 1):
+            pid, kp = oracle.select(Wn, Gn, lib, n_keep, score_mode=sm)
+            gp = torch.full((F, C), 255, dtype=torch.uint8, device="cuda")
+            gk = torch.full((F, C), 255, dtype=torch.uint8, device="cuda")
+            B.pc_pattern_select(ctx, Wd, Gd, F, C, lib, 0, n_keep, sm, gp, gk)
+            torch.cuda.synchronize()
+            assert np.array_equal(gp.cpu().numpy(), pid), (F, C, n_keep, sm)
+            assert np.array_equal(gk.cpu().numpy(), kp), (F, C, n_keep, sm)
+            assert int(kp.sum()) == F * min(n_keep, C)
+
+
+@pytest.mark.parametrize("shape", [(2, 9, 9, 40, 72, 1), (2, 8, 8, 6, 40, 1), (3, 7, 5, 130, 33, 2)])
+def test_update_values_bf16_tiles(B, ctx, oracle, shape):
+    """pc_update_values on a bf16 pack rebuilds the matrix-core operand tiles from the tables of the pack."""
+    layer = I.Layer(*shape)
+    case = Case(layer, "bf16", 8, I.kept_per_filter(0.4, layer.C), tag=("upd_bf16", shape))
+    pid, kp, M, Wm = oracle_masks(oracle, case)
+    g = GpuLayer(B, ctx, case)
+    try:
+        W2 = I.gen_weights(layer.F, layer.C, 123, ("upd_bf16_2", shape))
+        B.pc_update_values(ctx, g.pk, to_dev(W2))
+        Wm2 = oracle.apply_mask(oracle.bf16_round(W2), M)
+        assert np.array_equal(g.unpack(), Wm2)
+        assert rel_l2(g.fwd(), oracle.conv_fwd(case.x, Wm2, layer.stride)) <= 2e-2
+        assert rel_l2(g.bwd_data(), oracle.conv_bwd_data(case.dy, Wm2, case.x.shape, layer.stride)) <= 2e-2
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("shape", [(8, 8, 8, 64, 64, 1), (5, 6, 6, 130, 72, 1), (16, 4, 4, 256, 512, 1), (3, 9, 9, 3, 64, 2)])
+def test_backward_weight_without_count_readback(B, ctx, oracle, shape):
+    """After a re-pack the host does not know the kept-kernel count; backward-weight then sizes its partial planes
+    by the capacity of the pack and must give the same gradient, without forcing a read-back."""
+    import torch
+    layer = I.Layer(*shape)
+    case = Case(layer, "bf16", 8, I.kept_per_filter(0.3, layer.C), tag=("nocount", shape))
+    pid, kp, M, Wm = oracle_masks(oracle, case)
+    g = GpuLayer(B, ctx, case)
+    try:
+        ref = oracle.conv_bwd_weight(case.x, case.dy, M, layer.stride)
+        dw_known, guard = g.bwd_weight()
+        assert rel_l2(g.scatter(guard.body), ref) <= 1e-4
+        pk2 = B.pc_pack(ctx, g.W, g.pid, g.keep, layer.F, layer.C, case.lib, g.dt, reuse=g.pk)   # count unknown again
+        assert pk2 == g.pk
+        dw_cap, guard2 = g.bwd_weight()
+        assert np.array_equal(dw_cap, dw_known)
+        assert B.pc_packed_info(ctx, g.pk)[0] == g.nnzk
+    finally:
+        g.close()
+
+
+def test_select_and_pack_replay_in_a_graph(B, oracle):
+    """A step that re-selects and re-packs can be captured into a HIP graph: replays with other work between them
+    give the masks, the pack and the layer outputs of the eager calls."""
+    import torch
+    layer = I.Layer(4, 8, 8, 64, 64, 1)
+    case = Case(layer, "bf16", 8, 19, tag="graph")
+    pid, kp, M, Wm = oracle_masks(oracle, case)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = B.pc_create(0, stream.cuda_stream)
+        g = GpuLayer(B, ctx, case)
+        try:
+            y = torch.empty((layer.N, layer.Ho, layer.Wo, layer.F), dtype=torch.bfloat16, device="cuda")
+            dw = torch.empty((g.nnzk, 4), dtype=torch.float32, device="cuda")
+
+            def step():
+                B.pc_pattern_select(ctx, g.W, g.G, layer.F, layer.C, case.lib, 0, case.n_keep, 0, g.pid, g.keep)
+                B.pc_pack(ctx, g.W, g.pid, g.keep, layer.F, layer.C, case.lib, g.dt, reuse=g.pk)
+                B.pc_conv_fwd(ctx, g.desc, g.pk, g.x, y)
+                B.pc_conv_bwd_weight(ctx, g.desc, g.pk, g.x, g.dy, dw)
+
+            step()
+            stream.synchronize()
+            y_eager, dw_eager = y.clone(), dw.clone()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+            for rep in range(3):
+                g.pid.fill_(255); g.keep.fill_(255); y.zero_(); dw.zero_()
+                (torch.ones(1 << 16, device="cuda") * 2).sum().item()       # unrelated eager work between replays
+                graph.replay()
+                stream.synchronize()
+                assert np.array_equal(g.pid.cpu().numpy(), pid) and np.array_equal(g.keep.cpu().numpy(), kp), rep
+                assert torch.equal(y, y_eager) and torch.equal(dw, dw_eager), rep
+            assert B.pc_packed_info(ctx, g.pk)[0] == g.nnzk
+            assert np.array_equal(g.unpack(), Wm)
+        finally:
+            g.close()
+            B.pc_destroy(ctx)
+
+
 def test_mismatched_descriptor_is_rejected(B, ctx, oracle):
     layer = I.Layer(1, 4, 4, 8, 8, 1)
     case = Case(layer, "f32", 4, 4, tag="mismatch")
