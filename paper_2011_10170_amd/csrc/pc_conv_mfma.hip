@@ -40,7 +40,9 @@ constexpr int pc_prefetch_depth(int ns, int step_cycles)
 // A fragments are prefetched PF steps ahead from global memory, B fragments one step ahead from LDS.
 // With gridDim.z > 1 every split reduces its own range of channel chunks and writes float32 partial
 // sums [split][pixel][m] that pc_mfma_splitk_reduce_kernel adds in a fixed order.
-template <int A_T, int B_T, int WAVES_M, int WAVES_N, int NTAPS, int KC>
+// MC: the launch covers the four parity classes of a stride-2 backward-data pass (NTAPS = 4 is then the longest
+// tap list; a class with fewer taps skips the other steps, uniformly for the workgroup).
+template <int A_T, int B_T, int WAVES_M, int WAVES_N, int NTAPS, int KC, bool MC = false>
 __global__ void __launch_bounds__(256, 2)
 pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const uint16_t *__restrict__ wz,
                     float *__restrict__ partial, MfmaArgs g)
@@ -57,6 +59,18 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
     int bt = blockIdx.x;
+    int GH = g.GH, GW = g.GW, ooff_y = g.ooff_y, ooff_x = g.ooff_x, ntaps = NTAPS;
+    int tapw[NTAPS], tapo[NTAPS];
+    if constexpr (MC) {
+        const int cl = bt / g.cls_tiles;
+        bt -= cl * g.cls_tiles;
+        GH = g.cls_GH[cl]; GW = g.cls_GW[cl]; ooff_y = g.cls_ooy[cl]; ooff_x = g.cls_oox[cl]; ntaps = g.cls_ntaps[cl];
+#pragma unroll
+        for (int t = 0; t < NTAPS; ++t) { tapw[t] = g.cls_tap_w[cl][t]; tapo[t] = g.cls_tap_off[cl][t]; }
+    } else {
+#pragma unroll
+        for (int t = 0; t < NTAPS; ++t) { tapw[t] = g.tap_w[t]; tapo[t] = g.tap_off[t]; }
+    }
     const int tx = bt % g.tiles_x; bt /= g.tiles_x;
     const int ty = bt % g.tiles_y; bt /= g.tiles_y;
     const int tn = bt;
@@ -92,7 +106,7 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
     auto a_load = [&](int ch, int st, int i) -> bf16x8 {
         const int t = st / KSC, ks = st % KSC;
         const int chc = ch < ch1 ? ch : ch1 - 1;
-        return *reinterpret_cast<const bf16x8 *>(wzl + (int64_t)((i * 9 + g.tap_w[t]) * g.KS + chc * KSC + ks) * 512);
+        return *reinterpret_cast<const bf16x8 *>(wzl + (int64_t)((i * 9 + tapw[t]) * g.KS + chc * KSC + ks) * 512);
     };
     bf16x8 aring[PF][A_T];
 #pragma unroll
@@ -143,7 +157,7 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
             const int t1 = d / KSC, k1 = d % KSC;
 #pragma unroll
             for (int j = 0; j < B_T; ++j)
-                bring[d % RB][j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[t1] + k1 * 32);
+                bring[d % RB][j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + tapo[t1] + k1 * 32);
         }
 #pragma unroll
         for (int st = 0; st < NS; ++st) {
@@ -151,7 +165,7 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
                 const int t1 = (st + DB) / KSC, k1 = (st + DB) % KSC;
 #pragma unroll
                 for (int j = 0; j < B_T; ++j)
-                    bring[(st + DB) % RB][j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + g.tap_off[t1] + k1 * 32);
+                    bring[(st + DB) % RB][j] = *reinterpret_cast<const bf16x8 *>(lds + base[j] + tapo[t1] + k1 * 32);
             }
             bf16x8 anow[A_T];
 #pragma unroll
@@ -164,11 +178,13 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
                 for (int i = 0; i < A_T; ++i) aring[st % PF][i] = a_load(nch, nss, i);
             }
             __builtin_amdgcn_sched_barrier(0);
+            if (!MC || st / KSC < ntaps) {
 #pragma unroll
-            for (int i = 0; i < A_T; ++i)
+                for (int i = 0; i < A_T; ++i)
 #pragma unroll
-                for (int j = 0; j < B_T; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(anow[i], bring[st % RB][j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < B_T; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(anow[i], bring[st % RB][j], acc[i][j], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -182,8 +198,8 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
         int rem = q - ti * g.TH * g.TW;
         int y = rem / g.TW, x = rem - y * g.TW;
         int n = tn * g.TI + ti, gy = gy0 + y, gx = gx0 + x;
-        if (n >= g.N || gy >= g.GH || gx >= g.GW) continue;
-        int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
+        if (n >= g.N || gy >= GH || gx >= GW) continue;
+        int oy = gy * g.oscale + ooff_y, ox = gx * g.oscale + ooff_x;
         const int64_t opix = ((int64_t)n * g.out_H + oy) * g.out_W + ox;
         if (gridDim.z == 1) {
             uint16_t *op = out + opix * g.out_CH;
@@ -296,6 +312,8 @@ static const MfmaCfg kCfgs[] = {
 };
 // automatic choice tries these in order and keeps the first that yields enough workgroups (else the last)
 static const int kAutoOrder[] = {4, 5};
+// the same for a launch over the four parity classes (four times the workgroups: the 128-row tiles pay off earlier)
+static const int kAutoOrderClasses[] = {1, 3, 4, 5};
 static const int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
 void pc_plan_mfma_tiles(MfmaArgs *g, int BN, int ext)
@@ -315,22 +333,28 @@ void pc_plan_mfma_tiles(MfmaArgs *g, int BN, int ext)
     g->tiles_x = (g->GW + g->TW - 1) / g->TW;
 }
 
+// The four parity classes of a stride-2 backward-data pass: extent, output offset and tap list of each.
+struct ParityClasses {
+    int GH[4], GW[4], ooy[4], oox[4], ntaps[4];
+    int tap_w[4][4], tr[4][4], tc[4][4];
+};
+
 template <int A_T, int B_T, int WM, int WN, int KC>
-static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, int ntaps, const uint16_t *in, uint16_t *out,
+static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, bool classes, const uint16_t *in, uint16_t *out,
                        const uint16_t *wz, float *partial, const MfmaArgs &g)
 {
-    switch (ntaps) {
-    case 9: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 9, KC>), grid, dim3(256), lds, st, in, out, wz, partial, g); break;
-    case 4: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 4, KC>), grid, dim3(256), lds, st, in, out, wz, partial, g); break;
-    case 2: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 2, KC>), grid, dim3(256), lds, st, in, out, wz, partial, g); break;
-    default: hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 1, KC>), grid, dim3(256), lds, st, in, out, wz, partial, g); break;
-    }
+    if (classes)
+        hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 4, KC, true>), grid, dim3(256), lds, st, in, out, wz, partial, g);
+    else
+        hipLaunchKernelGGL((pc_mfma_conv_kernel<A_T, B_T, WM, WN, 9, KC, false>), grid, dim3(256), lds, st, in, out, wz, partial, g);
 }
 
 
 // g holds everything but the tile plan; ext = reach of the tap offsets (3 or 2); tap rows/cols in tr/tc.
+// With pcl (stride-2 backward-data) the launch covers the four parity classes: g.GH/GW are the largest class
+// extents, ntaps = 4, and tr/tc are unused.
 static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, const int *tr, const int *tc,
-                               const uint16_t *in, uint16_t *out, const uint16_t *wz)
+                               const uint16_t *in, uint16_t *out, const uint16_t *wz, const ParityClasses *pcl = nullptr)
 {
     int plan_cfg = (ctx->plan_cfg >= 10 && ctx->plan_cfg < 13) ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
     if (ntaps == 9 && (plan_cfg < 0 || plan_cfg >= 7) && ctx->plan_split == 0) {
@@ -374,12 +398,15 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
     int pick = -1, pick_split = 1;
     MfmaArgs best = g;
     const int64_t want = 2 * (int64_t)ctx->num_cu;
-    const int n_try = plan_cfg >= 0 ? 1 : (int)(sizeof(kAutoOrder) / sizeof(kAutoOrder[0]));
+    const int *order = pcl ? kAutoOrderClasses : kAutoOrder;
+    const int n_order = pcl ? (int)(sizeof(kAutoOrderClasses) / sizeof(int)) : (int)(sizeof(kAutoOrder) / sizeof(int));
+    const int n_try = plan_cfg >= 0 ? 1 : n_order;
     for (int k = 0; k < n_try; ++k) {
-        int ci = plan_cfg >= 0 ? plan_cfg : kAutoOrder[k];
+        int ci = plan_cfg >= 0 ? plan_cfg : order[k];
         if (plan_cfg < 0 && g.in_CH <= 16) ci = 6;   // a handful of input channels: one 16-channel k-step per tap
         const MfmaCfg &c = kCfgs[ci];
         int BM = 32 * c.a * c.wm, BN = 32 * c.b * c.wn;
+        if (plan_cfg < 0 && k + 1 < n_try && BM > (g.out_CH + 63) / 64 * 64) continue;   // row tile mostly padding
         MfmaArgs t = g;
         pc_plan_mfma_tiles(&t, BN, ext);
         // too large for LDS (strided or tiny images): fewer images, then fewer rows per tile (idle lanes)
@@ -394,7 +421,7 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
         size_t lds = (size_t)t.TI * t.IH * t.IW * (2 * c.kc + 16 + 8);
         if (lds > MF_LDS_MAX) continue;
         t.nchunks = (g.in_CH + c.kc - 1) / c.kc;
-        int64_t blocks = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x * ((g.out_CH + BM - 1) / BM);
+        int64_t blocks = (int64_t)((t.N + t.TI - 1) / t.TI) * t.tiles_y * t.tiles_x * ((g.out_CH + BM - 1) / BM) * (pcl ? 4 : 1);
         int split = 1;
         if (ctx->plan_split > 0) split = ctx->plan_split;
         else if (k == n_try - 1 && blocks <= ctx->num_cu && t.nchunks >= 8) split = 4;
@@ -410,10 +437,24 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
     if (pick < 0) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA conv: no tile configuration fits in LDS");
     g = best;
     const MfmaCfg &c = kCfgs[pick];
-    for (int t = 0; t < ntaps; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * (2 * c.kc + 16);
+    const int pix_tiles = ((g.N + g.TI - 1) / g.TI) * g.tiles_y * g.tiles_x;
+    if (pcl) {
+        g.cls_tiles = pix_tiles;
+        for (int cl = 0; cl < 4; ++cl) {
+            g.cls_GH[cl] = pcl->GH[cl]; g.cls_GW[cl] = pcl->GW[cl];
+            g.cls_ooy[cl] = pcl->ooy[cl]; g.cls_oox[cl] = pcl->oox[cl];
+            g.cls_ntaps[cl] = pcl->ntaps[cl];
+            for (int t = 0; t < 4; ++t) {
+                const int u = t < pcl->ntaps[cl] ? t : 0;   // unused entries repeat the first: valid addresses, never multiplied
+                g.cls_tap_w[cl][t] = pcl->tap_w[cl][u];
+                g.cls_tap_off[cl][t] = (pcl->tr[cl][u] * g.IW + pcl->tc[cl][u]) * (2 * c.kc + 16);
+            }
+        }
+    } else {
+        for (int t = 0; t < ntaps; ++t) g.tap_off[t] = (tr[t] * g.IW + tc[t]) * (2 * c.kc + 16);
+    }
     int BM = 32 * c.a * c.wm;
-    dim3 grid((unsigned)(((g.N + g.TI - 1) / g.TI) * g.tiles_y * g.tiles_x), (unsigned)((g.out_CH + BM - 1) / BM),
-              (unsigned)pick_split);
+    dim3 grid((unsigned)(pix_tiles * (pcl ? 4 : 1)), (unsigned)((g.out_CH + BM - 1) / BM), (unsigned)pick_split);
     size_t lds = (size_t)g.TI * g.IH * g.IW * (2 * c.kc + 16 + 8);
     float *partial = nullptr;
     const int64_t n_out = (int64_t)g.N * g.out_H * g.out_W * g.out_CH;
@@ -424,13 +465,13 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
         partial = (float *)scr;
     }
     switch (pick) {
-    case 0: launch_cfg<2, 4, 1, 4, 32>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
-    case 1: launch_cfg<2, 4, 2, 2, 32>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
-    case 2: launch_cfg<2, 2, 2, 2, 32>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
-    case 3: launch_cfg<2, 2, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
-    case 4: launch_cfg<1, 2, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
-    case 5: launch_cfg<1, 1, 2, 2, 64>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
-    default: launch_cfg<1, 2, 2, 2, 16>(ctx->stream, grid, lds, ntaps, in, out, wz, partial, g); break;
+    case 0: launch_cfg<2, 4, 1, 4, 32>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
+    case 1: launch_cfg<2, 4, 2, 2, 32>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
+    case 2: launch_cfg<2, 2, 2, 2, 32>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
+    case 3: launch_cfg<2, 2, 2, 2, 64>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
+    case 4: launch_cfg<1, 2, 2, 2, 64>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
+    case 5: launch_cfg<1, 1, 2, 2, 64>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
+    default: launch_cfg<1, 2, 2, 2, 16>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
     }
     pc_status s = pc_hip_check(ctx, hipGetLastError(), "MFMA conv launch");
     if (s != PC_OK || pick_split == 1) return s;
@@ -470,22 +511,28 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
         for (int t = 0; t < 9; ++t) { g.tap_w[t] = t; tr[t] = 2 - t / 3; tc[t] = 2 - t % 3; }
         return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd);
     }
-    for (int py = 0; py < 2; ++py)
-        for (int px = 0; px < 2; ++px) {
-            g.GH = (d->H - py + 1) / 2;
-            g.GW = (d->W - px + 1) / 2;
-            if (g.GH < 1 || g.GW < 1) continue;
-            g.oscale = 2; g.ooff_y = py; g.ooff_x = px; g.ioff_y = g.ioff_x = 0;
-            int nt = 0;
-            for (int t = 0; t < 9; ++t) {
-                int r = t / 3, s = t % 3;
-                if ((py + 1 - r) % 2 == 0 && (px + 1 - s) % 2 == 0) {
-                    g.tap_w[nt] = t; tr[nt] = (py + 1 - r) / 2; tc[nt] = (px + 1 - s) / 2;
-                    ++nt;
-                }
+    // stride 2: input pixel (iy, ix) of parity class (py, px) = (iy % 2, ix % 2) receives the taps (r, s) with
+    // (py + 1 - r) and (px + 1 - s) even, from output pixel ((iy + 1 - r) / 2, (ix + 1 - s) / 2). One launch takes
+    // all four classes, the one with 4 taps first.
+    ParityClasses pcl;
+    memset(&pcl, 0, sizeof(pcl));
+    static const int order[4][2] = {{1, 1}, {1, 0}, {0, 1}, {0, 0}};
+    for (int cl = 0; cl < 4; ++cl) {
+        const int py = order[cl][0], px = order[cl][1];
+        pcl.GH[cl] = (d->H - py + 1) / 2;
+        pcl.GW[cl] = (d->W - px + 1) / 2;
+        pcl.ooy[cl] = py; pcl.oox[cl] = px;
+        int nt = 0;
+        for (int t = 0; t < 9; ++t) {
+            const int r = t / 3, s = t % 3;
+            if ((py + 1 - r) % 2 == 0 && (px + 1 - s) % 2 == 0) {
+                pcl.tap_w[cl][nt] = t; pcl.tr[cl][nt] = (py + 1 - r) / 2; pcl.tc[cl][nt] = (px + 1 - s) / 2;
+                ++nt;
             }
-            pc_status s = run_mfma_conv(ctx, g, 2, nt, tr, tc, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd);
-            if (s != PC_OK) return s;
         }
-    return PC_OK;
+        pcl.ntaps[cl] = nt;
+    }
+    g.GH = (d->H + 1) / 2; g.GW = (d->W + 1) / 2;
+    g.oscale = 2; g.ioff_y = g.ioff_x = 0;
+    return run_mfma_conv(ctx, g, 2, 4, nullptr, nullptr, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd, &pcl);
 }

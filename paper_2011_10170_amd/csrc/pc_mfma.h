@@ -20,6 +20,11 @@ struct MfmaArgs {
     int32_t nchunks, cps;    // chunks of KC channels in total, and per split (blockIdx.z)
     int32_t tap_w[9];        // weight tap index of every list entry
     int32_t tap_off[9];      // LDS byte offset of every list entry
+    // stride-2 backward-data as one launch: the four input-pixel parity classes (1, 2, 2 and 4 taps) are four
+    // ranges of blockIdx.x, each with its own output offset, extent and tap list (cls_tiles = 0: not used)
+    int32_t cls_tiles;               // pixel tiles per class
+    int32_t cls_GH[4], cls_GW[4], cls_ooy[4], cls_oox[4], cls_ntaps[4];
+    int32_t cls_tap_w[4][4], cls_tap_off[4][4];   // entries past the class's tap count repeat a valid one
     // used by the wave-specialised kernel only
     int32_t m_tiles, total_tiles;   // row tiles of the output channels; all tiles
     int32_t m_fast, fdiv;           // tile index = slow * fdiv + fast; m_fast: the row tile is the fast index (fdiv = m_tiles), else the pixel tile
