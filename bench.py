@@ -166,7 +166,12 @@ def main() -> int:
     for li, which, e0, e1 in events:
         per_call.setdefault((li, which), []).append(e0.elapsed_time(e1))
     kinds = {}
-    log("%-3s %-22s %-10s %-5s %9s %10s %10s %8s" % ("#", "layer", "pass", "var", "us", "nz TF/s", "dense TF/s", "GB/s"))
+    # roof = the call's roofline time / its measured time, roofline time = max(algorithmic bytes / HBM peak, issued
+    # flops / unit peak): issued flops are the dense zero-filled tile flops on the matrix-core kernels (bf16 peak) and
+    # the nonzero flops on the gather kernels (float32 vector peak); select and pack are priced by bytes alone
+    t_roof_sum = 0.0
+    t_meas_sum = 0.0
+    log("%-3s %-22s %-10s %-5s %9s %10s %10s %8s %6s" % ("#", "layer", "pass", "var", "us", "nz TF/s", "dense TF/s", "GB/s", "roof"))
     for (li, which), ts in sorted(per_call.items()):
         d = layers[li]
         L = d["L"]
@@ -188,9 +193,13 @@ def main() -> int:
                 byts = d["act_in"] + d["act_out"] + 16 * d["nnzk"]
         kk = kinds.setdefault(kind, dict(us=0.0, flops=0.0, dense=0.0, bytes=0.0, n=0))
         kk["us"] += us; kk["flops"] += fl; kk["dense"] += dfl; kk["bytes"] += byts; kk["n"] += 1
-        log("%-3d %-22s %-10s %-5s %9.1f %10.2f %10.1f %8.0f" % (
+        t_unit_us = (dfl / (PEAK_BF16_MFMA_TFLOPS * 1e6)) if var == "mfma" else (fl / (PEAK_F32_VALU_TFLOPS * 1e6))
+        t_roof_us = max(byts / (PEAK_HBM_GBS * 1e3), t_unit_us)
+        t_roof_sum += t_roof_us
+        t_meas_sum += us
+        log("%-3d %-22s %-10s %-5s %9.1f %10.2f %10.1f %8.0f %6.3f" % (
             li, "%dx%d %d->%d s%d" % (L.H, L.W, L.C, L.F, L.stride), which, var, us,
-            fl / us / 1e6, dfl / us / 1e6, byts / us / 1e3))
+            fl / us / 1e6, dfl / us / 1e6, byts / us / 1e3, t_roof_us / us))
     dom = max(kinds.items(), key=lambda kv: kv[1]["us"])
     dk, dv = dom
     t_hbm = dv["bytes"] / (PEAK_HBM_GBS * 1e9) * 1e6
@@ -236,6 +245,8 @@ def main() -> int:
         "algorithmic_gbs": round(dv["bytes"] / dv["us"] / 1e3, 1),
         "ideal_sparse_frac": round(max(t_hbm, dv["flops"] / (PEAK_F32_VALU_TFLOPS * 1e12) * 1e6) / dv["us"], 4),
         "share_of_step": round(dv["us"] / sum(k["us"] for k in kinds.values()), 3),
+        # all calls of the step: sum of their roofline times / the step time
+        "path_frac": round(t_roof_sum / (ms_per_step * 1e3), 4),
     }
     for kname, kv in sorted(kinds.items()):
         log("kind %-18s launches %3d  total %9.1f us  nz %8.2f TF/s  dense %8.1f TF/s  alg %7.0f GB/s" % (

@@ -358,8 +358,17 @@ pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, int64_t pstrid
     const int q = threadIdx.x % SPB, sg = threadIdx.x / SPB;
     const int64_t slot = (int64_t)blockIdx.x * SPB + q;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (slot < nnzk) {
-        for (int gi = sg; gi < G; gi += TPS) {
+    if (slot < pstride) {   // every plane holds pstride slots, so the loads need not wait for the count
+        // loads run ahead in groups of 8, the additions keep their order
+        int gi = sg;
+        for (; gi + 7 * TPS < G; gi += 8 * TPS) {
+            float4 p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) p[u] = partial[(int64_t)(gi + u * TPS) * pstride + slot];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { s.x += p[u].x; s.y += p[u].y; s.z += p[u].z; s.w += p[u].w; }
+        }
+        for (; gi < G; gi += TPS) {
             float4 p = partial[(int64_t)gi * pstride + slot];
             s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
         }
@@ -387,7 +396,10 @@ pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, int64
     if (nslots <= 0) return PC_OK;
     const float4 *pp = (const float4 *)partial;
     float4 *out = (float4 *)dw;
-    if (G >= 32)
+    if (G >= 128)
+        hipLaunchKernelGGL(pc_wgrad_reduce_kernel<64>, dim3((unsigned)((nslots + 3) / 4)), dim3(256), 0, ctx->stream, pp, G,
+                           pstride, pk->v, out);
+    else if (G >= 32)
         hipLaunchKernelGGL(pc_wgrad_reduce_kernel<16>, dim3((unsigned)((nslots + 15) / 16)), dim3(256), 0, ctx->stream, pp, G,
                            pstride, pk->v, out);
     else if (G >= 8)
