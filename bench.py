@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
     ap.add_argument("--cpu-sample-batch", type=int, default=128)
+    ap.add_argument("--train-steps", action="store_true",
+                    help="also time pool generation, finalisation counters and the group-lasso gradient over the workload's layers")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the batch would shard across GPUs with one "
@@ -261,6 +263,52 @@ def main() -> int:
         torch.cuda.synchronize()
         log("calibration copy: %d MiB read + %d MiB written" % (args.calib_copy_mb, args.calib_copy_mb))
 
+    # ---- the training-side steps over the same layers (one graph of all layers per step kind), HBM-bound
+    train_steps = None
+    if args.train_steps:
+        train_steps = {}
+        hist = torch.zeros(512, dtype=torch.int32, device="cuda")
+        for d in layers:
+            L = d["L"]
+            d["counts"] = torch.zeros((L.F, L.C, wl.P), dtype=torch.int32, device="cuda")
+            d["gdense"] = torch.zeros((L.F, L.C, 9), dtype=torch.float32, device="cuda")
+        pen = torch.zeros(1, dtype=torch.float64, device="cuda")
+        kinds_ts = {
+            "dppg_accumulate": (lambda d: B.pc_dppg_accumulate(ctx, d["W"], d["G"], d["L"].F, d["L"].C, hist, None), 72),
+            "finalize_count": (lambda d: B.pc_finalize_count(ctx, d["pid"], d["L"].F, d["L"].C, wl.P, d["counts"]), 9),
+            "finalize_pick": (lambda d: B.pc_finalize_pick(ctx, d["counts"], d["L"].F, d["L"].C, wl.P, d["pid"]), 4 * wl.P + 1),
+            "group_lasso_grad": (lambda d: B.pc_group_lasso_grad(ctx, d["W"], d["pid"], d["keep"], d["L"].F, d["L"].C, lib,
+                                                                 1e-4, 1e-4, d["gdense"], pen), 110),
+        }
+        n_kern = sum(d["L"].F * d["L"].C for d in layers)
+        for name, (fn, bytes_per_kernel) in kinds_ts.items():
+            for d in layers:
+                fn(d)
+            torch.cuda.synchronize()
+            gts = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gts, stream=stream):
+                for d in layers:
+                    fn(d)
+            gts.replay()
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                gts.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 10
+            gbs = n_kern * bytes_per_kernel / us / 1e3
+            train_steps[name] = {"us_all_layers": round(us, 1), "algorithmic_gbs": round(gbs, 1),
+                                 "hbm_frac": round(gbs / PEAK_HBM_GBS, 4)}
+            log("train step %-18s %2d layers %8.1f us  alg %7.0f GB/s (%d B per kernel position)" % (
+                name, len(layers), us, gbs, bytes_per_kernel))
+        # selection was overwritten by finalize_pick: restore the packs' masks for anything that follows
+        for d in layers:
+            run_pass(d, "select")
+        torch.cuda.synchronize()
+
     # ---- the CPU oracle on a bounded sample of the same workload (reported, not a target)
     cpu = None
     if not args.no_cpu_baseline:
@@ -299,6 +347,8 @@ def main() -> int:
                    "nonzero_gflop_per_step": round(total_flops / 1e9, 3)},
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if train_steps is not None:
+        out["train_steps"] = train_steps
     print(json.dumps(out), flush=True)
     for d in layers:
         B.pc_packed_free(d["pk"])

@@ -100,8 +100,9 @@ pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
  *   14, 15 as 9 with 128-channel chunks, and with tiles of 32 output channels x 32 pixels
  *   17, 18 as 13, 16 with 16-channel chunks (first layers); 19 as 13 with tiles of 32 output channels
  *   10, 11 backward-weight: the cooperative / the wave-specialised kernel (the other passes stay automatic)
- * The wave-specialised forward/backward-data kernel takes 9-tap launches only: the tap subsets of a strided
- * backward-data pass use the automatic choice. split_k > 0 forces that many splits of the reduction in the
+ * The wave-specialised forward/backward-data kernel takes 9-tap launches only: a stride-2 backward-data pass
+ * (one launch of the cooperative kernel over the four parity classes of input pixels) takes 0..6 and uses the
+ * automatic choice otherwise. split_k > 0 forces that many splits of the reduction in the
  * cooperative forward/backward-data kernel (0 = automatic). A configuration that does not fit a layer makes
  * the conv call return PC_ERR_UNSUPPORTED. Results do not depend on the choice beyond float32 summation
  * order. Returns PC_ERR_INVALID_ARG for values outside these ranges. */
@@ -152,7 +153,11 @@ pc_status pc_pack(pc_ctx *ctx, const float *W_dev, const uint8_t *pid_dev, const
  * dense-to-sparse conversion of Section 5.1). */
 pc_status pc_update_values(pc_ctx *ctx, pc_packed *pk, const float *W_dev);
 
-/* nnz_kernels = number of kept kernels (waits for the pack to finish); variant = family in use. */
+/* nnz_kernels = number of kept kernels; variant = family in use. The count is read back from the device the
+ * first time it is asked for after a pack: that call waits for the pack to finish (for a pack that was
+ * enqueued while its stream was being captured into a HIP graph it waits for the whole stream of ctx, and it
+ * must not be made during the capture). No other call needs the count on the host: a step of
+ * pc_pattern_select, pc_pack and the three passes enqueues without any read-back and can be captured. */
 pc_status pc_packed_info(pc_ctx *ctx, const pc_packed *pk, int64_t *nnz_kernels, int32_t *variant);
 void pc_packed_free(pc_packed *pk);
 
@@ -182,6 +187,51 @@ pc_status pc_conv_bwd_data(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packe
  * Deterministic: no floating-point atomics. */
 pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
                              const void *x_dev, const void *dy_dev, float *dw_compact_dev);
+
+/* ---- training-side steps around the path: pattern pool generation (Section 4.2), adaptive
+ *      finalisation (Section 4.3), modified group lasso (Section 4.4, Eq. 3 and Eq. 4) ---------- */
+
+/* Steps 1-4 of the pool generation for every kernel (f,c), from the tap importances s_t of
+ * pc_pattern_select: (1) the position with the highest importance; (2) the best of its horizontal, vertical
+ * and diagonal neighbours; (3) candidate positions = horizontal and vertical neighbours of those two;
+ * (4) the pair of candidates that gives the four-tap pattern with the highest importance
+ * ((s_a+s_b)+s_c)+s_d, taps ascending. Every arg max takes the first maximum (positions ascending, pairs in
+ * lexicographic order). The kernel's candidate pattern adds 1 to its competitive score:
+ *   hist_dev  : uint32 [512] device, indexed by the 9-bit mask; accumulated, the caller zeroes it before the
+ *               first call (step 5 repeats the call over the epochs)
+ *   masks_dev : uint16 [F][C] device or NULL; the candidate pattern of every kernel
+ * Float32 in the fixed order above, integer counting: bit-reproducible. */
+pc_status pc_dppg_accumulate(pc_ctx *ctx, const float *W_dev, const float *G_dev, int32_t F, int32_t C,
+                             uint32_t *hist_dev, uint16_t *masks_dev);
+
+/* Step 6: the n_patterns candidate patterns with the highest competitive scores, equal scores ordered by the
+ * lower mask; patterns never produced are not returned. Waits for the stream of ctx.
+ *   lib_host   : uint16 [n_patterns] host, output (the first *n_found entries are written)
+ *   score_host : uint32 [n_patterns] host or NULL, their scores */
+pc_status pc_dppg_pool(pc_ctx *ctx, const uint32_t *hist_dev, int32_t n_patterns, uint16_t *lib_host,
+                       uint32_t *score_host, int32_t *n_found);
+
+/* One batch of the adaptive finalisation: counts_dev[f][c][pid_dev[f][c]] += 1 with pid_dev from
+ * pc_pattern_select (the caller skips batches its loss margin rules out).
+ *   counts_dev : uint32 [F][C][P] device, accumulated; the caller zeroes it first */
+pc_status pc_finalize_count(pc_ctx *ctx, const uint8_t *pid_dev, int32_t F, int32_t C, int32_t P,
+                            uint32_t *counts_dev);
+
+/* The final pattern of every kernel: the most frequent of its per-batch best patterns (lowest id on ties).
+ *   pid_dev : uint8 [F][C] device, output */
+pc_status pc_finalize_pick(pc_ctx *ctx, const uint32_t *counts_dev, int32_t F, int32_t C, int32_t P,
+                           uint8_t *pid_dev);
+
+/* Gradient of the modified group-lasso penalty, added to a dense weight gradient. With one group per kernel,
+ * Z = the weights outside the kernel's pattern, U = all 9 weights of a kernel with keep = 0 (else 0):
+ *   dW[f][c][t] += lambda_p * Z_t / ||Z||_2 + lambda_i * U_t / ||U||_2     (a term whose norm is 0 adds 0)
+ *   *penalty_dev = lambda_p * sum ||Z|| + lambda_i * sum ||U|| over the layer (float64, NULL: not computed;
+ *                  summed in a fixed order)
+ * Float32 per kernel (squares added in ascending tap order, correctly rounded square root and division).
+ *   W_dev : float32 [F][C][9]; pid_dev, keep_dev : uint8 [F][C]; dW_dev : float32 [F][C][9], accumulated */
+pc_status pc_group_lasso_grad(pc_ctx *ctx, const float *W_dev, const uint8_t *pid_dev, const uint8_t *keep_dev,
+                              int32_t F, int32_t C, const uint16_t *lib_host, int32_t P,
+                              float lambda_p, float lambda_i, float *dW_dev, double *penalty_dev);
 
 #ifdef __cplusplus
 }

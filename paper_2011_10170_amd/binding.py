@@ -25,6 +25,7 @@ EXPORTS = [
     "pc_check_library", "pc_check_conv_desc", "pc_pattern_select", "pc_pack", "pc_update_values",
     "pc_packed_info", "pc_packed_free", "pc_scatter_dense", "pc_unpack_dense",
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
+    "pc_dppg_accumulate", "pc_dppg_pool", "pc_finalize_count", "pc_finalize_pick", "pc_group_lasso_grad",
 ]
 
 
@@ -74,6 +75,11 @@ def load():
     lib.pc_conv_fwd.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp]
     lib.pc_conv_bwd_data.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp]
     lib.pc_conv_bwd_weight.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp, vp]
+    lib.pc_dppg_accumulate.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.pc_dppg_pool.argtypes = [vp, vp, i32, vp, vp, ct.POINTER(i32)]
+    lib.pc_finalize_count.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.pc_finalize_pick.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.pc_group_lasso_grad.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, ct.c_float, ct.c_float, vp, vp]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("pc_destroy", "pc_packed_free", "pc_status_str", "pc_last_error"):
@@ -183,3 +189,31 @@ def pc_conv_bwd_data(ctx, desc, pk, dy, dx) -> None:
 
 def pc_conv_bwd_weight(ctx, desc, pk, x, dy, dw_compact) -> None:
     _check(ctx, load().pc_conv_bwd_weight(ctx, ct.byref(desc), pk, _ptr(x), _ptr(dy), _ptr(dw_compact)))
+
+
+def pc_dppg_accumulate(ctx, W, G, F, C, hist, masks=None) -> None:
+    _check(ctx, load().pc_dppg_accumulate(ctx, _ptr(W), _ptr(G), int(F), int(C), _ptr(hist), _ptr(masks)))
+
+
+def pc_dppg_pool(ctx, hist, n_patterns: int):
+    """Returns (masks, scores) of the patterns with the highest competitive scores (at most n_patterns)."""
+    lib_out = (ct.c_uint16 * n_patterns)()
+    score_out = (ct.c_uint32 * n_patterns)()
+    n = ct.c_int32()
+    _check(ctx, load().pc_dppg_pool(ctx, _ptr(hist), int(n_patterns), ct.cast(lib_out, ct.c_void_p),
+                                    ct.cast(score_out, ct.c_void_p), ct.byref(n)))
+    return [int(lib_out[i]) for i in range(n.value)], [int(score_out[i]) for i in range(n.value)]
+
+
+def pc_finalize_count(ctx, pid, F, C, P, counts) -> None:
+    _check(ctx, load().pc_finalize_count(ctx, _ptr(pid), int(F), int(C), int(P), _ptr(counts)))
+
+
+def pc_finalize_pick(ctx, counts, F, C, P, pid) -> None:
+    _check(ctx, load().pc_finalize_pick(ctx, _ptr(counts), int(F), int(C), int(P), _ptr(pid)))
+
+
+def pc_group_lasso_grad(ctx, W, pid, keep, F, C, masks, lambda_p, lambda_i, dW, penalty=None) -> None:
+    arr = _lib_arr(masks)
+    _check(ctx, load().pc_group_lasso_grad(ctx, _ptr(W), _ptr(pid), _ptr(keep), int(F), int(C), ct.cast(arr, ct.c_void_p),
+                                           len(masks), float(lambda_p), float(lambda_i), _ptr(dW), _ptr(penalty)))
