@@ -61,35 +61,6 @@ pc_select_score_kernel(const float *__restrict__ W, const float *__restrict__ G,
     R[k] = r;
 }
 
-// Exact rank inside a segment of length L: element i is kept iff fewer than n_keep elements
-// precede it in the order (score descending, index ascending).
-#define PC_RANK_CHUNK 2048
-__global__ void __launch_bounds__(256)
-pc_select_rank_kernel(const float *__restrict__ R, int64_t L, int64_t n_keep, uint8_t *__restrict__ keep)
-{
-    __shared__ float tile[PC_RANK_CHUNK];
-    const float *seg = R + (int64_t)blockIdx.y * L;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    bool live = i < L;
-    float mine = live ? seg[i] : 0.0f;
-    int64_t before = 0;
-    for (int64_t j0 = 0; j0 < L; j0 += PC_RANK_CHUNK) {
-        int64_t m = L - j0 < PC_RANK_CHUNK ? L - j0 : PC_RANK_CHUNK;
-        __syncthreads();
-        for (int64_t j = threadIdx.x; j < m; j += blockDim.x) tile[j] = seg[j0 + j];
-        __syncthreads();
-        if (live) {
-            int cnt = 0;
-            for (int64_t j = 0; j < m; ++j) {
-                float o = tile[j];
-                cnt += (o > mine) || (o == mine && (j0 + j) < i);
-            }
-            before += cnt;
-        }
-    }
-    if (live) keep[(int64_t)blockIdx.y * L + i] = before < n_keep ? 1 : 0;
-}
-
 // Exact top-n_keep of every row of R (n rows of length L, L <= PC_TOPN_MAX) in the order (score descending,
 // index ascending), one workgroup per row: a 4-pass radix select over order-preserving 32-bit keys finds the
 // score of the n_keep-th kernel and how many kernels with exactly that score are kept; those are the ones
@@ -284,6 +255,156 @@ pc_select_row_kernel(const float *__restrict__ W, const float *__restrict__ G, i
     }
 }
 
+// ---- exact top-n_keep of long segments (more than PC_TOPN_MAX scores): the same radix select across workgroups.
+// Segment g has L scores; state per segment: hist[4][256] (zeroed first), then per-workgroup counts of the scores
+// equal to the threshold. Pass q counts the digit (bits 31-8q .. 24-8q of the order-preserving key) of the
+// scores whose higher digits equal the prefix chosen by the passes before; every workgroup derives that prefix
+// again from the finished histograms (a 256-bin scan per pass) instead of reading it from a single writer.
+#define PC_TOPN_CHUNK 2048      // scores per workgroup in the counting and writing kernels
+
+// Wave 0 replays passes 0..upto-1: prefix and remaining count after them. All threads call it; ends with a barrier.
+__device__ __forceinline__ void pc_topn_replay(const uint32_t *__restrict__ hist, int upto, int n_keep, uint32_t *s_prefix,
+                                               int *s_rem)
+{
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        uint32_t prefix = 0u;
+        int rem = n_keep;
+        for (int q = 0; q < upto; ++q) {
+            const uint32_t *h = hist + q * 256 + 4 * lane;      // lane owns digits 4*lane .. 4*lane+3
+            const int h0 = (int)h[0], h1 = (int)h[1], h2 = (int)h[2], h3 = (int)h[3];
+            const int mine = h0 + h1 + h2 + h3;
+            int incl = mine;
+            for (int off = 1; off < 64; off <<= 1) {
+                const int t = __shfl_down(incl, off);
+                if (lane + off < 64) incl += t;
+            }
+            const int e3 = incl - mine, e2 = e3 + h3, e1 = e2 + h2, e0 = e1 + h1;   // candidates with a larger digit
+            int d = -1, ex = 0;
+            if (e3 < rem && rem <= e3 + h3) { d = 3; ex = e3; }
+            else if (e2 < rem && rem <= e2 + h2) { d = 2; ex = e2; }
+            else if (e1 < rem && rem <= e1 + h1) { d = 1; ex = e1; }
+            else if (e0 < rem && rem <= e0 + h0) { d = 0; ex = e0; }
+            const unsigned long long found = __ballot(d >= 0);  // exactly one lane while 1 <= rem <= candidates
+            const int src = found ? __ffsll((long long)found) - 1 : 0;
+            const int digit = __shfl(4 * lane + (d < 0 ? 0 : d), src);
+            const int exs = __shfl(ex, src);
+            prefix |= (uint32_t)digit << (24 - 8 * q);
+            rem -= exs;
+        }
+        if (lane == 0) { *s_prefix = prefix; *s_rem = rem; }
+    }
+    __syncthreads();
+}
+
+__global__ void __launch_bounds__(256) pc_topn_zero_kernel(uint32_t *__restrict__ state, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) state[i] = 0u;
+}
+
+__global__ void __launch_bounds__(256)
+pc_topn_hist_kernel(const float *__restrict__ R, int64_t L, int n_keep, uint32_t *__restrict__ hist_all, int pass)
+{
+    __shared__ int lh[256];
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_rem;
+    const float *seg = R + (int64_t)blockIdx.y * L;
+    uint32_t *hist = hist_all + (int64_t)blockIdx.y * 1024;
+    lh[threadIdx.x] = 0;
+    pc_topn_replay(hist, pass, n_keep, &s_prefix, &s_rem);
+    const uint32_t prefix = s_prefix;
+    const int shift = 24 - 8 * pass;
+    const uint32_t himask = pass == 0 ? 0u : 0xFFFFFFFFu << (shift + 8);
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < L; i += (int64_t)gridDim.x * 256) {
+        const uint32_t k = pc_order_key(seg[i]);
+        if ((k & himask) == prefix) atomicAdd(&lh[(k >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    if (lh[threadIdx.x]) atomicAdd(&hist[pass * 256 + threadIdx.x], (uint32_t)lh[threadIdx.x]);   // integers: order-free
+}
+
+// Scores equal to the threshold in every chunk of PC_TOPN_CHUNK scores.
+__global__ void __launch_bounds__(256)
+pc_topn_count_equal_kernel(const float *__restrict__ R, int64_t L, int n_keep, const uint32_t *__restrict__ hist_all,
+                           uint32_t *__restrict__ blk_eq, int nchunks)
+{
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_rem, s_cnt[4];
+    const float *seg = R + (int64_t)blockIdx.y * L;
+    pc_topn_replay(hist_all + (int64_t)blockIdx.y * 1024, 4, n_keep, &s_prefix, &s_rem);
+    const uint32_t T = s_prefix;
+    const int64_t i0 = (int64_t)blockIdx.x * PC_TOPN_CHUNK;
+    int cnt = 0;
+    for (int j = threadIdx.x; j < PC_TOPN_CHUNK; j += 256)
+        if (i0 + j < L && pc_order_key(seg[i0 + j]) == T) ++cnt;
+    for (int off = 32; off > 0; off >>= 1) cnt += __shfl_down(cnt, off);
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) blk_eq[(int64_t)blockIdx.y * nchunks + blockIdx.x] = (uint32_t)(s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3]);
+}
+
+// In-place exclusive scan of the chunk counts of every segment (one workgroup per segment).
+__global__ void __launch_bounds__(256) pc_topn_scan_kernel(uint32_t *__restrict__ blk_eq, int nchunks)
+{
+    __shared__ uint32_t part[256];
+    uint32_t *v = blk_eq + (int64_t)blockIdx.x * nchunks;
+    const int per = (nchunks + 255) / 256;
+    const int lo = threadIdx.x * per, hi = lo + per < nchunks ? lo + per : nchunks;
+    uint32_t sum = 0;
+    for (int i = lo; i < hi; ++i) sum += v[i];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {
+        const uint32_t add = threadIdx.x >= d ? part[threadIdx.x - d] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint32_t run = part[threadIdx.x] - sum;
+    for (int i = lo; i < hi; ++i) {
+        const uint32_t c = v[i];
+        v[i] = run;
+        run += c;
+    }
+}
+
+// keep = 1 for scores above the threshold and for the first take_equal scores equal to it (by index).
+__global__ void __launch_bounds__(256)
+pc_topn_write_kernel(const float *__restrict__ R, int64_t L, int n_keep, const uint32_t *__restrict__ hist_all,
+                     const uint32_t *__restrict__ blk_excl, int nchunks, uint8_t *__restrict__ keep)
+{
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_rem, s_wave_cnt[4];
+    const float *seg = R + (int64_t)blockIdx.y * L;
+    uint8_t *out = keep + (int64_t)blockIdx.y * L;
+    pc_topn_replay(hist_all + (int64_t)blockIdx.y * 1024, 4, n_keep, &s_prefix, &s_rem);
+    const uint32_t T = s_prefix;
+    const int take_equal = s_rem;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int base = (int)blk_excl[(int64_t)blockIdx.y * nchunks + blockIdx.x];
+    const int64_t i0 = (int64_t)blockIdx.x * PC_TOPN_CHUNK;
+    for (int j0 = 0; j0 < PC_TOPN_CHUNK; j0 += 256) {
+        const int64_t i = i0 + j0 + threadIdx.x;
+        const uint32_t k = i < L ? pc_order_key(seg[i]) : 0u;
+        const bool eq = i < L && k == T;
+        const unsigned long long b = __ballot(eq);
+        if (lane == 0) s_wave_cnt[wave] = __popcll(b);
+        __syncthreads();
+        int before = base + __popcll(b & ((1ull << lane) - 1ull));
+        for (int w2 = 0; w2 < wave; ++w2) before += s_wave_cnt[w2];
+        if (i < L) out[i] = (k > T || (eq && before < take_equal)) ? 1 : 0;
+        base += s_wave_cnt[0] + s_wave_cnt[1] + s_wave_cnt[2] + s_wave_cnt[3];
+        __syncthreads();
+    }
+}
+
+__global__ void __launch_bounds__(256) pc_fill_u8_kernel(uint8_t *__restrict__ p, int64_t n, uint8_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
 pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, int C, const LibArg &la,
                            pc_keep_mode km, int64_t n_keep, pc_score_mode sm, uint8_t *pid, uint8_t *keep)
 {
@@ -302,20 +423,38 @@ pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, i
                            nk_row, pid, keep);
         return pc_hip_check(ctx, hipGetLastError(), "select launch");
     }
+    const int64_t L = (km == PC_KEEP_PER_FILTER) ? C : nk;
+    const unsigned nseg = (km == PC_KEEP_PER_FILTER) ? (unsigned)F : 1u;
+    if (L >= ((int64_t)1 << 31)) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "select: %lld scores in one segment (limit 2^31 - 1)", (long long)L);
+    const int nchunks = (int)((L + PC_TOPN_CHUNK - 1) / PC_TOPN_CHUNK);
+    const size_t r_bytes = (sizeof(float) * (size_t)nk + 255) / 256 * 256;
+    const size_t state_words = L > PC_TOPN_MAX ? (size_t)nseg * (1024 + (size_t)nchunks) : 0;
     void *scr = nullptr;
-    pc_status s = pc_scratch(ctx, sizeof(float) * (size_t)nk, &scr);
+    pc_status s = pc_scratch(ctx, r_bytes + sizeof(uint32_t) * state_words, &scr);
     if (s != PC_OK) return s;
     float *R = (float *)scr;
     unsigned blocks = (unsigned)((nk + 255) / 256);
     hipLaunchKernelGGL(pc_select_score_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, G, nk, la, (int)sm, pid, R);
-    int64_t L = (km == PC_KEEP_PER_FILTER) ? C : nk;
-    unsigned nseg = (km == PC_KEEP_PER_FILTER) ? (unsigned)F : 1u;
     if (L <= PC_TOPN_MAX) {
         hipLaunchKernelGGL(pc_select_topn_row_kernel, dim3(nseg), dim3(256), sizeof(uint32_t) * (size_t)L, ctx->stream, R, (int)L,
                            (int)(n_keep < L ? n_keep : L), keep);
+    } else if (n_keep <= 0 || n_keep >= L) {
+        hipLaunchKernelGGL(pc_fill_u8_kernel, dim3(blocks), dim3(256), 0, ctx->stream, keep, nk, (uint8_t)(n_keep > 0 ? 1 : 0));
     } else {
-        dim3 grid((unsigned)((L + 255) / 256), nseg);
-        hipLaunchKernelGGL(pc_select_rank_kernel, grid, dim3(256), 0, ctx->stream, R, L, n_keep, keep);
+        uint32_t *hist = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(scr) + r_bytes);
+        uint32_t *blk_eq = hist + (size_t)nseg * 1024;
+        hipLaunchKernelGGL(pc_topn_zero_kernel, dim3((unsigned)((nseg * 1024 + 255) / 256)), dim3(256), 0, ctx->stream, hist,
+                           (int64_t)nseg * 1024);
+        int hb = (int)((L + 255) / 256);
+        const int hb_max = nseg >= 64 ? 8 : 4 * ctx->num_cu;     // workgroups per segment in the counting passes
+        if (hb > hb_max) hb = hb_max;
+        for (int pass = 0; pass < 4; ++pass)
+            hipLaunchKernelGGL(pc_topn_hist_kernel, dim3((unsigned)hb, nseg), dim3(256), 0, ctx->stream, R, L, (int)n_keep, hist, pass);
+        hipLaunchKernelGGL(pc_topn_count_equal_kernel, dim3((unsigned)nchunks, nseg), dim3(256), 0, ctx->stream, R, L, (int)n_keep,
+                           hist, blk_eq, nchunks);
+        hipLaunchKernelGGL(pc_topn_scan_kernel, dim3(nseg), dim3(256), 0, ctx->stream, blk_eq, nchunks);
+        hipLaunchKernelGGL(pc_topn_write_kernel, dim3((unsigned)nchunks, nseg), dim3(256), 0, ctx->stream, R, L, (int)n_keep, hist,
+                           blk_eq, nchunks, keep);
     }
     return pc_hip_check(ctx, hipGetLastError(), "select launch");
 }

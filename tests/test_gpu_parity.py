@@ -336,6 +336,34 @@ def test_select_long_rows_with_partial_ties(B, ctx, oracle):
             assert int(kp.sum()) == F * min(n_keep, C)
 
 
+def test_select_per_layer_long_segments(B, ctx, oracle):
+    """Per-layer keep mode on layers of more than 8192 kernels (the radix select runs across workgroups): random
+    scores, scores with many ties at the cut, and the degenerate counts."""
+    import torch
+    rng = np.random.default_rng(17)
+    lib = I.make_library(8)
+    cases = []
+    for F, C in ((29, 700), (128, 130), (512, 512)):
+        Wq = rng.integers(-3, 4, size=(F, C, 9)).astype(np.float32) * 0.25
+        Gq = rng.integers(-2, 3, size=(F, C, 9)).astype(np.float32)
+        cases.append((Wq, Gq, [1, F * C // 3, F * C - 1, 0, F * C]))
+        cases.append((I.gen_weights(F, C, I.BASE_SEED, ("perlayer", F)), I.gen_weight_grads(F, C, I.BASE_SEED, ("perlayer", F)),
+                      [F * C * 3 // 10]))
+    for Wn, Gn, counts in cases:
+        F, C = Wn.shape[:2]
+        Wd, Gd = to_dev(Wn), to_dev(Gn)
+        for n_keep in counts:
+            for sm in (0, 1):
+                pid, kp = oracle.select(Wn, Gn, lib, n_keep, keep_mode=1, score_mode=sm)
+                gp = torch.full((F, C), 255, dtype=torch.uint8, device="cuda")
+                gk = torch.full((F, C), 255, dtype=torch.uint8, device="cuda")
+                B.pc_pattern_select(ctx, Wd, Gd, F, C, lib, 1, n_keep, sm, gp, gk)
+                torch.cuda.synchronize()
+                assert np.array_equal(gp.cpu().numpy(), pid), (F, C, n_keep, sm)
+                assert np.array_equal(gk.cpu().numpy(), kp), (F, C, n_keep, sm)
+                assert int(kp.sum()) == n_keep
+
+
 @pytest.mark.parametrize("shape", [(2, 9, 9, 40, 72, 1), (2, 8, 8, 6, 40, 1), (3, 7, 5, 130, 33, 2)])
 def test_update_values_bf16_tiles(B, ctx, oracle, shape):
     """pc_update_values on a bf16 pack rebuilds the matrix-core operand tiles from the tables of the pack."""
