@@ -62,13 +62,14 @@ MEDIUM_BF16 = [
 ]
 
 
-def run_case(B, ctx, oracle, shape, dtype, P, keep, variant, tag):
+def run_case(B, ctx, oracle, shape, dtype, P, keep, variant, tag, keep_mode=0):
     N, H, W, C, F, stride = shape
     layer = I.Layer(N, H, W, C, F, stride)
-    case = Case(layer, dtype, P, I.kept_per_filter(keep, C), tag=(tag, shape, dtype))
-    say("case", tag, shape, dtype, "P", P, "keep", keep, "variant", variant)
-    pid, kp, M, Wm = oracle_masks(oracle, case)
-    g = GpuLayer(B, ctx, case, variant=variant)
+    n_keep = I.kept_per_filter(keep, C) if keep_mode == 0 else max(1, int(keep * F * C + 0.5))
+    case = Case(layer, dtype, P, n_keep, tag=(tag, shape, dtype))
+    say("case", tag, shape, dtype, "P", P, "keep", keep, "variant", variant, "keep_mode", keep_mode)
+    pid, kp, M, Wm = oracle_masks(oracle, case, keep_mode=keep_mode)
+    g = GpuLayer(B, ctx, case, variant=variant, keep_mode=keep_mode)
     try:
         gpid, gkeep = g.masks()
         assert np.array_equal(gpid, pid), "pattern ids differ"
@@ -188,6 +189,17 @@ def test_medium_bf16_valu(B, ctx, oracle, shape):
 @pytest.mark.parametrize("shape", MEDIUM_BF16)
 def test_medium_bf16_auto(B, ctx, oracle, shape):
     run_case(B, ctx, oracle, shape, "bf16", 16, 0.25, B.PC_VARIANT_AUTO, "medium")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 9, 9, 24, 40, 1), (3, 8, 8, 64, 64, 2), (2, 6, 6, 130, 96, 1)])
+def test_per_layer_keep_unbalanced_rows(B, ctx, oracle, shape, dtype):
+    """Kept kernels chosen over the whole layer: filters keep different numbers of kernels (some possibly none)."""
+    N, H, W, C, F, stride = shape
+    run_case(B, ctx, oracle, shape, dtype, 8, 0.15, B.PC_VARIANT_AUTO, "perlayer", keep_mode=1)
+    layer_case = Case(I.Layer(*shape), dtype, 8, max(1, int(0.15 * F * C + 0.5)), tag=("perlayer", shape, dtype))
+    _, kp, _, _ = oracle_masks(oracle, layer_case, keep_mode=1)
+    assert len(set(kp.sum(axis=1).tolist())) > 1          # the rows really are unbalanced
 
 
 def test_full_pool_and_every_pattern_f32(B, ctx, oracle):
