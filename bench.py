@@ -309,6 +309,40 @@ def main() -> int:
             run_pass(d, "select")
         torch.cuda.synchronize()
 
+    # ---- context only: the paper's one absolute time for this path is the demonstration layer of its Section 5.1
+    # (256 filters x 128 channels on a 224x224 map, batch 1: a 256x1152 by 1152x50176 SpMM, about 3000 us on one
+    # Quadro RTX 5000, precision and sparsity not stated). The same layer shape through pc_conv_fwd here:
+    paper_context = None
+    if wl.dtype == "bf16":
+        Lp = I.Layer(1, 224, 224, 128, 256, 1)
+        Wp = up(I.gen_weights(Lp.F, Lp.C, I.BASE_SEED, "paper_demo"))
+        kp_n = I.kept_per_filter(wl.keep, Lp.C)
+        pidp = torch.empty((Lp.F, Lp.C), dtype=torch.uint8, device="cuda")
+        keepp = torch.empty((Lp.F, Lp.C), dtype=torch.uint8, device="cuda")
+        B.pc_pattern_select(ctx, Wp, None, Lp.F, Lp.C, lib, B.PC_KEEP_PER_FILTER, kp_n, B.PC_SCORE_RETAINED, pidp, keepp)
+        pkp = B.pc_pack(ctx, Wp, pidp, keepp, Lp.F, Lp.C, lib, dt)
+        xp = up(I.gen_activations((1, 224, 224, 128), I.BASE_SEED, "paper_demo_x", True, wl.dtype)[1])
+        yp = torch.empty((1, 224, 224, 256), dtype=tdt, device="cuda")
+        descp = B.make_desc(1, 224, 224, 128, 256, 1, dt)
+        for _ in range(3):
+            B.pc_conv_fwd(ctx, descp, pkp, xp, yp)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(20):
+            B.pc_conv_fwd(ctx, descp, pkp, xp, yp)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us_p = e0.elapsed_time(e1) * 1e3 / 20
+        B.pc_packed_free(pkp)
+        paper_context = {"layer": "1x224x224, 128->256 (the 256x1152 by 1152x50176 product of Section 5.1)",
+                         "fwd_us_here": round(us_p, 1), "keep": wl.keep, "dtype": wl.dtype,
+                         "paper_us": 3000, "paper_hardware": "1x Quadro RTX 5000, precision and sparsity not stated",
+                         "note": "context only, not a target"}
+        log("paper's demonstration layer (Section 5.1), forward: %.1f us here (bf16, keep %.2f); paper: about 3000 us "
+            "SpMM on one Quadro RTX 5000 (context only)" % (us_p, wl.keep))
+
     # ---- the CPU oracle on a bounded sample of the same workload (reported, not a target)
     cpu = None
     if not args.no_cpu_baseline:
@@ -349,6 +383,8 @@ def main() -> int:
     }
     if train_steps is not None:
         out["train_steps"] = train_steps
+    if paper_context is not None:
+        out["paper_context"] = paper_context
     print(json.dumps(out), flush=True)
     for d in layers:
         B.pc_packed_free(d["pk"])
