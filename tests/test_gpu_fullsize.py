@@ -66,15 +66,29 @@ def test_full_size_layer(B, ctx, oracle, name, li):
     L = wl.layers[li]
     print("full-size", name, li, L, flush=True)
     sys.stdout.flush()
-    rng = np.random.default_rng(1000 + li)
-    case = Case(L, wl.dtype, wl.P, I.kept_per_filter(wl.keep, L.C), tag=("full", name, li))
+    _check_layer_sampled(B, ctx, oracle, L, wl.dtype, wl.P, wl.keep, ("full", name, li), 1000 + li)
+
+
+@pytest.mark.timeout(600)
+def test_tensors_beyond_2_gib(B, ctx, oracle):
+    """An activation tensor of more than 2^31 bytes: the kernels that address through 32-bit buffer offsets step
+    aside and the passes run on the kernels with 64-bit addressing. Sampled outputs include the last image."""
+    L = I.Layer(5, 1024, 1024, 256, 8, 1)
+    assert L.N * L.H * L.W * L.C * 2 > (1 << 31)
+    print("beyond 2 GiB", L, flush=True)
+    _check_layer_sampled(B, ctx, oracle, L, "bf16", 8, 0.3, ("huge",), 77)
+
+
+def _check_layer_sampled(B, ctx, oracle, L, dtype, P, keep, tag, seed):
+    rng = np.random.default_rng(seed)
+    case = Case(L, dtype, P, I.kept_per_filter(keep, L.C), tag=tag)
     pid, kp, M, Wm = oracle_masks(oracle, case)
     g = GpuLayer(B, ctx, case)
     try:
         assert g.variant == B.PC_VARIANT_MFMA
         gpid, gkeep = g.masks()
         assert np.array_equal(gpid, pid) and np.array_equal(gkeep, kp)
-        assert g.nnzk == int(kp.sum()) == L.F * I.kept_per_filter(wl.keep, L.C)
+        assert g.nnzk == int(kp.sum()) == L.F * I.kept_per_filter(keep, L.C)
         assert np.array_equal(g.unpack(), Wm)
 
         y = g.fwd().reshape(-1)
@@ -94,7 +108,7 @@ def test_full_size_layer(B, ctx, oracle, name, li):
         del dx
 
         dw, guard = g.bwd_weight()
-        sf, sc = oracle.compact_order(pid, kp, wl.P)
+        sf, sc = oracle.compact_order(pid, kp, P)
         slots = rng.integers(0, g.nnzk, size=N_WSAMPLES)
         widx, got = [], []
         for s in slots:
