@@ -184,7 +184,10 @@ pc_status pc_conv_bwd_data(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packe
 
 /* Weight gradient at kept taps only, float32 [nnz_kernels][4] in compact slot order:
  * dw[f,c,t] = sum_{n,oy,ox} dy[n,oy,ox,f] * x[n, oy*stride+r-1, ox*stride+s-1, c].
- * Deterministic: no floating-point atomics. */
+ * Deterministic: no floating-point atomics (per-split partial sums in the context's scratch buffer, added in a
+ * fixed order). The call never reads the kept-kernel count back: until pc_packed_info has been asked for it
+ * after the last pack, the partial sums are laid out for F*C slots (16 bytes x splits x F*C of scratch, touched
+ * only at kept slots). dw_compact_dev must hold nnz_kernels x 4 floats. */
 pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
                              const void *x_dev, const void *dy_dev, float *dw_compact_dev);
 
