@@ -389,15 +389,15 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 #define KS_LDS_MAX (160 * 1024)
 
 template <int A_T, int B_T, int KC, int KSP>
-static hipError_t launch_ks(hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out, const uint16_t *wz,
-                            const MfmaArgs &g)
+static hipError_t launch_ks(int device, hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out,
+                            const uint16_t *wz, const MfmaArgs &g)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
+    static pc_per_device_once attr;
+    if (pc_once_pending(attr, device)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, KS_LDS_MAX);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        pc_once_done(attr, device);
     }
     hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
     return hipGetLastError();
@@ -511,16 +511,16 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
     const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;
     hipError_t e;
     switch (best_k) {
-    case 0: e = launch_ks<2, 4, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 1: e = launch_ks<2, 2, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 2: e = launch_ks<2, 1, 64, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 3: e = launch_ks<2, 4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 4: e = launch_ks<2, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 5: e = launch_ks<1, 1, 128, 4>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 6: e = launch_ks<2, 2, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 7: e = launch_ks<2, 4, 16, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 8: e = launch_ks<2, 2, 16, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
-    default: e = launch_ks<1, 4, 32, 1>(ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 0: e = launch_ks<2, 4, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 1: e = launch_ks<2, 2, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 2: e = launch_ks<2, 1, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 3: e = launch_ks<2, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 4: e = launch_ks<2, 1, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 5: e = launch_ks<1, 1, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 6: e = launch_ks<2, 2, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 7: e = launch_ks<2, 4, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 8: e = launch_ks<2, 2, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<1, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
     }
     *launched = true;
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");

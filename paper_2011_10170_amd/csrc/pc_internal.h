@@ -72,6 +72,12 @@ struct LibArg {
     uint8_t taps[PC_MAX_P][4];
 };
 
+// A kernel's dynamic-LDS limit is a function attribute of a device: it is raised on first use per device.
+#define PC_MAX_DEVICES 64
+struct pc_per_device_once { bool done[PC_MAX_DEVICES]; };
+inline bool pc_once_pending(const pc_per_device_once &o, int device) { return device < 0 || device >= PC_MAX_DEVICES || !o.done[device]; }
+inline void pc_once_done(pc_per_device_once &o, int device) { if (device >= 0 && device < PC_MAX_DEVICES) o.done[device] = true; }
+
 pc_status pc_fail(pc_ctx *ctx, pc_status s, const char *fmt, ...);
 pc_status pc_hip_check(pc_ctx *ctx, hipError_t e, const char *what);
 pc_status pc_scratch(pc_ctx *ctx, size_t bytes, void **out);

@@ -412,11 +412,11 @@ pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, i
     if (km == PC_KEEP_PER_FILTER && C <= PC_TOPN_MAX) {
         const int T = C <= 256 ? 256 : 512;
         const size_t lds = sizeof(uint32_t) * (size_t)C + 2 * sizeof(float) * 9 * (size_t)T;   // at most 68 KiB
-        static bool attr_done = false;
-        if (!attr_done) {
+        static pc_per_device_once attr;
+        if (pc_once_pending(attr, ctx->device)) {
             PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_select_row_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                             (int)(sizeof(uint32_t) * PC_TOPN_MAX + 2 * sizeof(float) * 9 * 512)));
-            attr_done = true;
+            pc_once_done(attr, ctx->device);
         }
         const int nk_row = (int)(n_keep < C ? n_keep : C);
         hipLaunchKernelGGL(pc_select_row_kernel, dim3((unsigned)F), dim3((unsigned)T), lds, ctx->stream, W, G, C, la, (int)sm,
