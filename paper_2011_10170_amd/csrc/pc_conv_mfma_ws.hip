@@ -458,9 +458,11 @@ static bool plan_ks(const MfmaArgs &g, int ext, int at, int bt, int ksp, int kc,
     // cycles of one workgroup: tiles per workgroup x (MFMAs of a tile at 32 cycles each per wavefront + the tile's
     // fixed cost: the reduction across wavefronts, or just the store)
     const int64_t rounds = (total + num_cu - 1) / num_cu;
-    // (an item also costs a barrier and the refill of the fragment pipelines: about 450 cycles)
-    if (ksp == 4) *est = (double)rounds * ((double)t.nchunks * (288.0 * at * bt * kc / 64 + 450.0) + 2500.0);
-    else *est = (double)rounds * ((double)t.nchunks * (18.0 * kc * at * bt + 450.0) + 1200.0);
+    // (an item also costs a barrier and the refill of the fragment pipelines: about 450 cycles; inside an item the
+    // MFMAs issue at about 70 % of their peak rate in both splits, which weighs the fixed costs against them)
+    const double mfma_eff = 0.7;
+    if (ksp == 4) *est = (double)rounds * ((double)t.nchunks * (288.0 * at * bt * kc / 64 / mfma_eff + 450.0) + 2500.0);
+    else *est = (double)rounds * ((double)t.nchunks * (18.0 * kc * at * bt / mfma_eff + 450.0) + 1200.0);
     // A workgroup with a single 512-pixel tile overlaps nothing: it loads its whole input, multiplies, then stores.
     // Two 256-pixel tiles hide the second load and the first store (measured with cold caches on 32x32 maps,
     // 64 -> 64 channels, batch 128: 23.5 us against 29.8 us), which the cycle count above does not see.
@@ -477,10 +479,10 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
 {
     *launched = false;
     // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
-    enum { NCAND = 10 };
-    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1, 2, 2, 2, 1}, kBt[NCAND] = {4, 2, 1, 4, 1, 1, 2, 4, 2, 4},
-                     kKsp[NCAND] = {4, 4, 4, 1, 4, 4, 1, 1, 1, 1}, kKc[NCAND] = {64, 64, 64, 32, 128, 128, 32, 16, 16, 32},
-                     kCode[NCAND] = {7, 8, 9, 13, 14, 15, 16, 17, 18, 19};
+    enum { NCAND = 11 };
+    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1, 2, 2, 2, 1, 2}, kBt[NCAND] = {4, 2, 1, 4, 1, 1, 2, 4, 2, 4, 2},
+                     kKsp[NCAND] = {4, 4, 4, 1, 4, 4, 1, 1, 1, 1, 1}, kKc[NCAND] = {64, 64, 64, 32, 128, 128, 32, 16, 16, 32, 64},
+                     kCode[NCAND] = {7, 8, 9, 13, 14, 15, 16, 17, 18, 19, 20};
     MfmaArgs best;
     size_t best_lds = 0;
     double best_est = 0.0;
@@ -520,7 +522,8 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
     case 6: e = launch_ks<2, 2, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
     case 7: e = launch_ks<2, 4, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
     case 8: e = launch_ks<2, 2, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    default: e = launch_ks<1, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 9: e = launch_ks<1, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<2, 2, 64, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
     }
     *launched = true;
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");
