@@ -99,7 +99,7 @@ pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
  *          32-channel chunks)
  *   14, 15 as 9 with 128-channel chunks, and with tiles of 32 output channels x 32 pixels
  *   17, 18 as 13, 16 with 16-channel chunks (first layers); 19 as 13 with tiles of 32 output channels;
- *          20 as 16 with 64-channel chunks
+ *          20 as 16 with 64-channel chunks; 21 as 8 with 128-channel chunks
  *   10, 11 backward-weight: the cooperative / the wave-specialised kernel (the other passes stay automatic)
  * The wave-specialised forward/backward-data kernel takes 9-tap launches only: a stride-2 backward-data pass
  * (one launch of the cooperative kernel over the four parity classes of input pixels) takes 0..6 and uses the

@@ -479,10 +479,10 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
 {
     *launched = false;
     // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
-    enum { NCAND = 11 };
-    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1, 2, 2, 2, 1, 2}, kBt[NCAND] = {4, 2, 1, 4, 1, 1, 2, 4, 2, 4, 2},
-                     kKsp[NCAND] = {4, 4, 4, 1, 4, 4, 1, 1, 1, 1, 1}, kKc[NCAND] = {64, 64, 64, 32, 128, 128, 32, 16, 16, 32, 64},
-                     kCode[NCAND] = {7, 8, 9, 13, 14, 15, 16, 17, 18, 19, 20};
+    enum { NCAND = 12 };
+    static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1, 2, 2, 2, 1, 2, 2}, kBt[NCAND] = {4, 2, 1, 4, 1, 1, 2, 4, 2, 4, 2, 2},
+                     kKsp[NCAND] = {4, 4, 4, 1, 4, 4, 1, 1, 1, 1, 1, 4}, kKc[NCAND] = {64, 64, 64, 32, 128, 128, 32, 16, 16, 32, 64, 128},
+                     kCode[NCAND] = {7, 8, 9, 13, 14, 15, 16, 17, 18, 19, 20, 21};
     MfmaArgs best;
     size_t best_lds = 0;
     double best_est = 0.0;
@@ -523,7 +523,8 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
     case 7: e = launch_ks<2, 4, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
     case 8: e = launch_ks<2, 2, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
     case 9: e = launch_ks<1, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    default: e = launch_ks<2, 2, 64, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 10: e = launch_ks<2, 2, 64, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    default: e = launch_ks<2, 2, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
     }
     *launched = true;
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");

@@ -140,11 +140,11 @@ WAVE_SPEC = [
 ]
 
 
-@pytest.mark.parametrize("cfg", [7, 8, 9, 13, 14, 15, 16, 17, 18, 19, 20])
+@pytest.mark.parametrize("cfg", [7, 8, 9, 13, 14, 15, 16, 17, 18, 19, 20, 21])
 @pytest.mark.parametrize("shape", WAVE_SPEC)
 def test_wave_specialised_kernel(B, ctx, oracle, cfg, shape):
     """The persistent kernel with loader wavefronts: the reduction split over four MFMA wavefronts for each of
-    its pixel-tile widths (7, 8, 9: 128, 64 and 32 pixels; 14: 32 pixels with 128-channel chunks; 15: the same with 32 output channels), and the
+    its pixel-tile widths (7, 8, 9: 128, 64 and 32 pixels; 14, 21: 32 and 64 pixels with 128-channel chunks; 15: the same with 32 output channels), and the
     pixel split (13: 512-pixel tiles, 16: 256-pixel tiles; 17, 18: the same with 16-channel chunks; 19: 512-pixel
     tiles of 32 output channels; 20: 256-pixel tiles with 64-channel chunks)."""
     B.pc_set_plan_override(ctx, cfg, 0)
