@@ -350,7 +350,8 @@ pc_wgrad_valu_kernel(const T *__restrict__ x, const T *__restrict__ dy, WgradArg
 // partial is [G][pstride] float4; the number of live slots is read on the device.
 template <int TPS>
 __global__ void __launch_bounds__(256)
-pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, int64_t pstride, PackView v, float4 *__restrict__ dw)
+pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, int64_t pstride, int64_t nslots_exact, PackView v,
+                       float4 *__restrict__ dw)
 {
     constexpr int SPB = 256 / TPS;
     __shared__ float4 sub[TPS > 1 ? TPS : 1][TPS > 1 ? SPB : 1];
@@ -358,7 +359,9 @@ pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, int64_t pstrid
     const int q = threadIdx.x % SPB, sg = threadIdx.x / SPB;
     const int64_t slot = (int64_t)blockIdx.x * SPB + q;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (slot < pstride) {   // every plane holds pstride slots, so the loads need not wait for the count
+    // A plane holds pstride slots. When that is the exact count the loads need not wait for the count read from
+    // the device; when it is the pack's capacity they do, or they would fetch the unused part of every plane.
+    if (slot < (pstride == nslots_exact ? pstride : (int64_t)nnzk)) {
         // loads run ahead in groups of 8, the additions keep their order
         int gi = sg;
         for (; gi + 7 * TPS < G; gi += 8 * TPS) {
@@ -394,20 +397,21 @@ pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, int64
                                  const pc_packed *pk, float *dw)
 {
     if (nslots <= 0) return PC_OK;
+    const int64_t exact = pk->nnzk >= 0 ? pk->nnzk : -1;   // -1: not known on the host
     const float4 *pp = (const float4 *)partial;
     float4 *out = (float4 *)dw;
     if (G >= 128)
         hipLaunchKernelGGL(pc_wgrad_reduce_kernel<64>, dim3((unsigned)((nslots + 3) / 4)), dim3(256), 0, ctx->stream, pp, G,
-                           pstride, pk->v, out);
+                           pstride, exact, pk->v, out);
     else if (G >= 32)
         hipLaunchKernelGGL(pc_wgrad_reduce_kernel<16>, dim3((unsigned)((nslots + 15) / 16)), dim3(256), 0, ctx->stream, pp, G,
-                           pstride, pk->v, out);
+                           pstride, exact, pk->v, out);
     else if (G >= 8)
         hipLaunchKernelGGL(pc_wgrad_reduce_kernel<4>, dim3((unsigned)((nslots + 63) / 64)), dim3(256), 0, ctx->stream, pp, G,
-                           pstride, pk->v, out);
+                           pstride, exact, pk->v, out);
     else
         hipLaunchKernelGGL(pc_wgrad_reduce_kernel<1>, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, ctx->stream, pp, G,
-                           pstride, pk->v, out);
+                           pstride, exact, pk->v, out);
     return pc_hip_check(ctx, hipGetLastError(), "bwd_weight reduce launch");
 }
 
