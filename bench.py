@@ -42,6 +42,7 @@ def main() -> int:
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
     ap.add_argument("--cpu-sample-batch", type=int, default=128)
+    ap.add_argument("--no-paper-context", action="store_true", help="skip the paper's demonstration layer (profiles of the workload alone)")
     ap.add_argument("--train-steps", action="store_true",
                     help="also time pool generation, finalisation counters and the group-lasso gradient over the workload's layers")
     args = ap.parse_args()
@@ -313,7 +314,7 @@ def main() -> int:
     # (256 filters x 128 channels on a 224x224 map, batch 1: a 256x1152 by 1152x50176 SpMM, about 3000 us on one
     # Quadro RTX 5000, precision and sparsity not stated). The same layer shape through pc_conv_fwd here:
     paper_context = None
-    if wl.dtype == "bf16":
+    if wl.dtype == "bf16" and not args.no_paper_context:
         Lp = I.Layer(1, 224, 224, 128, 256, 1)
         Wp = up(I.gen_weights(Lp.F, Lp.C, I.BASE_SEED, "paper_demo"))
         kp_n = I.kept_per_filter(wl.keep, Lp.C)
