@@ -105,7 +105,6 @@ pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, int64
                                  const pc_packed *pk, float *dw);
 
 bool pc_mfma_supports(int F, int C);
-pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W);
 pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y);
 pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx);
 pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,

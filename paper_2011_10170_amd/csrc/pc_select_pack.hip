@@ -595,13 +595,6 @@ pc_pack_stage1_kernel(const float *__restrict__ W, const uint8_t *__restrict__ p
     pc_pack_tile_block<false>(W, pid, keep, la, v, b / tiles_c, b % tiles_c);
 }
 
-// Operand tiles again from new weights, masks from the kinfo table (values change, tables do not).
-__global__ void __launch_bounds__(256)
-pc_pack_retile_kernel(const float *__restrict__ W, LibArg la, PackView v, int tiles_c)
-{
-    pc_pack_tile_block<true>(W, nullptr, nullptr, la, v, blockIdx.x / tiles_c, blockIdx.x % tiles_c);
-}
-
 // The 4 kept weights of kernel k; taps holds the 4 tap indices, one per byte, ascending from the low byte.
 __device__ __forceinline__ float4 pc_gather_taps(const float *__restrict__ W, int64_t k, uint32_t taps, bool bf16)
 {
@@ -617,6 +610,23 @@ __device__ __forceinline__ float4 pc_gather_taps(const float *__restrict__ W, in
 __device__ __forceinline__ uint32_t pc_taps_word(const LibArg &la, int p)
 {
     return (uint32_t)la.taps[p][0] | ((uint32_t)la.taps[p][1] << 8) | ((uint32_t)la.taps[p][2] << 16) | ((uint32_t)la.taps[p][3] << 24);
+}
+
+// Values again from new weights with unchanged tables, one launch for the matrix-core variant: workgroups
+// [0, ntiles) rebuild the operand tiles (masks from the kinfo table), the others re-gather the compact values.
+__global__ void __launch_bounds__(256)
+pc_pack_revalue_kernel(const float *__restrict__ W, LibArg la, int bf16, PackView v, int tiles_c, int ntiles)
+{
+    if ((int)blockIdx.x < ntiles) {
+        pc_pack_tile_block<true>(W, nullptr, nullptr, la, v, blockIdx.x / tiles_c, blockIdx.x % tiles_c);
+        return;
+    }
+    const int64_t k = (int64_t)(blockIdx.x - ntiles) * 256 + threadIdx.x;
+    if (k >= (int64_t)v.F * v.C) return;
+    const uint32_t u = v.kinfo[k];
+    if (u == 0xFFFFFFFFu) return;
+    const int slot = (int)(u >> 9);
+    v.fm_val[slot] = pc_gather_taps(W, k, pc_taps_word(la, v.fm_pid[slot]), bf16 != 0);
 }
 
 // Places the kept kernels of one row at (kept kernels of the rows before) + (pattern group start) + (rank inside
@@ -743,16 +753,6 @@ pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8
     return pc_hip_check(ctx, hipGetLastError(), "pack launch");
 }
 
-pc_status pc_launch_pack_tiles(pc_ctx *ctx, pc_packed *pk, const float *W)
-{
-    PackView v = pk->v;
-    LibArg la;
-    pc_fill_lib(&la, pk->lib, v.P);
-    const int tiles_c = v.Cp / 32;
-    hipLaunchKernelGGL(pc_pack_retile_kernel, dim3((unsigned)((v.Fp / 32) * tiles_c)), dim3(256), 0, ctx->stream, W, la, v, tiles_c);
-    return pc_hip_check(ctx, hipGetLastError(), "pack tiles launch");
-}
-
 pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W)
 {
     PackView v = pk->v;
@@ -761,12 +761,15 @@ pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W)
     int bf16 = pk->dtype == PC_BF16;
     int64_t nk = (int64_t)v.F * v.C;
     unsigned blocks = (unsigned)((nk + 255) / 256);
-    hipLaunchKernelGGL(pc_pack_regather_fm_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, la, bf16, v);
-    if (pk->variant != PC_VARIANT_MFMA)
+    if (pk->variant == PC_VARIANT_MFMA) {
+        const int tiles_c = v.Cp / 32, ntiles = (v.Fp / 32) * tiles_c;
+        hipLaunchKernelGGL(pc_pack_revalue_kernel, dim3((unsigned)ntiles + blocks), dim3(256), 0, ctx->stream, W, la, bf16, v,
+                           tiles_c, ntiles);
+    } else {
+        hipLaunchKernelGGL(pc_pack_regather_fm_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, la, bf16, v);
         hipLaunchKernelGGL(pc_pack_regather_cm_kernel, dim3(blocks), dim3(256), 0, ctx->stream, v);
-    pc_status s = pc_hip_check(ctx, hipGetLastError(), "update_values launch");
-    if (s == PC_OK && pk->variant == PC_VARIANT_MFMA) s = pc_launch_pack_tiles(ctx, pk, W);
-    return s;
+    }
+    return pc_hip_check(ctx, hipGetLastError(), "update_values launch");
 }
 
 // dense[f][c][t] = value of the kept tap, 0 elsewhere. Source: a compact array or the pack's own values.
