@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
     ap.add_argument("--cpu-sample-batch", type=int, default=128)
+    ap.add_argument("--update-values", action="store_true",
+                    help="re-gather the kept weights of every layer in the step (pc_update_values: the per-iteration conversion of Section 5.1)")
     ap.add_argument("--no-paper-context", action="store_true", help="skip the paper's demonstration layer (profiles of the workload alone)")
     ap.add_argument("--train-steps", action="store_true",
                     help="also time pool generation, finalisation counters and the group-lasso gradient over the workload's layers")
@@ -109,6 +111,8 @@ def main() -> int:
         if which == "select":
             B.pc_pattern_select(ctx, d["W"], d["G"], d["L"].F, d["L"].C, lib, B.PC_KEEP_PER_FILTER, d["k"],
                                 B.PC_SCORE_RETAINED, d["pid"], d["keep"])
+        elif which == "update":
+            B.pc_update_values(ctx, d["pk"], d["W"])
         elif which == "pack":
             B.pc_pack(ctx, d["W"], d["pid"], d["keep"], d["L"].F, d["L"].C, lib, dt, reuse=d["pk"])
         elif which == "fwd":
@@ -118,7 +122,7 @@ def main() -> int:
         else:
             B.pc_conv_bwd_weight(ctx, d["desc"], d["pk"], d["x"], d["dy"], d["dw"])
 
-    passes = (["select", "pack"] if wl.with_select else []) + ["fwd", "bwd_data", "bwd_weight"]
+    passes = (["select", "pack"] if wl.with_select else (["update"] if args.update_values else [])) + ["fwd", "bwd_data", "bwd_weight"]
 
     def step(events=None):
         for li, d in enumerate(layers):
@@ -180,7 +184,7 @@ def main() -> int:
         L = d["L"]
         us = float(np.median(ts)) * 1e3
         var = "mfma" if d["variant"] == B.PC_VARIANT_MFMA else "valu"
-        if which in ("select", "pack"):
+        if which in ("select", "pack", "update"):
             kind = which
             byts = L.F * L.C * (74 if which == "select" else 38 + 0.0)
             fl = dfl = 0.0
