@@ -10,10 +10,11 @@
 // 16-byte reads) and every tap is a constant LDS offset.
 //   forward        : in = x,  m = filter,  k = channel, 9 taps at (r, s)
 //   backward-data  : in = dy, m = channel, k = filter; stride 1: 9 taps at (2-r, 2-s) (rot180);
-//                    stride 2: four parity classes of input pixels with 1, 2, 2 and 4 taps
+//                    stride 2: four parity classes of input pixels with 1, 2, 2 and 4 taps, one launch
 //   backward-weight: pc_wgrad_mfma.hip
 // This file holds the cooperative kernel (every wavefront stages and multiplies; output split over the
-// wavefronts), the operand-tile packing and the planner; the persistent wave-specialised kernel that takes
+// wavefronts), the channel-padding copies and the planner (the operand tiles are written at pack time, in
+// pc_select_pack.hip); the persistent wave-specialised kernel that takes
 // most full 3x3 launches is in pc_conv_mfma_ws.hip.
 //
 // Operand layout of v_mfma_f32_32x32x16_bf16 used here: lane l holds row (A) / column (B) l%32 and
