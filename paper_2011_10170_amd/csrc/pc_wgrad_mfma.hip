@@ -343,7 +343,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     };
     float *pout = a.ksplit > 1 ? partial + (int64_t)bz * a.pstride * 4 : dw;
     const float *ot = reinterpret_cast<const float *>(lds);
-    // gathers the 4 kept taps of every kept kernel of filter half fh from the parked tile
+    // gathers the 4 kept taps of every kept kernel of filter half fh from the parked tiles (half fh at fh * 72 KiB)
     auto gather = [&](int fh) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -351,7 +351,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             const uint32_t info = kinf[fh][k];
             if (info != 0xFFFFFFFFu) {
                 uint32_t m = info & 0x1FFu;
-                const float *ob = ot + (p >> 6) * WG_T + (p & 63);
+                const float *ob = ot + fh * (9 * 32 * WG_T) + (p >> 6) * WG_T + (p & 63);
                 float o[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -453,12 +453,10 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             put(A0, B0, 0);           issue(A0, B0); sync();
         }
         if (i < nt) { put(A1, B1, a.buf_bytes); issue(A1, B1); sync(); }
-#pragma unroll
-        for (int fh = 0; fh < 2; ++fh) {
-            __syncthreads();
-            __syncthreads();
-            gather(fh);
-        }
+        __syncthreads();
+        __syncthreads();
+        gather(0);
+        gather(1);
     } else {
         // ------------------------------------------------------------ MFMA wavefronts
         // wave = (channel half, tap group); the 18 (filter half, tap) units are split 9/9 as in the kernel above
@@ -519,17 +517,17 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             }
             __syncthreads();
         }
-        // epilogue, one filter half at a time: park the half's tiles as out[tap][filter][channel] (72 KiB)
+        // epilogue: park both filter halves' tiles as out[half][tap][filter][channel] (2 x 72 KiB), then gather
         float *otw = reinterpret_cast<float *>(lds);
+        __syncthreads();
 #pragma unroll
         for (int fh = 0; fh < 2; ++fh) {
-            __syncthreads();
             const int h = fh == first_half ? 0 : 1;
 #pragma unroll
             for (int b = 0; b < 5; ++b) {
                 if (h == 0 || b < 4) {
                     const int tap = tg ? 8 - b : b;
-                    float *tp = otw + (tap * 32) * WG_T + cl;
+                    float *tp = otw + fh * (9 * 32 * WG_T) + (tap * 32) * WG_T + cl;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int fr = 8 * (i >> 2) + 4 * g + (i & 3);
@@ -537,9 +535,10 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
                     }
                 }
             }
-            __syncthreads();
-            gather(fh);
         }
+        __syncthreads();
+        gather(0);
+        gather(1);
     }
 
 }
@@ -610,7 +609,7 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     }
     a.buf_bytes = (WG_T * WS_DY_PLANE + 128 + WG_T * a.xplane + 128 + 255) / 256 * 256;
     size_t lds = 2 * (size_t)a.buf_bytes;
-    if (lds < (size_t)9 * 32 * WG_T * sizeof(float)) lds = (size_t)9 * 32 * WG_T * sizeof(float);   // the epilogue parks one filter half
+    if (lds < (size_t)2 * 9 * 32 * WG_T * sizeof(float)) lds = (size_t)2 * 9 * 32 * WG_T * sizeof(float);   // the epilogue parks both filter halves
     if (lds > WS_LDS_MAX) return PC_OK;
     int ks = ctx->num_cu / (ft * ct);
     if (ks > a.n_ktiles) ks = a.n_ktiles;
