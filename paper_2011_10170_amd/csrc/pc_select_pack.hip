@@ -536,13 +536,21 @@ __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, 
     if ((v.C & 3) == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0) {
         // a filter row of the block is ncols*9 contiguous floats starting on a 16-byte boundary
         const int nq = ncols * 9 / 4;
+        // all 9 loads of the thread are issued before the first value is used: one memory round trip, not nine
+        float4 wq[9];
 #pragma unroll
         for (int it = 0; it < 9; ++it) {
             const int q = it * 256 + tid;            // 32 rows x 72 quads
             const int r = q / 72, jq = q - r * 72;
-            float4 w4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            wq[it] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (f0 + r < v.F && jq < nq)
-                w4 = *reinterpret_cast<const float4 *>(W + ((int64_t)(f0 + r) * v.C + c0) * 9 + jq * 4);
+                wq[it] = *reinterpret_cast<const float4 *>(W + ((int64_t)(f0 + r) * v.C + c0) * 9 + jq * 4);
+        }
+#pragma unroll
+        for (int it = 0; it < 9; ++it) {
+            const int q = it * 256 + tid;
+            const int r = q / 72, jq = q - r * 72;
+            const float4 w4 = wq[it];
             const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
