@@ -160,12 +160,21 @@ pc_select_row_kernel(const float *__restrict__ W, const float *__restrict__ G, i
         const float *wsrc = W + (row0 + c0) * 9;
         const float *gsrc = G ? G + (row0 + c0) * 9 : nullptr;
         if (c0) __syncthreads();
+        // all loads of the thread first (index clamped, so they are unconditional), then the LDS writes: one memory
+        // round trip per chunk instead of one per element
+        float rw[9], rg[9];
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+            const int i = j * T + tid, ic = i < n * 9 ? i : n * 9 - 1;
+            rw[j] = wsrc[ic];
+            rg[j] = gsrc ? gsrc[ic] : 0.0f;
+        }
 #pragma unroll
         for (int j = 0; j < 9; ++j) {
             const int i = j * T + tid;
             if (i < n * 9) {
-                sw[i] = wsrc[i];
-                if (gsrc) sg[i] = gsrc[i];
+                sw[i] = rw[j];
+                if (gsrc) sg[i] = rg[j];
             }
         }
         __syncthreads();
@@ -477,7 +486,8 @@ __device__ __forceinline__ void pc_pack_count_row(const uint8_t *__restrict__ pi
     __syncthreads();
     for (int e = threadIdx.x; e < len; e += blockDim.x) {
         int64_t k = row * row_stride + e * elem_stride;
-        if (keep[k] && pid[k] < P) atomicAdd(&hist[pid[k]], 1);   // integer counts: order does not matter
+        const int kp = keep[k], pd = pid[k];                      // both loads at once, not one behind the other
+        if (kp && pd < P) atomicAdd(&hist[pd], 1);                // integer counts: order does not matter
     }
     __syncthreads();
     for (int p = threadIdx.x; p < P; p += blockDim.x) grp[(int64_t)row * (PC_MAX_P + 1) + p] = hist[p];

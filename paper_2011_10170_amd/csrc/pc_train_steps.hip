@@ -14,10 +14,17 @@
 // 9 floats of TS_BLOCK consecutive kernels from global memory to LDS with contiguous loads.
 __device__ __forceinline__ void ts_stage(float *dst, const float *__restrict__ src, int n)
 {
+    // all loads first (index clamped, so they are unconditional), then the LDS writes: one memory round trip
+    float r[9];
 #pragma unroll
     for (int j = 0; j < 9; ++j) {
         const int i = j * TS_BLOCK + threadIdx.x;
-        if (i < n * 9) dst[i] = src[i];
+        r[j] = src[i < n * 9 ? i : n * 9 - 1];
+    }
+#pragma unroll
+    for (int j = 0; j < 9; ++j) {
+        const int i = j * TS_BLOCK + threadIdx.x;
+        if (i < n * 9) dst[i] = r[j];
     }
 }
 
