@@ -129,23 +129,48 @@ pc_mfma_conv_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
     }
     for (int ch = ch0; ch < ch1; ++ch) {
         __syncthreads();
-        for (int e = threadIdx.x; e < HP * PARTS; e += 256) {
-            const int q = e / PARTS, part = e - q * PARTS;
-            const int c = ch * KC + part * 8;
-            const int64_t po = pixoff[q];
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (po >= 0 && c < g.in_CH) {
-                if ((g.in_CH & 7) == 0) {
-                    v = *reinterpret_cast<const uint4 *>(in + po + c);
-                } else {   // channel count not a multiple of 8: rows are not 16-byte aligned, load by element
+        if ((g.in_CH & 7) == 0) {
+            // four elements per thread and round: the loads are unconditional (address clamped to the tensor's
+            // start, value masked afterwards) and all issued before the first LDS write, so a round costs one
+            // memory round trip instead of four
+            constexpr int U = 4;
+            const int total = HP * PARTS;
+            for (int e0 = threadIdx.x; e0 < total; e0 += 256 * U) {
+                uint4 vv[U];
+                bool okv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int e = e0 + 256 * u, ec = e < total ? e : total - 1;
+                    const int q = ec / PARTS, part = ec - q * PARTS;
+                    const int c = ch * KC + part * 8;
+                    const int64_t po = pixoff[q];
+                    okv[u] = po >= 0 && c < g.in_CH;
+                    vv[u] = *reinterpret_cast<const uint4 *>(in + (okv[u] ? po + c : 0));
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int e = e0 + 256 * u;
+                    if (e < total) {
+                        const int q = e / PARTS, part = e - q * PARTS;
+                        *reinterpret_cast<uint4 *>(lds + q * PITCH + part * 16) = okv[u] ? vv[u] : make_uint4(0u, 0u, 0u, 0u);
+                    }
+                }
+            }
+        } else {
+            for (int e = threadIdx.x; e < HP * PARTS; e += 256) {
+                const int q = e / PARTS, part = e - q * PARTS;
+                const int c = ch * KC + part * 8;
+                const int64_t po = pixoff[q];
+                uint4 v = make_uint4(0u, 0u, 0u, 0u);
+                if (po >= 0 && c < g.in_CH) {   // channel count not a multiple of 8: rows are not 16-byte aligned, load by element
                     uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
                     for (int i = 0; i < 8; ++i)
                         if (c + i < g.in_CH) w[i >> 1] |= (uint32_t)in[po + c + i] << ((i & 1) * 16);
                     v = make_uint4(w[0], w[1], w[2], w[3]);
                 }
+                *reinterpret_cast<uint4 *>(lds + q * PITCH + part * 16) = v;
             }
-            *reinterpret_cast<uint4 *>(lds + q * PITCH + part * 16) = v;
         }
         __syncthreads();
         // B fragments are read DB steps ahead of their MFMAs (LDS latency is longer than one small step);
