@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--update-values", action="store_true",
                     help="re-gather the kept weights of every layer in the step (pc_update_values: the per-iteration conversion of Section 5.1)")
     ap.add_argument("--no-paper-context", action="store_true", help="skip the paper's demonstration layer (profiles of the workload alone)")
+    ap.add_argument("--wgrad-streams", type=int, default=0,
+                    help="enqueue bwd_weight on this many side streams in turn (one context each), forked after the layer's "
+                         "forward call and joined at the end of the step: it overlaps bwd_data of the same layer and what follows")
     ap.add_argument("--train-steps", action="store_true",
                     help="also time pool generation, finalisation counters and the group-lasso gradient over the workload's layers")
     args = ap.parse_args()
@@ -71,6 +74,9 @@ def main() -> int:
     torch.cuda.set_stream(stream)
     ctx = B.pc_create(0, stream.cuda_stream)
     B.pc_set_variant(ctx, {"auto": B.PC_VARIANT_AUTO, "valu": B.PC_VARIANT_VALU, "mfma": B.PC_VARIANT_MFMA}[args.variant])
+    # a pack belongs to no context: another context on another stream may use it, ordered by events
+    streams_w = [torch.cuda.Stream() for _ in range(args.wgrad_streams)]
+    ctxs_w = [B.pc_create(0, s.cuda_stream) for s in streams_w]
     lib = I.make_library(wl.P)
 
     def up(arr):
@@ -125,16 +131,25 @@ def main() -> int:
     passes = (["select", "pack"] if wl.with_select else (["update"] if args.update_values else [])) + ["fwd", "bwd_data", "bwd_weight"]
 
     def step(events=None):
+        overlap = bool(ctxs_w) and events is None
         for li, d in enumerate(layers):
             for which in passes:
                 if events is not None:
                     e0 = torch.cuda.Event(enable_timing=True)
                     e1 = torch.cuda.Event(enable_timing=True)
                     e0.record(stream)
-                run_pass(d, which)
+                if overlap and which == "bwd_data":
+                    streams_w[li % len(ctxs_w)].wait_stream(stream)    # fork: x, dy and the pack of this layer are ready
+                if overlap and which == "bwd_weight":
+                    B.pc_conv_bwd_weight(ctxs_w[li % len(ctxs_w)], d["desc"], d["pk"], d["x"], d["dy"], d["dw"])
+                else:
+                    run_pass(d, which)
                 if events is not None:
                     e1.record(stream)
                     events.append((li, which, e0, e1))
+        if overlap:
+            for s_w in streams_w:
+                stream.wait_stream(s_w)                # join: the step ends when every stream has drained
 
     # The step is launch-bound on the host (dozens of short kernels), so it is captured once into a HIP graph
     # and replayed; no call of the step reads anything back to the host, re-selection and re-packing included.
@@ -383,6 +398,7 @@ def main() -> int:
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "layers": len(wl.layers), "batch": wl.layers[0].N, "patterns": wl.P,
                    "keep": wl.keep, "variant": args.variant, "passes": "+".join(passes), "launch": "hip_graph" if graph is not None else "host",
+                   "streams": 1 + len(ctxs_w),
                    "nonzero_gflop_per_step": round(total_flops / 1e9, 3)},
         "roofline": roofline, "cpu_baseline": cpu,
     }
@@ -393,6 +409,8 @@ def main() -> int:
     print(json.dumps(out), flush=True)
     for d in layers:
         B.pc_packed_free(d["pk"])
+    for c_w in ctxs_w:
+        B.pc_destroy(c_w)
     B.pc_destroy(ctx)
     return 0
 

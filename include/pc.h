@@ -237,6 +237,29 @@ pc_status pc_group_lasso_grad(pc_ctx *ctx, const float *W_dev, const uint8_t *pi
                               int32_t F, int32_t C, const uint16_t *lib_host, int32_t P,
                               float lambda_p, float lambda_i, float *dW_dev, double *penalty_dev);
 
+/* ---- between two chained layers --------------------------------------------------------- */
+
+/* The step from one layer's output z to the next layer's input a (Section 5.2, "Backward Phase Acceleration":
+ * a = sigma(z)), for the networks of Section 6: sigma = ReLU, then a max pooling of pool x pool windows with
+ * stride pool (pool = 1: none, 2: the VGG pooling). Exact in both dtypes (comparisons and copies only).
+ *   z_dev   : dtype [N][H][W][C] device
+ *   a_dev   : dtype [N][H/pool][W/pool][C] device, output (an odd last row / column of z is dropped);
+ *             relu(z) = z where z > 0, else +0
+ *   sel_dev : uint8, shape of a, output: what pc_act_pool_bwd needs. The window position 2*dr + dc of the
+ *             maximum (the first in row-major order among equal maxima), 255 where the maximum is not positive
+ * 16-byte accesses when C is a multiple of 8 (bfloat16) / 4 (float32), z_dev and a_dev are 16-byte aligned and
+ * sel_dev is 8-byte aligned; one element per thread otherwise. PC_ERR_BAD_SHAPE when H or W < pool. */
+pc_status pc_act_pool_fwd(pc_ctx *ctx, const void *z_dev, int32_t N, int32_t H, int32_t W, int32_t C,
+                          pc_dtype dtype, int32_t pool, void *a_dev, uint8_t *sel_dev);
+
+/* The backward pass of pc_act_pool_fwd (the error times sigma'(z) of Section 5.2, through the pooling): the
+ * error of a pooled element goes to the window position sel names, every other element of dz is 0 (also an odd
+ * last row / column). N, H, W, C are those of z.
+ *   da_dev : dtype [N][H/pool][W/pool][C] device; sel_dev : as written by the forward call
+ *   dz_dev : dtype [N][H][W][C] device, output (every element written) */
+pc_status pc_act_pool_bwd(pc_ctx *ctx, const void *da_dev, const uint8_t *sel_dev, int32_t N, int32_t H, int32_t W,
+                          int32_t C, pc_dtype dtype, int32_t pool, void *dz_dev);
+
 #ifdef __cplusplus
 }
 #endif

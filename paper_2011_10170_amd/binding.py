@@ -26,6 +26,7 @@ EXPORTS = [
     "pc_packed_info", "pc_packed_free", "pc_scatter_dense", "pc_unpack_dense",
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
     "pc_dppg_accumulate", "pc_dppg_pool", "pc_finalize_count", "pc_finalize_pick", "pc_group_lasso_grad",
+    "pc_act_pool_fwd", "pc_act_pool_bwd",
 ]
 
 
@@ -80,6 +81,8 @@ def load():
     lib.pc_finalize_count.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.pc_finalize_pick.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.pc_group_lasso_grad.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, ct.c_float, ct.c_float, vp, vp]
+    lib.pc_act_pool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp, vp]
+    lib.pc_act_pool_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("pc_destroy", "pc_packed_free", "pc_status_str", "pc_last_error"):
@@ -217,3 +220,11 @@ def pc_group_lasso_grad(ctx, W, pid, keep, F, C, masks, lambda_p, lambda_i, dW, 
     arr = _lib_arr(masks)
     _check(ctx, load().pc_group_lasso_grad(ctx, _ptr(W), _ptr(pid), _ptr(keep), int(F), int(C), ct.cast(arr, ct.c_void_p),
                                            len(masks), float(lambda_p), float(lambda_i), _ptr(dW), _ptr(penalty)))
+
+
+def pc_act_pool_fwd(ctx, z, N, H, W, C, dtype, pool, a, sel) -> None:
+    _check(ctx, load().pc_act_pool_fwd(ctx, _ptr(z), int(N), int(H), int(W), int(C), int(dtype), int(pool), _ptr(a), _ptr(sel)))
+
+
+def pc_act_pool_bwd(ctx, da, sel, N, H, W, C, dtype, pool, dz) -> None:
+    _check(ctx, load().pc_act_pool_bwd(ctx, _ptr(da), _ptr(sel), int(N), int(H), int(W), int(C), int(dtype), int(pool), _ptr(dz)))
