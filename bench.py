@@ -45,9 +45,12 @@ def main() -> int:
     ap.add_argument("--update-values", action="store_true",
                     help="re-gather the kept weights of every layer in the step (pc_update_values: the per-iteration conversion of Section 5.1)")
     ap.add_argument("--no-paper-context", action="store_true", help="skip the paper's demonstration layer (profiles of the workload alone)")
-    ap.add_argument("--wgrad-streams", type=int, default=0,
+    ap.add_argument("--wgrad-streams", type=int, default=1,
                     help="enqueue bwd_weight on this many side streams in turn (one context each), forked after the layer's "
                          "forward call and joined at the end of the step: it overlaps bwd_data of the same layer and what follows")
+    ap.add_argument("--chained", action="store_true",
+                    help="also time the layers as one network (VGG workloads): forward through every layer with ReLU and "
+                         "2x2 max pooling between them (pc_act_pool_fwd), then backward in reverse order")
     ap.add_argument("--train-steps", action="store_true",
                     help="also time pool generation, finalisation counters and the group-lasso gradient over the workload's layers")
     args = ap.parse_args()
@@ -283,6 +286,104 @@ def main() -> int:
         torch.cuda.synchronize()
         log("calibration copy: %d MiB read + %d MiB written" % (args.calib_copy_mb, args.calib_copy_mb))
 
+    # ---- the same layers as one network: every layer's input is the previous layer's output after ReLU (and a 2x2
+    # max pooling where the next map is half the size), the backward pass runs in reverse order; bwd_weight of a
+    # layer is forked to the side stream once its error tensor exists. No gradient reaches the network's input.
+    chained = None
+    if args.chained:
+        ok = all(L.stride == 1 for L in wl.layers) and all(
+            (b.C == a.F and b.H in (a.Ho, a.Ho // 2) and b.N == a.N) for a, b in zip(wl.layers, wl.layers[1:]))
+        if not ok:
+            log("--chained: workload %s is not a plain chain of stride-1 layers, skipped" % wl.name)
+        else:
+            nl = len(layers)
+            for li, d in enumerate(layers):
+                L = d["L"]
+                nxt = wl.layers[li + 1] if li + 1 < nl else None
+                d["pool"] = (2 if nxt.H == L.Ho // 2 and nxt.H != L.Ho else 1) if nxt is not None else (2 if L.Ho >= 2 else 1)
+                q = d["pool"]
+                d["a"] = torch.empty((L.N, L.Ho // q, L.Wo // q, L.F), dtype=tdt, device="cuda")
+                d["sel"] = torch.empty((L.N, L.Ho // q, L.Wo // q, L.F), dtype=torch.uint8, device="cuda")
+            last = layers[-1]
+            da_last = up(I.gen_activations(tuple(last["a"].shape), I.BASE_SEED, (wl.name, "chain_da"), False, wl.dtype)[1])
+
+            def chain_step(side):
+                xin = layers[0]["x"]
+                for d in layers:
+                    L = d["L"]
+                    B.pc_conv_fwd(ctx, d["desc"], d["pk"], xin, d["y"])
+                    B.pc_act_pool_fwd(ctx, d["y"], L.N, L.Ho, L.Wo, L.F, dt, d["pool"], d["a"], d["sel"])
+                    d["xin"] = xin
+                    xin = d["a"]
+                da = da_last
+                for li in range(nl - 1, -1, -1):
+                    d = layers[li]
+                    L = d["L"]
+                    B.pc_act_pool_bwd(ctx, da, d["sel"], L.N, L.Ho, L.Wo, L.F, dt, d["pool"], d["dy"])   # d["dy"] reused as dz
+                    if side:
+                        streams_w[0].wait_stream(stream)
+                        B.pc_conv_bwd_weight(ctxs_w[0], d["desc"], d["pk"], d["xin"], d["dy"], d["dw"])
+                    else:
+                        B.pc_conv_bwd_weight(ctx, d["desc"], d["pk"], d["xin"], d["dy"], d["dw"])
+                    if li > 0:
+                        B.pc_conv_bwd_data(ctx, d["desc"], d["pk"], d["dy"], d["dx"])
+                        da = d["dx"]
+                if side:
+                    stream.wait_stream(streams_w[0])
+
+            def time_chain(side):
+                chain_step(side)
+                torch.cuda.synchronize()
+                gch = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gch, stream=stream):
+                    chain_step(side)
+                for _ in range(3):
+                    gch.replay()
+                torch.cuda.synchronize()
+                t0c = time.perf_counter()
+                for _ in range(args.steps):
+                    gch.replay()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0c) * 1e3 / args.steps
+
+            ms_by_streams = {1: time_chain(False)}
+            if ctxs_w:
+                ms_by_streams[2] = time_chain(True)
+            finite = bool(torch.isfinite(layers[0]["dw"]).all().item()) and bool(torch.isfinite(last["a"].float()).all().item())
+            n_str, ms_chain = min(ms_by_streams.items(), key=lambda kv: kv[1])
+            fl_chain = sum(3.0 * d["flops"] for d in layers) - layers[0]["flops"]
+            # the act / pool calls alone (one graph), priced by their bytes: z in, a and sel out; da and sel in, dz out
+            def act_only():
+                for d in layers:
+                    L = d["L"]
+                    B.pc_act_pool_fwd(ctx, d["y"], L.N, L.Ho, L.Wo, L.F, dt, d["pool"], d["a"], d["sel"])
+                for d in reversed(layers):
+                    L = d["L"]
+                    B.pc_act_pool_bwd(ctx, d["a"], d["sel"], L.N, L.Ho, L.Wo, L.F, dt, d["pool"], d["dy"])
+            gact = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gact, stream=stream):
+                act_only()
+            gact.replay()
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                gact.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us_act = e0.elapsed_time(e1) * 1e3 / 10
+            by_act = sum(2 * (d["act_out"] + d["a"].numel() * (esz + 1)) for d in layers)
+            chained = {"ms_per_step": round(ms_chain, 4), "value": round(fl_chain / (ms_chain * 1e-3) / 1e12, 4), "unit": "TFLOP/s",
+                       "calls": "%d fwd + %d act_pool_fwd + %d act_pool_bwd + %d bwd_weight + %d bwd_data" % (nl, nl, nl, nl, nl - 1),
+                       "streams": n_str, "ms_per_step_by_streams": {str(k): round(v, 4) for k, v in ms_by_streams.items()},
+                       "finite": finite,
+                       "act_pool_us": round(us_act, 1), "act_pool_gbs": round(by_act / us_act / 1e3, 1),
+                       "act_pool_hbm_frac": round(by_act / us_act / 1e3 / PEAK_HBM_GBS, 4)}
+            log("chained network: %.4f ms per step (%.1f nonzero TFLOP/s over %d calls, %d stream(s)); ReLU/pool calls alone "
+                "%.1f us (%.0f GB/s algorithmic)" % (ms_chain, chained["value"], 5 * nl - 1, chained["streams"], us_act, by_act / us_act / 1e3))
+            torch.cuda.synchronize()
+
     # ---- the training-side steps over the same layers (one graph of all layers per step kind), HBM-bound
     train_steps = None
     if args.train_steps:
@@ -402,6 +503,8 @@ def main() -> int:
                    "nonzero_gflop_per_step": round(total_flops / 1e9, 3)},
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if chained is not None:
+        out["chained"] = chained
     if train_steps is not None:
         out["train_steps"] = train_steps
     if paper_context is not None:

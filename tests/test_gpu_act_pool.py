@@ -148,3 +148,80 @@ def test_argument_checks(B, ctx):
         B.pc_act_pool_bwd(ctx, t, s, 0, 4, 4, 4, B.PC_F32, 2, t)
     with pytest.raises(B.PcError):
         B.pc_act_pool_bwd(ctx, t, s, 1, 4, 4, 4, 7, 2, t)
+
+
+def test_three_layer_chain_f32(B, ctx, T, oracle):
+    """conv -> ReLU/pool -> conv -> ReLU -> conv -> ReLU/pool and the whole backward pass, float32, against the same
+    chain of oracle calls. Float32 rounding can flip a comparison only between nearly equal values, so the chain as
+    a whole is held to the float32 tolerance of a single pass (relative L2 error 1e-4)."""
+    import torch
+    from tests._harness import rel_l2
+    N, H, W = 3, 12, 10
+    chans = [5, 16, 24, 8]
+    pools = [2, 1, 2]
+    lib = I.make_library(8)
+    Ls, packs, Wms, Ms = [], [], [], []
+    h, w = H, W
+    for li in range(3):
+        L = I.Layer(N, h, w, chans[li], chans[li + 1], 1)
+        Wn = I.gen_weights(L.F, L.C, I.BASE_SEED, ("chain", li))
+        k = I.kept_per_filter(0.6, L.C)
+        pid, keep = oracle.select(Wn, None, lib, k)
+        M = oracle.mask(pid, keep, lib)
+        Wms.append(oracle.apply_mask(Wn, M))
+        Ms.append(M)
+        pd, kd = torch.empty((L.F, L.C), dtype=torch.uint8, device="cuda"), torch.empty((L.F, L.C), dtype=torch.uint8, device="cuda")
+        Wd = to_dev(Wn)
+        B.pc_pattern_select(ctx, Wd, None, L.F, L.C, lib, B.PC_KEEP_PER_FILTER, k, B.PC_SCORE_RETAINED, pd, kd)
+        packs.append(B.pc_pack(ctx, Wd, pd, kd, L.F, L.C, lib, B.PC_F32))
+        Ls.append(L)
+        h, w = h // pools[li], w // pools[li]
+    x0 = I.gen_activations((N, H, W, chans[0]), I.BASE_SEED, ("chain", "x"), True, "f32")[1]
+    # oracle chain
+    xs, zs, sels = [x0], [], []
+    for li in range(3):
+        z = oracle.conv_fwd(xs[-1], Wms[li], 1)
+        a, sel = T.act_pool_fwd(z, pools[li])
+        zs.append(z); sels.append(sel); xs.append(a)
+    da = I.gen_activations(xs[-1].shape, I.BASE_SEED, ("chain", "da"), False, "f32")[1]
+    ref_dw = [None] * 3
+    g = da
+    for li in (2, 1, 0):
+        L = Ls[li]
+        dz = T.act_pool_bwd(g, sels[li], L.Ho, L.Wo, pools[li])
+        ref_dw[li] = oracle.conv_bwd_weight(xs[li], dz, Ms[li], 1)
+        g = oracle.conv_bwd_data(dz, Wms[li], xs[li].shape, 1)
+    ref_dx0 = g
+    # the same chain through the library
+    dxs = [to_dev(x0)]
+    dsel = []
+    for li in range(3):
+        L = Ls[li]
+        desc = B.make_desc(L.N, L.H, L.W, L.C, L.F, 1, B.PC_F32)
+        z = torch.empty((N, L.Ho, L.Wo, L.F), dtype=torch.float32, device="cuda")
+        B.pc_conv_fwd(ctx, desc, packs[li], dxs[-1], z)
+        q = pools[li]
+        a = torch.empty((N, L.Ho // q, L.Wo // q, L.F), dtype=torch.float32, device="cuda")
+        s = torch.empty(a.shape, dtype=torch.uint8, device="cuda")
+        B.pc_act_pool_fwd(ctx, z, N, L.Ho, L.Wo, L.F, B.PC_F32, q, a, s)
+        dxs.append(a); dsel.append(s)
+    torch.cuda.synchronize()
+    assert rel_l2(dxs[-1].cpu().numpy(), xs[-1]) <= 1e-4
+    gd = to_dev(da)
+    for li in (2, 1, 0):
+        L = Ls[li]
+        desc = B.make_desc(L.N, L.H, L.W, L.C, L.F, 1, B.PC_F32)
+        dz = torch.empty((N, L.Ho, L.Wo, L.F), dtype=torch.float32, device="cuda")
+        B.pc_act_pool_bwd(ctx, gd, dsel[li], N, L.Ho, L.Wo, L.F, B.PC_F32, pools[li], dz)
+        nnzk, _ = B.pc_packed_info(ctx, packs[li])
+        dw = torch.empty((nnzk, 4), dtype=torch.float32, device="cuda")
+        B.pc_conv_bwd_weight(ctx, desc, packs[li], dxs[li], dz, dw)
+        dense = torch.zeros((L.F, L.C, 9), dtype=torch.float32, device="cuda")
+        B.pc_scatter_dense(ctx, packs[li], dw, dense)
+        gd = torch.empty((N, L.H, L.W, L.C), dtype=torch.float32, device="cuda")
+        B.pc_conv_bwd_data(ctx, desc, packs[li], dz, gd)
+        torch.cuda.synchronize()
+        assert rel_l2(dense.cpu().numpy(), ref_dw[li]) <= 1e-4
+    assert rel_l2(gd.cpu().numpy(), ref_dx0) <= 1e-4
+    for pk in packs:
+        B.pc_packed_free(pk)
