@@ -145,7 +145,11 @@ pc_status pc_pattern_select(pc_ctx *ctx, const float *W_dev, const float *G_dev,
  * ascending tap index.
  * *out == NULL: a new handle is allocated (device memory sized for F*C kernels).
  * *out != NULL: that handle is re-packed in place; it must have the same F, C and dtype.
- * pid/keep values are trusted to be < P and 0/1. */
+ * pid/keep values are trusted to be < P and 0/1.
+ * A pack is bound to its device, not to the context that made it: any context of that device may pass it to
+ * the conv calls, on its own stream (for example pc_conv_bwd_weight on a second context and stream beside
+ * pc_conv_bwd_data on the first). The caller orders the streams: the pack or value update must have run before
+ * another stream's call reads it, and every reader must have finished before the handle is re-packed or freed. */
 pc_status pc_pack(pc_ctx *ctx, const float *W_dev, const uint8_t *pid_dev, const uint8_t *keep_dev,
                   int32_t F, int32_t C, const uint16_t *lib_host, int32_t P,
                   pc_dtype compute_dtype, pc_packed **out);

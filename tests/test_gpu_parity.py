@@ -457,6 +457,71 @@ def test_select_and_pack_replay_in_a_graph(B, oracle):
             B.pc_destroy(ctx)
 
 
+def test_bwd_weight_on_a_second_context_and_stream(B, oracle):
+    """A pack belongs to no context: a second context on a second stream runs pc_conv_bwd_weight while the first
+    runs pc_conv_bwd_data (fork after the forward call, join at the end), eagerly and replayed from a HIP graph,
+    with a re-pack inside the step. Outputs equal those of the one-stream eager calls bit for bit."""
+    import torch
+    shapes = [I.Layer(16, 8, 8, 64, 128, 1), I.Layer(16, 4, 4, 128, 128, 1), I.Layer(8, 16, 16, 24, 64, 2)]
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    with torch.cuda.stream(main):
+        ctx = B.pc_create(0, main.cuda_stream)
+        ctx_w = B.pc_create(0, side.cuda_stream)
+        gs = []
+        try:
+            for li, layer in enumerate(shapes):
+                case = Case(layer, "bf16", 8, I.kept_per_filter(0.3, layer.C), tag=("two_streams", li))
+                g = GpuLayer(B, ctx, case)
+                g.y = torch.empty((layer.N, layer.Ho, layer.Wo, layer.F), dtype=torch.bfloat16, device="cuda")
+                g.dx = torch.empty((layer.N, layer.H, layer.W, layer.C), dtype=torch.bfloat16, device="cuda")
+                g.dw = torch.empty((g.nnzk, 4), dtype=torch.float32, device="cuda")
+                gs.append(g)
+
+            def step(two):
+                for g in gs:
+                    L, c = g.case.layer, g.case
+                    B.pc_pack(ctx, g.W, g.pid, g.keep, L.F, L.C, c.lib, g.dt, reuse=g.pk)
+                    B.pc_conv_fwd(ctx, g.desc, g.pk, g.x, g.y)
+                    if two:
+                        side.wait_stream(main)
+                    B.pc_conv_bwd_data(ctx, g.desc, g.pk, g.dy, g.dx)
+                    B.pc_conv_bwd_weight(ctx_w if two else ctx, g.desc, g.pk, g.x, g.dy, g.dw)
+                if two:
+                    main.wait_stream(side)
+
+            def outputs():
+                torch.cuda.synchronize()
+                return [t.clone() for g in gs for t in (g.y, g.dx, g.dw)]
+
+            def clear():
+                for g in gs:
+                    g.y.zero_(); g.dx.zero_(); g.dw.zero_()
+
+            step(False)
+            ref = outputs()
+            for g, (y, dx, dw) in zip(gs, zip(ref[0::3], ref[1::3], ref[2::3])):
+                L, c = g.case.layer, g.case
+                pid, kp, M, Wm = oracle_masks(oracle, c)
+                assert rel_l2(g.scatter(dw), oracle.conv_bwd_weight(c.x, c.dy, M, L.stride)) <= 1e-4
+            clear()
+            step(True)                                       # eager, two streams (also grows the side context's scratch)
+            assert all(torch.equal(a, b) for a, b in zip(outputs(), ref))
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=main):
+                step(True)
+            for rep in range(3):
+                clear()
+                (torch.ones(1 << 16, device="cuda") * 2).sum().item()
+                graph.replay()
+                assert all(torch.equal(a, b) for a, b in zip(outputs(), ref)), rep
+        finally:
+            torch.cuda.synchronize()
+            for g in gs:
+                g.close()
+            B.pc_destroy(ctx_w)
+            B.pc_destroy(ctx)
+
+
 def test_mismatched_descriptor_is_rejected(B, ctx, oracle):
     layer = I.Layer(1, 4, 4, 8, 8, 1)
     case = Case(layer, "f32", 4, 4, tag="mismatch")
