@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--wgrad-streams", type=int, default=1,
                     help="enqueue bwd_weight on this many side streams in turn (one context each), forked after the layer's "
                          "forward call and joined at the end of the step: it overlaps bwd_data of the same layer and what follows")
+    ap.add_argument("--no-prep-overlap", action="store_true",
+                    help="keep selection and packing (or the value update) of a step on the main stream, before each layer's "
+                         "forward call, instead of running them for all layers on the side stream from the start of the step")
     ap.add_argument("--chained", action="store_true",
                     help="also time the layers as one network (VGG workloads): forward through every layer with ReLU and "
                          "2x2 max pooling between them (pc_act_pool_fwd), then backward in reverse order")
@@ -116,7 +119,7 @@ def main() -> int:
     torch.cuda.synchronize()
     log("set-up %.1f s, %d layers, workload %s" % (time.time() - t_setup, len(layers), wl.name))
 
-    def run_pass(d, which):
+    def run_pass(d, which, ctx=ctx):
         if which == "select":
             B.pc_pattern_select(ctx, d["W"], d["G"], d["L"].F, d["L"].C, lib, B.PC_KEEP_PER_FILTER, d["k"],
                                 B.PC_SCORE_RETAINED, d["pid"], d["keep"])
@@ -133,10 +136,28 @@ def main() -> int:
 
     passes = (["select", "pack"] if wl.with_select else (["update"] if args.update_values else [])) + ["fwd", "bwd_data", "bwd_weight"]
 
+    prep = [w for w in passes if w in ("select", "pack", "update")]
+
     def step(events=None):
         overlap = bool(ctxs_w) and events is None
+        # selection and packing need only W and G, which exist when the step starts: with a side stream they are
+        # enqueued there for all layers first, and the main stream waits for a layer's pack before its forward call
+        prep_side = overlap and bool(prep) and not args.no_prep_overlap
+        ready = []
+        if prep_side:
+            streams_w[0].wait_stream(stream)
+            for d in layers:
+                for which in prep:
+                    run_pass(d, which, ctxs_w[0])
+                ev = torch.cuda.Event()
+                ev.record(streams_w[0])
+                ready.append(ev)
         for li, d in enumerate(layers):
+            if prep_side:
+                stream.wait_event(ready[li])
             for which in passes:
+                if prep_side and which in prep:
+                    continue
                 if events is not None:
                     e0 = torch.cuda.Event(enable_timing=True)
                     e1 = torch.cuda.Event(enable_timing=True)

@@ -459,8 +459,9 @@ def test_select_and_pack_replay_in_a_graph(B, oracle):
 
 def test_bwd_weight_on_a_second_context_and_stream(B, oracle):
     """A pack belongs to no context: a second context on a second stream runs pc_conv_bwd_weight while the first
-    runs pc_conv_bwd_data (fork after the forward call, join at the end), eagerly and replayed from a HIP graph,
-    with a re-pack inside the step. Outputs equal those of the one-stream eager calls bit for bit."""
+    runs pc_conv_bwd_data (fork after the forward call, join at the end), and selects and packs every layer ahead
+    of the first context's forward calls, eagerly and replayed from a HIP graph. Outputs equal those of the
+    one-stream eager calls bit for bit."""
     import torch
     shapes = [I.Layer(16, 8, 8, 64, 128, 1), I.Layer(16, 4, 4, 128, 128, 1), I.Layer(8, 16, 16, 24, 64, 2)]
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
@@ -477,10 +478,25 @@ def test_bwd_weight_on_a_second_context_and_stream(B, oracle):
                 g.dw = torch.empty((g.nnzk, 4), dtype=torch.float32, device="cuda")
                 gs.append(g)
 
+            def prep(g, cx):
+                L, c = g.case.layer, g.case
+                B.pc_pattern_select(cx, g.W, g.G, L.F, L.C, c.lib, 0, c.n_keep, 0, g.pid, g.keep)
+                B.pc_pack(cx, g.W, g.pid, g.keep, L.F, L.C, c.lib, g.dt, reuse=g.pk)
+
             def step(two):
-                for g in gs:
-                    L, c = g.case.layer, g.case
-                    B.pc_pack(ctx, g.W, g.pid, g.keep, L.F, L.C, c.lib, g.dt, reuse=g.pk)
+                ready = []
+                if two:                                      # selection and packing of every layer on the side stream first
+                    side.wait_stream(main)
+                    for g in gs:
+                        prep(g, ctx_w)
+                        ev = torch.cuda.Event()
+                        ev.record(side)
+                        ready.append(ev)
+                for li, g in enumerate(gs):
+                    if two:
+                        main.wait_event(ready[li])
+                    else:
+                        prep(g, ctx)
                     B.pc_conv_fwd(ctx, g.desc, g.pk, g.x, g.y)
                     if two:
                         side.wait_stream(main)
@@ -495,7 +511,7 @@ def test_bwd_weight_on_a_second_context_and_stream(B, oracle):
 
             def clear():
                 for g in gs:
-                    g.y.zero_(); g.dx.zero_(); g.dw.zero_()
+                    g.y.zero_(); g.dx.zero_(); g.dw.zero_(); g.pid.fill_(255); g.keep.fill_(255)
 
             step(False)
             ref = outputs()
