@@ -154,6 +154,29 @@ pc_status pc_pack(pc_ctx *ctx, const float *W_dev, const uint8_t *pid_dev, const
                   int32_t F, int32_t C, const uint16_t *lib_host, int32_t P,
                   pc_dtype compute_dtype, pc_packed **out);
 
+/* pc_pattern_select for several layers at once (the per-batch selection of Section 4.3 runs over every layer of the
+ * network): the same results as n_layers single calls, from one launch per 32 layers where every row has at most
+ * 8192 kernels and keep_mode is PC_KEEP_PER_FILTER (other layers are served one by one inside the call).
+ * One pool, keep mode and score mode for all layers.
+ *   W_dev_host, G_dev_host, pid_dev_host, keep_dev_host : HOST arrays [n_layers] of device pointers with the
+ *       meaning they have in pc_pattern_select (G_dev_host may be NULL, and so may any of its entries)
+ *   F_host, C_host, n_keep_host : HOST arrays [n_layers]
+ * The arrays are read before the call returns. */
+pc_status pc_pattern_select_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W_dev_host,
+                                  const float *const *G_dev_host, const int32_t *F_host, const int32_t *C_host,
+                                  const uint16_t *lib_host, int32_t P, pc_keep_mode keep_mode,
+                                  const int64_t *n_keep_host, pc_score_mode score_mode,
+                                  uint8_t *const *pid_dev_host, uint8_t *const *keep_dev_host);
+
+/* Re-packs several existing handles (each made by pc_pack for its layer's F, C and dtype; all distinct) with one
+ * pool: the same tables and tiles as n_layers pc_pack calls, from two or three launches per 32 layers. Every
+ * handle keeps the kernel family it has.
+ *   W_dev_host, pid_dev_host, keep_dev_host : HOST arrays [n_layers] of device pointers as in pc_pack
+ *   packs_host : HOST array [n_layers] of handles */
+pc_status pc_pack_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W_dev_host,
+                        const uint8_t *const *pid_dev_host, const uint8_t *const *keep_dev_host,
+                        const uint16_t *lib_host, int32_t P, pc_packed *const *packs_host);
+
 /* Re-gathers the kept weights from a dense tensor with unchanged tables (the per-iteration
  * dense-to-sparse conversion of Section 5.1). */
 pc_status pc_update_values(pc_ctx *ctx, pc_packed *pk, const float *W_dev);

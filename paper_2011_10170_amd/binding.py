@@ -26,7 +26,7 @@ EXPORTS = [
     "pc_packed_info", "pc_packed_free", "pc_scatter_dense", "pc_unpack_dense",
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
     "pc_dppg_accumulate", "pc_dppg_pool", "pc_finalize_count", "pc_finalize_pick", "pc_group_lasso_grad",
-    "pc_act_pool_fwd", "pc_act_pool_bwd",
+    "pc_act_pool_fwd", "pc_act_pool_bwd", "pc_pattern_select_batch", "pc_pack_batch",
 ]
 
 
@@ -81,6 +81,8 @@ def load():
     lib.pc_finalize_count.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.pc_finalize_pick.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.pc_group_lasso_grad.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, ct.c_float, ct.c_float, vp, vp]
+    lib.pc_pattern_select_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, ct.c_int, vp, ct.c_int, vp, vp]
+    lib.pc_pack_batch.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.pc_act_pool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp, vp]
     lib.pc_act_pool_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp]
     for name in EXPORTS:
@@ -228,3 +230,25 @@ def pc_act_pool_fwd(ctx, z, N, H, W, C, dtype, pool, a, sel) -> None:
 
 def pc_act_pool_bwd(ctx, da, sel, N, H, W, C, dtype, pool, dz) -> None:
     _check(ctx, load().pc_act_pool_bwd(ctx, _ptr(da), _ptr(sel), int(N), int(H), int(W), int(C), int(dtype), int(pool), _ptr(dz)))
+
+
+def _ptr_array(items):
+    return (ct.c_void_p * len(items))(*[_ptr(t) for t in items])
+
+
+def pc_pattern_select_batch(ctx, W, G, F, C, masks, keep_mode, n_keep, score_mode, pid, keep) -> None:
+    """W, G (or None), pid, keep: lists of device tensors; F, C, n_keep: lists of ints."""
+    n = len(W)
+    arr = _lib_arr(masks)
+    _check(ctx, load().pc_pattern_select_batch(
+        ctx, n, _ptr_array(W), _ptr_array(G) if G is not None else None, (ct.c_int32 * n)(*[int(v) for v in F]),
+        (ct.c_int32 * n)(*[int(v) for v in C]), ct.cast(arr, ct.c_void_p), len(masks), int(keep_mode),
+        (ct.c_int64 * n)(*[int(v) for v in n_keep]), int(score_mode), _ptr_array(pid), _ptr_array(keep)))
+
+
+def pc_pack_batch(ctx, W, pid, keep, masks, packs) -> None:
+    """Re-packs the existing handles `packs` (a list) from lists of device tensors."""
+    n = len(W)
+    arr = _lib_arr(masks)
+    _check(ctx, load().pc_pack_batch(ctx, n, _ptr_array(W), _ptr_array(pid), _ptr_array(keep), ct.cast(arr, ct.c_void_p),
+                                     len(masks), (ct.c_void_p * n)(*[int(p) for p in packs])))

@@ -176,11 +176,42 @@ extern "C" pc_status pc_pattern_select(pc_ctx *ctx, const float *W, const float 
     return pc_launch_select(ctx, W, G, F, C, la, km, n_keep, sm, pid, keep);
 }
 
+extern "C" pc_status pc_pattern_select_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W, const float *const *G,
+                                             const int32_t *F, const int32_t *C, const uint16_t *lib, int32_t P,
+                                             pc_keep_mode km, const int64_t *n_keep, pc_score_mode sm, uint8_t *const *pid,
+                                             uint8_t *const *keep)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (n_layers < 0) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select_batch: n_layers %d", n_layers);
+    if (n_layers == 0) return PC_OK;
+    if (!W || !F || !C || !n_keep || !pid || !keep || !lib)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select_batch: null pointer");
+    pc_status s = pc_check_library(lib, P);
+    if (s != PC_OK) return pc_fail(ctx, s, "pc_pattern_select_batch: bad library (P=%d)", P);
+    if (km != PC_KEEP_PER_FILTER && km != PC_KEEP_PER_LAYER)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select_batch: keep_mode %d", (int)km);
+    if (sm != PC_SCORE_RETAINED && sm != PC_SCORE_KERNEL)
+        return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select_batch: score_mode %d", (int)sm);
+    for (int l = 0; l < n_layers; ++l) {
+        if (!W[l] || !pid[l] || !keep[l]) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select_batch: null pointer in layer %d", l);
+        if (F[l] < 1 || C[l] < 1 || F[l] > 65535 || C[l] > 65535)
+            return pc_fail(ctx, PC_ERR_BAD_SHAPE, "pc_pattern_select_batch: layer %d: F=%d C=%d out of range", l, F[l], C[l]);
+        const int64_t lim = (km == PC_KEEP_PER_FILTER) ? (int64_t)C[l] : (int64_t)F[l] * C[l];
+        if (n_keep[l] < 0 || n_keep[l] > lim)
+            return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pattern_select_batch: layer %d: n_keep %lld outside 0..%lld", l,
+                           (long long)n_keep[l], (long long)lim);
+    }
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    LibArg la;
+    pc_fill_lib(&la, lib, P);
+    return pc_launch_select_batch(ctx, n_layers, W, G, F, C, la, km, n_keep, sm, pid, keep);
+}
+
 // ------------------------------------------------------------------ pack
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Carves the slab. With base == nullptr only the size is computed.
-static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
+static size_t carve(PackView *v, PackView **v_dev, char *base, int F, int C, bool mfma)
 {
     size_t off = 0;
     size_t cap = (size_t)F * C;
@@ -195,6 +226,7 @@ static size_t carve(PackView *v, char *base, int F, int C, bool mfma)
     v->Cp = (C + 127) / 128 * 128;
     v->Fk = (F + 63) / 64 * 64;
     v->Ck = (C + 63) / 64 * 64;
+    *v_dev = (PackView *)take(sizeof(PackView));
     v->fm_rowptr = (int32_t *)take(sizeof(int32_t) * (F + 1));
     v->fm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)F * (PC_MAX_P + 1));
     v->fm_rowtot = (int32_t *)take(sizeof(int32_t) * F);
@@ -268,13 +300,19 @@ extern "C" pc_status pc_pack(pc_ctx *ctx, const float *W, const uint8_t *pid, co
         pk->device = ctx->device;
         pk->dtype = dt;
         bool tiles = (dt == PC_BF16) && pc_mfma_supports(F, C);
-        pk->slab_bytes = carve(&pk->v, nullptr, F, C, tiles);
+        pk->slab_bytes = carve(&pk->v, &pk->v_dev, nullptr, F, C, tiles);
         hipError_t e = hipMalloc(&pk->slab, pk->slab_bytes);
         if (e != hipSuccess) {
             delete pk;
             return pc_hip_check(ctx, e, "pc_pack: hipMalloc");
         }
-        carve(&pk->v, (char *)pk->slab, F, C, tiles);
+        carve(&pk->v, &pk->v_dev, (char *)pk->slab, F, C, tiles);
+        e = hipMemcpy(pk->v_dev, &pk->v, sizeof(PackView), hipMemcpyHostToDevice);   // pointers and extents: fixed for the handle's life
+        if (e != hipSuccess) {
+            (void)hipFree(pk->slab);
+            delete pk;
+            return pc_hip_check(ctx, e, "pc_pack: hipMemcpy");
+        }
         if (hipEventCreateWithFlags(&pk->packed_evt, hipEventDisableTiming) != hipSuccess) {
             (void)hipFree(pk->slab);
             delete pk;
@@ -306,6 +344,49 @@ extern "C" pc_status pc_pack(pc_ctx *ctx, const float *W, const uint8_t *pid, co
         return s;
     }
     *out = pk;
+    return PC_OK;
+}
+
+extern "C" pc_status pc_pack_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W, const uint8_t *const *pid,
+                                   const uint8_t *const *keep, const uint16_t *lib, int32_t P, pc_packed *const *packs)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (n_layers < 0) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack_batch: n_layers %d", n_layers);
+    if (n_layers == 0) return PC_OK;
+    if (!W || !pid || !keep || !lib || !packs) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack_batch: null pointer");
+    pc_status s = pc_check_library(lib, P);
+    if (s != PC_OK) return pc_fail(ctx, s, "pc_pack_batch: bad library (P=%d)", P);
+    for (int l = 0; l < n_layers; ++l) {
+        if (!W[l] || !pid[l] || !keep[l] || !packs[l])
+            return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack_batch: null pointer in layer %d", l);
+        if (packs[l]->device != ctx->device) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack_batch: layer %d: other device", l);
+        for (int m = 0; m < l; ++m)
+            if (packs[m] == packs[l]) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack_batch: layers %d and %d share a handle", m, l);
+    }
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    LibArg la;
+    pc_fill_lib(&la, lib, P);
+    for (int l = 0; l < n_layers; ++l) {
+        pc_packed *pk = packs[l];
+        pk->v.P = P;
+        pk->nnzk = -1;
+        pk->evt_recorded = false;
+        memcpy(pk->lib, lib, sizeof(uint16_t) * P);
+        memcpy(pk->taps, la.taps, sizeof(pk->taps));
+    }
+    s = pc_launch_pack_batch(ctx, n_layers, packs, W, pid, keep, la);
+    if (s != PC_OK) return s;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(ctx->stream, &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        cap = hipStreamCaptureStatusNone;
+    }
+    if (cap == hipStreamCaptureStatusNone)
+        for (int l = 0; l < n_layers; ++l) {
+            s = pc_hip_check(ctx, hipEventRecord(packs[l]->packed_evt, ctx->stream), "hipEventRecord");
+            if (s != PC_OK) return s;
+            packs[l]->evt_recorded = true;
+        }
     return PC_OK;
 }
 

@@ -60,6 +60,7 @@ struct pc_packed {
     void *slab;
     size_t slab_bytes;
     PackView v;
+    PackView *v_dev;             // copy of v at the start of the slab, for kernels that serve several packs at once
     hipEvent_t packed_evt;       // recorded after the last pack on this handle
     bool evt_recorded;           // false when that pack was enqueued under stream capture (no event then)
     int64_t nnzk;                // -1 until read back
@@ -93,6 +94,13 @@ void pc_fill_lib(LibArg *la, const uint16_t *lib, int P);
 pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, int C, const LibArg &la,
                            pc_keep_mode km, int64_t n_keep, pc_score_mode sm, uint8_t *pid, uint8_t *keep);
 pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8_t *pid, const uint8_t *keep);
+// Several layers per launch (at most PC_BATCH_MAX per kernel; longer lists are cut into groups).
+#define PC_BATCH_MAX 32
+pc_status pc_launch_select_batch(pc_ctx *ctx, int n, const float *const *W, const float *const *G, const int32_t *F,
+                                 const int32_t *C, const LibArg &la, pc_keep_mode km, const int64_t *n_keep, pc_score_mode sm,
+                                 uint8_t *const *pid, uint8_t *const *keep);
+pc_status pc_launch_pack_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const float *const *W, const uint8_t *const *pid,
+                               const uint8_t *const *keep, const LibArg &la);
 pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W);
 pc_status pc_launch_scatter(pc_ctx *ctx, const pc_packed *pk, const float *compact, float *dense, int from_pack);
 

@@ -140,9 +140,9 @@ pc_select_topn_row_kernel(const float *__restrict__ R, int L, int n_keep, uint8_
 // Selection of one filter row in one workgroup (rows of up to PC_TOPN_MAX kernels): scores as in the kernel
 // above, then the top n_keep of the row by the same radix select, without the round trip of the scores through
 // memory. W and G reach the lanes through LDS so that the global loads are contiguous.
-__global__ void __launch_bounds__(512)
-pc_select_row_kernel(const float *__restrict__ W, const float *__restrict__ G, int C, LibArg la, int score_mode,
-                     int n_keep, uint8_t *__restrict__ pid, uint8_t *__restrict__ keep)
+__device__ __forceinline__ void pc_select_row_body(const float *__restrict__ W, const float *__restrict__ G, int C, const LibArg &la,
+                                                   int score_mode, int n_keep, uint8_t *__restrict__ pid,
+                                                   uint8_t *__restrict__ keep, int row)
 {
     extern __shared__ uint32_t dyn[];           // C keys, then blockDim.x * 9 floats of W, then as many of G
     __shared__ int hist[256];
@@ -154,7 +154,7 @@ pc_select_row_kernel(const float *__restrict__ W, const float *__restrict__ G, i
     uint32_t *keys = dyn;
     float *sw = reinterpret_cast<float *>(dyn + C);
     float *sg = sw + (size_t)T * 9;
-    const int64_t row0 = (int64_t)blockIdx.x * C;
+    const int64_t row0 = (int64_t)row * C;
     for (int c0 = 0; c0 < C; c0 += T) {
         const int n = C - c0 < T ? C - c0 : T;
         const float *wsrc = W + (row0 + c0) * 9;
@@ -262,6 +262,37 @@ pc_select_row_kernel(const float *__restrict__ W, const float *__restrict__ G, i
         }
         __syncthreads();
     }
+}
+
+__global__ void __launch_bounds__(512)
+pc_select_row_kernel(const float *__restrict__ W, const float *__restrict__ G, int C, LibArg la, int score_mode,
+                     int n_keep, uint8_t *__restrict__ pid, uint8_t *__restrict__ keep)
+{
+    pc_select_row_body(W, G, C, la, score_mode, n_keep, pid, keep, (int)blockIdx.x);
+}
+
+// The same for the filter rows of several layers in one launch: workgroup b serves row b - row0[l] of the layer l
+// whose range holds b. Dynamic LDS is sized for the widest layer.
+struct SelBatchArg {
+    int32_t n, score_mode;
+    int32_t row0[PC_BATCH_MAX + 1];
+    int32_t C[PC_BATCH_MAX], n_keep[PC_BATCH_MAX];
+    const float *W[PC_BATCH_MAX], *G[PC_BATCH_MAX];
+    uint8_t *pid[PC_BATCH_MAX], *keep[PC_BATCH_MAX];
+};
+
+// Index of the range [first[l], first[l + 1]) that holds b (uniform over the workgroup).
+__device__ __forceinline__ int pc_batch_find(const int32_t *first, int n, int b)
+{
+    int l = 0;
+    while (l + 1 < n && b >= first[l + 1]) ++l;
+    return l;
+}
+
+__global__ void __launch_bounds__(512) pc_select_rows_batch_kernel(SelBatchArg b, LibArg la)
+{
+    const int l = pc_batch_find(b.row0, b.n, (int)blockIdx.x);
+    pc_select_row_body(b.W[l], b.G[l], b.C[l], la, b.score_mode, b.n_keep[l], b.pid[l], b.keep[l], (int)blockIdx.x - b.row0[l]);
 }
 
 // ---- exact top-n_keep of long segments (more than PC_TOPN_MAX scores): the same radix select across workgroups.
@@ -468,6 +499,51 @@ pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, i
     return pc_hip_check(ctx, hipGetLastError(), "select launch");
 }
 
+// Layers whose rows fit the one-workgroup kernel go into launches of up to PC_BATCH_MAX layers; the others are
+// served one by one by pc_launch_select.
+pc_status pc_launch_select_batch(pc_ctx *ctx, int n, const float *const *W, const float *const *G, const int32_t *F,
+                                 const int32_t *C, const LibArg &la, pc_keep_mode km, const int64_t *n_keep, pc_score_mode sm,
+                                 uint8_t *const *pid, uint8_t *const *keep)
+{
+    static pc_per_device_once attr;
+    if (pc_once_pending(attr, ctx->device)) {
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_select_rows_batch_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)(sizeof(uint32_t) * PC_TOPN_MAX + 2 * sizeof(float) * 9 * 512)));
+        pc_once_done(attr, ctx->device);
+    }
+    SelBatchArg b;
+    memset(&b, 0, sizeof(b));
+    b.score_mode = (int)sm;
+    int cmax = 0;
+    auto flush = [&]() -> pc_status {
+        if (b.n == 0) return PC_OK;
+        const int T = cmax <= 256 ? 256 : 512;
+        const size_t lds = sizeof(uint32_t) * (size_t)cmax + 2 * sizeof(float) * 9 * (size_t)T;
+        hipLaunchKernelGGL(pc_select_rows_batch_kernel, dim3((unsigned)b.row0[b.n]), dim3((unsigned)T), lds, ctx->stream, b, la);
+        b.n = 0;
+        cmax = 0;
+        return pc_hip_check(ctx, hipGetLastError(), "select (several layers) launch");
+    };
+    for (int l = 0; l < n; ++l) {
+        if (km != PC_KEEP_PER_FILTER || C[l] > PC_TOPN_MAX) {
+            pc_status s = pc_launch_select(ctx, W[l], G ? G[l] : nullptr, F[l], C[l], la, km, n_keep[l], sm, pid[l], keep[l]);
+            if (s != PC_OK) return s;
+            continue;
+        }
+        const int i = b.n;
+        b.W[i] = W[l]; b.G[i] = G ? G[l] : nullptr; b.C[i] = C[l];
+        b.n_keep[i] = (int32_t)(n_keep[l] < C[l] ? n_keep[l] : C[l]);
+        b.pid[i] = pid[l]; b.keep[i] = keep[l];
+        b.row0[i + 1] = b.row0[i] + F[l];
+        if (C[l] > cmax) cmax = C[l];
+        if (++b.n == PC_BATCH_MAX) {
+            pc_status s = flush();
+            if (s != PC_OK) return s;
+        }
+    }
+    return flush();
+}
+
 // ------------------------------------------------------------------ packing
 // Table rows are filters (row stride C, element stride 1 in the [F][C] maps) for the
 // filter-major table, channels (row stride 1, element stride C) for the channel-major one.
@@ -595,11 +671,10 @@ __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, 
 
 // First launch of a pack: workgroups [0, F) count the filter rows, [F, F + ncm) the channel rows (ncm = C for the
 // gather variant, else 0), the rest write the operand tiles (matrix-core variant), one 32 x 32 block each.
-__global__ void __launch_bounds__(256)
-pc_pack_stage1_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep,
-                      LibArg la, PackView v, int ncm, int tiles_c)
+__device__ __forceinline__ void pc_pack_stage1_body(const float *__restrict__ W, const uint8_t *__restrict__ pid,
+                                                    const uint8_t *__restrict__ keep, const LibArg &la, const PackView &v, int ncm,
+                                                    int tiles_c, int b)
 {
-    int b = blockIdx.x;
     if (b < v.F) {
         pc_pack_count_row(pid, keep, b, v.C, (int64_t)v.C, 1, v.P, v.fm_grp, v.fm_rowtot);
         return;
@@ -611,6 +686,32 @@ pc_pack_stage1_kernel(const float *__restrict__ W, const uint8_t *__restrict__ p
     }
     b -= ncm;
     pc_pack_tile_block<false>(W, pid, keep, la, v, b / tiles_c, b % tiles_c);
+}
+
+__global__ void __launch_bounds__(256)
+pc_pack_stage1_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep,
+                      LibArg la, PackView v, int ncm, int tiles_c)
+{
+    pc_pack_stage1_body(W, pid, keep, la, v, ncm, tiles_c, (int)blockIdx.x);
+}
+
+// Several packs per launch: workgroup b serves block b - blk0[l] of pack l. The packs' views are read from their
+// device copies (the pool is the launch's, so its size replaces the view's).
+struct PackBatchArg {
+    int32_t n;
+    int32_t blk0[PC_BATCH_MAX + 1];
+    const float *W[PC_BATCH_MAX];
+    const uint8_t *pid[PC_BATCH_MAX], *keep[PC_BATCH_MAX];
+    const PackView *view[PC_BATCH_MAX];
+    int32_t ncm[PC_BATCH_MAX], tiles_c[PC_BATCH_MAX], bf16[PC_BATCH_MAX];
+};
+
+__global__ void __launch_bounds__(256) pc_pack_stage1_batch_kernel(PackBatchArg b, LibArg la)
+{
+    const int l = pc_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    PackView v = *b.view[l];
+    v.P = la.P;
+    pc_pack_stage1_body(b.W[l], b.pid[l], b.keep[l], la, v, b.ncm[l], b.tiles_c[l], (int)blockIdx.x - b.blk0[l]);
 }
 
 // The 4 kept weights of kernel k; taps holds the 4 tap indices, one per byte, ascending from the low byte.
@@ -652,16 +753,16 @@ pc_pack_revalue_kernel(const float *__restrict__ W, LibArg la, int bf16, PackVie
 // inside a group is ascending. The row is walked 256 elements at a time: every wave ballots each pattern id,
 // the per-wave counts go through LDS. All counts are integers, so no result depends on an execution order.
 template <bool FM>
-__global__ void __launch_bounds__(256)
-pc_pack_place_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep,
-                     int rows, int len, int64_t row_stride, int64_t elem_stride, LibArg la, int bf16, PackView v)
+__device__ __forceinline__ void pc_pack_place_body(const float *__restrict__ W, const uint8_t *__restrict__ pid,
+                                                   const uint8_t *__restrict__ keep, int rows, int len, int64_t row_stride,
+                                                   int64_t elem_stride, const LibArg &la, int bf16, const PackView &v, int row)
 {
     __shared__ int start[PC_MAX_P + 1];          // next free slot of every pattern group
     __shared__ int wcnt[4][PC_MAX_P + 2];        // members of every group in the current 256 elements, per wave
     __shared__ int red[4];
     __shared__ uint32_t ltaps[PC_MAX_P + 2];      // tap lists and masks of the pool
     __shared__ uint16_t lmask[PC_MAX_P + 2];
-    const int row = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int P = la.P;
     if (tid < P) { ltaps[tid] = pc_taps_word(la, tid); lmask[tid] = la.mask[tid]; }
     int32_t *grp = (FM ? v.fm_grp : v.cm_grp) + (int64_t)row * (PC_MAX_P + 1);
@@ -732,6 +833,24 @@ pc_pack_place_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pi
     }
 }
 
+template <bool FM>
+__global__ void __launch_bounds__(256)
+pc_pack_place_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep,
+                     int rows, int len, int64_t row_stride, int64_t elem_stride, LibArg la, int bf16, PackView v)
+{
+    pc_pack_place_body<FM>(W, pid, keep, rows, len, row_stride, elem_stride, la, bf16, v, (int)blockIdx.x);
+}
+
+template <bool FM> __global__ void __launch_bounds__(256) pc_pack_place_batch_kernel(PackBatchArg b, LibArg la)
+{
+    const int l = pc_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    PackView v = *b.view[l];
+    v.P = la.P;
+    const int row = (int)blockIdx.x - b.blk0[l];
+    if constexpr (FM) pc_pack_place_body<true>(b.W[l], b.pid[l], b.keep[l], v.F, v.C, (int64_t)v.C, (int64_t)1, la, b.bf16[l], v, row);
+    else pc_pack_place_body<false>(b.W[l], b.pid[l], b.keep[l], v.C, v.F, (int64_t)1, (int64_t)v.C, la, b.bf16[l], v, row);
+}
+
 // Re-gathers values with unchanged tables (one thread per kernel (f,c)).
 __global__ void __launch_bounds__(256)
 pc_pack_regather_fm_kernel(const float *__restrict__ W, LibArg la, int bf16, PackView v)
@@ -769,6 +888,44 @@ pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8
         hipLaunchKernelGGL(pc_pack_place_kernel<false>, dim3(v.C), dim3(256), 0, st, W, pid, keep, v.C, v.F, (int64_t)1,
                            (int64_t)v.C, la, bf16, v);
     return pc_hip_check(ctx, hipGetLastError(), "pack launch");
+}
+
+// Re-packs several handles with one pool: three launches per group of up to PC_BATCH_MAX packs (two when none uses
+// the gather kernels).
+pc_status pc_launch_pack_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const float *const *W, const uint8_t *const *pid,
+                               const uint8_t *const *keep, const LibArg &la)
+{
+    for (int l0 = 0; l0 < n; l0 += PC_BATCH_MAX) {
+        const int m = n - l0 < PC_BATCH_MAX ? n - l0 : PC_BATCH_MAX;
+        PackBatchArg s1, fm, cm;
+        memset(&s1, 0, sizeof(s1));
+        s1.n = m;
+        for (int i = 0; i < m; ++i) {
+            const pc_packed *p = pk[l0 + i];
+            const bool mfma = p->variant == PC_VARIANT_MFMA;
+            s1.W[i] = W[l0 + i]; s1.pid[i] = pid[l0 + i]; s1.keep[i] = keep[l0 + i];
+            s1.view[i] = p->v_dev;
+            s1.ncm[i] = mfma ? 0 : p->v.C;
+            s1.tiles_c[i] = p->v.Cp / 32;
+            s1.bf16[i] = p->dtype == PC_BF16;
+        }
+        fm = s1;
+        cm = s1;
+        for (int i = 0; i < m; ++i) {
+            const pc_packed *p = pk[l0 + i];
+            const bool mfma = p->variant == PC_VARIANT_MFMA;
+            s1.blk0[i + 1] = s1.blk0[i] + p->v.F + s1.ncm[i] + (mfma ? (p->v.Fp / 32) * s1.tiles_c[i] : 0);
+            fm.blk0[i + 1] = fm.blk0[i] + p->v.F;
+            cm.blk0[i + 1] = cm.blk0[i] + (mfma ? 0 : p->v.C);
+        }
+        hipLaunchKernelGGL(pc_pack_stage1_batch_kernel, dim3((unsigned)s1.blk0[m]), dim3(256), 0, ctx->stream, s1, la);
+        hipLaunchKernelGGL(pc_pack_place_batch_kernel<true>, dim3((unsigned)fm.blk0[m]), dim3(256), 0, ctx->stream, fm, la);
+        if (cm.blk0[m] > 0)
+            hipLaunchKernelGGL(pc_pack_place_batch_kernel<false>, dim3((unsigned)cm.blk0[m]), dim3(256), 0, ctx->stream, cm, la);
+        pc_status s = pc_hip_check(ctx, hipGetLastError(), "pack (several layers) launch");
+        if (s != PC_OK) return s;
+    }
+    return PC_OK;
 }
 
 pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W)

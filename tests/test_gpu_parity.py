@@ -538,6 +538,76 @@ def test_bwd_weight_on_a_second_context_and_stream(B, oracle):
             B.pc_destroy(ctx)
 
 
+def test_select_and_pack_batch(B, ctx, oracle):
+    """pc_pattern_select_batch and pc_pack_batch over layers of mixed shapes, dtypes and kernel families (one row too
+    long for the one-workgroup kernel, one float32 layer on the gather kernels): masks bit-exact against the oracle,
+    the re-packed handles hold W (.) M, their kept-kernel counts are right and a forward pass through each is within
+    tolerance. The handles were first packed with other masks (selection with gradients), so a stale table would show."""
+    import torch
+    shapes = [(2, 6, 6, 3, 64, "bf16"), (2, 6, 6, 64, 64, "bf16"), (2, 5, 4, 64, 128, "bf16"), (2, 4, 4, 24, 40, "f32"),
+              (1, 4, 4, 256, 256, "bf16"), (1, 2, 2, 9000, 8, "bf16"), (3, 3, 3, 40, 72, "bf16")]
+    gs, cases = [], []
+    try:
+        for li, (N, H, W_, C, F, dtype) in enumerate(shapes):
+            layer = I.Layer(N, H, W_, C, F, 1)
+            case = Case(layer, dtype, 8, I.kept_per_filter(0.3, C), tag=("batch", li))
+            cases.append(case)
+            gs.append(GpuLayer(B, ctx, case))                       # select with gradients + pack, one layer at a time
+        for g in gs:
+            g.pid.fill_(255); g.keep.fill_(255)
+        lib = cases[0].lib
+        B.pc_pattern_select_batch(ctx, [g.W for g in gs], None, [c.layer.F for c in cases], [c.layer.C for c in cases], lib,
+                                  B.PC_KEEP_PER_FILTER, [c.n_keep for c in cases], B.PC_SCORE_RETAINED,
+                                  [g.pid for g in gs], [g.keep for g in gs])
+        B.pc_pack_batch(ctx, [g.W for g in gs], [g.pid for g in gs], [g.keep for g in gs], lib, [g.pk for g in gs])
+        for g, case in zip(gs, cases):
+            L = case.layer
+            pid, kp, M, Wm = oracle_masks(oracle, case, with_grad=False)
+            gpid, gkeep = g.masks()
+            assert np.array_equal(gpid, pid) and np.array_equal(gkeep, kp), L
+            assert B.pc_packed_info(ctx, g.pk)[0] == int(kp.sum())
+            assert np.array_equal(g.unpack(), Wm), L
+            tol = 2e-2 if case.dtype == "bf16" else 1e-4
+            assert rel_l2(g.fwd(), oracle.conv_fwd(case.x, Wm, 1)) <= tol, L
+            dw, guard = g.bwd_weight()
+            assert rel_l2(g.scatter(guard.body), oracle.conv_bwd_weight(case.x, case.dy, M, 1)) <= 1e-4, L
+    finally:
+        for g in gs:
+            g.close()
+
+
+def test_select_and_pack_batch_of_many_layers(B, ctx, oracle):
+    """More layers than one launch takes (40 > 32), with gradients and with one gradient pointer missing."""
+    import torch
+    rng = np.random.default_rng(77)
+    gs, cases = [], []
+    try:
+        for li in range(40):
+            F, C = int(rng.integers(1, 40)), int(rng.integers(1, 70))
+            case = Case(I.Layer(1, 3, 3, C, F, 1), "f32" if li % 5 == 0 else "bf16", 8, I.kept_per_filter(0.4, C), tag=("many", li))
+            cases.append(case)
+            gs.append(GpuLayer(B, ctx, case, with_grad=False))
+        for g in gs:
+            g.pid.fill_(255); g.keep.fill_(255)
+        Gs = [to_dev(c.G) for c in cases]
+        Gs[7] = None
+        lib = cases[0].lib
+        B.pc_pattern_select_batch(ctx, [g.W for g in gs], Gs, [c.layer.F for c in cases], [c.layer.C for c in cases], lib,
+                                  B.PC_KEEP_PER_FILTER, [c.n_keep for c in cases], B.PC_SCORE_RETAINED,
+                                  [g.pid for g in gs], [g.keep for g in gs])
+        B.pc_pack_batch(ctx, [g.W for g in gs], [g.pid for g in gs], [g.keep for g in gs], lib, [g.pk for g in gs])
+        for li, (g, case) in enumerate(zip(gs, cases)):
+            pid, kp, M, Wm = oracle_masks(oracle, case, with_grad=li != 7)
+            gpid, gkeep = g.masks()
+            assert np.array_equal(gpid, pid) and np.array_equal(gkeep, kp), li
+            assert np.array_equal(g.unpack(), Wm), li
+        with pytest.raises(B.PcError):
+            B.pc_pack_batch(ctx, [gs[0].W, gs[0].W], [gs[0].pid] * 2, [gs[0].keep] * 2, lib, [gs[0].pk, gs[0].pk])
+    finally:
+        for g in gs:
+            g.close()
+
+
 def test_mismatched_descriptor_is_rejected(B, ctx, oracle):
     layer = I.Layer(1, 4, 4, 8, 8, 1)
     case = Case(layer, "f32", 4, 4, tag="mismatch")
