@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--no-prep-overlap", action="store_true",
                     help="keep selection and packing (or the value update) of a step on the main stream, before each layer's "
                          "forward call, instead of running them for all layers on the side stream from the start of the step")
+    ap.add_argument("--no-batch-prep", action="store_true",
+                    help="select and pack layer by layer (pc_pattern_select, pc_pack) instead of all layers per launch "
+                         "(pc_pattern_select_batch, pc_pack_batch)")
     ap.add_argument("--chained", action="store_true",
                     help="also time the layers as one network (VGG workloads): forward through every layer with ReLU and "
                          "2x2 max pooling between them (pc_act_pool_fwd), then backward in reverse order")
@@ -137,14 +140,36 @@ def main() -> int:
     passes = (["select", "pack"] if wl.with_select else (["update"] if args.update_values else [])) + ["fwd", "bwd_data", "bwd_weight"]
 
     prep = [w for w in passes if w in ("select", "pack", "update")]
+    batch_prep = wl.with_select and not args.no_batch_prep
+
+    def run_batch(which, ctx=ctx):
+        if which == "select":
+            B.pc_pattern_select_batch(ctx, [d["W"] for d in layers], [d["G"] for d in layers], [d["L"].F for d in layers],
+                                      [d["L"].C for d in layers], lib, B.PC_KEEP_PER_FILTER, [d["k"] for d in layers],
+                                      B.PC_SCORE_RETAINED, [d["pid"] for d in layers], [d["keep"] for d in layers])
+        else:
+            B.pc_pack_batch(ctx, [d["W"] for d in layers], [d["pid"] for d in layers], [d["keep"] for d in layers], lib,
+                            [d["pk"] for d in layers])
 
     def step(events=None):
         overlap = bool(ctxs_w) and events is None
-        # selection and packing need only W and G, which exist when the step starts: with a side stream they are
-        # enqueued there for all layers first, and the main stream waits for a layer's pack before its forward call
+        # selection and packing need only W and G, which exist when the step starts. Layer by layer
+        # (--no-batch-prep, or the value update) they are enqueued on the side stream for all layers first, and the
+        # main stream waits for a layer's pack before its forward call
         prep_side = overlap and bool(prep) and not args.no_prep_overlap
         ready = []
-        if prep_side:
+        if batch_prep:
+            # all layers per launch: three launches at the start of the step, nothing left to overlap
+            for which in prep:
+                if events is not None:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                run_batch(which)
+                if events is not None:
+                    e1.record(stream)
+                    events.append((-1, which, e0, e1))
+        elif prep_side:
             streams_w[0].wait_stream(stream)
             for d in layers:
                 for which in prep:
@@ -153,10 +178,10 @@ def main() -> int:
                 ev.record(streams_w[0])
                 ready.append(ev)
         for li, d in enumerate(layers):
-            if prep_side:
+            if ready:
                 stream.wait_event(ready[li])
             for which in passes:
-                if prep_side and which in prep:
+                if (batch_prep or prep_side) and which in prep:
                     continue
                 if events is not None:
                     e0 = torch.cuda.Event(enable_timing=True)
@@ -225,7 +250,8 @@ def main() -> int:
         var = "mfma" if d["variant"] == B.PC_VARIANT_MFMA else "valu"
         if which in ("select", "pack", "update"):
             kind = which
-            byts = L.F * L.C * (74 if which == "select" else 38 + 0.0)
+            n_pos = sum(x["L"].F * x["L"].C for x in layers) if li < 0 else L.F * L.C   # li = -1: one call for all layers
+            byts = n_pos * (74 if which == "select" else 38 + 0.0)
             fl = dfl = 0.0
         else:
             kind = "%s_%s" % (var, which)
@@ -244,7 +270,7 @@ def main() -> int:
         t_roof_sum += t_roof_us
         t_meas_sum += us
         log("%-3d %-22s %-10s %-5s %9.1f %10.2f %10.1f %8.0f %6.3f" % (
-            li, "%dx%d %d->%d s%d" % (L.H, L.W, L.C, L.F, L.stride), which, var, us,
+            li, "all %d layers" % len(layers) if li < 0 else "%dx%d %d->%d s%d" % (L.H, L.W, L.C, L.F, L.stride), which, var, us,
             fl / us / 1e6, dfl / us / 1e6, byts / us / 1e3, t_roof_us / us))
     dom = max(kinds.items(), key=lambda kv: kv[1]["us"])
     dk, dv = dom
