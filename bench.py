@@ -140,10 +140,12 @@ def main() -> int:
     passes = (["select", "pack"] if wl.with_select else (["update"] if args.update_values else [])) + ["fwd", "bwd_data", "bwd_weight"]
 
     prep = [w for w in passes if w in ("select", "pack", "update")]
-    batch_prep = wl.with_select and not args.no_batch_prep
+    batch_prep = bool(prep) and not args.no_batch_prep
 
     def run_batch(which, ctx=ctx):
-        if which == "select":
+        if which == "update":
+            B.pc_update_values_batch(ctx, [d["pk"] for d in layers], [d["W"] for d in layers])
+        elif which == "select":
             B.pc_pattern_select_batch(ctx, [d["W"] for d in layers], [d["G"] for d in layers], [d["L"].F for d in layers],
                                       [d["L"].C for d in layers], lib, B.PC_KEEP_PER_FILTER, [d["k"] for d in layers],
                                       B.PC_SCORE_RETAINED, [d["pid"] for d in layers], [d["keep"] for d in layers])

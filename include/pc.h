@@ -181,6 +181,12 @@ pc_status pc_pack_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W_dev
  * dense-to-sparse conversion of Section 5.1). */
 pc_status pc_update_values(pc_ctx *ctx, pc_packed *pk, const float *W_dev);
 
+/* pc_update_values for several handles (all distinct) at once: one launch per 32 matrix-core packs that were made
+ * with the same pool; other packs are updated one by one inside the call.
+ *   packs_host : HOST array [n_layers] of handles; W_dev_host : HOST array [n_layers] of device pointers */
+pc_status pc_update_values_batch(pc_ctx *ctx, int32_t n_layers, pc_packed *const *packs_host,
+                                 const float *const *W_dev_host);
+
 /* nnz_kernels = number of kept kernels; variant = family in use. The count is read back from the device the
  * first time it is asked for after a pack: that call waits for the pack to finish (for a pack that was
  * enqueued while its stream was being captured into a HIP graph it waits for the whole stream of ctx, and it

@@ -26,7 +26,7 @@ EXPORTS = [
     "pc_packed_info", "pc_packed_free", "pc_scatter_dense", "pc_unpack_dense",
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
     "pc_dppg_accumulate", "pc_dppg_pool", "pc_finalize_count", "pc_finalize_pick", "pc_group_lasso_grad",
-    "pc_act_pool_fwd", "pc_act_pool_bwd", "pc_pattern_select_batch", "pc_pack_batch",
+    "pc_act_pool_fwd", "pc_act_pool_bwd", "pc_pattern_select_batch", "pc_pack_batch", "pc_update_values_batch",
 ]
 
 
@@ -83,6 +83,7 @@ def load():
     lib.pc_group_lasso_grad.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, ct.c_float, ct.c_float, vp, vp]
     lib.pc_pattern_select_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, ct.c_int, vp, ct.c_int, vp, vp]
     lib.pc_pack_batch.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
+    lib.pc_update_values_batch.argtypes = [vp, i32, vp, vp]
     lib.pc_act_pool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp, vp]
     lib.pc_act_pool_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp]
     for name in EXPORTS:
@@ -252,3 +253,8 @@ def pc_pack_batch(ctx, W, pid, keep, masks, packs) -> None:
     arr = _lib_arr(masks)
     _check(ctx, load().pc_pack_batch(ctx, n, _ptr_array(W), _ptr_array(pid), _ptr_array(keep), ct.cast(arr, ct.c_void_p),
                                      len(masks), (ct.c_void_p * n)(*[int(p) for p in packs])))
+
+
+def pc_update_values_batch(ctx, packs, W) -> None:
+    n = len(packs)
+    _check(ctx, load().pc_update_values_batch(ctx, n, (ct.c_void_p * n)(*[int(p) for p in packs]), _ptr_array(W)))

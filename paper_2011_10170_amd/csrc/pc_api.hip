@@ -399,6 +399,23 @@ extern "C" pc_status pc_update_values(pc_ctx *ctx, pc_packed *pk, const float *W
     return pc_launch_update_values(ctx, pk, W);
 }
 
+extern "C" pc_status pc_update_values_batch(pc_ctx *ctx, int32_t n_layers, pc_packed *const *packs, const float *const *W)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (n_layers < 0) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_update_values_batch: n_layers %d", n_layers);
+    if (n_layers == 0) return PC_OK;
+    if (!packs || !W) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_update_values_batch: null pointer");
+    for (int l = 0; l < n_layers; ++l) {
+        if (!packs[l] || !W[l]) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_update_values_batch: null pointer in layer %d", l);
+        if (packs[l]->device != ctx->device) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_update_values_batch: layer %d: other device", l);
+        for (int m = 0; m < l; ++m)
+            if (packs[m] == packs[l])
+                return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_update_values_batch: layers %d and %d share a handle", m, l);
+    }
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    return pc_launch_update_values_batch(ctx, n_layers, packs, W);
+}
+
 extern "C" pc_status pc_packed_info(pc_ctx *ctx, const pc_packed *pk, int64_t *nnz, int32_t *variant)
 {
     if (!ctx) return PC_ERR_INVALID_ARG;

@@ -99,6 +99,7 @@ pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8
 pc_status pc_launch_select_batch(pc_ctx *ctx, int n, const float *const *W, const float *const *G, const int32_t *F,
                                  const int32_t *C, const LibArg &la, pc_keep_mode km, const int64_t *n_keep, pc_score_mode sm,
                                  uint8_t *const *pid, uint8_t *const *keep);
+pc_status pc_launch_update_values_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const float *const *W);
 pc_status pc_launch_pack_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const float *const *W, const uint8_t *const *pid,
                                const uint8_t *const *keep, const LibArg &la);
 pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W);

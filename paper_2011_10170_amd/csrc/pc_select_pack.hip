@@ -733,19 +733,35 @@ __device__ __forceinline__ uint32_t pc_taps_word(const LibArg &la, int p)
 
 // Values again from new weights with unchanged tables, one launch for the matrix-core variant: workgroups
 // [0, ntiles) rebuild the operand tiles (masks from the kinfo table), the others re-gather the compact values.
-__global__ void __launch_bounds__(256)
-pc_pack_revalue_kernel(const float *__restrict__ W, LibArg la, int bf16, PackView v, int tiles_c, int ntiles)
+__device__ __forceinline__ void pc_pack_revalue_body(const float *__restrict__ W, const LibArg &la, int bf16, const PackView &v,
+                                                     int tiles_c, int ntiles, int b)
 {
-    if ((int)blockIdx.x < ntiles) {
-        pc_pack_tile_block<true>(W, nullptr, nullptr, la, v, blockIdx.x / tiles_c, blockIdx.x % tiles_c);
+    if (b < ntiles) {
+        pc_pack_tile_block<true>(W, nullptr, nullptr, la, v, b / tiles_c, b % tiles_c);
         return;
     }
-    const int64_t k = (int64_t)(blockIdx.x - ntiles) * 256 + threadIdx.x;
+    const int64_t k = (int64_t)(b - ntiles) * 256 + threadIdx.x;
     if (k >= (int64_t)v.F * v.C) return;
     const uint32_t u = v.kinfo[k];
     if (u == 0xFFFFFFFFu) return;
     const int slot = (int)(u >> 9);
     v.fm_val[slot] = pc_gather_taps(W, k, pc_taps_word(la, v.fm_pid[slot]), bf16 != 0);
+}
+
+__global__ void __launch_bounds__(256)
+pc_pack_revalue_kernel(const float *__restrict__ W, LibArg la, int bf16, PackView v, int tiles_c, int ntiles)
+{
+    pc_pack_revalue_body(W, la, bf16, v, tiles_c, ntiles, (int)blockIdx.x);
+}
+
+// Value update of several matrix-core packs (ncm holds the tile count of pack l here; the pool's tap lists are
+// those of the pool the packs were made with).
+__global__ void __launch_bounds__(256) pc_pack_revalue_batch_kernel(PackBatchArg b, LibArg la)
+{
+    const int l = pc_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    PackView v = *b.view[l];
+    v.P = la.P;
+    pc_pack_revalue_body(b.W[l], la, b.bf16[l], v, b.tiles_c[l], b.ncm[l], (int)blockIdx.x - b.blk0[l]);
 }
 
 // Places the kept kernels of one row at (kept kernels of the rows before) + (pattern group start) + (rank inside
@@ -926,6 +942,49 @@ pc_status pc_launch_pack_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const f
         if (s != PC_OK) return s;
     }
     return PC_OK;
+}
+
+// Matrix-core packs made with the pool of the first such pack share launches of up to PC_BATCH_MAX; the others
+// (gather-kernel packs, other pools) are updated one by one.
+pc_status pc_launch_update_values_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const float *const *W)
+{
+    PackBatchArg b;
+    memset(&b, 0, sizeof(b));
+    LibArg la;
+    const pc_packed *first = nullptr;
+    auto flush = [&]() -> pc_status {
+        if (b.n == 0) return PC_OK;
+        hipLaunchKernelGGL(pc_pack_revalue_batch_kernel, dim3((unsigned)b.blk0[b.n]), dim3(256), 0, ctx->stream, b, la);
+        b.n = 0;
+        return pc_hip_check(ctx, hipGetLastError(), "update_values (several layers) launch");
+    };
+    for (int l = 0; l < n; ++l) {
+        pc_packed *p = pk[l];
+        bool same = p->variant == PC_VARIANT_MFMA;
+        if (same && !first) {
+            first = p;
+            pc_fill_lib(&la, p->lib, p->v.P);
+        }
+        if (same && (p->v.P != first->v.P || memcmp(p->lib, first->lib, sizeof(uint16_t) * p->v.P) != 0)) same = false;
+        const int64_t nblk = ((int64_t)p->v.F * p->v.C + 255) / 256;
+        if (!same) {
+            pc_status s = pc_launch_update_values(ctx, p, W[l]);
+            if (s != PC_OK) return s;
+            continue;
+        }
+        const int i = b.n;
+        b.W[i] = W[l];
+        b.view[i] = p->v_dev;
+        b.tiles_c[i] = p->v.Cp / 32;
+        b.ncm[i] = (p->v.Fp / 32) * b.tiles_c[i];
+        b.bf16[i] = p->dtype == PC_BF16;
+        b.blk0[i + 1] = b.blk0[i] + b.ncm[i] + (int32_t)nblk;
+        if (++b.n == PC_BATCH_MAX) {
+            pc_status s = flush();
+            if (s != PC_OK) return s;
+        }
+    }
+    return flush();
 }
 
 pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W)

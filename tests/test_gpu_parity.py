@@ -571,6 +571,18 @@ def test_select_and_pack_batch(B, ctx, oracle):
             assert rel_l2(g.fwd(), oracle.conv_fwd(case.x, Wm, 1)) <= tol, L
             dw, guard = g.bwd_weight()
             assert rel_l2(g.scatter(guard.body), oracle.conv_bwd_weight(case.x, case.dy, M, 1)) <= 1e-4, L
+        # new weights, unchanged tables, all handles in one call (the per-iteration conversion of Section 5.1)
+        W2 = [I.gen_weights(c.layer.F, c.layer.C, I.BASE_SEED, ("batch_new", li)) for li, c in enumerate(cases)]
+        W2d = [to_dev(w) for w in W2]
+        B.pc_update_values_batch(ctx, [g.pk for g in gs], W2d)
+        for g, case, w2 in zip(gs, cases, W2):
+            pid, kp, M, _ = oracle_masks(oracle, case, with_grad=False)
+            src = oracle.bf16_round(w2) if case.dtype == "bf16" else w2
+            assert np.array_equal(g.unpack(), oracle.apply_mask(src, M)), case.layer
+            tol = 2e-2 if case.dtype == "bf16" else 1e-4
+            assert rel_l2(g.fwd(), oracle.conv_fwd(case.x, oracle.apply_mask(src, M), 1)) <= tol, case.layer
+            dx_ref = oracle.conv_bwd_data(case.dy, oracle.apply_mask(src, M), case.x.shape, 1)
+            assert rel_l2(g.bwd_data(), dx_ref) <= tol, case.layer
     finally:
         for g in gs:
             g.close()
