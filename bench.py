@@ -451,14 +451,28 @@ def main() -> int:
                                                                  1e-4, 1e-4, d["gdense"], pen), 110),
         }
         n_kern = sum(d["L"].F * d["L"].C for d in layers)
+        Fs, Cs = [d["L"].F for d in layers], [d["L"].C for d in layers]
+        col = lambda key: [d[key] for d in layers]
+        # all layers per call (one launch each; the group-lasso penalty adds a one-workgroup sum)
+        batch_ts = {
+            "dppg_accumulate": lambda: B.pc_dppg_accumulate_batch(ctx, col("W"), col("G"), Fs, Cs, hist, None),
+            "finalize_count": lambda: B.pc_finalize_count_batch(ctx, col("pid"), Fs, Cs, wl.P, col("counts")),
+            "finalize_pick": lambda: B.pc_finalize_pick_batch(ctx, col("counts"), Fs, Cs, wl.P, col("pid")),
+            "group_lasso_grad": lambda: B.pc_group_lasso_grad_batch(ctx, col("W"), col("pid"), col("keep"), Fs, Cs, lib, 1e-4, 1e-4,
+                                                                    col("gdense"), pen),
+        }
         for name, (fn, bytes_per_kernel) in kinds_ts.items():
-            for d in layers:
-                fn(d)
+            def run_kind():
+                if args.no_batch_prep or len(layers) > 32:
+                    for d in layers:
+                        fn(d)
+                else:
+                    batch_ts[name]()
+            run_kind()
             torch.cuda.synchronize()
             gts = torch.cuda.CUDAGraph()
             with torch.cuda.graph(gts, stream=stream):
-                for d in layers:
-                    fn(d)
+                run_kind()
             gts.replay()
             torch.cuda.synchronize()
             e0 = torch.cuda.Event(enable_timing=True)

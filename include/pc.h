@@ -270,6 +270,25 @@ pc_status pc_group_lasso_grad(pc_ctx *ctx, const float *W_dev, const uint8_t *pi
                               int32_t F, int32_t C, const uint16_t *lib_host, int32_t P,
                               float lambda_p, float lambda_i, float *dW_dev, double *penalty_dev);
 
+/* The four calls above for the layers of a network at once (one launch per 32 layers; the same results as the single
+ * calls layer by layer). Arrays named *_host are HOST arrays [n_layers], of device pointers where the single call
+ * takes a device pointer; they are read before the call returns. G_dev_host and masks_dev_host may be NULL, and so
+ * may their entries. hist_dev is the one pool all layers count into. penalty_dev receives the penalty of all layers
+ * together (NULL: not computed; with a penalty at most 32 layers per call, else PC_ERR_UNSUPPORTED). */
+pc_status pc_dppg_accumulate_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W_dev_host,
+                                   const float *const *G_dev_host, const int32_t *F_host, const int32_t *C_host,
+                                   uint32_t *hist_dev, uint16_t *const *masks_dev_host);
+pc_status pc_finalize_count_batch(pc_ctx *ctx, int32_t n_layers, const uint8_t *const *pid_dev_host,
+                                  const int32_t *F_host, const int32_t *C_host, int32_t P,
+                                  uint32_t *const *counts_dev_host);
+pc_status pc_finalize_pick_batch(pc_ctx *ctx, int32_t n_layers, const uint32_t *const *counts_dev_host,
+                                 const int32_t *F_host, const int32_t *C_host, int32_t P,
+                                 uint8_t *const *pid_dev_host);
+pc_status pc_group_lasso_grad_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W_dev_host,
+                                    const uint8_t *const *pid_dev_host, const uint8_t *const *keep_dev_host,
+                                    const int32_t *F_host, const int32_t *C_host, const uint16_t *lib_host, int32_t P,
+                                    float lambda_p, float lambda_i, float *const *dW_dev_host, double *penalty_dev);
+
 /* ---- between two chained layers --------------------------------------------------------- */
 
 /* The step from one layer's output z to the next layer's input a (Section 5.2, "Backward Phase Acceleration":

@@ -27,6 +27,7 @@ EXPORTS = [
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
     "pc_dppg_accumulate", "pc_dppg_pool", "pc_finalize_count", "pc_finalize_pick", "pc_group_lasso_grad",
     "pc_act_pool_fwd", "pc_act_pool_bwd", "pc_pattern_select_batch", "pc_pack_batch", "pc_update_values_batch",
+    "pc_dppg_accumulate_batch", "pc_finalize_count_batch", "pc_finalize_pick_batch", "pc_group_lasso_grad_batch",
 ]
 
 
@@ -84,6 +85,10 @@ def load():
     lib.pc_pattern_select_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, ct.c_int, vp, ct.c_int, vp, vp]
     lib.pc_pack_batch.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.pc_update_values_batch.argtypes = [vp, i32, vp, vp]
+    lib.pc_dppg_accumulate_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.pc_finalize_count_batch.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    lib.pc_finalize_pick_batch.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    lib.pc_group_lasso_grad_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, ct.c_float, ct.c_float, vp, vp]
     lib.pc_act_pool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp, vp]
     lib.pc_act_pool_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp]
     for name in EXPORTS:
@@ -258,3 +263,28 @@ def pc_pack_batch(ctx, W, pid, keep, masks, packs) -> None:
 def pc_update_values_batch(ctx, packs, W) -> None:
     n = len(packs)
     _check(ctx, load().pc_update_values_batch(ctx, n, (ct.c_void_p * n)(*[int(p) for p in packs]), _ptr_array(W)))
+
+
+def _i32_array(vals):
+    return (ct.c_int32 * len(vals))(*[int(v) for v in vals])
+
+
+def pc_dppg_accumulate_batch(ctx, W, G, F, C, hist, masks=None) -> None:
+    _check(ctx, load().pc_dppg_accumulate_batch(ctx, len(W), _ptr_array(W), _ptr_array(G) if G is not None else None,
+                                                _i32_array(F), _i32_array(C), _ptr(hist),
+                                                _ptr_array(masks) if masks is not None else None))
+
+
+def pc_finalize_count_batch(ctx, pid, F, C, P, counts) -> None:
+    _check(ctx, load().pc_finalize_count_batch(ctx, len(pid), _ptr_array(pid), _i32_array(F), _i32_array(C), int(P), _ptr_array(counts)))
+
+
+def pc_finalize_pick_batch(ctx, counts, F, C, P, pid) -> None:
+    _check(ctx, load().pc_finalize_pick_batch(ctx, len(pid), _ptr_array(counts), _i32_array(F), _i32_array(C), int(P), _ptr_array(pid)))
+
+
+def pc_group_lasso_grad_batch(ctx, W, pid, keep, F, C, masks, lambda_p, lambda_i, dW, penalty=None) -> None:
+    arr = _lib_arr(masks)
+    _check(ctx, load().pc_group_lasso_grad_batch(ctx, len(W), _ptr_array(W), _ptr_array(pid), _ptr_array(keep), _i32_array(F),
+                                                 _i32_array(C), ct.cast(arr, ct.c_void_p), len(masks), float(lambda_p),
+                                                 float(lambda_i), _ptr_array(dW), _ptr(penalty)))

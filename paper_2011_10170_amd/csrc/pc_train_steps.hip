@@ -44,17 +44,10 @@ __device__ __forceinline__ unsigned ts_neighbours(int t, bool diagonal)
     return m;
 }
 
-__global__ void __launch_bounds__(TS_BLOCK)
-pc_dppg_kernel(const float *__restrict__ W, const float *__restrict__ G, int64_t nk, uint32_t *__restrict__ hist,
-               uint16_t *__restrict__ masks)
+// One chunk of TS_BLOCK kernels starting at k0: candidate pattern of every kernel, counted in the LDS histogram lh.
+__device__ __forceinline__ void ts_dppg_chunk(const float *__restrict__ W, const float *__restrict__ G, int64_t nk, int64_t k0,
+                                              uint32_t *lh, uint16_t *__restrict__ masks, float *sw, float *sg)
 {
-    // A workgroup walks chunks of TS_BLOCK kernels with the grid as stride and counts in LDS; it adds its counts
-    // to the pool once, at the end (few workgroups: little contention on the pool's 44 live counters).
-    __shared__ float sw[TS_BLOCK * 9], sg[TS_BLOCK * 9];
-    __shared__ uint32_t lh[512];
-    lh[threadIdx.x] = 0u;
-    lh[threadIdx.x + 256] = 0u;
-    for (int64_t k0 = (int64_t)blockIdx.x * TS_BLOCK; k0 < nk; k0 += (int64_t)gridDim.x * TS_BLOCK) {
     const int n = nk - k0 < TS_BLOCK ? (int)(nk - k0) : TS_BLOCK;
     ts_stage(sw, W + k0 * 9, n);
     if (G) ts_stage(sg, G + k0 * 9, n);
@@ -117,9 +110,55 @@ pc_dppg_kernel(const float *__restrict__ W, const float *__restrict__ G, int64_t
         if (masks) masks[k0 + threadIdx.x] = (uint16_t)best_m;
     }
     __syncthreads();                                // the staging buffers are free again; lh is complete after the last chunk
-    }
+}
+
+__global__ void __launch_bounds__(TS_BLOCK)
+pc_dppg_kernel(const float *__restrict__ W, const float *__restrict__ G, int64_t nk, uint32_t *__restrict__ hist,
+               uint16_t *__restrict__ masks)
+{
+    // A workgroup walks chunks of TS_BLOCK kernels with the grid as stride and counts in LDS; it adds its counts
+    // to the pool once, at the end (few workgroups: little contention on the pool's 44 live counters).
+    __shared__ float sw[TS_BLOCK * 9], sg[TS_BLOCK * 9];
+    __shared__ uint32_t lh[512];
+    lh[threadIdx.x] = 0u;
+    lh[threadIdx.x + 256] = 0u;
+    for (int64_t k0 = (int64_t)blockIdx.x * TS_BLOCK; k0 < nk; k0 += (int64_t)gridDim.x * TS_BLOCK)
+        ts_dppg_chunk(W, G, nk, k0, lh, masks, sw, sg);
     for (int i = threadIdx.x; i < 512; i += TS_BLOCK)
         if (lh[i]) atomicAdd(&hist[i], lh[i]);      // integer counts: the order of the additions does not matter
+}
+
+// The layers of a network in one launch: chunk ch belongs to the layer l with blk0[l] <= ch < blk0[l + 1].
+struct TsBatchArg {
+    int32_t n;
+    int32_t blk0[PC_BATCH_MAX + 1];
+    int64_t nk[PC_BATCH_MAX];
+    const float *W[PC_BATCH_MAX], *G[PC_BATCH_MAX];
+    const uint8_t *pid[PC_BATCH_MAX], *keep[PC_BATCH_MAX];
+    void *out[PC_BATCH_MAX];          // masks (pool generation), counts, picked ids or dW, by kernel
+    const uint32_t *counts[PC_BATCH_MAX];
+};
+
+__device__ __forceinline__ int ts_batch_find(const int32_t *first, int n, int b)
+{
+    int l = 0;
+    while (l + 1 < n && b >= first[l + 1]) ++l;
+    return l;
+}
+
+__global__ void __launch_bounds__(TS_BLOCK) pc_dppg_batch_kernel(TsBatchArg b, uint32_t *__restrict__ hist)
+{
+    __shared__ float sw[TS_BLOCK * 9], sg[TS_BLOCK * 9];
+    __shared__ uint32_t lh[512];
+    lh[threadIdx.x] = 0u;
+    lh[threadIdx.x + 256] = 0u;
+    const int total = b.blk0[b.n];
+    for (int ch = (int)blockIdx.x; ch < total; ch += (int)gridDim.x) {
+        const int l = ts_batch_find(b.blk0, b.n, ch);
+        ts_dppg_chunk(b.W[l], b.G[l], b.nk[l], (int64_t)(ch - b.blk0[l]) * TS_BLOCK, lh, static_cast<uint16_t *>(b.out[l]), sw, sg);
+    }
+    for (int i = threadIdx.x; i < 512; i += TS_BLOCK)
+        if (lh[i]) atomicAdd(&hist[i], lh[i]);
 }
 
 extern "C" pc_status pc_dppg_accumulate(pc_ctx *ctx, const float *W, const float *G, int32_t F, int32_t C,
@@ -185,6 +224,30 @@ pc_finalize_pick_kernel(const uint32_t *__restrict__ counts, int64_t nk, int P, 
     pid[k] = (uint8_t)best;
 }
 
+__global__ void __launch_bounds__(256) pc_finalize_count_batch_kernel(TsBatchArg b, int P)
+{
+    const int l = ts_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    const int64_t k = (int64_t)((int)blockIdx.x - b.blk0[l]) * 256 + threadIdx.x;
+    if (k >= b.nk[l]) return;
+    const int p = b.pid[l][k];
+    if (p < P) static_cast<uint32_t *>(b.out[l])[k * P + p] += 1u;
+}
+
+__global__ void __launch_bounds__(256) pc_finalize_pick_batch_kernel(TsBatchArg b, int P)
+{
+    const int l = ts_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    const int64_t k = (int64_t)((int)blockIdx.x - b.blk0[l]) * 256 + threadIdx.x;
+    if (k >= b.nk[l]) return;
+    const uint32_t *counts = b.counts[l];
+    int best = 0;
+    uint32_t bc = counts[k * P];
+    for (int p = 1; p < P; ++p) {
+        const uint32_t c = counts[k * P + p];
+        if (c > bc) { bc = c; best = p; }
+    }
+    static_cast<uint8_t *>(b.out[l])[k] = (uint8_t)best;
+}
+
 static pc_status ts_check_counts(pc_ctx *ctx, const char *who, const void *a, const void *b, int32_t F, int32_t C, int32_t P)
 {
     if (!a || !b) return pc_fail(ctx, PC_ERR_INVALID_ARG, "%s: null pointer", who);
@@ -217,14 +280,15 @@ extern "C" pc_status pc_finalize_pick(pc_ctx *ctx, const uint32_t *counts, int32
 
 // ------------------------------------------------------------------ modified group lasso
 // One thread per kernel; W and dW pass through LDS so that global accesses are contiguous.
-__global__ void __launch_bounds__(TS_BLOCK)
-pc_group_lasso_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep, int64_t nk,
-                      LibArg la, float lambda_p, float lambda_i, float *__restrict__ dW, double *__restrict__ block_pen)
+__device__ __forceinline__ void ts_group_lasso_block(const float *__restrict__ W, const uint8_t *__restrict__ pid,
+                                                     const uint8_t *__restrict__ keep, int64_t nk, const LibArg &la, float lambda_p,
+                                                     float lambda_i, float *__restrict__ dW, double *__restrict__ block_pen,
+                                                     int blk)
 {
     __shared__ float sw[TS_BLOCK * 9], sd[TS_BLOCK * 9];
     __shared__ uint16_t lmask[PC_MAX_P + 2];
     __shared__ double red[TS_BLOCK];
-    const int64_t k0 = (int64_t)blockIdx.x * TS_BLOCK;
+    const int64_t k0 = (int64_t)blk * TS_BLOCK;
     const int n = nk - k0 < TS_BLOCK ? (int)(nk - k0) : TS_BLOCK;
     if (threadIdx.x < la.P) lmask[threadIdx.x] = la.mask[threadIdx.x];
     ts_stage(sw, W + k0 * 9, n);
@@ -268,8 +332,23 @@ pc_group_lasso_kernel(const float *__restrict__ W, const uint8_t *__restrict__ p
             if (threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
             __syncthreads();
         }
-        if (threadIdx.x == 0) block_pen[blockIdx.x] = red[0];
+        if (threadIdx.x == 0) block_pen[blockIdx.x] = red[0];    // one slot per workgroup of the launch
     }
+}
+
+__global__ void __launch_bounds__(TS_BLOCK)
+pc_group_lasso_kernel(const float *__restrict__ W, const uint8_t *__restrict__ pid, const uint8_t *__restrict__ keep, int64_t nk,
+                      LibArg la, float lambda_p, float lambda_i, float *__restrict__ dW, double *__restrict__ block_pen)
+{
+    ts_group_lasso_block(W, pid, keep, nk, la, lambda_p, lambda_i, dW, block_pen, (int)blockIdx.x);
+}
+
+__global__ void __launch_bounds__(TS_BLOCK)
+pc_group_lasso_batch_kernel(TsBatchArg b, LibArg la, float lambda_p, float lambda_i, double *__restrict__ block_pen)
+{
+    const int l = ts_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    ts_group_lasso_block(b.W[l], b.pid[l], b.keep[l], b.nk[l], la, lambda_p, lambda_i, static_cast<float *>(b.out[l]), block_pen,
+                         (int)blockIdx.x - b.blk0[l]);
 }
 
 // penalty = the workgroup sums added in a fixed order by one workgroup
@@ -314,4 +393,133 @@ extern "C" pc_status pc_group_lasso_grad(pc_ctx *ctx, const float *W, const uint
     if (penalty)
         hipLaunchKernelGGL(pc_group_lasso_sum_kernel, dim3(1), dim3(256), 0, ctx->stream, block_pen, (int)nb, penalty);
     return pc_hip_check(ctx, hipGetLastError(), "group lasso launch");
+}
+
+// ------------------------------------------------------------------ the same steps for the layers of a network at once
+// Fills the table for layers [l0, l0 + m); false with a message when a layer is malformed.
+static pc_status ts_fill_batch(pc_ctx *ctx, const char *who, TsBatchArg *b, int l0, int m, const int32_t *F, const int32_t *C)
+{
+    memset(b, 0, sizeof(*b));
+    b->n = m;
+    for (int i = 0; i < m; ++i) {
+        const int l = l0 + i;
+        if (F[l] < 1 || C[l] < 1 || F[l] > 65535 || C[l] > 65535)
+            return pc_fail(ctx, PC_ERR_BAD_SHAPE, "%s: layer %d: F=%d C=%d out of range", who, l, F[l], C[l]);
+        b->nk[i] = (int64_t)F[l] * C[l];
+        b->blk0[i + 1] = b->blk0[i] + (int32_t)((b->nk[i] + TS_BLOCK - 1) / TS_BLOCK);
+    }
+    return PC_OK;
+}
+
+extern "C" pc_status pc_dppg_accumulate_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W, const float *const *G,
+                                              const int32_t *F, const int32_t *C, uint32_t *hist, uint16_t *const *masks)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (n_layers < 0) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_dppg_accumulate_batch: n_layers %d", n_layers);
+    if (n_layers == 0) return PC_OK;
+    if (!W || !F || !C || !hist) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_dppg_accumulate_batch: null pointer");
+    for (int l = 0; l < n_layers; ++l)
+        if (!W[l]) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_dppg_accumulate_batch: null pointer in layer %d", l);
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    for (int l0 = 0; l0 < n_layers; l0 += PC_BATCH_MAX) {
+        const int m = n_layers - l0 < PC_BATCH_MAX ? n_layers - l0 : PC_BATCH_MAX;
+        TsBatchArg b;
+        pc_status s = ts_fill_batch(ctx, "pc_dppg_accumulate_batch", &b, l0, m, F, C);
+        if (s != PC_OK) return s;
+        for (int i = 0; i < m; ++i) {
+            b.W[i] = W[l0 + i];
+            b.G[i] = G ? G[l0 + i] : nullptr;
+            b.out[i] = masks ? masks[l0 + i] : nullptr;
+        }
+        int nb = b.blk0[m];
+        if (nb > 2 * ctx->num_cu) nb = 2 * ctx->num_cu;
+        hipLaunchKernelGGL(pc_dppg_batch_kernel, dim3((unsigned)nb), dim3(TS_BLOCK), 0, ctx->stream, b, hist);
+    }
+    return pc_hip_check(ctx, hipGetLastError(), "pool generation (several layers) launch");
+}
+
+extern "C" pc_status pc_finalize_count_batch(pc_ctx *ctx, int32_t n_layers, const uint8_t *const *pid, const int32_t *F,
+                                             const int32_t *C, int32_t P, uint32_t *const *counts)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (n_layers < 0) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_finalize_count_batch: n_layers %d", n_layers);
+    if (n_layers == 0) return PC_OK;
+    if (!pid || !F || !C || !counts) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_finalize_count_batch: null pointer");
+    if (P < 1 || P > PC_MAX_P) return pc_fail(ctx, PC_ERR_BAD_LIBRARY, "pc_finalize_count_batch: P=%d outside 1..%d", P, PC_MAX_P);
+    for (int l = 0; l < n_layers; ++l)
+        if (!pid[l] || !counts[l]) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_finalize_count_batch: null pointer in layer %d", l);
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    for (int l0 = 0; l0 < n_layers; l0 += PC_BATCH_MAX) {
+        const int m = n_layers - l0 < PC_BATCH_MAX ? n_layers - l0 : PC_BATCH_MAX;
+        TsBatchArg b;
+        pc_status s = ts_fill_batch(ctx, "pc_finalize_count_batch", &b, l0, m, F, C);
+        if (s != PC_OK) return s;
+        for (int i = 0; i < m; ++i) { b.pid[i] = pid[l0 + i]; b.out[i] = counts[l0 + i]; }
+        hipLaunchKernelGGL(pc_finalize_count_batch_kernel, dim3((unsigned)b.blk0[m]), dim3(256), 0, ctx->stream, b, P);
+    }
+    return pc_hip_check(ctx, hipGetLastError(), "finalisation count (several layers) launch");
+}
+
+extern "C" pc_status pc_finalize_pick_batch(pc_ctx *ctx, int32_t n_layers, const uint32_t *const *counts, const int32_t *F,
+                                            const int32_t *C, int32_t P, uint8_t *const *pid)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (n_layers < 0) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_finalize_pick_batch: n_layers %d", n_layers);
+    if (n_layers == 0) return PC_OK;
+    if (!pid || !F || !C || !counts) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_finalize_pick_batch: null pointer");
+    if (P < 1 || P > PC_MAX_P) return pc_fail(ctx, PC_ERR_BAD_LIBRARY, "pc_finalize_pick_batch: P=%d outside 1..%d", P, PC_MAX_P);
+    for (int l = 0; l < n_layers; ++l)
+        if (!pid[l] || !counts[l]) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_finalize_pick_batch: null pointer in layer %d", l);
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    for (int l0 = 0; l0 < n_layers; l0 += PC_BATCH_MAX) {
+        const int m = n_layers - l0 < PC_BATCH_MAX ? n_layers - l0 : PC_BATCH_MAX;
+        TsBatchArg b;
+        pc_status s = ts_fill_batch(ctx, "pc_finalize_pick_batch", &b, l0, m, F, C);
+        if (s != PC_OK) return s;
+        for (int i = 0; i < m; ++i) { b.counts[i] = counts[l0 + i]; b.out[i] = pid[l0 + i]; }
+        hipLaunchKernelGGL(pc_finalize_pick_batch_kernel, dim3((unsigned)b.blk0[m]), dim3(256), 0, ctx->stream, b, P);
+    }
+    return pc_hip_check(ctx, hipGetLastError(), "finalisation pick (several layers) launch");
+}
+
+extern "C" pc_status pc_group_lasso_grad_batch(pc_ctx *ctx, int32_t n_layers, const float *const *W, const uint8_t *const *pid,
+                                               const uint8_t *const *keep, const int32_t *F, const int32_t *C, const uint16_t *lib,
+                                               int32_t P, float lambda_p, float lambda_i, float *const *dW, double *penalty)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (n_layers < 0) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_group_lasso_grad_batch: n_layers %d", n_layers);
+    if (n_layers == 0) return PC_OK;
+    if (!W || !pid || !keep || !F || !C || !lib || !dW) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_group_lasso_grad_batch: null pointer");
+    if (n_layers > PC_BATCH_MAX && penalty)
+        return pc_fail(ctx, PC_ERR_UNSUPPORTED, "pc_group_lasso_grad_batch: the penalty of more than %d layers takes several calls", PC_BATCH_MAX);
+    for (int l = 0; l < n_layers; ++l)
+        if (!W[l] || !pid[l] || !keep[l] || !dW[l])
+            return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_group_lasso_grad_batch: null pointer in layer %d", l);
+    pc_status s = pc_check_library(lib, P);
+    if (s != PC_OK) return pc_fail(ctx, s, "pc_group_lasso_grad_batch: bad library (P=%d)", P);
+    PC_HIP(ctx, hipSetDevice(ctx->device));
+    LibArg la;
+    pc_fill_lib(&la, lib, P);
+    for (int l0 = 0; l0 < n_layers; l0 += PC_BATCH_MAX) {
+        const int m = n_layers - l0 < PC_BATCH_MAX ? n_layers - l0 : PC_BATCH_MAX;
+        TsBatchArg b;
+        s = ts_fill_batch(ctx, "pc_group_lasso_grad_batch", &b, l0, m, F, C);
+        if (s != PC_OK) return s;
+        for (int i = 0; i < m; ++i) {
+            b.W[i] = W[l0 + i]; b.pid[i] = pid[l0 + i]; b.keep[i] = keep[l0 + i]; b.out[i] = dW[l0 + i];
+        }
+        const int nb = b.blk0[m];
+        double *block_pen = nullptr;
+        if (penalty) {
+            void *scr = nullptr;
+            s = pc_scratch(ctx, sizeof(double) * (size_t)nb, &scr);
+            if (s != PC_OK) return s;
+            block_pen = (double *)scr;
+        }
+        hipLaunchKernelGGL(pc_group_lasso_batch_kernel, dim3((unsigned)nb), dim3(TS_BLOCK), 0, ctx->stream, b, la, lambda_p, lambda_i,
+                           block_pen);
+        if (penalty)
+            hipLaunchKernelGGL(pc_group_lasso_sum_kernel, dim3(1), dim3(256), 0, ctx->stream, block_pen, nb, penalty);
+    }
+    return pc_hip_check(ctx, hipGetLastError(), "group lasso (several layers) launch");
 }

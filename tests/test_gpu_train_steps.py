@@ -182,6 +182,75 @@ def test_group_lasso_zero_groups(B, ctx, T):
     assert rel_l2(got, T.group_lasso_grad(Wn, pid, keep, lib, 0.5, 0.25)) <= 1e-6
 
 
+def test_batch_calls_equal_the_oracle_layer_by_layer(B, ctx, T):
+    """The training-side steps over 35 layers of mixed sizes in one call each (more than one launch takes): masks,
+    pool counts, finalisation counts and picks bit-exact, the group-lasso gradient and its total penalty within the
+    single call's tolerance."""
+    import torch
+    rng = np.random.default_rng(51)
+    P = 8
+    lib = I.make_library(P)
+    shapes = [(int(rng.integers(1, 50)), int(rng.integers(1, 90))) for _ in range(33)] + [(130, 257), (64, 64)]
+    Ws = [I.gen_weights(F, C, I.BASE_SEED, ("tsb", i)) for i, (F, C) in enumerate(shapes)]
+    Gs = [I.gen_weight_grads(F, C, I.BASE_SEED, ("tsb", i)) for i, (F, C) in enumerate(shapes)]
+    Fs, Cs = [f for f, _ in shapes], [c for _, c in shapes]
+    Wd, Gd = [to_dev(w) for w in Ws], [to_dev(g) for g in Gs]
+    Gd[3] = None
+    # pool generation
+    hist = torch.zeros(512, dtype=torch.int32, device="cuda")
+    masks = [torch.full((F, C), -1, dtype=torch.int16, device="cuda") for F, C in shapes]
+    B.pc_dppg_accumulate_batch(ctx, Wd, Gd, Fs, Cs, hist, masks)
+    torch.cuda.synchronize()
+    ref_hist = np.zeros(512, dtype=np.uint32)
+    for i, (w, g) in enumerate(zip(Ws, Gs)):
+        gg = None if i == 3 else g
+        assert np.array_equal(masks[i].cpu().numpy().view(np.uint16), T.dppg_candidate_masks(w, gg)), i
+        ref_hist = T.dppg_accumulate(ref_hist, w, gg)
+    assert np.array_equal(hist.cpu().numpy().view(np.uint32), ref_hist)
+    hist2 = torch.zeros(512, dtype=torch.int32, device="cuda")
+    B.pc_dppg_accumulate_batch(ctx, Wd, Gd, Fs, Cs, hist2, None)
+    torch.cuda.synchronize()
+    assert torch.equal(hist2, hist)
+    # finalisation counters over three batches, then the pick
+    counts = [torch.zeros((F, C, P), dtype=torch.int32, device="cuda") for F, C in shapes]
+    ref_counts = [np.zeros((F, C, P), dtype=np.uint32) for F, C in shapes]
+    for batch in range(3):
+        pids = [rng.integers(0, min(P, 3 + batch), size=(F, C)).astype(np.uint8) for F, C in shapes]
+        B.pc_finalize_count_batch(ctx, [to_dev(p) for p in pids], Fs, Cs, P, counts)
+        ref_counts = [T.finalize_count(r, p) for r, p in zip(ref_counts, pids)]
+    picks = [torch.full((F, C), 255, dtype=torch.uint8, device="cuda") for F, C in shapes]
+    B.pc_finalize_pick_batch(ctx, counts, Fs, Cs, P, picks)
+    torch.cuda.synchronize()
+    for i in range(len(shapes)):
+        assert np.array_equal(counts[i].cpu().numpy().view(np.uint32), ref_counts[i]), i
+        assert np.array_equal(picks[i].cpu().numpy(), T.finalize_pick(ref_counts[i])), i
+    # group lasso: 32 layers with the penalty, all 35 without
+    pid_h = [rng.integers(0, P, size=(F, C)).astype(np.uint8) for F, C in shapes]
+    keep_h = [(rng.random((F, C)) < 0.4).astype(np.uint8) for F, C in shapes]
+    dW0 = [rng.standard_normal((F, C, 9)).astype(np.float32) for F, C in shapes]
+    lp, li = 0.37, 1.6
+    pd, kd = [to_dev(p) for p in pid_h], [to_dev(k) for k in keep_h]
+    dW = [to_dev(d.copy()) for d in dW0]
+    pen = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+    sel = list(range(3, 35))
+    pick = lambda xs: [xs[i] for i in sel]
+    B.pc_group_lasso_grad_batch(ctx, pick(Wd), pick(pd), pick(kd), pick(Fs), pick(Cs), lib, lp, li, pick(dW), pen)
+    torch.cuda.synchronize()
+    ref_pen = 0.0
+    for i in sel:
+        ref = dW0[i].astype(np.float64) + T.group_lasso_grad(Ws[i], pid_h[i], keep_h[i], lib, lp, li)
+        assert rel_l2(dW[i].cpu().numpy(), ref) <= 1e-6, i
+        ref_pen += T.group_lasso_penalty(Ws[i], pid_h[i], keep_h[i], lib, np.float32(lp), np.float32(li))
+    assert abs(float(pen.item()) - ref_pen) <= 1e-6 * abs(ref_pen)
+    dW2 = [to_dev(d.copy()) for d in dW0]
+    B.pc_group_lasso_grad_batch(ctx, Wd, pd, kd, Fs, Cs, lib, lp, li, dW2, None)
+    torch.cuda.synchronize()
+    for i in sel:
+        assert torch.equal(dW2[i], dW[i]), i
+    with pytest.raises(B.PcError):
+        B.pc_group_lasso_grad_batch(ctx, Wd, pd, kd, Fs, Cs, lib, lp, li, dW2, pen)     # 35 layers with a penalty
+
+
 def test_argument_checks(B, ctx):
     import torch
     t = torch.zeros(512, dtype=torch.int32, device="cuda")
