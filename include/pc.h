@@ -225,6 +225,18 @@ pc_status pc_conv_bwd_data(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packe
 pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
                              const void *x_dev, const void *dy_dev, float *dw_compact_dev);
 
+/* pc_conv_bwd_weight for several layers at once. The weight gradients of a network's layers do not depend on each
+ * other (dE/dW of a layer needs only its own a_prev and delta, Section 5.2), so once every x and dy exists they can
+ * all be computed together: the matrix-core layers in one launch per 20 layers plus one reduction launch, each
+ * layer with the tiles, splits and order of additions of its own call (bit-identical results); layers on the
+ * gather kernels one by one. Every layer's partial sums have their own region of the context's scratch buffer.
+ *   descs_host : HOST array [n_layers] of descriptors; packs_host : HOST array [n_layers] of handles
+ *   x_dev_host, dy_dev_host, dw_compact_dev_host : HOST arrays [n_layers] of device pointers as in
+ *       pc_conv_bwd_weight (the dw buffers all distinct) */
+pc_status pc_conv_bwd_weight_batch(pc_ctx *ctx, int32_t n_layers, const pc_conv_desc *descs_host,
+                                   const pc_packed *const *packs_host, const void *const *x_dev_host,
+                                   const void *const *dy_dev_host, float *const *dw_compact_dev_host);
+
 /* ---- training-side steps around the path: pattern pool generation (Section 4.2), adaptive
  *      finalisation (Section 4.3), modified group lasso (Section 4.4, Eq. 3 and Eq. 4) ---------- */
 

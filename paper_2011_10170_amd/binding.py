@@ -27,7 +27,7 @@ EXPORTS = [
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
     "pc_dppg_accumulate", "pc_dppg_pool", "pc_finalize_count", "pc_finalize_pick", "pc_group_lasso_grad",
     "pc_act_pool_fwd", "pc_act_pool_bwd", "pc_pattern_select_batch", "pc_pack_batch", "pc_update_values_batch",
-    "pc_dppg_accumulate_batch", "pc_finalize_count_batch", "pc_finalize_pick_batch", "pc_group_lasso_grad_batch",
+    "pc_dppg_accumulate_batch", "pc_finalize_count_batch", "pc_finalize_pick_batch", "pc_group_lasso_grad_batch", "pc_conv_bwd_weight_batch",
 ]
 
 
@@ -85,6 +85,7 @@ def load():
     lib.pc_pattern_select_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, ct.c_int, vp, ct.c_int, vp, vp]
     lib.pc_pack_batch.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.pc_update_values_batch.argtypes = [vp, i32, vp, vp]
+    lib.pc_conv_bwd_weight_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.pc_dppg_accumulate_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.pc_finalize_count_batch.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     lib.pc_finalize_pick_batch.argtypes = [vp, i32, vp, vp, vp, i32, vp]
@@ -288,3 +289,11 @@ def pc_group_lasso_grad_batch(ctx, W, pid, keep, F, C, masks, lambda_p, lambda_i
     _check(ctx, load().pc_group_lasso_grad_batch(ctx, len(W), _ptr_array(W), _ptr_array(pid), _ptr_array(keep), _i32_array(F),
                                                  _i32_array(C), ct.cast(arr, ct.c_void_p), len(masks), float(lambda_p),
                                                  float(lambda_i), _ptr_array(dW), _ptr(penalty)))
+
+
+def pc_conv_bwd_weight_batch(ctx, descs, packs, x, dy, dw) -> None:
+    """descs: list of pc_conv_desc; packs: list of handles; x, dy, dw: lists of device tensors."""
+    n = len(descs)
+    darr = (pc_conv_desc * n)(*descs)
+    _check(ctx, load().pc_conv_bwd_weight_batch(ctx, n, ct.cast(darr, ct.c_void_p), (ct.c_void_p * n)(*[int(p) for p in packs]),
+                                                _ptr_array(x), _ptr_array(dy), _ptr_array(dw)))

@@ -6,6 +6,8 @@
 
 #include "pc_internal.h"
 
+#include <vector>
+
 // ------------------------------------------------------------------ errors
 pc_status pc_fail(pc_ctx *ctx, pc_status s, const char *fmt, ...)
 {
@@ -495,4 +497,35 @@ extern "C" pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, cons
     if (s != PC_OK) return s;
     return pk->variant == PC_VARIANT_MFMA ? pc_mfma_bwd_weight(ctx, d, pk, x, dy, dw)
                                           : pc_valu_bwd_weight(ctx, d, pk, x, dy, dw);
+}
+
+extern "C" pc_status pc_conv_bwd_weight_batch(pc_ctx *ctx, int32_t n_layers, const pc_conv_desc *descs, const pc_packed *const *packs,
+                                              const void *const *x, const void *const *dy, float *const *dw)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    if (n_layers < 0) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_conv_bwd_weight_batch: n_layers %d", n_layers);
+    if (n_layers == 0) return PC_OK;
+    if (!descs || !packs || !x || !dy || !dw) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_conv_bwd_weight_batch: null pointer");
+    std::vector<pc_conv_desc> md;
+    std::vector<const pc_packed *> mp;
+    std::vector<const void *> mx, mdy;
+    std::vector<float *> mdw;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!packs[l]) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_conv_bwd_weight_batch: null handle in layer %d", l);
+        pc_status s = check_conv(ctx, "pc_conv_bwd_weight_batch", &descs[l], packs[l], x[l], dy[l], dw[l]);
+        if (s != PC_OK) return s;
+        for (int m = 0; m < l; ++m)
+            if (dw[m] == dw[l]) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_conv_bwd_weight_batch: layers %d and %d share dw", m, l);
+    }
+    // the gather kernels one layer at a time, then the matrix-core layers together
+    for (int l = 0; l < n_layers; ++l) {
+        if (packs[l]->variant == PC_VARIANT_MFMA) {
+            md.push_back(descs[l]); mp.push_back(packs[l]); mx.push_back(x[l]); mdy.push_back(dy[l]); mdw.push_back(dw[l]);
+        } else {
+            pc_status s = pc_valu_bwd_weight(ctx, &descs[l], packs[l], x[l], dy[l], dw[l]);
+            if (s != PC_OK) return s;
+        }
+    }
+    if (md.empty()) return PC_OK;
+    return pc_mfma_bwd_weight_group(ctx, (int)md.size(), md.data(), mp.data(), mx.data(), mdy.data(), mdw.data());
 }

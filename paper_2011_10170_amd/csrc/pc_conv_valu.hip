@@ -349,15 +349,14 @@ pc_wgrad_valu_kernel(const T *__restrict__ x, const T *__restrict__ dy, WgradArg
 // partial (ascending), then one thread adds the TPS sub-sums in order. 256 / TPS consecutive slots per workgroup.
 // partial is [G][pstride] float4; the number of live slots is read on the device.
 template <int TPS>
-__global__ void __launch_bounds__(256)
-pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, int64_t pstride, int64_t nslots_exact, PackView v,
-                       float4 *__restrict__ dw)
+__device__ __forceinline__ void pc_wgrad_reduce_body(const float4 *__restrict__ partial, int G, int64_t pstride, int64_t nslots_exact,
+                                                     const int32_t *__restrict__ nnzk_dev, float4 *__restrict__ dw, int blk)
 {
     constexpr int SPB = 256 / TPS;
     __shared__ float4 sub[TPS > 1 ? TPS : 1][TPS > 1 ? SPB : 1];
-    const int nnzk = v.fm_rowptr[v.F];
+    const int nnzk = *nnzk_dev;
     const int q = threadIdx.x % SPB, sg = threadIdx.x / SPB;
-    const int64_t slot = (int64_t)blockIdx.x * SPB + q;
+    const int64_t slot = (int64_t)blk * SPB + q;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     // A plane holds pstride slots. When that is the exact count the loads need not wait for the count read from
     // the device; when it is the pack's capacity they do, or they would fetch the unused part of every plane.
@@ -390,6 +389,61 @@ pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, int64_t pstrid
         }
         dw[slot] = t;
     }
+}
+
+template <int TPS>
+__global__ void __launch_bounds__(256)
+pc_wgrad_reduce_kernel(const float4 *__restrict__ partial, int G, int64_t pstride, int64_t nslots_exact, PackView v,
+                       float4 *__restrict__ dw)
+{
+    pc_wgrad_reduce_body<TPS>(partial, G, pstride, nslots_exact, v.fm_rowptr + v.F, dw, (int)blockIdx.x);
+}
+
+// The reductions of several layers in one launch: workgroup b serves workgroup b - blk0[l] of layer l, with that
+// layer's number of threads per slot.
+struct WgradReduceGroup {
+    int32_t n;
+    int32_t blk0[PC_REDUCE_GROUP_MAX + 1];
+    WgradReduceItem item[PC_REDUCE_GROUP_MAX];
+};
+
+__global__ void __launch_bounds__(256) pc_wgrad_reduce_group_kernel(WgradReduceGroup g)
+{
+    int l = 0;
+    while (l + 1 < g.n && (int)blockIdx.x >= g.blk0[l + 1]) ++l;
+    const WgradReduceItem &y = g.item[l];
+    const int blk = (int)blockIdx.x - g.blk0[l];
+    const float4 *pp = reinterpret_cast<const float4 *>(y.partial);
+    float4 *out = reinterpret_cast<float4 *>(y.dw);
+    if (y.tps == 64) pc_wgrad_reduce_body<64>(pp, y.G, y.pstride, y.exact, y.nnzk_dev, out, blk);
+    else if (y.tps == 16) pc_wgrad_reduce_body<16>(pp, y.G, y.pstride, y.exact, y.nnzk_dev, out, blk);
+    else if (y.tps == 4) pc_wgrad_reduce_body<4>(pp, y.G, y.pstride, y.exact, y.nnzk_dev, out, blk);
+    else pc_wgrad_reduce_body<1>(pp, y.G, y.pstride, y.exact, y.nnzk_dev, out, blk);
+}
+
+// items: partial planes, split count G, plane stride, upper bound of the live slots (nslots) per layer; tps and exact
+// are filled here. One launch per PC_REDUCE_GROUP_MAX layers.
+pc_status pc_launch_wgrad_reduce_group(pc_ctx *ctx, int n, WgradReduceItem *items, const int64_t *nslots, const pc_packed *const *pk)
+{
+    for (int l0 = 0; l0 < n; l0 += PC_REDUCE_GROUP_MAX) {
+        const int m = n - l0 < PC_REDUCE_GROUP_MAX ? n - l0 : PC_REDUCE_GROUP_MAX;
+        WgradReduceGroup g;
+        memset(&g, 0, sizeof(g));
+        g.n = m;
+        for (int i = 0; i < m; ++i) {
+            WgradReduceItem y = items[l0 + i];
+            const pc_packed *p = pk[l0 + i];
+            y.exact = p->nnzk >= 0 ? p->nnzk : -1;
+            y.nnzk_dev = p->v.fm_rowptr + p->v.F;
+            y.tps = y.G >= 128 ? 64 : y.G >= 32 ? 16 : y.G >= 8 ? 4 : 1;      // as in the launch of one layer
+            const int spb = 256 / y.tps;
+            g.item[i] = y;
+            g.blk0[i + 1] = g.blk0[i] + (int32_t)((nslots[l0 + i] + spb - 1) / spb);
+        }
+        if (g.blk0[m] > 0)
+            hipLaunchKernelGGL(pc_wgrad_reduce_group_kernel, dim3((unsigned)g.blk0[m]), dim3(256), 0, ctx->stream, g);
+    }
+    return pc_hip_check(ctx, hipGetLastError(), "bwd_weight reduce (several layers) launch");
 }
 
 // nslots bounds the live slots from above (the exact count when the host knows it, else the pack's capacity)

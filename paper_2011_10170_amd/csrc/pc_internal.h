@@ -99,6 +99,16 @@ pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8
 pc_status pc_launch_select_batch(pc_ctx *ctx, int n, const float *const *W, const float *const *G, const int32_t *F,
                                  const int32_t *C, const LibArg &la, pc_keep_mode km, const int64_t *n_keep, pc_score_mode sm,
                                  uint8_t *const *pid, uint8_t *const *keep);
+// One layer of a grouped split reduction (partial planes of G splits -> dw in compact order).
+#define PC_REDUCE_GROUP_MAX 20
+struct WgradReduceItem {
+    const float *partial;
+    float *dw;
+    const int32_t *nnzk_dev;     // the pack's kept-kernel count on the device
+    int64_t pstride, exact;      // plane stride in slots; the count when the host knows it, else -1
+    int32_t G, tps;
+};
+pc_status pc_launch_wgrad_reduce_group(pc_ctx *ctx, int n, WgradReduceItem *items, const int64_t *nslots, const pc_packed *const *pk);
 pc_status pc_launch_update_values_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const float *const *W);
 pc_status pc_launch_pack_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const float *const *W, const uint8_t *const *pid,
                                const uint8_t *const *keep, const LibArg &la);
@@ -116,6 +126,8 @@ pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, int64
 bool pc_mfma_supports(int F, int C);
 pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y);
 pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx);
+pc_status pc_mfma_bwd_weight_group(pc_ctx *ctx, int n, const pc_conv_desc *d, const pc_packed *const *pk, const void *const *x,
+                                   const void *const *dy, float *const *dw);
 pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,
                              const void *dy, float *dw);
 

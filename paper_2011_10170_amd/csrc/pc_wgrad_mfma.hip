@@ -294,14 +294,37 @@ struct WgradWsArgs {
     int32_t buf_bytes;                     // one LDS buffer: dyT planes, then xT planes
     uint32_t x_bytes, dy_bytes;            // tensor sizes (bounds of the buffer loads)
     uint32_t mg_tc, mg_tr;                 // multiply-high constants of the divisions by tiles_c and tiles_r
-    int16_t xb_tab[WS_NSLOT];              // x slot read by dy slot s for tap (0,0)
-    uint32_t dy_tab[WS_NSLOT];             // dy slot -> (image group << 16) | (row << 8) | column; 0xFFFFFFFF = unused
-    uint32_t x_tab[WS_XSLOTS];             // x slot  -> (image group << 16) | (row << 8) | column inside the x region
+    uint32_t mg_npos, mg_TC, mg_xs, mg_IC; // and by npos, TC, xs_per_g, IC (slot tables below)
 };
 
-__global__ void __launch_bounds__(512, 1)
-pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradWsArgs a, PackView v,
-                        float *__restrict__ partial, float *__restrict__ dw)
+// dy slot -> (image group << 16) | (row << 8) | column of the pixel tile; 0xFFFFFFFF = unused
+__device__ __forceinline__ uint32_t ws_dy_tab(const WgradWsArgs &a, int sl)
+{
+    const int ig = (int)pc_udiv((uint32_t)sl, a.mg_npos), pos = sl - ig * a.npos;
+    const int py = (int)pc_udiv((uint32_t)pos, a.mg_TC), px = pos - py * a.TC;
+    return ig < a.ng ? ((uint32_t)ig << 16) | ((uint32_t)py << 8) | (uint32_t)px : 0xFFFFFFFFu;
+}
+
+// x slot read by dy slot sl for tap (0,0)
+__device__ __forceinline__ int ws_xb_tab(const WgradWsArgs &a, int sl)
+{
+    const int ig = (int)pc_udiv((uint32_t)sl, a.mg_npos), pos = sl - ig * a.npos;
+    const int py = (int)pc_udiv((uint32_t)pos, a.mg_TC), px = pos - py * a.TC;
+    return ig < a.ng ? ig * a.xs_per_g + py * a.stride * a.IC + px * a.stride : 0;
+}
+
+// x slot -> (image group << 16) | (row << 8) | column inside the x region; 0xFFFFFFFF = unused
+__device__ __forceinline__ uint32_t ws_x_tab(const WgradWsArgs &a, int xs)
+{
+    const int ig = (int)pc_udiv((uint32_t)xs, a.mg_xs), rem = xs - ig * a.xs_per_g;
+    const int r = (int)pc_udiv((uint32_t)rem, a.mg_IC), q = rem - r * a.IC;
+    return ig < a.ng ? ((uint32_t)ig << 16) | ((uint32_t)r << 8) | (uint32_t)q : 0xFFFFFFFFu;
+}
+
+// lin: index of the workgroup in the layer's grid of gx x gy tiles x ksplit splits (x fastest).
+__device__ __forceinline__ void pc_mfma_wgrad_ws_body(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy,
+                                                      const WgradWsArgs &a, const uint32_t *__restrict__ kinfo,
+                                                      float *__restrict__ partial, float *__restrict__ dw, int lin, int gx, int gy)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int XT_OFF = WG_T * WS_DY_PLANE + 128;   // xT planes inside a buffer
@@ -310,10 +333,9 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     // Workgroups go to the XCDs round-robin by their linear index. The index is re-read so that the workgroups of
     // one XCD share as few pixel splits as possible: each XCD's L2 then fetches its own slice of x and dy once,
     // instead of every XCD fetching all of both.
-    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    int bx = lin % gx, by = (lin / gx) % gy, bz = lin / (gx * gy);
     {
-        const int T = gridDim.x * gridDim.y, ks = a.ksplit;
-        const int lin = bx + gridDim.x * (by + gridDim.y * bz);
+        const int T = gx * gy, ks = a.ksplit;
         const int xcd = lin & 7, r = lin >> 3;
         int tile = -1;
         if ((ks & 7) == 0) {                           // an XCD owns ks/8 splits, all tiles of each
@@ -323,7 +345,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             bz = xcd % ks;
             tile = r * (8 / ks) + xcd / ks;
         }
-        if (tile >= 0) { bx = tile % (int)gridDim.x; by = tile / (int)gridDim.x; }
+        if (tile >= 0) { bx = tile % gx; by = tile / gx; }
     }
     const int c0 = bx * WG_T, f0 = by * WG_T;
     const int nt = (a.n_ktiles - bz + a.ksplit - 1) / a.ksplit;   // pixel tiles of this workgroup
@@ -338,7 +360,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             for (int k = 0; k < 4; ++k) {
                 const int p = threadIdx.x + 512 * k;
                 const int f = f0 + fh * 32 + (p >> 6), c = c0 + (p & 63);
-                kinf[fh][k] = (f < a.F && c < a.Creal) ? v.kinfo[(int64_t)f * a.Creal + c] : 0xFFFFFFFFu;
+                kinf[fh][k] = (f < a.F && c < a.Creal) ? kinfo[(int64_t)f * a.Creal + c] : 0xFFFFFFFFu;
             }
     };
     float *pout = a.ksplit > 1 ? partial + (int64_t)bz * a.pstride * 4 : dw;
@@ -377,8 +399,8 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
         // task 0: slot tl>>3 (dy) or (tl-128)>>3 (x slots 0..15); task 1: x slot 16 + tl>>3 (x slots 16..47)
         const int slot0 = dy0 ? tl >> 3 : (tl - 128) >> 3;
         const int slot1 = 16 + (tl >> 3);
-        const uint32_t tab0 = dy0 ? a.dy_tab[slot0] : (slot0 < a.xslots ? a.x_tab[slot0] : 0xFFFFFFFFu);
-        const uint32_t tab1 = slot1 < a.xslots ? a.x_tab[slot1] : 0xFFFFFFFFu;
+        const uint32_t tab0 = dy0 ? ws_dy_tab(a, slot0) : (slot0 < a.xslots ? ws_x_tab(a, slot0) : 0xFFFFFFFFu);
+        const uint32_t tab1 = slot1 < a.xslots ? ws_x_tab(a, slot1) : 0xFFFFFFFFu;
         const int ig0 = (int)(tab0 >> 16) & 255, r0 = (int)(tab0 >> 8) & 255, q0 = (int)tab0 & 255;
         const int ig1 = (int)(tab1 >> 16) & 255, r1 = (int)(tab1 >> 8) & 255, q1 = (int)tab1 & 255;
         const bool chan0 = dy0 ? f0 + cg * 8 < a.F : c0 + cg * 8 < a.C;
@@ -472,7 +494,7 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
         int xb[WS_NKS];
 #pragma unroll
-        for (int kk = 0; kk < WS_NKS; ++kk) xb[kk] = a.xb_tab[2 * kk + g];
+        for (int kk = 0; kk < WS_NKS; ++kk) xb[kk] = ws_xb_tab(a, 2 * kk + g);
         int toff[5];
 #pragma unroll
         for (int b = 0; b < 5; ++b) {
@@ -540,15 +562,49 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
         gather(0);
         gather(1);
     }
-
 }
 
-// Wave-specialised backward-weight: plan and launch. *launched stays false when the layer is outside what
-// that kernel takes (the caller then uses the cooperative kernel).
-static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
-                                       float *dw, int64_t nslots, bool *launched)
+__global__ void __launch_bounds__(512, 1)
+pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dy, WgradWsArgs a,
+                        const uint32_t *__restrict__ kinfo, float *__restrict__ partial, float *__restrict__ dw)
 {
-    *launched = false;
+    const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    pc_mfma_wgrad_ws_body(x, dy, a, kinfo, partial, dw, lin, (int)gridDim.x, (int)gridDim.y);
+}
+
+// The layers of a network in one launch (all of them independent once every x and dy exists): workgroup b serves
+// workgroup b - blk0[l] of layer l. blk0 entries are multiples of 8, so a layer's workgroups meet the XCDs as
+// they would in a launch of their own; the workgroups that pad a layer's count return at once.
+#define WS_GROUP_MAX 20
+struct WgradWsLayer {
+    WgradWsArgs a;
+    const uint16_t *x, *dy;
+    const uint32_t *kinfo;
+    float *partial, *dw;
+    int32_t gx, gy;
+};
+struct WgradWsGroup {
+    int32_t n;
+    int32_t blk0[WS_GROUP_MAX + 1];
+    WgradWsLayer layer[WS_GROUP_MAX];
+};
+
+__global__ void __launch_bounds__(512, 1) pc_mfma_wgrad_ws_group_kernel(WgradWsGroup g)
+{
+    int l = 0;
+    while (l + 1 < g.n && (int)blockIdx.x >= g.blk0[l + 1]) ++l;
+    const WgradWsLayer &y = g.layer[l];
+    const int lin = (int)blockIdx.x - g.blk0[l];
+    if (lin >= y.gx * y.gy * y.a.ksplit) return;
+    pc_mfma_wgrad_ws_body(y.x, y.dy, y.a, y.kinfo, y.partial, y.dw, lin, y.gx, y.gy);
+}
+
+// Plan of the wave-specialised kernel for one layer; false when the layer is outside what that kernel takes (the
+// caller then uses the cooperative kernel). nslots strides the partial planes. *xb = bytes of the channel-padded
+// copy of x the kernel reads when *pad_x.
+static bool ws_plan(const pc_ctx *ctx, const pc_conv_desc *d, int64_t nslots, WgradWsArgs *out, int *ct_out, int *ft_out,
+                    size_t *lds_out, bool *pad_x_out, int64_t *xb_out)
+{
     WgradWsArgs a;
     memset(&a, 0, sizeof(a));
     const int st = d->stride;
@@ -557,10 +613,10 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     // 16-byte buffer loads of 8 channels. An input whose channel count is no multiple of 8 (the first layer's 3)
     // is first copied to rows padded to 8 channels; an output-gradient with such a filter count is left to the
     // cooperative kernel, which reads by element.
-    if (a.F & 7) return PC_OK;
+    if (a.F & 7) return false;
     const bool pad_x = a.C != a.Creal;
     const int64_t xb = (int64_t)a.N * a.H * a.W * a.C * 2, db = (int64_t)a.N * a.Ho * a.Wo * a.F * 2;
-    if (xb >= ((int64_t)1 << 31) || db >= ((int64_t)1 << 31)) return PC_OK;
+    if (xb >= ((int64_t)1 << 31) || db >= ((int64_t)1 << 31)) return false;
     const int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
     a.x_bytes = (uint32_t)xb; a.dy_bytes = (uint32_t)db;
     int best_tr = 0, best_tc = 0, best_ng = 0;
@@ -581,40 +637,60 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
             const double eff = cover * fill * (0.75 + 0.25 * halo);
             if (eff > best_eff) { best_eff = eff; best_tr = tr; best_tc = tc; best_ng = ngc; }
         }
-    if (best_eff < 0.0) return PC_OK;
+    if (best_eff < 0.0) return false;
     a.TR = best_tr; a.TC = best_tc; a.npos = a.TR * a.TC; a.ng = best_ng;
     a.IR = (a.TR - 1) * st + 3; a.IC = (a.TC - 1) * st + 3;
     a.xs_per_g = a.IR * a.IC;
     a.xslots = (a.ng * a.xs_per_g + 7) / 8 * 8;
-    if (a.xslots > WS_XSLOTS) return PC_OK;
+    if (a.xslots > WS_XSLOTS) return false;
     a.xplane = a.xslots * 16 + 16;
     a.tiles_r = (a.Ho + a.TR - 1) / a.TR;
     a.tiles_c = (a.Wo + a.TC - 1) / a.TC;
     const int tiles_n = (ngroups + a.ng - 1) / a.ng;
     const int64_t nkt = (int64_t)tiles_n * a.tiles_r * a.tiles_c;
-    if (nkt * (a.tiles_r > a.tiles_c ? a.tiles_r : a.tiles_c) >= ((int64_t)1 << 31)) return PC_OK;
+    if (nkt * (a.tiles_r > a.tiles_c ? a.tiles_r : a.tiles_c) >= ((int64_t)1 << 31)) return false;
     a.n_ktiles = (int)nkt;
     a.pstride = (int32_t)nslots;
     auto magic = [](int dd) { return pc_udiv_magic(dd); };
     a.mg_tc = magic(a.tiles_c); a.mg_tr = magic(a.tiles_r);
-    for (int sl = 0; sl < WS_NSLOT; ++sl) {
-        const int ig = sl / a.npos, pos = sl % a.npos, py = pos / a.TC, px = pos % a.TC;
-        const bool ok = ig < a.ng;
-        a.dy_tab[sl] = ok ? ((uint32_t)ig << 16) | ((uint32_t)py << 8) | (uint32_t)px : 0xFFFFFFFFu;
-        a.xb_tab[sl] = ok ? (int16_t)(ig * a.xs_per_g + py * st * a.IC + px * st) : (int16_t)0;
-    }
-    for (int xs = 0; xs < WS_XSLOTS; ++xs) {
-        const int ig = xs / a.xs_per_g, rem = xs % a.xs_per_g;
-        a.x_tab[xs] = (ig < a.ng) ? ((uint32_t)ig << 16) | ((uint32_t)(rem / a.IC) << 8) | (uint32_t)(rem % a.IC) : 0xFFFFFFFFu;
-    }
+    a.mg_npos = magic(a.npos); a.mg_TC = magic(a.TC); a.mg_xs = magic(a.xs_per_g); a.mg_IC = magic(a.IC);
     a.buf_bytes = (WG_T * WS_DY_PLANE + 128 + WG_T * a.xplane + 128 + 255) / 256 * 256;
     size_t lds = 2 * (size_t)a.buf_bytes;
     if (lds < (size_t)2 * 9 * 32 * WG_T * sizeof(float)) lds = (size_t)2 * 9 * 32 * WG_T * sizeof(float);   // the epilogue parks both filter halves
-    if (lds > WS_LDS_MAX) return PC_OK;
+    if (lds > WS_LDS_MAX) return false;
     int ks = ctx->num_cu / (ft * ct);
     if (ks > a.n_ktiles) ks = a.n_ktiles;
     if (ks < 1) ks = 1;
     a.ksplit = ks;
+    *out = a;
+    *ct_out = ct; *ft_out = ft; *lds_out = lds; *pad_x_out = pad_x; *xb_out = xb;
+    return true;
+}
+
+static pc_status ws_set_lds_attr(pc_ctx *ctx)
+{
+    static pc_per_device_once attr;
+    if (pc_once_pending(attr, ctx->device)) {
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS_MAX));
+        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_ws_group_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS_MAX));
+        pc_once_done(attr, ctx->device);
+    }
+    return PC_OK;
+}
+
+// Wave-specialised backward-weight of one layer: plan and launch. *launched stays false when the layer is outside
+// what that kernel takes.
+static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
+                                       float *dw, int64_t nslots, bool *launched)
+{
+    *launched = false;
+    WgradWsArgs a;
+    int ct, ft;
+    size_t lds;
+    bool pad_x;
+    int64_t xb;
+    if (!ws_plan(ctx, d, nslots, &a, &ct, &ft, &lds, &pad_x, &xb)) return PC_OK;
+    const int ks = a.ksplit;
     void *scr = nullptr;
     const size_t part_bytes = ks > 1 ? (sizeof(float) * 4 * (size_t)ks * (size_t)nslots + 255) / 256 * 256 : 0;
     if (part_bytes || pad_x) {
@@ -626,15 +702,12 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
         pc_launch_pad_channels(ctx, (const uint16_t *)x, xp, (int64_t)a.N * a.H * a.W, a.Creal, a.C);
         x = xp;
     }
-    static pc_per_device_once attr;
-    if (pc_once_pending(attr, ctx->device)) {
-        PC_HIP(ctx, hipFuncSetAttribute((const void *)pc_mfma_wgrad_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS_MAX));
-        pc_once_done(attr, ctx->device);
-    }
+    pc_status s = ws_set_lds_attr(ctx);
+    if (s != PC_OK) return s;
     hipLaunchKernelGGL(pc_mfma_wgrad_ws_kernel, dim3((unsigned)ct, (unsigned)ft, (unsigned)ks), dim3(512), lds, ctx->stream,
-                       (const uint16_t *)x, (const uint16_t *)dy, a, pk->v, (float *)scr, dw);
+                       (const uint16_t *)x, (const uint16_t *)dy, a, pk->v.kinfo, (float *)scr, dw);
     *launched = true;
-    pc_status s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight (wave-specialised) launch");
+    s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight (wave-specialised) launch");
     if (s != PC_OK || ks == 1) return s;
     return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, nslots, nslots, pk, dw);
 }
@@ -734,4 +807,93 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight launch");
     if (s != PC_OK) return s;
     return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, nslots, nslots, pk, dw);
+}
+
+// Backward-weight of several layers: the layers the wave-specialised kernel takes run in one launch per
+// WS_GROUP_MAX layers, followed by one grouped reduction; each layer computes exactly what its own call would
+// (same tiles, same splits, same order of additions). The other layers go through pc_mfma_bwd_weight first.
+// Every layer has its own region of the context's scratch buffer (partial planes, padded copy of x).
+pc_status pc_mfma_bwd_weight_group(pc_ctx *ctx, int n, const pc_conv_desc *d, const pc_packed *const *pk, const void *const *x,
+                                   const void *const *dy, float *const *dw)
+{
+    struct Item { int l; WgradWsArgs a; int ct, ft; size_t lds, part_off, pad_off; bool pad_x; int64_t xb, nslots; };
+    std::vector<Item> items;
+    std::vector<int> single;
+    size_t total = 0;
+    for (int l = 0; l < n; ++l) {
+        const int64_t nslots = pk[l]->nnzk >= 0 ? pk[l]->nnzk : (int64_t)pk[l]->v.F * pk[l]->v.C;
+        if (nslots == 0) continue;
+        Item it;
+        it.l = l;
+        it.nslots = nslots;
+        if (ctx->plan_cfg == 10 || !ws_plan(ctx, &d[l], nslots, &it.a, &it.ct, &it.ft, &it.lds, &it.pad_x, &it.xb)) {
+            single.push_back(l);
+            continue;
+        }
+        it.part_off = total;
+        if (it.a.ksplit > 1) total += (sizeof(float) * 4 * (size_t)it.a.ksplit * (size_t)nslots + 255) / 256 * 256;
+        it.pad_off = total;
+        if (it.pad_x) total += ((size_t)it.xb + 255) / 256 * 256;
+        items.push_back(it);
+    }
+    void *scr = nullptr;
+    pc_status s = PC_OK;
+    if (total) {
+        s = pc_scratch(ctx, total, &scr);      // grows the buffer, if it must, before anything is enqueued
+        if (s != PC_OK) return s;
+    }
+    for (int l : single) {
+        s = pc_mfma_bwd_weight(ctx, &d[l], pk[l], x[l], dy[l], dw[l]);
+        if (s != PC_OK) return s;
+    }
+    if (items.empty()) return PC_OK;
+    if (total) {
+        s = pc_scratch(ctx, total, &scr);      // the base may have moved if one of the calls above needed more
+        if (s != PC_OK) return s;
+    }
+    s = ws_set_lds_attr(ctx);
+    if (s != PC_OK) return s;
+    unsigned char *base = static_cast<unsigned char *>(scr);
+    std::vector<WgradReduceItem> red;
+    std::vector<int64_t> red_nslots;
+    std::vector<const pc_packed *> red_pk;
+    for (size_t i0 = 0; i0 < items.size(); i0 += WS_GROUP_MAX) {
+        const int m = (int)(items.size() - i0 < WS_GROUP_MAX ? items.size() - i0 : WS_GROUP_MAX);
+        WgradWsGroup g;
+        memset(&g, 0, sizeof(g));
+        g.n = m;
+        size_t lds = 0;
+        for (int i = 0; i < m; ++i) {
+            const Item &it = items[i0 + i];
+            WgradWsLayer &y = g.layer[i];
+            y.a = it.a;
+            y.x = (const uint16_t *)x[it.l];
+            if (it.pad_x) {
+                void *xp = base + it.pad_off;
+                pc_launch_pad_channels(ctx, (const uint16_t *)x[it.l], xp, (int64_t)it.a.N * it.a.H * it.a.W, it.a.Creal, it.a.C);
+                y.x = (const uint16_t *)xp;
+            }
+            y.dy = (const uint16_t *)dy[it.l];
+            y.kinfo = pk[it.l]->v.kinfo;
+            y.partial = it.a.ksplit > 1 ? reinterpret_cast<float *>(base + it.part_off) : nullptr;
+            y.dw = dw[it.l];
+            y.gx = it.ct; y.gy = it.ft;
+            const int nwg = it.ct * it.ft * it.a.ksplit;
+            g.blk0[i + 1] = g.blk0[i] + (nwg + 7) / 8 * 8;
+            if (it.lds > lds) lds = it.lds;
+            if (it.a.ksplit > 1) {
+                WgradReduceItem r;
+                memset(&r, 0, sizeof(r));
+                r.partial = y.partial; r.dw = y.dw; r.pstride = it.nslots; r.G = it.a.ksplit;
+                red.push_back(r);
+                red_nslots.push_back(it.nslots);
+                red_pk.push_back(pk[it.l]);
+            }
+        }
+        hipLaunchKernelGGL(pc_mfma_wgrad_ws_group_kernel, dim3((unsigned)g.blk0[m]), dim3(512), lds, ctx->stream, g);
+        s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight (several layers) launch");
+        if (s != PC_OK) return s;
+    }
+    if (red.empty()) return PC_OK;
+    return pc_launch_wgrad_reduce_group(ctx, (int)red.size(), red.data(), red_nslots.data(), red_pk.data());
 }

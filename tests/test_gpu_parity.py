@@ -620,6 +620,74 @@ def test_select_and_pack_batch_of_many_layers(B, ctx, oracle):
             g.close()
 
 
+def test_bwd_weight_batch_equals_the_single_calls(B, ctx, oracle):
+    """pc_conv_bwd_weight_batch over layers of every kind (3 input channels: padded copy; a filter count the
+    wave-specialised kernel does not take; a float32 layer on the gather kernels; stride 2; a layer with as many tiles
+    as CUs, i.e. no split; a pack whose count is not known on the host): bit-identical to pc_conv_bwd_weight layer by
+    layer, and within tolerance of the oracle."""
+    import torch
+    shapes = [(8, 8, 8, 3, 64, 1, "bf16"), (8, 8, 8, 64, 64, 1, "bf16"), (4, 6, 6, 40, 36, 1, "bf16"), (2, 5, 5, 16, 24, 1, "f32"),
+              (8, 9, 9, 64, 128, 2, "bf16"), (2, 2, 2, 1024, 1024, 1, "bf16"), (16, 4, 4, 256, 128, 1, "bf16")]
+    gs, cases = [], []
+    try:
+        for li, (N, H, W_, C, F, st, dtype) in enumerate(shapes):
+            case = Case(I.Layer(N, H, W_, C, F, st), dtype, 8, I.kept_per_filter(0.3, C), tag=("wgb", li))
+            cases.append(case)
+            gs.append(GpuLayer(B, ctx, case))
+        single = []
+        for g in gs:
+            dw, guard = g.bwd_weight()
+            single.append(guard.body.clone())
+        # the last pack again without a read-back of its count: planes strided by the capacity
+        g = gs[-1]
+        B.pc_pack(ctx, g.W, g.pid, g.keep, cases[-1].layer.F, cases[-1].layer.C, cases[-1].lib, g.dt, reuse=g.pk)
+        from tests._harness import Guarded
+        outs = [Guarded(g.nnzk * 4, torch.float32) for g in gs]
+        B.pc_conv_bwd_weight_batch(ctx, [g.desc for g in gs], [g.pk for g in gs], [g.x for g in gs], [g.dy for g in gs],
+                                   [o.ptr for o in outs])
+        torch.cuda.synchronize()
+        for g, case, o, ref in zip(gs, cases, outs, single):
+            assert o.margins_intact(), case.layer
+            assert torch.equal(o.body, ref), case.layer
+            pid, kp, M, Wm = oracle_masks(oracle, case)
+            assert rel_l2(g.scatter(o.body), oracle.conv_bwd_weight(case.x, case.dy, M, case.layer.stride)) <= 1e-4, case.layer
+    finally:
+        for g in gs:
+            g.close()
+
+
+def test_bwd_weight_batch_full_size_vgg16_cifar(B, ctx):
+    """The 13 layers of the VGG-16 / CIFAR workload at batch 128 in one call: bit-identical to the single calls (which the
+    full-size tests check against the oracle)."""
+    import torch
+    wl = I.WORKLOADS["vgg16_cifar"]
+    lib = I.make_library(wl.P)
+    packs, descs, xs, dys, refs, outs = [], [], [], [], [], []
+    try:
+        for li, L in enumerate(wl.layers):
+            W = to_dev(I.gen_weights(L.F, L.C, I.BASE_SEED, ("wgf", li)))
+            pid = torch.empty((L.F, L.C), dtype=torch.uint8, device="cuda")
+            keep = torch.empty((L.F, L.C), dtype=torch.uint8, device="cuda")
+            k = I.kept_per_filter(wl.keep, L.C)
+            B.pc_pattern_select(ctx, W, None, L.F, L.C, lib, B.PC_KEEP_PER_FILTER, k, B.PC_SCORE_RETAINED, pid, keep)
+            pk = B.pc_pack(ctx, W, pid, keep, L.F, L.C, lib, B.PC_BF16)
+            nnzk, _ = B.pc_packed_info(ctx, pk)
+            x = torch.randn((L.N, L.H, L.W, L.C), device="cuda").relu().bfloat16()
+            dy = torch.randn((L.N, L.Ho, L.Wo, L.F), device="cuda").bfloat16()
+            desc = B.make_desc(L.N, L.H, L.W, L.C, L.F, L.stride, B.PC_BF16)
+            ref = torch.full((nnzk, 4), float("nan"), dtype=torch.float32, device="cuda")
+            B.pc_conv_bwd_weight(ctx, desc, pk, x, dy, ref)
+            packs.append(pk); descs.append(desc); xs.append(x); dys.append(dy); refs.append(ref)
+            outs.append(torch.full((nnzk, 4), float("nan"), dtype=torch.float32, device="cuda"))
+        B.pc_conv_bwd_weight_batch(ctx, descs, packs, xs, dys, outs)
+        torch.cuda.synchronize()
+        for li, (o, r) in enumerate(zip(outs, refs)):
+            assert torch.isfinite(r).all() and torch.equal(o, r), li
+    finally:
+        for pk in packs:
+            B.pc_packed_free(pk)
+
+
 def test_mismatched_descriptor_is_rejected(B, ctx, oracle):
     layer = I.Layer(1, 4, 4, 8, 8, 1)
     case = Case(layer, "f32", 4, 4, tag="mismatch")
