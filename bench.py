@@ -51,6 +51,11 @@ def main() -> int:
     ap.add_argument("--no-prep-overlap", action="store_true",
                     help="keep selection and packing (or the value update) of a step on the main stream, before each layer's "
                          "forward call, instead of running them for all layers on the side stream from the start of the step")
+    ap.add_argument("--wgrad", default="auto", choices=["auto", "group", "layer"],
+                    help="group: one pc_conv_bwd_weight_batch call for all layers at the end of the step (a layer's weight "
+                         "gradient needs only its own x and dy, so it can wait until all of them exist); layer: "
+                         "pc_conv_bwd_weight per layer, on the side stream when there is one; auto: the faster of the two "
+                         "in a short trial before the timed steps")
     ap.add_argument("--no-batch-prep", action="store_true",
                     help="select and pack layer by layer (pc_pattern_select, pc_pack) instead of all layers per launch "
                          "(pc_pattern_select_batch, pc_pack_batch)")
@@ -141,6 +146,12 @@ def main() -> int:
 
     prep = [w for w in passes if w in ("select", "pack", "update")]
     batch_prep = bool(prep) and not args.no_batch_prep
+    mode = {"wgrad": "group" if args.wgrad == "auto" else args.wgrad}
+
+    def wgrad_batch(c, lo, hi):
+        ls = layers[lo:hi]
+        B.pc_conv_bwd_weight_batch(c, [d["desc"] for d in ls], [d["pk"] for d in ls], [d["x"] for d in ls],
+                                   [d["dy"] for d in ls], [d["dw"] for d in ls])
 
     def run_batch(which, ctx=ctx):
         if which == "update":
@@ -179,11 +190,14 @@ def main() -> int:
                 ev = torch.cuda.Event()
                 ev.record(streams_w[0])
                 ready.append(ev)
+        wg = mode["wgrad"]
         for li, d in enumerate(layers):
             if ready:
                 stream.wait_event(ready[li])
             for which in passes:
                 if (batch_prep or prep_side) and which in prep:
+                    continue
+                if wg != "layer" and which == "bwd_weight":
                     continue
                 if events is not None:
                     e0 = torch.cuda.Event(enable_timing=True)
@@ -198,6 +212,15 @@ def main() -> int:
                 if events is not None:
                     e1.record(stream)
                     events.append((li, which, e0, e1))
+        if wg == "group":
+            if events is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+            wgrad_batch(ctx, 0, len(layers))
+            if events is not None:
+                e1.record(stream)
+                events.append((-1, "bwd_weight", e0, e1))
         if overlap:
             for s_w in streams_w:
                 stream.wait_stream(s_w)                # join: the step ends when every stream has drained
@@ -210,10 +233,34 @@ def main() -> int:
     torch.cuda.synchronize()
     graph = None
     if use_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=stream):
-            step()
-        torch.cuda.synchronize()
+        def capture():
+            step()                                         # eager once: scratch buffers reach their size outside the capture
+            torch.cuda.synchronize()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=stream):
+                step()
+            torch.cuda.synchronize()
+            return gr
+        if args.wgrad == "auto":
+            # where the weight gradients run is a launch choice: try the candidates for a few replays, keep the fastest
+            trial = {}
+            for cand in ["group", "layer"]:
+                mode["wgrad"] = cand
+                gr = capture()
+                for _ in range(3):
+                    gr.replay()
+                torch.cuda.synchronize()
+                tt = time.perf_counter()
+                for _ in range(10):
+                    gr.replay()
+                torch.cuda.synchronize()
+                trial[cand] = (time.perf_counter() - tt) * 1e2
+                # a trial graph is never replayed again: a later candidate may grow a context's scratch buffer, which
+                # frees the address this graph's kernels were captured with
+                del gr
+            mode["wgrad"] = min(trial, key=trial.get)
+            log("weight-gradient placement: " + ", ".join("%s %.4f ms" % (c, v) for c, v in trial.items()) + " -> " + mode["wgrad"])
+        graph = capture()                                   # captured after every buffer has reached its final size
         for _ in range(args.warmup):
             graph.replay()
         torch.cuda.synchronize()
@@ -255,6 +302,11 @@ def main() -> int:
             n_pos = sum(x["L"].F * x["L"].C for x in layers) if li < 0 else L.F * L.C   # li = -1: one call for all layers
             byts = n_pos * (74 if which == "select" else 38 + 0.0)
             fl = dfl = 0.0
+        elif li < 0:                                         # the weight gradients of all layers in one call
+            var = "mfma" if all(x["variant"] == B.PC_VARIANT_MFMA for x in layers) else "valu"
+            kind = "%s_%s" % (var, which)
+            fl, dfl = sum(x["flops"] for x in layers), sum(x["dense_flops"] for x in layers)
+            byts = sum(x["act_in"] + x["act_out"] + 16 * x["nnzk"] for x in layers)
         else:
             kind = "%s_%s" % (var, which)
             fl, dfl = d["flops"], d["dense_flops"]
@@ -562,7 +614,7 @@ def main() -> int:
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "layers": len(wl.layers), "batch": wl.layers[0].N, "patterns": wl.P,
                    "keep": wl.keep, "variant": args.variant, "passes": "+".join(passes), "launch": "hip_graph" if graph is not None else "host",
-                   "streams": 1 + len(ctxs_w),
+                   "streams": 1 + len(ctxs_w), "wgrad": mode["wgrad"],
                    "nonzero_gflop_per_step": round(total_flops / 1e9, 3)},
         "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -227,9 +227,9 @@ pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *desc, const pc_pac
 
 /* pc_conv_bwd_weight for several layers at once. The weight gradients of a network's layers do not depend on each
  * other (dE/dW of a layer needs only its own a_prev and delta, Section 5.2), so once every x and dy exists they can
- * all be computed together: the matrix-core layers in one launch per 20 layers plus one reduction launch, each
- * layer with the tiles, splits and order of additions of its own call (bit-identical results); layers on the
- * gather kernels one by one. Every layer's partial sums have their own region of the context's scratch buffer.
+ * all be computed together: the matrix-core layers in one launch per 20 layers plus one reduction launch (the
+ * layers share the chip, so each is split less than in its own call: deterministic, equal to the single call up
+ * to the float32 order of additions); layers on the gather kernels one by one. Every layer's partial sums have their own region of the context's scratch buffer.
  *   descs_host : HOST array [n_layers] of descriptors; packs_host : HOST array [n_layers] of handles
  *   x_dev_host, dy_dev_host, dw_compact_dev_host : HOST arrays [n_layers] of device pointers as in
  *       pc_conv_bwd_weight (the dw buffers all distinct) */

@@ -810,8 +810,9 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
 }
 
 // Backward-weight of several layers: the layers the wave-specialised kernel takes run in one launch per
-// WS_GROUP_MAX layers, followed by one grouped reduction; each layer computes exactly what its own call would
-// (same tiles, same splits, same order of additions). The other layers go through pc_mfma_bwd_weight first.
+// WS_GROUP_MAX layers, followed by one grouped reduction; each layer has the tiles of its own call and at most
+// its splits (fixed order of additions: deterministic, but not the bits of the single call when the split differs).
+// The other layers go through pc_mfma_bwd_weight first.
 // Every layer has its own region of the context's scratch buffer (partial planes, padded copy of x).
 pc_status pc_mfma_bwd_weight_group(pc_ctx *ctx, int n, const pc_conv_desc *d, const pc_packed *const *pk, const void *const *x,
                                    const void *const *dy, float *const *dw)
@@ -830,11 +831,23 @@ pc_status pc_mfma_bwd_weight_group(pc_ctx *ctx, int n, const pc_conv_desc *d, co
             single.push_back(l);
             continue;
         }
+        items.push_back(it);
+    }
+    // A layer's own call splits its pixel tiles until the layer alone fills the chip; here the layers fill it
+    // together, so every workgroup gets about the same share of all (tile, pixel tile) units, two workgroups per CU
+    // in all: fewer splits, longer main loops per prologue and epilogue, fewer partial planes.
+    int64_t units = 0;
+    for (const Item &it : items) units += (int64_t)it.ct * it.ft * it.a.n_ktiles;
+    int64_t share = units / (2 * (int64_t)ctx->num_cu);
+    if (share < 1) share = 1;
+    for (Item &it : items) {
+        int64_t ks = (it.a.n_ktiles + share - 1) / share;
+        if (ks < 1) ks = 1;
+        if (ks < it.a.ksplit) it.a.ksplit = (int32_t)ks;
         it.part_off = total;
-        if (it.a.ksplit > 1) total += (sizeof(float) * 4 * (size_t)it.a.ksplit * (size_t)nslots + 255) / 256 * 256;
+        if (it.a.ksplit > 1) total += (sizeof(float) * 4 * (size_t)it.a.ksplit * (size_t)it.nslots + 255) / 256 * 256;
         it.pad_off = total;
         if (it.pad_x) total += ((size_t)it.xb + 255) / 256 * 256;
-        items.push_back(it);
     }
     void *scr = nullptr;
     pc_status s = PC_OK;

@@ -623,8 +623,9 @@ def test_select_and_pack_batch_of_many_layers(B, ctx, oracle):
 def test_bwd_weight_batch_equals_the_single_calls(B, ctx, oracle):
     """pc_conv_bwd_weight_batch over layers of every kind (3 input channels: padded copy; a filter count the
     wave-specialised kernel does not take; a float32 layer on the gather kernels; stride 2; a layer with as many tiles
-    as CUs, i.e. no split; a pack whose count is not known on the host): bit-identical to pc_conv_bwd_weight layer by
-    layer, and within tolerance of the oracle."""
+    as CUs, i.e. no split; a pack whose count is not known on the host): within tolerance of the oracle and of
+    pc_conv_bwd_weight layer by layer (the split of a layer, hence the float32 order of additions, may differ), and
+    the same bits from call to call."""
     import torch
     shapes = [(8, 8, 8, 3, 64, 1, "bf16"), (8, 8, 8, 64, 64, 1, "bf16"), (4, 6, 6, 40, 36, 1, "bf16"), (2, 5, 5, 16, 24, 1, "f32"),
               (8, 9, 9, 64, 128, 2, "bf16"), (2, 2, 2, 1024, 1024, 1, "bf16"), (16, 4, 4, 256, 128, 1, "bf16")]
@@ -648,17 +649,22 @@ def test_bwd_weight_batch_equals_the_single_calls(B, ctx, oracle):
         torch.cuda.synchronize()
         for g, case, o, ref in zip(gs, cases, outs, single):
             assert o.margins_intact(), case.layer
-            assert torch.equal(o.body, ref), case.layer
+            assert rel_l2(o.body.cpu().numpy(), ref.cpu().numpy()) <= 1e-5, case.layer
             pid, kp, M, Wm = oracle_masks(oracle, case)
             assert rel_l2(g.scatter(o.body), oracle.conv_bwd_weight(case.x, case.dy, M, case.layer.stride)) <= 1e-4, case.layer
+        again = [Guarded(g.nnzk * 4, torch.float32) for g in gs]
+        B.pc_conv_bwd_weight_batch(ctx, [g.desc for g in gs], [g.pk for g in gs], [g.x for g in gs], [g.dy for g in gs],
+                                   [o.ptr for o in again])
+        torch.cuda.synchronize()
+        assert all(torch.equal(a.body, o.body) for a, o in zip(again, outs))
     finally:
         for g in gs:
             g.close()
 
 
 def test_bwd_weight_batch_full_size_vgg16_cifar(B, ctx):
-    """The 13 layers of the VGG-16 / CIFAR workload at batch 128 in one call: bit-identical to the single calls (which the
-    full-size tests check against the oracle)."""
+    """The 13 layers of the VGG-16 / CIFAR workload at batch 128 in one call: equal to the single calls (which the
+    full-size tests check against the oracle) up to the float32 order of additions."""
     import torch
     wl = I.WORKLOADS["vgg16_cifar"]
     lib = I.make_library(wl.P)
@@ -682,7 +688,8 @@ def test_bwd_weight_batch_full_size_vgg16_cifar(B, ctx):
         B.pc_conv_bwd_weight_batch(ctx, descs, packs, xs, dys, outs)
         torch.cuda.synchronize()
         for li, (o, r) in enumerate(zip(outs, refs)):
-            assert torch.isfinite(r).all() and torch.equal(o, r), li
+            assert torch.isfinite(r).all() and torch.isfinite(o).all(), li
+            assert rel_l2(o.cpu().numpy(), r.cpu().numpy()) <= 1e-5, li
     finally:
         for pk in packs:
             B.pc_packed_free(pk)
