@@ -242,25 +242,35 @@ def main() -> int:
             torch.cuda.synchronize()
             return gr
         if args.wgrad == "auto":
-            # where the weight gradients run is a launch choice: try the candidates for a few replays, keep the fastest
-            trial = {}
-            for cand in ["group", "layer"]:
+            # where the weight gradients run is a launch choice: try both placements for a few replays, keep the faster.
+            # Every candidate first runs eagerly, so that each context's scratch buffer has its final size before
+            # any graph is captured (a growth would free the address earlier graphs were captured with).
+            cands = ["group", "layer"]
+            for cand in cands:
                 mode["wgrad"] = cand
-                gr = capture()
-                for _ in range(3):
-                    gr.replay()
-                torch.cuda.synchronize()
-                tt = time.perf_counter()
-                for _ in range(10):
-                    gr.replay()
-                torch.cuda.synchronize()
-                trial[cand] = (time.perf_counter() - tt) * 1e2
-                # a trial graph is never replayed again: a later candidate may grow a context's scratch buffer, which
-                # frees the address this graph's kernels were captured with
-                del gr
+                step()
+            torch.cuda.synchronize()
+            graphs = {}
+            for cand in cands:
+                mode["wgrad"] = cand
+                graphs[cand] = capture()
+            trial = {c: float("inf") for c in cands}
+            for _ in range(2):                                  # alternate, keep each candidate's best
+                for cand in cands:
+                    for _ in range(5):
+                        graphs[cand].replay()
+                    torch.cuda.synchronize()
+                    tt = time.perf_counter()
+                    for _ in range(10):
+                        graphs[cand].replay()
+                    torch.cuda.synchronize()
+                    trial[cand] = min(trial[cand], (time.perf_counter() - tt) * 1e2)
             mode["wgrad"] = min(trial, key=trial.get)
             log("weight-gradient placement: " + ", ".join("%s %.4f ms" % (c, v) for c, v in trial.items()) + " -> " + mode["wgrad"])
-        graph = capture()                                   # captured after every buffer has reached its final size
+            graph = graphs[mode["wgrad"]]
+            del graphs
+        else:
+            graph = capture()
         for _ in range(args.warmup):
             graph.replay()
         torch.cuda.synchronize()

@@ -576,6 +576,14 @@ pc_mfma_wgrad_ws_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 // workgroup b - blk0[l] of layer l. blk0 entries are multiples of 8, so a layer's workgroups meet the XCDs as
 // they would in a launch of their own; the workgroups that pad a layer's count return at once.
 #define WS_GROUP_MAX 20
+// A grouped launch aims at one workgroup per CU while a workgroup's share stays below PC_GROUP_UNITS (tile,
+// pixel tile) units (the prologue and epilogue of a workgroup cost as much as several), then at up to 4 per CU
+// (long workgroups: balance matters more). Measured: vgg16_cifar 105 / 113 / 123 us and vgg16_imagenet
+// 1017 / 1029 / 915 / 895 us at 1 / 2 / 3 / 4 workgroups per CU; with the threshold at 16 / 32 / 64 units:
+// vgg16_cifar 112 / 105 / 106 us, resnet50_imagenet 312 / 312 / 300 us, vgg16_imagenet 910 / 914 / 1030 us.
+#ifndef PC_GROUP_UNITS
+#define PC_GROUP_UNITS 32
+#endif
 struct WgradWsLayer {
     WgradWsArgs a;
     const uint16_t *x, *dy;
@@ -834,11 +842,14 @@ pc_status pc_mfma_bwd_weight_group(pc_ctx *ctx, int n, const pc_conv_desc *d, co
         items.push_back(it);
     }
     // A layer's own call splits its pixel tiles until the layer alone fills the chip; here the layers fill it
-    // together, so every workgroup gets about the same share of all (tile, pixel tile) units, two workgroups per CU
-    // in all: fewer splits, longer main loops per prologue and epilogue, fewer partial planes.
+    // together, so every workgroup gets about the same share of all (tile, pixel tile) units: fewer splits, longer
+    // main loops per prologue and epilogue, fewer partial planes.
     int64_t units = 0;
     for (const Item &it : items) units += (int64_t)it.ct * it.ft * it.a.n_ktiles;
-    int64_t share = units / (2 * (int64_t)ctx->num_cu);
+    int64_t rounds = units / ((int64_t)PC_GROUP_UNITS * ctx->num_cu);
+    if (rounds < 1) rounds = 1;
+    if (rounds > 4) rounds = 4;
+    int64_t share = units / (rounds * (int64_t)ctx->num_cu);
     if (share < 1) share = 1;
     for (Item &it : items) {
         int64_t ks = (it.a.n_ktiles + share - 1) / share;
