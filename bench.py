@@ -431,7 +431,9 @@ def main() -> int:
                     d = layers[li]
                     L = d["L"]
                     B.pc_act_pool_bwd(ctx, da, d["sel"], L.N, L.Ho, L.Wo, L.F, dt, d["pool"], d["dy"])   # d["dy"] reused as dz
-                    if side:
+                    if side == "group":
+                        pass                                                         # all weight gradients at the end
+                    elif side:
                         streams_w[0].wait_stream(stream)
                         B.pc_conv_bwd_weight(ctxs_w[0], d["desc"], d["pk"], d["xin"], d["dy"], d["dw"])
                     else:
@@ -439,7 +441,10 @@ def main() -> int:
                     if li > 0:
                         B.pc_conv_bwd_data(ctx, d["desc"], d["pk"], d["dy"], d["dx"])
                         da = d["dx"]
-                if side:
+                if side == "group":
+                    B.pc_conv_bwd_weight_batch(ctx, [d["desc"] for d in layers], [d["pk"] for d in layers],
+                                               [d["xin"] for d in layers], [d["dy"] for d in layers], [d["dw"] for d in layers])
+                elif side:
                     stream.wait_stream(streams_w[0])
 
             def time_chain(side):
@@ -457,7 +462,7 @@ def main() -> int:
                 torch.cuda.synchronize()
                 return (time.perf_counter() - t0c) * 1e3 / args.steps
 
-            ms_by_streams = {1: time_chain(False)}
+            ms_by_streams = {1: time_chain(False), "1, weight gradients grouped": time_chain("group")}
             if ctxs_w:
                 ms_by_streams[2] = time_chain(True)
             finite = bool(torch.isfinite(layers[0]["dw"]).all().item()) and bool(torch.isfinite(last["a"].float()).all().item())
@@ -491,7 +496,7 @@ def main() -> int:
                        "finite": finite,
                        "act_pool_us": round(us_act, 1), "act_pool_gbs": round(by_act / us_act / 1e3, 1),
                        "act_pool_hbm_frac": round(by_act / us_act / 1e3 / PEAK_HBM_GBS, 4)}
-            log("chained network: %.4f ms per step (%.1f nonzero TFLOP/s over %d calls, %d stream(s)); ReLU/pool calls alone "
+            log("chained network: %.4f ms per step (%.1f nonzero TFLOP/s over %d calls, stream(s): %s); ReLU/pool calls alone "
                 "%.1f us (%.0f GB/s algorithmic)" % (ms_chain, chained["value"], 5 * nl - 1, chained["streams"], us_act, by_act / us_act / 1e3))
             torch.cuda.synchronize()
 
