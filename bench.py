@@ -356,11 +356,11 @@ def main() -> int:
     prof = os.path.join(ROOT, "profiles", "%s_hbm_counters.md" % wl.name)
     # kernels one library call of that kind launches: the first entry is the kernel that does the work (its
     # dispatches count the calls), the others are helpers whose bytes belong to the same call
-    knames = {"mfma_bwd_weight": ("pc_mfma_wgrad", "pc_wgrad_reduce_kernel", "pc_pad_channels_kernel"),
+    knames = {"mfma_bwd_weight": ("pc_mfma_wgrad", "pc_wgrad_reduce", "pc_pad_channels_kernel"),
               "mfma_fwd": ("pc_mfma_conv", "pc_mfma_splitk_reduce_kernel"),
               "mfma_bwd_data": ("pc_mfma_conv", "pc_mfma_splitk_reduce_kernel", "pc_unpad_channels_kernel"),
               "valu_fwd": ("pc_gather_conv_kernel",), "valu_bwd_data": ("pc_gather_conv_kernel",),
-              "valu_bwd_weight": ("pc_wgrad_valu_kernel", "pc_wgrad_reduce_kernel")}.get(dk)
+              "valu_bwd_weight": ("pc_wgrad_valu_kernel", "pc_wgrad_reduce")}.get(dk)
     if knames and os.path.exists(prof):
         tot_b, tot_n = 0.0, 0
         for line in open(prof):
