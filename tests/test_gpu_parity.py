@@ -662,11 +662,12 @@ def test_bwd_weight_batch_equals_the_single_calls(B, ctx, oracle):
             g.close()
 
 
-def test_bwd_weight_batch_full_size_vgg16_cifar(B, ctx):
-    """The 13 layers of the VGG-16 / CIFAR workload at batch 128 in one call: equal to the single calls (which the
+@pytest.mark.parametrize("workload", ["vgg16_cifar", "resnet18_cifar", "resnet50_imagenet", "vgg16_imagenet"])
+def test_bwd_weight_batch_full_size(B, ctx, workload):
+    """All layers of a benchmark workload at its batch size in one call: equal to the single calls (which the
     full-size tests check against the oracle) up to the float32 order of additions."""
     import torch
-    wl = I.WORKLOADS["vgg16_cifar"]
+    wl = I.WORKLOADS[workload]
     lib = I.make_library(wl.P)
     packs, descs, xs, dys, refs, outs = [], [], [], [], [], []
     try:
@@ -688,8 +689,8 @@ def test_bwd_weight_batch_full_size_vgg16_cifar(B, ctx):
         B.pc_conv_bwd_weight_batch(ctx, descs, packs, xs, dys, outs)
         torch.cuda.synchronize()
         for li, (o, r) in enumerate(zip(outs, refs)):
-            assert torch.isfinite(r).all() and torch.isfinite(o).all(), li
-            assert rel_l2(o.cpu().numpy(), r.cpu().numpy()) <= 1e-5, li
+            assert torch.isfinite(r).all() and torch.isfinite(o).all(), (workload, li)
+            assert rel_l2(o.cpu().numpy(), r.cpu().numpy()) <= 1e-5, (workload, li)
     finally:
         for pk in packs:
             B.pc_packed_free(pk)
