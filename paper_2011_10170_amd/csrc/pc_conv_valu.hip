@@ -409,8 +409,7 @@ struct WgradReduceGroup {
 
 __global__ void __launch_bounds__(256) pc_wgrad_reduce_group_kernel(WgradReduceGroup g)
 {
-    int l = 0;
-    while (l + 1 < g.n && (int)blockIdx.x >= g.blk0[l + 1]) ++l;
+    const int l = pc_batch_find(g.blk0, g.n, (int)blockIdx.x);
     const WgradReduceItem &y = g.item[l];
     const int blk = (int)blockIdx.x - g.blk0[l];
     const float4 *pp = reinterpret_cast<const float4 *>(y.partial);

@@ -96,6 +96,13 @@ pc_status pc_launch_select(pc_ctx *ctx, const float *W, const float *G, int F, i
 pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8_t *pid, const uint8_t *keep);
 // Several layers per launch (at most PC_BATCH_MAX per kernel; longer lists are cut into groups).
 #define PC_BATCH_MAX 32
+// Index l of the range [first[l], first[l + 1]) that holds workgroup b, 0 <= l < n (uniform over the workgroup).
+__device__ __forceinline__ int pc_batch_find(const int32_t *first, int n, int b)
+{
+    int l = 0;
+    while (l + 1 < n && b >= first[l + 1]) ++l;
+    return l;
+}
 pc_status pc_launch_select_batch(pc_ctx *ctx, int n, const float *const *W, const float *const *G, const int32_t *F,
                                  const int32_t *C, const LibArg &la, pc_keep_mode km, const int64_t *n_keep, pc_score_mode sm,
                                  uint8_t *const *pid, uint8_t *const *keep);

@@ -281,14 +281,6 @@ struct SelBatchArg {
     uint8_t *pid[PC_BATCH_MAX], *keep[PC_BATCH_MAX];
 };
 
-// Index of the range [first[l], first[l + 1]) that holds b (uniform over the workgroup).
-__device__ __forceinline__ int pc_batch_find(const int32_t *first, int n, int b)
-{
-    int l = 0;
-    while (l + 1 < n && b >= first[l + 1]) ++l;
-    return l;
-}
-
 __global__ void __launch_bounds__(512) pc_select_rows_batch_kernel(SelBatchArg b, LibArg la)
 {
     const int l = pc_batch_find(b.row0, b.n, (int)blockIdx.x);

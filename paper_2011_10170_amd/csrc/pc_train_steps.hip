@@ -139,13 +139,6 @@ struct TsBatchArg {
     const uint32_t *counts[PC_BATCH_MAX];
 };
 
-__device__ __forceinline__ int ts_batch_find(const int32_t *first, int n, int b)
-{
-    int l = 0;
-    while (l + 1 < n && b >= first[l + 1]) ++l;
-    return l;
-}
-
 __global__ void __launch_bounds__(TS_BLOCK) pc_dppg_batch_kernel(TsBatchArg b, uint32_t *__restrict__ hist)
 {
     __shared__ float sw[TS_BLOCK * 9], sg[TS_BLOCK * 9];
@@ -154,7 +147,7 @@ __global__ void __launch_bounds__(TS_BLOCK) pc_dppg_batch_kernel(TsBatchArg b, u
     lh[threadIdx.x + 256] = 0u;
     const int total = b.blk0[b.n];
     for (int ch = (int)blockIdx.x; ch < total; ch += (int)gridDim.x) {
-        const int l = ts_batch_find(b.blk0, b.n, ch);
+        const int l = pc_batch_find(b.blk0, b.n, ch);
         ts_dppg_chunk(b.W[l], b.G[l], b.nk[l], (int64_t)(ch - b.blk0[l]) * TS_BLOCK, lh, static_cast<uint16_t *>(b.out[l]), sw, sg);
     }
     for (int i = threadIdx.x; i < 512; i += TS_BLOCK)
@@ -226,7 +219,7 @@ pc_finalize_pick_kernel(const uint32_t *__restrict__ counts, int64_t nk, int P, 
 
 __global__ void __launch_bounds__(256) pc_finalize_count_batch_kernel(TsBatchArg b, int P)
 {
-    const int l = ts_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    const int l = pc_batch_find(b.blk0, b.n, (int)blockIdx.x);
     const int64_t k = (int64_t)((int)blockIdx.x - b.blk0[l]) * 256 + threadIdx.x;
     if (k >= b.nk[l]) return;
     const int p = b.pid[l][k];
@@ -235,7 +228,7 @@ __global__ void __launch_bounds__(256) pc_finalize_count_batch_kernel(TsBatchArg
 
 __global__ void __launch_bounds__(256) pc_finalize_pick_batch_kernel(TsBatchArg b, int P)
 {
-    const int l = ts_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    const int l = pc_batch_find(b.blk0, b.n, (int)blockIdx.x);
     const int64_t k = (int64_t)((int)blockIdx.x - b.blk0[l]) * 256 + threadIdx.x;
     if (k >= b.nk[l]) return;
     const uint32_t *counts = b.counts[l];
@@ -346,7 +339,7 @@ pc_group_lasso_kernel(const float *__restrict__ W, const uint8_t *__restrict__ p
 __global__ void __launch_bounds__(TS_BLOCK)
 pc_group_lasso_batch_kernel(TsBatchArg b, LibArg la, float lambda_p, float lambda_i, double *__restrict__ block_pen)
 {
-    const int l = ts_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    const int l = pc_batch_find(b.blk0, b.n, (int)blockIdx.x);
     ts_group_lasso_block(b.W[l], b.pid[l], b.keep[l], b.nk[l], la, lambda_p, lambda_i, static_cast<float *>(b.out[l]), block_pen,
                          (int)blockIdx.x - b.blk0[l]);
 }

@@ -599,8 +599,7 @@ struct WgradWsGroup {
 
 __global__ void __launch_bounds__(512, 1) pc_mfma_wgrad_ws_group_kernel(WgradWsGroup g)
 {
-    int l = 0;
-    while (l + 1 < g.n && (int)blockIdx.x >= g.blk0[l + 1]) ++l;
+    const int l = pc_batch_find(g.blk0, g.n, (int)blockIdx.x);
     const WgradWsLayer &y = g.layer[l];
     const int lin = (int)blockIdx.x - g.blk0[l];
     if (lin >= y.gx * y.gy * y.a.ksplit) return;
