@@ -300,6 +300,7 @@ def main() -> int:
     # flops / unit peak): issued flops are the dense zero-filled tile flops on the matrix-core kernels (bf16 peak) and
     # the nonzero flops on the gather kernels (float32 vector peak); select and pack are priced by bytes alone
     t_roof_sum = 0.0
+    t_sparse_sum = 0.0
     t_meas_sum = 0.0
     log("%-3s %-22s %-10s %-5s %9s %10s %10s %8s %6s" % ("#", "layer", "pass", "var", "us", "nz TF/s", "dense TF/s", "GB/s", "roof"))
     for (li, which), ts in sorted(per_call.items()):
@@ -332,6 +333,7 @@ def main() -> int:
         t_unit_us = (dfl / (PEAK_BF16_MFMA_TFLOPS * 1e6)) if var == "mfma" else (fl / (PEAK_F32_VALU_TFLOPS * 1e6))
         t_roof_us = max(byts / (PEAK_HBM_GBS * 1e3), t_unit_us)
         t_roof_sum += t_roof_us
+        t_sparse_sum += max(byts / (PEAK_HBM_GBS * 1e3), fl / (PEAK_F32_VALU_TFLOPS * 1e6))
         t_meas_sum += us
         log("%-3d %-22s %-10s %-5s %9.1f %10.2f %10.1f %8.0f %6.3f" % (
             li, "all %d layers" % len(layers) if li < 0 else "%dx%d %d->%d s%d" % (L.H, L.W, L.C, L.F, L.stride), which, var, us,
@@ -383,6 +385,8 @@ def main() -> int:
         "share_of_step": round(dv["us"] / sum(k["us"] for k in kinds.values()), 3),
         # all calls of the step: sum of their roofline times / the step time
         "path_frac": round(t_roof_sum / (ms_per_step * 1e3), 4),
+        # the same against the ideal sparse execution: max(algorithmic bytes / HBM peak, nonzero flops / float32 vector peak)
+        "path_ideal_sparse_frac": round(t_sparse_sum / (ms_per_step * 1e3), 4),
     }
     for kname, kv in sorted(kinds.items()):
         log("kind %-18s launches %3d  total %9.1f us  nz %8.2f TF/s  dense %8.1f TF/s  alg %7.0f GB/s" % (
