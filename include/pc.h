@@ -216,6 +216,20 @@ pc_status pc_conv_fwd(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk
 pc_status pc_conv_bwd_data(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
                            const void *dy_dev, void *dx_dev);
 
+/* pc_conv_fwd followed by the activation of Section 5.2 (a = sigma(z), sigma = ReLU) in the same launch where the
+ * kernel that serves the layer can, else in a second one: a = relu(conv(x)), bit-identical to pc_conv_fwd
+ * followed by pc_act_pool_fwd with pool = 1. No selection bytes are written: the backward pass reads the
+ * derivative from a itself (pc_conv_bwd_data_relu of the next layer). */
+pc_status pc_conv_fwd_relu(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
+                           const void *x_dev, void *a_dev);
+
+/* pc_conv_bwd_data followed by the factor sigma'(z) of Section 5.2 for the layer BEFORE this one, whose ReLU output
+ * is this layer's input x: dx = (dy (*) rot180(W)) where x > 0, else +0 (x > 0 exactly where that layer's z > 0).
+ * Same launch where the kernel can, else a second one; bit-identical to pc_conv_bwd_data followed by that mask.
+ *   x_dev : dtype [N][H][W][C], the tensor this layer's forward pass read */
+pc_status pc_conv_bwd_data_relu(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
+                                const void *dy_dev, const void *x_dev, void *dx_dev);
+
 /* Weight gradient at kept taps only, float32 [nnz_kernels][4] in compact slot order:
  * dw[f,c,t] = sum_{n,oy,ox} dy[n,oy,ox,f] * x[n, oy*stride+r-1, ox*stride+s-1, c].
  * Deterministic: no floating-point atomics (per-split partial sums in the context's scratch buffer, added in a

@@ -27,7 +27,7 @@ EXPORTS = [
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
     "pc_dppg_accumulate", "pc_dppg_pool", "pc_finalize_count", "pc_finalize_pick", "pc_group_lasso_grad",
     "pc_act_pool_fwd", "pc_act_pool_bwd", "pc_pattern_select_batch", "pc_pack_batch", "pc_update_values_batch",
-    "pc_dppg_accumulate_batch", "pc_finalize_count_batch", "pc_finalize_pick_batch", "pc_group_lasso_grad_batch", "pc_conv_bwd_weight_batch",
+    "pc_dppg_accumulate_batch", "pc_finalize_count_batch", "pc_finalize_pick_batch", "pc_group_lasso_grad_batch", "pc_conv_bwd_weight_batch", "pc_conv_fwd_relu", "pc_conv_bwd_data_relu",
 ]
 
 
@@ -86,6 +86,8 @@ def load():
     lib.pc_pack_batch.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.pc_update_values_batch.argtypes = [vp, i32, vp, vp]
     lib.pc_conv_bwd_weight_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.pc_conv_fwd_relu.argtypes = [vp, vp, vp, vp, vp]
+    lib.pc_conv_bwd_data_relu.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.pc_dppg_accumulate_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.pc_finalize_count_batch.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     lib.pc_finalize_pick_batch.argtypes = [vp, i32, vp, vp, vp, i32, vp]
@@ -297,3 +299,11 @@ def pc_conv_bwd_weight_batch(ctx, descs, packs, x, dy, dw) -> None:
     darr = (pc_conv_desc * n)(*descs)
     _check(ctx, load().pc_conv_bwd_weight_batch(ctx, n, ct.cast(darr, ct.c_void_p), (ct.c_void_p * n)(*[int(p) for p in packs]),
                                                 _ptr_array(x), _ptr_array(dy), _ptr_array(dw)))
+
+
+def pc_conv_fwd_relu(ctx, desc, pk, x, a) -> None:
+    _check(ctx, load().pc_conv_fwd_relu(ctx, ct.byref(desc), pk, _ptr(x), _ptr(a)))
+
+
+def pc_conv_bwd_data_relu(ctx, desc, pk, dy, x, dx) -> None:
+    _check(ctx, load().pc_conv_bwd_data_relu(ctx, ct.byref(desc), pk, _ptr(dy), _ptr(x), _ptr(dx)))

@@ -197,3 +197,42 @@ extern "C" pc_status pc_act_pool_bwd(pc_ctx *ctx, const void *da, const uint8_t 
     }
     return pc_hip_check(ctx, hipGetLastError(), "activation + pooling backward launch");
 }
+
+// ------------------------------------------------------------------ ReLU alone, in place
+// z = relu(z); and dz = dz where a > 0, else +0 (the ReLU derivative read from the activation itself: a > 0 exactly
+// where z > 0). Used where a conv launch cannot apply the step itself.
+template <typename T, int VEC, bool MASK>
+__global__ void __launch_bounds__(AP_BLOCK) pc_relu_kernel(T *__restrict__ z, const T *__restrict__ a, int64_t nv)
+{
+    typedef ApVec<T, VEC> V;
+    const int64_t i = (int64_t)blockIdx.x * AP_BLOCK + threadIdx.x;
+    if (i >= nv) return;
+    V v = reinterpret_cast<V *>(z)[i];
+    V m = v;
+    if (MASK) m = reinterpret_cast<const V *>(a)[i];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) v.e[j] = ap_value(m.e[j]) > 0.0f ? v.e[j] : (T)0;
+    reinterpret_cast<V *>(z)[i] = v;
+}
+
+template <bool MASK>
+static pc_status ap_launch_relu(pc_ctx *ctx, void *z, const void *a, int64_t n, pc_dtype dtype)
+{
+    if (n <= 0) return PC_OK;
+    if (ap_too_large(n)) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "ReLU: tensor too large");
+    const int vec = dtype == PC_BF16 ? 8 : 4;
+    const bool wide = n % vec == 0 && ap_aligned16(z) && (!MASK || ap_aligned16(a));
+    const int64_t nv = wide ? n / vec : n;
+    const dim3 grid((unsigned)((nv + AP_BLOCK - 1) / AP_BLOCK));
+    if (dtype == PC_BF16) {
+        if (wide) hipLaunchKernelGGL((pc_relu_kernel<uint16_t, 8, MASK>), grid, dim3(AP_BLOCK), 0, ctx->stream, (uint16_t *)z, (const uint16_t *)a, nv);
+        else hipLaunchKernelGGL((pc_relu_kernel<uint16_t, 1, MASK>), grid, dim3(AP_BLOCK), 0, ctx->stream, (uint16_t *)z, (const uint16_t *)a, nv);
+    } else {
+        if (wide) hipLaunchKernelGGL((pc_relu_kernel<float, 4, MASK>), grid, dim3(AP_BLOCK), 0, ctx->stream, (float *)z, (const float *)a, nv);
+        else hipLaunchKernelGGL((pc_relu_kernel<float, 1, MASK>), grid, dim3(AP_BLOCK), 0, ctx->stream, (float *)z, (const float *)a, nv);
+    }
+    return pc_hip_check(ctx, hipGetLastError(), "ReLU launch");
+}
+
+pc_status pc_launch_relu(pc_ctx *ctx, void *z, int64_t n, pc_dtype dtype) { return ap_launch_relu<false>(ctx, z, nullptr, n, dtype); }
+pc_status pc_launch_relu_mask(pc_ctx *ctx, void *dz, const void *a, int64_t n, pc_dtype dtype) { return ap_launch_relu<true>(ctx, dz, a, n, dtype); }

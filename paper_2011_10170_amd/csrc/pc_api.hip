@@ -5,6 +5,7 @@
 #include <new>
 
 #include "pc_internal.h"
+#include "pc_mfma.h"
 
 #include <vector>
 
@@ -487,6 +488,31 @@ extern "C" pc_status pc_conv_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const 
     pc_status s = check_conv(ctx, "pc_conv_bwd_data", d, pk, dy, dx, dx);
     if (s != PC_OK) return s;
     return pk->variant == PC_VARIANT_MFMA ? pc_mfma_bwd_data(ctx, d, pk, dy, dx) : pc_valu_bwd_data(ctx, d, pk, dy, dx);
+}
+
+extern "C" pc_status pc_conv_fwd_relu(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *a)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    pc_status s = check_conv(ctx, "pc_conv_fwd_relu", d, pk, x, a, a);
+    if (s != PC_OK) return s;
+    bool fused = false;
+    s = pk->variant == PC_VARIANT_MFMA ? pc_mfma_fwd(ctx, d, pk, x, a, PC_ACT_RELU, &fused) : pc_valu_fwd(ctx, d, pk, x, a);
+    if (s != PC_OK || fused) return s;
+    const int64_t n = (int64_t)d->N * ((d->H - 1) / d->stride + 1) * ((d->W - 1) / d->stride + 1) * d->F;
+    return pc_launch_relu(ctx, a, n, d->dtype);
+}
+
+extern "C" pc_status pc_conv_bwd_data_relu(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, const void *x,
+                                           void *dx)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    pc_status s = check_conv(ctx, "pc_conv_bwd_data_relu", d, pk, dy, x, dx);
+    if (s != PC_OK) return s;
+    bool fused = false;
+    s = pk->variant == PC_VARIANT_MFMA ? pc_mfma_bwd_data(ctx, d, pk, dy, dx, PC_ACT_RELU_MASK, x, &fused)
+                                       : pc_valu_bwd_data(ctx, d, pk, dy, dx);
+    if (s != PC_OK || fused) return s;
+    return pc_launch_relu_mask(ctx, dx, x, (int64_t)d->N * d->H * d->W * d->C, d->dtype);
 }
 
 extern "C" pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,

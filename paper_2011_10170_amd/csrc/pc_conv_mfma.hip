@@ -379,9 +379,14 @@ static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, bool classes, cons
 // g holds everything but the tile plan; ext = reach of the tap offsets (3 or 2); tap rows/cols in tr/tc.
 // With pcl (stride-2 backward-data) the launch covers the four parity classes: g.GH/GW are the largest class
 // extents, ntaps = 4, and tr/tc are unused.
+// act / act_mask / fused: a fused activation step (PC_ACT_*) is applied when the wave-specialised kernel takes the
+// launch and writes the output tensor itself; *fused then becomes true. Otherwise the plain conv runs and the caller
+// applies the step.
 static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, const int *tr, const int *tc,
-                               const uint16_t *in, uint16_t *out, const uint16_t *wz, const ParityClasses *pcl = nullptr)
+                               const uint16_t *in, uint16_t *out, const uint16_t *wz, const ParityClasses *pcl = nullptr,
+                               int act = PC_ACT_NONE, const uint16_t *act_mask = nullptr, bool *fused = nullptr)
 {
+    g.act_mask = nullptr;
     int plan_cfg = (ctx->plan_cfg >= 10 && ctx->plan_cfg < 13) ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
     if (ntaps == 9 && (plan_cfg < 0 || plan_cfg >= 7) && ctx->plan_split == 0) {
         // The wave-specialised kernel reads and writes whole groups of 8 channels. The first layer's few channels
@@ -409,9 +414,12 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
         }
         if ((gw.in_CH & 7) == 0 && (gw.in_CH >= 32 || pad_in)) {
             bool launched = false;
-            pc_status s = pc_run_mfma_conv_ws(ctx, plan_cfg, gw, ext, tr, tc, inw, outw, wz, &launched);
+            const int act_here = (fused && !pad_out) ? act : PC_ACT_NONE;
+            gw.act_mask = act_here == PC_ACT_RELU_MASK ? act_mask : nullptr;
+            pc_status s = pc_run_mfma_conv_ws(ctx, plan_cfg, gw, ext, tr, tc, inw, outw, wz, &launched, act_here);
             if (s != PC_OK) return s;
             if (launched) {
+                if (fused) *fused = act_here != PC_ACT_NONE;
                 if (pad_out) pc_launch_unpad_channels(ctx, outw, out, out_pix, g.out_CH);
                 return pc_hip_check(ctx, hipGetLastError(), "channel copy launch");
             }
@@ -507,7 +515,7 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
     return pc_hip_check(ctx, hipGetLastError(), "split-K reduce launch");
 }
 
-pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y)
+pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y, int act, bool *fused)
 {
     MfmaArgs g;
     memset(&g, 0, sizeof(g));
@@ -519,10 +527,11 @@ pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, c
     g.KS = pk->v.Ck / 16;
     int tr[9], tc[9];
     for (int t = 0; t < 9; ++t) { g.tap_w[t] = t; tr[t] = t / 3; tc[t] = t % 3; }
-    return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)x, (uint16_t *)y, pk->v.wz_fwd);
+    return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)x, (uint16_t *)y, pk->v.wz_fwd, nullptr, act, nullptr, fused);
 }
 
-pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx)
+pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx, int act,
+                           const void *act_mask, bool *fused)
 {
     MfmaArgs g;
     memset(&g, 0, sizeof(g));
@@ -535,7 +544,8 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
     if (st == 1) {
         g.GH = d->H; g.GW = d->W; g.oscale = 1; g.ioff_y = g.ioff_x = -1;
         for (int t = 0; t < 9; ++t) { g.tap_w[t] = t; tr[t] = 2 - t / 3; tc[t] = 2 - t % 3; }
-        return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd);
+        return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd, nullptr, act,
+                             (const uint16_t *)act_mask, fused);
     }
     // stride 2: input pixel (iy, ix) of parity class (py, px) = (iy % 2, ix % 2) receives the taps (r, s) with
     // (py + 1 - r) and (px + 1 - s) even, from output pixel ((iy + 1 - r) / 2, (ix + 1 - s) / 2). One launch takes

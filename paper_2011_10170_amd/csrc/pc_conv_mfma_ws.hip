@@ -32,7 +32,23 @@ constexpr int pc_ring_depth(int nf, int cap)
     return best;
 }
 
-template <int A_T, int B_T, int NTAPS, int KC, int KSP>
+// Two bf16 values in a word: each one that is negative (or -0) becomes +0.
+__device__ __forceinline__ uint32_t pc_relu_bf16x2(uint32_t u)
+{
+    return u & ~(((u & 0x80008000u) >> 15) * 0xFFFFu);
+}
+
+// Two bf16 values in a word: each one is kept where the matching value of a is positive, else +0.
+__device__ __forceinline__ uint32_t pc_mask_bf16x2(uint32_t u, uint32_t a)
+{
+    const uint32_t lo = ((a & 0xFFFFu) - 1u) < 0x7FFFu ? 0x0000FFFFu : 0u;   // sign clear and not zero
+    const uint32_t hi = ((a >> 16) - 1u) < 0x7FFFu ? 0xFFFF0000u : 0u;
+    return u & (lo | hi);
+}
+
+// ACT: PC_ACT_NONE, or a fused step on the stored values: PC_ACT_RELU (negative outputs become +0) or
+// PC_ACT_RELU_MASK (outputs are kept where g.act_mask, a tensor of the output's shape, is positive).
+template <int A_T, int B_T, int NTAPS, int KC, int KSP, int ACT = PC_ACT_NONE>
 __global__ void __launch_bounds__(512, 1)
 pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const uint16_t *__restrict__ wz, MfmaArgs g)
 {
@@ -174,6 +190,9 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     const int o_x = qo - o_ti * g.TH * g.TW - o_y * g.TW;
 
     const __amdgpu_buffer_rsrc_t osrc = __builtin_amdgcn_make_buffer_rsrc(out, 0, g.out_bytes, 0x00020000);
+    // the mask tensor has the output's shape: it is read at the offsets the output is stored at (past the end: zeros)
+    const __amdgpu_buffer_rsrc_t msrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(ACT == PC_ACT_RELU_MASK ? g.act_mask : out), 0, g.out_bytes, 0x00020000);
     constexpr uint32_t OOB_OUT = 0x80000000u;
     // A fragments: buffer loads with the lane's 16 bytes as the vector offset and everything else in the scalar
     // offset. This kernel only runs the full 3x3 tap list in tap order (weight tap t at list position t), so
@@ -330,7 +349,15 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                     const bool ok = q < npix && n < g.N && gy < g.GH && gx < g.GW && m < g.out_CH && c16 < 4 * A_T;
                     const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
                     const uint32_t off = ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) + (uint32_t)(m * 2) : OOB_OUT;
-                    const v4u32 pv = {v.x, v.y, v.z, v.w};
+                    v4u32 pv = {v.x, v.y, v.z, v.w};
+                    if (ACT == PC_ACT_RELU) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) pv[e] = pc_relu_bf16x2(pv[e]);
+                    } else if (ACT == PC_ACT_RELU_MASK) {
+                        const v4u32 mk = __builtin_amdgcn_raw_buffer_load_b128(msrc, (int)off, 0, 0);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) pv[e] = pc_mask_bf16x2(pv[e], mk[e]);
+                    }
                     __builtin_amdgcn_raw_buffer_store_b128(pv, osrc, (int)off, 0, 0);
                 }
             }
@@ -366,8 +393,17 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                         uint2 pkd;
                         pkd.x = pc_pack_bf16x2(s.x, s.y);
                         pkd.y = pc_pack_bf16x2(s.z, s.w);
-                        const v2u32 pv = {pkd.x, pkd.y};
-                        __builtin_amdgcn_raw_buffer_store_b64(pv, osrc, (int)((m < g.out_CH ? opix_off : OOB_OUT) + (uint32_t)(m * 2)), 0, 0);
+                        v2u32 pv = {pkd.x, pkd.y};
+                        const int ooff = (int)((m < g.out_CH ? opix_off : OOB_OUT) + (uint32_t)(m * 2));
+                        if (ACT == PC_ACT_RELU) {
+                            pv[0] = pc_relu_bf16x2(pv[0]);
+                            pv[1] = pc_relu_bf16x2(pv[1]);
+                        } else if (ACT == PC_ACT_RELU_MASK) {
+                            const v2u32 mk = __builtin_amdgcn_raw_buffer_load_b64(msrc, ooff, 0, 0);
+                            pv[0] = pc_mask_bf16x2(pv[0], mk[0]);
+                            pv[1] = pc_mask_bf16x2(pv[1], mk[1]);
+                        }
+                        __builtin_amdgcn_raw_buffer_store_b64(pv, osrc, ooff, 0, 0);
                     }
                 }
             }
@@ -388,19 +424,28 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 // ---- wave-specialised kernel: plan and launch (9-tap launches whose channel count is a multiple of 8)
 #define KS_LDS_MAX (160 * 1024)
 
-template <int A_T, int B_T, int KC, int KSP>
-static hipError_t launch_ks(int device, hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out,
-                            const uint16_t *wz, const MfmaArgs &g)
+template <int A_T, int B_T, int KC, int KSP, int ACT>
+static hipError_t launch_ks_act(int device, hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out,
+                                const uint16_t *wz, const MfmaArgs &g)
 {
     static pc_per_device_once attr;
     if (pc_once_pending(attr, device)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP, ACT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, KS_LDS_MAX);
         if (e != hipSuccess) return e;
         pc_once_done(attr, device);
     }
-    hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
+    hipLaunchKernelGGL((pc_mfma_conv_ks_kernel<A_T, B_T, 9, KC, KSP, ACT>), dim3((unsigned)grid), dim3(512), lds, st, in, out, wz, g);
     return hipGetLastError();
+}
+
+template <int A_T, int B_T, int KC, int KSP>
+static hipError_t launch_ks(int device, hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out,
+                            const uint16_t *wz, const MfmaArgs &g, int act)
+{
+    if (act == PC_ACT_RELU) return launch_ks_act<A_T, B_T, KC, KSP, PC_ACT_RELU>(device, st, grid, lds, in, out, wz, g);
+    if (act == PC_ACT_RELU_MASK) return launch_ks_act<A_T, B_T, KC, KSP, PC_ACT_RELU_MASK>(device, st, grid, lds, in, out, wz, g);
+    return launch_ks_act<A_T, B_T, KC, KSP, PC_ACT_NONE>(device, st, grid, lds, in, out, wz, g);
 }
 
 // Fills the tile plan; false when the staged tile does not fit. ksp = 4: the MFMA wavefronts split the
@@ -475,7 +520,7 @@ static bool plan_ks(const MfmaArgs &g, int ext, int at, int bt, int ksp, int kc,
 
 // PC_OK: launched. PC_ERR_UNSUPPORTED without a message: not applicable, the caller uses the other kernel.
 pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext, const int *tr, const int *tc,
-                              const uint16_t *in, uint16_t *out, const uint16_t *wz, bool *launched)
+                              const uint16_t *in, uint16_t *out, const uint16_t *wz, bool *launched, int act)
 {
     *launched = false;
     // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
@@ -513,18 +558,18 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
     const int grid = g.total_tiles < ctx->num_cu ? g.total_tiles : ctx->num_cu;
     hipError_t e;
     switch (best_k) {
-    case 0: e = launch_ks<2, 4, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 1: e = launch_ks<2, 2, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 2: e = launch_ks<2, 1, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 3: e = launch_ks<2, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 4: e = launch_ks<2, 1, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 5: e = launch_ks<1, 1, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 6: e = launch_ks<2, 2, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 7: e = launch_ks<2, 4, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 8: e = launch_ks<2, 2, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 9: e = launch_ks<1, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    case 10: e = launch_ks<2, 2, 64, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
-    default: e = launch_ks<2, 2, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g); break;
+    case 0: e = launch_ks<2, 4, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 1: e = launch_ks<2, 2, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 2: e = launch_ks<2, 1, 64, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 3: e = launch_ks<2, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 4: e = launch_ks<2, 1, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 5: e = launch_ks<1, 1, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 6: e = launch_ks<2, 2, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 7: e = launch_ks<2, 4, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 8: e = launch_ks<2, 2, 16, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 9: e = launch_ks<1, 4, 32, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    case 10: e = launch_ks<2, 2, 64, 1>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
+    default: e = launch_ks<2, 2, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
     }
     *launched = true;
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");

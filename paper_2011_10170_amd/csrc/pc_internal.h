@@ -131,8 +131,15 @@ pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, int64
                                  const pc_packed *pk, float *dw);
 
 bool pc_mfma_supports(int F, int C);
-pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y);
-pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx);
+// act (PC_ACT_* of pc_mfma.h, 0 = none), act_mask, fused: a ReLU step fused into the launch when the kernel that takes
+// it can; *fused tells whether it was (fused == nullptr: never).
+pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y, int act = 0,
+                      bool *fused = nullptr);
+pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx, int act = 0,
+                           const void *act_mask = nullptr, bool *fused = nullptr);
+// In-place ReLU of n elements; and in-place "keep where the matching element of a is positive, else +0".
+pc_status pc_launch_relu(pc_ctx *ctx, void *z, int64_t n, pc_dtype dtype);
+pc_status pc_launch_relu_mask(pc_ctx *ctx, void *dz, const void *a, int64_t n, pc_dtype dtype);
 pc_status pc_mfma_bwd_weight_group(pc_ctx *ctx, int n, const pc_conv_desc *d, const pc_packed *const *pk, const void *const *x,
                                    const void *const *dy, float *const *dw);
 pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,

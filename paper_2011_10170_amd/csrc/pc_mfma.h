@@ -33,7 +33,13 @@ struct MfmaArgs {
     int32_t tap_o0, tap_dr, tap_ds; // LDS byte offset of tap 3r+s = tap_o0 + r*tap_dr + s*tap_ds
     // divisions by these run as a multiply-high with floor(2^32 / d) + 1 (exact while dividend * d < 2^32)
     uint32_t mg_IW, mg_IH, mg_TW, mg_THTW, mg_fd, mg_tx, mg_ty;
+    // wave-specialised kernel with a fused activation step: a tensor of the output's shape whose positive elements
+    // let the output through (the ReLU derivative of the backward pass); unused otherwise
+    const uint16_t *act_mask;
 };
+
+// Fused step at the end of a conv launch (Section 5.2: a = sigma(z) forward, the error times sigma'(z) backward).
+enum { PC_ACT_NONE = 0, PC_ACT_RELU = 1, PC_ACT_RELU_MASK = 2 };
 
 // q / d with mg = floor(2^32 / d) + 1 from the host (exact while q * d < 2^32); mg == 0 stands for d == 1
 __device__ __forceinline__ uint32_t pc_udiv(uint32_t q, uint32_t mg) { return mg ? __umulhi(q, mg) : q; }
@@ -45,7 +51,7 @@ void pc_plan_mfma_tiles(MfmaArgs *g, int BN, int ext);
 // Wave-specialised forward/backward-data kernel for full 3x3 tap lists. pcfg: -1 = take it when the plan says it
 // wins, >= 7 = the forced variant. *launched stays false when the launch is left to the cooperative kernel.
 pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext, const int *tr, const int *tc,
-                              const uint16_t *in, uint16_t *out, const uint16_t *wz, bool *launched);
+                              const uint16_t *in, uint16_t *out, const uint16_t *wz, bool *launched, int act = PC_ACT_NONE);
 
 // Copies between a tensor with C < 8 channels per pixel and one with 8-channel (16-byte) pixel rows.
 void pc_launch_pad_channels(pc_ctx *ctx, const uint16_t *x, void *xp, int64_t npix, int C, int Cp);

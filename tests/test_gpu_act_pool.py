@@ -225,3 +225,76 @@ def test_three_layer_chain_f32(B, ctx, T, oracle):
     assert rel_l2(gd.cpu().numpy(), ref_dx0) <= 1e-4
     for pk in packs:
         B.pc_packed_free(pk)
+
+
+FUSED_LAYERS = [I.Layer(4, 8, 8, 64, 64, 1), I.Layer(2, 9, 7, 128, 96, 1), I.Layer(3, 6, 6, 3, 64, 1), I.Layer(3, 6, 6, 64, 3, 1),
+                I.Layer(2, 9, 9, 64, 64, 2), I.Layer(2, 5, 5, 40, 72, 1)]
+
+
+@pytest.mark.parametrize("layer", FUSED_LAYERS)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_conv_with_fused_relu_equals_the_two_calls(B, ctx, T, oracle, layer, dtype):
+    """pc_conv_fwd_relu and pc_conv_bwd_data_relu against pc_conv_fwd / pc_conv_bwd_data followed by the ReLU step on
+    the stored values (bit for bit: the step only zeroes elements), and against the oracle chain within the conv
+    tolerance. Layers the fused kernels take, and layers that fall back to a second launch (3 channels out,
+    stride-2 backward, float32)."""
+    import torch
+    from tests._harness import Case, GpuLayer, oracle_masks, rel_l2, from_dev_f32
+    case = Case(layer, dtype, 8, I.kept_per_filter(0.4, layer.C), tag=("fused", layer.C, layer.F, layer.stride))
+    g = GpuLayer(B, ctx, case)
+    try:
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        L = layer
+        y = torch.empty((L.N, L.Ho, L.Wo, L.F), dtype=tdt, device="cuda")
+        a = torch.full_like(y, float("nan"))
+        B.pc_conv_fwd(ctx, g.desc, g.pk, g.x, y)
+        B.pc_conv_fwd_relu(ctx, g.desc, g.pk, g.x, a)
+        torch.cuda.synchronize()
+        want = torch.where(y > 0, y, torch.zeros_like(y))
+        assert torch.equal(a.view(torch.int16 if dtype == "bf16" else torch.int32), want.view(torch.int16 if dtype == "bf16" else torch.int32))
+        pid, kp, M, Wm = oracle_masks(oracle, case)
+        ref = np.maximum(oracle.conv_fwd(case.x, Wm, L.stride), 0)
+        assert rel_l2(from_dev_f32(a), ref) <= (2e-2 if dtype == "bf16" else 1e-4)
+        # backward: the mask is this layer's input; once as it is (post-ReLU: zeros and positives), once with negatives
+        dx = torch.empty((L.N, L.H, L.W, L.C), dtype=tdt, device="cuda")
+        B.pc_conv_bwd_data(ctx, g.desc, g.pk, g.dy, dx)
+        for mask in (g.x, (g.x.float() - 0.3).to(tdt)):
+            dz = torch.full_like(dx, float("nan"))
+            B.pc_conv_bwd_data_relu(ctx, g.desc, g.pk, g.dy, mask, dz)
+            torch.cuda.synchronize()
+            want = torch.where(mask > 0, dx, torch.zeros_like(dx))
+            assert torch.equal(dz.view(torch.int16 if dtype == "bf16" else torch.int32),
+                               want.view(torch.int16 if dtype == "bf16" else torch.int32))
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("cfg", [7, 8, 9, 13, 14, 15, 16, 19, 20, 21])
+def test_fused_relu_in_every_tile_configuration(B, ctx, cfg):
+    """The fused step in both store paths of the wave-specialised kernel (reduction split and pixel split) and
+    every tile shape: bit-identical to the plain launch of the same configuration followed by the step."""
+    import torch
+    from tests._harness import Case, GpuLayer
+    layer = I.Layer(6, 10, 9, 128, 160, 1)
+    case = Case(layer, "bf16", 8, I.kept_per_filter(0.3, layer.C), tag=("fused_cfg", cfg))
+    g = GpuLayer(B, ctx, case)
+    try:
+        B.pc_set_plan_override(ctx, cfg, 0)
+        L = layer
+        y = torch.empty((L.N, L.Ho, L.Wo, L.F), dtype=torch.bfloat16, device="cuda")
+        a = torch.full_like(y, float("nan"))
+        dx = torch.empty((L.N, L.H, L.W, L.C), dtype=torch.bfloat16, device="cuda")
+        dz = torch.full_like(dx, float("nan"))
+        try:
+            B.pc_conv_fwd(ctx, g.desc, g.pk, g.x, y)
+        except B.PcError:
+            pytest.skip("this configuration does not take the layer")
+        B.pc_conv_fwd_relu(ctx, g.desc, g.pk, g.x, a)
+        B.pc_conv_bwd_data(ctx, g.desc, g.pk, g.dy, dx)
+        B.pc_conv_bwd_data_relu(ctx, g.desc, g.pk, g.dy, g.x, dz)
+        torch.cuda.synchronize()
+        assert torch.equal(a.view(torch.int16), torch.where(y > 0, y, torch.zeros_like(y)).view(torch.int16))
+        assert torch.equal(dz.view(torch.int16), torch.where(g.x > 0, dx, torch.zeros_like(dx)).view(torch.int16))
+    finally:
+        B.pc_set_plan_override(ctx, -1, 0)
+        g.close()
