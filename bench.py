@@ -422,19 +422,25 @@ def main() -> int:
             last = layers[-1]
             da_last = up(I.gen_activations(tuple(last["a"].shape), I.BASE_SEED, (wl.name, "chain_da"), False, wl.dtype)[1])
 
-            def chain_step(side):
+            def chain_step(side, fuse=False):
+                # fuse: where no pooling follows a layer, its ReLU runs inside the conv launch (pc_conv_fwd_relu) and
+                # its derivative inside the next layer's backward-data launch (pc_conv_bwd_data_relu)
                 xin = layers[0]["x"]
                 for d in layers:
                     L = d["L"]
-                    B.pc_conv_fwd(ctx, d["desc"], d["pk"], xin, d["y"])
-                    B.pc_act_pool_fwd(ctx, d["y"], L.N, L.Ho, L.Wo, L.F, dt, d["pool"], d["a"], d["sel"])
+                    if fuse and d["pool"] == 1 and d is not layers[-1]:
+                        B.pc_conv_fwd_relu(ctx, d["desc"], d["pk"], xin, d["a"])
+                    else:
+                        B.pc_conv_fwd(ctx, d["desc"], d["pk"], xin, d["y"])
+                        B.pc_act_pool_fwd(ctx, d["y"], L.N, L.Ho, L.Wo, L.F, dt, d["pool"], d["a"], d["sel"])
                     d["xin"] = xin
                     xin = d["a"]
-                da = da_last
+                # the error of the last layer's output through its ReLU / pooling; d["dy"] holds a layer's dz from here on
+                last_d = layers[-1]
+                B.pc_act_pool_bwd(ctx, da_last, last_d["sel"], last_d["L"].N, last_d["L"].Ho, last_d["L"].Wo, last_d["L"].F, dt,
+                                  last_d["pool"], last_d["dy"])
                 for li in range(nl - 1, -1, -1):
                     d = layers[li]
-                    L = d["L"]
-                    B.pc_act_pool_bwd(ctx, da, d["sel"], L.N, L.Ho, L.Wo, L.F, dt, d["pool"], d["dy"])   # d["dy"] reused as dz
                     if side == "group":
                         pass                                                         # all weight gradients at the end
                     elif side:
@@ -443,20 +449,25 @@ def main() -> int:
                     else:
                         B.pc_conv_bwd_weight(ctx, d["desc"], d["pk"], d["xin"], d["dy"], d["dw"])
                     if li > 0:
-                        B.pc_conv_bwd_data(ctx, d["desc"], d["pk"], d["dy"], d["dx"])
-                        da = d["dx"]
+                        prev = layers[li - 1]
+                        Lp = prev["L"]
+                        if fuse and prev["pool"] == 1:
+                            B.pc_conv_bwd_data_relu(ctx, d["desc"], d["pk"], d["dy"], d["xin"], prev["dy"])
+                        else:
+                            B.pc_conv_bwd_data(ctx, d["desc"], d["pk"], d["dy"], d["dx"])
+                            B.pc_act_pool_bwd(ctx, d["dx"], prev["sel"], Lp.N, Lp.Ho, Lp.Wo, Lp.F, dt, prev["pool"], prev["dy"])
                 if side == "group":
                     B.pc_conv_bwd_weight_batch(ctx, [d["desc"] for d in layers], [d["pk"] for d in layers],
                                                [d["xin"] for d in layers], [d["dy"] for d in layers], [d["dw"] for d in layers])
                 elif side:
                     stream.wait_stream(streams_w[0])
 
-            def time_chain(side):
-                chain_step(side)
+            def time_chain(side, fuse=False):
+                chain_step(side, fuse)
                 torch.cuda.synchronize()
                 gch = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(gch, stream=stream):
-                    chain_step(side)
+                    chain_step(side, fuse)
                 for _ in range(3):
                     gch.replay()
                 torch.cuda.synchronize()
@@ -466,7 +477,8 @@ def main() -> int:
                 torch.cuda.synchronize()
                 return (time.perf_counter() - t0c) * 1e3 / args.steps
 
-            ms_by_streams = {1: time_chain(False), "1, weight gradients grouped": time_chain("group")}
+            ms_by_streams = {1: time_chain(False), "1, weight gradients grouped": time_chain("group"),
+                             "1, weight gradients grouped, ReLU fused": time_chain("group", True)}
             if ctxs_w:
                 ms_by_streams[2] = time_chain(True)
             finite = bool(torch.isfinite(layers[0]["dw"]).all().item()) and bool(torch.isfinite(last["a"].float()).all().item())
@@ -495,13 +507,13 @@ def main() -> int:
             us_act = e0.elapsed_time(e1) * 1e3 / 10
             by_act = sum(2 * (d["act_out"] + d["a"].numel() * (esz + 1)) for d in layers)
             chained = {"ms_per_step": round(ms_chain, 4), "value": round(fl_chain / (ms_chain * 1e-3) / 1e12, 4), "unit": "TFLOP/s",
-                       "calls": "%d fwd + %d act_pool_fwd + %d act_pool_bwd + %d bwd_weight + %d bwd_data" % (nl, nl, nl, nl, nl - 1),
+                       "passes": "%d fwd + %d bwd_weight + %d bwd_data, ReLU / pooling between the layers" % (nl, nl, nl - 1),
                        "streams": n_str, "ms_per_step_by_streams": {str(k): round(v, 4) for k, v in ms_by_streams.items()},
                        "finite": finite,
                        "act_pool_us": round(us_act, 1), "act_pool_gbs": round(by_act / us_act / 1e3, 1),
                        "act_pool_hbm_frac": round(by_act / us_act / 1e3 / PEAK_HBM_GBS, 4)}
-            log("chained network: %.4f ms per step (%.1f nonzero TFLOP/s over %d calls, stream(s): %s); ReLU/pool calls alone "
-                "%.1f us (%.0f GB/s algorithmic)" % (ms_chain, chained["value"], 5 * nl - 1, chained["streams"], us_act, by_act / us_act / 1e3))
+            log("chained network: %.4f ms per step (%.1f nonzero TFLOP/s; %s); all ReLU/pool calls alone "
+                "%.1f us (%.0f GB/s algorithmic)" % (ms_chain, chained["value"], chained["streams"], us_act, by_act / us_act / 1e3))
             torch.cuda.synchronize()
 
     # ---- the training-side steps over the same layers (one graph of all layers per step kind), HBM-bound
