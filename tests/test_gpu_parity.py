@@ -696,6 +696,35 @@ def test_bwd_weight_batch_full_size(B, ctx, workload):
             B.pc_packed_free(pk)
 
 
+def test_bwd_weight_batch_of_more_layers_than_one_launch_takes(B, ctx, oracle):
+    """23 layers (a launch takes 20, and so does the grouped reduction): every layer within tolerance of its own call
+    and of the oracle."""
+    import torch
+    rng = np.random.default_rng(91)
+    gs, cases = [], []
+    try:
+        for li in range(23):
+            C, F = int(rng.choice([8, 16, 40, 64])), int(rng.choice([8, 24, 64, 72]))
+            layer = I.Layer(int(rng.choice([2, 8, 16])), int(rng.choice([3, 4, 8])), int(rng.choice([3, 4, 8])), C, F, 1)
+            case = Case(layer, "bf16", 8, I.kept_per_filter(0.5, C), tag=("wgb23", li))
+            cases.append(case)
+            gs.append(GpuLayer(B, ctx, case))
+        refs = []
+        for g in gs:
+            refs.append(g.bwd_weight()[1].body.clone())
+        outs = [torch.full((g.nnzk, 4), float("nan"), dtype=torch.float32, device="cuda") for g in gs]
+        B.pc_conv_bwd_weight_batch(ctx, [g.desc for g in gs], [g.pk for g in gs], [g.x for g in gs], [g.dy for g in gs], outs)
+        torch.cuda.synchronize()
+        for li, (g, case, o, r) in enumerate(zip(gs, cases, outs, refs)):
+            assert torch.isfinite(o).all(), li
+            assert rel_l2(o.cpu().numpy(), r.cpu().numpy()) <= 1e-5, li
+            pid, kp, M, Wm = oracle_masks(oracle, case)
+            assert rel_l2(g.scatter(o), oracle.conv_bwd_weight(case.x, case.dy, M, 1)) <= 1e-4, li
+    finally:
+        for g in gs:
+            g.close()
+
+
 def test_mismatched_descriptor_is_rejected(B, ctx, oracle):
     layer = I.Layer(1, 4, 4, 8, 8, 1)
     case = Case(layer, "f32", 4, 4, tag="mismatch")
