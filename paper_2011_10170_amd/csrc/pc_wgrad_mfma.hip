@@ -853,6 +853,11 @@ pc_status pc_mfma_bwd_weight_group(pc_ctx *ctx, int n, const pc_conv_desc *d, co
     for (Item &it : items) {
         int64_t ks = (it.a.n_ktiles + share - 1) / share;
         if (ks < 1) ks = 1;
+        // split counts the XCD-aware re-reading of the workgroup index can use: a multiple of 8, or a divisor of 8
+        // (resnet50_imagenet: 317 us against 339 us with arbitrary counts; within 1 % elsewhere)
+        if (ks >= 8) ks = (ks + 7) / 8 * 8;
+        else if (ks > 4) ks = 8;
+        else if (ks == 3) ks = 4;
         if (ks < it.a.ksplit) it.a.ksplit = (int32_t)ks;
         it.part_off = total;
         if (it.a.ksplit > 1) total += (sizeof(float) * 4 * (size_t)it.a.ksplit * (size_t)it.nslots + 255) / 256 * 256;
