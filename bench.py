@@ -59,9 +59,10 @@ def main() -> int:
     ap.add_argument("--no-batch-prep", action="store_true",
                     help="select and pack layer by layer (pc_pattern_select, pc_pack) instead of all layers per launch "
                          "(pc_pattern_select_batch, pc_pack_batch)")
-    ap.add_argument("--chained", action="store_true",
-                    help="also time the layers as one network (VGG workloads): forward through every layer with ReLU and "
-                         "2x2 max pooling between them (pc_act_pool_fwd), then backward in reverse order")
+    ap.add_argument("--chained", action="store_true", help="(the default where the workload is a chain of layers; kept for old command lines)")
+    ap.add_argument("--no-chained", action="store_true",
+                    help="skip the second measurement of a VGG workload: its layers as one network, forward through every "
+                         "layer with ReLU and 2x2 max pooling between them, then backward in reverse order")
     ap.add_argument("--train-steps", action="store_true",
                     help="also time pool generation, finalisation counters and the group-lasso gradient over the workload's layers")
     args = ap.parse_args()
@@ -405,11 +406,12 @@ def main() -> int:
     # max pooling where the next map is half the size), the backward pass runs in reverse order; bwd_weight of a
     # layer is forked to the side stream once its error tensor exists. No gradient reaches the network's input.
     chained = None
-    if args.chained:
+    if not args.no_chained and len(wl.layers) > 1:
         ok = all(L.stride == 1 for L in wl.layers) and all(
             (b.C == a.F and b.H in (a.Ho, a.Ho // 2) and b.N == a.N) for a, b in zip(wl.layers, wl.layers[1:]))
         if not ok:
-            log("--chained: workload %s is not a plain chain of stride-1 layers, skipped" % wl.name)
+            if args.chained:
+                log("--chained: workload %s is not a plain chain of stride-1 layers, skipped" % wl.name)
         else:
             nl = len(layers)
             for li, d in enumerate(layers):
