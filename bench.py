@@ -479,10 +479,10 @@ def main() -> int:
                 torch.cuda.synchronize()
                 return (time.perf_counter() - t0c) * 1e3 / args.steps
 
-            ms_by_streams = {1: time_chain(False), "1, weight gradients grouped": time_chain("group"),
-                             "1, weight gradients grouped, ReLU fused": time_chain("group", True)}
+            ms_by_streams = {"per layer, one stream": time_chain(False), "weight gradients grouped": time_chain("group"),
+                             "weight gradients grouped, ReLU fused": time_chain("group", True)}
             if ctxs_w:
-                ms_by_streams[2] = time_chain(True)
+                ms_by_streams["per layer, weight gradients on a side stream"] = time_chain(True)
             finite = bool(torch.isfinite(layers[0]["dw"]).all().item()) and bool(torch.isfinite(last["a"].float()).all().item())
             n_str, ms_chain = min(ms_by_streams.items(), key=lambda kv: kv[1])
             fl_chain = sum(3.0 * d["flops"] for d in layers) - layers[0]["flops"]
@@ -510,12 +510,12 @@ def main() -> int:
             by_act = sum(2 * (d["act_out"] + d["a"].numel() * (esz + 1)) for d in layers)
             chained = {"ms_per_step": round(ms_chain, 4), "value": round(fl_chain / (ms_chain * 1e-3) / 1e12, 4), "unit": "TFLOP/s",
                        "passes": "%d fwd + %d bwd_weight + %d bwd_data, ReLU / pooling between the layers" % (nl, nl, nl - 1),
-                       "streams": n_str, "ms_per_step_by_streams": {str(k): round(v, 4) for k, v in ms_by_streams.items()},
+                       "variant": n_str, "ms_per_step_by_variant": {str(k): round(v, 4) for k, v in ms_by_streams.items()},
                        "finite": finite,
                        "act_pool_us": round(us_act, 1), "act_pool_gbs": round(by_act / us_act / 1e3, 1),
                        "act_pool_hbm_frac": round(by_act / us_act / 1e3 / PEAK_HBM_GBS, 4)}
             log("chained network: %.4f ms per step (%.1f nonzero TFLOP/s; %s); all ReLU/pool calls alone "
-                "%.1f us (%.0f GB/s algorithmic)" % (ms_chain, chained["value"], chained["streams"], us_act, by_act / us_act / 1e3))
+                "%.1f us (%.0f GB/s algorithmic)" % (ms_chain, chained["value"], chained["variant"], us_act, by_act / us_act / 1e3))
             torch.cuda.synchronize()
 
     # ---- the training-side steps over the same layers (one graph of all layers per step kind), HBM-bound
