@@ -76,11 +76,10 @@ typedef struct {
  * (NULL = the default stream); all later work of this context is enqueued there.
  * Fails with PC_ERR_DEVICE when the device cannot be used.
  * A context owns one device scratch buffer (partial sums of split reductions, channel-padded copies of a
- * first layer's tensors). It grows when a call needs more than any call before: that call synchronises the
- * stream and reallocates with hipMalloc/hipFree. A HIP graph captured from calls on this context keeps the
- * scratch address of capture time: run every layer shape once before capturing (no allocation may happen
- * during capture, and a later growth would leave the graph with a freed address), or give a captured step a
- * context of its own. Calls on one context must not overlap (one stream, one scratch buffer). */
+ * first layer's tensors). It grows when a call needs more than any call before: that call allocates a larger
+ * buffer with hipMalloc and keeps the old one until pc_destroy, so work that is already enqueued, or captured in a
+ * HIP graph, keeps a valid address. No allocation may happen during a stream capture: run every layer shape once
+ * before capturing. Calls on one context must not overlap (one stream, one scratch buffer). */
 pc_status pc_create(pc_ctx **out, int device, void *hip_stream);
 void pc_destroy(pc_ctx *ctx);
 const char *pc_status_str(pc_status s);

@@ -115,6 +115,7 @@ extern "C" void pc_destroy(pc_ctx *ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->scratch) (void)hipFree(ctx->scratch);
+    for (int i = 0; i < ctx->n_retired; ++i) (void)hipFree(ctx->retired[i]);
     if (ctx->nnz_pinned) (void)hipHostFree(ctx->nnz_pinned);
     delete ctx;
 }
@@ -141,13 +142,20 @@ extern "C" pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t
 pc_status pc_scratch(pc_ctx *ctx, size_t bytes, void **out)
 {
     if (bytes > ctx->scratch_bytes) {
-        // earlier work on the stream may still read the old buffer
-        PC_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        if (ctx->scratch) PC_HIP(ctx, hipFree(ctx->scratch));
-        ctx->scratch = nullptr;
-        ctx->scratch_bytes = 0;
-        size_t want = bytes + bytes / 4 + (1u << 20);
-        PC_HIP(ctx, hipMalloc(&ctx->scratch, want));
+        // Work that is enqueued, or captured in a HIP graph, keeps the address it was given: the old buffer is not
+        // freed before pc_destroy (only when the list of old buffers is full: then after the stream has drained).
+        size_t want = bytes + bytes / 2 + (1u << 20);
+        void *fresh = nullptr;
+        PC_HIP(ctx, hipMalloc(&fresh, want));
+        if (ctx->scratch) {
+            if (ctx->n_retired < (int)(sizeof(ctx->retired) / sizeof(ctx->retired[0]))) {
+                ctx->retired[ctx->n_retired++] = ctx->scratch;
+            } else {
+                (void)hipStreamSynchronize(ctx->stream);
+                (void)hipFree(ctx->scratch);
+            }
+        }
+        ctx->scratch = fresh;
         ctx->scratch_bytes = want;
     }
     *out = ctx->scratch;

@@ -21,6 +21,8 @@ struct pc_ctx {
     // scratch owned by the context (grown on demand, never shrunk)
     void *scratch;
     size_t scratch_bytes;
+    void *retired[64];     // superseded scratch buffers, kept until pc_destroy: enqueued or captured work may still use them
+    int n_retired;
     int64_t *nnz_pinned;   // pinned host word for reading back a pack's kernel count
 };
 

@@ -725,6 +725,46 @@ def test_bwd_weight_batch_of_more_layers_than_one_launch_takes(B, ctx, oracle):
             g.close()
 
 
+def test_graph_survives_a_later_growth_of_the_scratch_buffer(B, oracle):
+    """A graph captured while the context's scratch buffer was small is replayed after a larger layer made the buffer
+    grow: the superseded buffer is kept until pc_destroy, so the replay gives the eager result."""
+    import torch
+    small = Case(I.Layer(8, 8, 8, 64, 64, 1), "bf16", 8, 19, tag="grow_small")
+    big = Case(I.Layer(16, 8, 8, 512, 512, 1), "bf16", 8, 154, tag="grow_big")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = B.pc_create(0, stream.cuda_stream)
+        gs = GpuLayer(B, ctx, small)
+        gb = GpuLayer(B, ctx, big)
+        try:
+            dw = torch.empty((gs.nnzk, 4), dtype=torch.float32, device="cuda")
+            B.pc_conv_bwd_weight(ctx, gs.desc, gs.pk, gs.x, gs.dy, dw)          # scratch reaches the small layer's size
+            stream.synchronize()
+            ref = dw.clone()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                B.pc_conv_bwd_weight(ctx, gs.desc, gs.pk, gs.x, gs.dy, dw)
+            dwb = torch.empty((gb.nnzk, 4), dtype=torch.float32, device="cuda")
+            # re-packed without a read-back of the count: the partial planes are strided by the capacity, 4 x 512 x 512
+            # slots of 16 bytes, several times the small layer's need, so a larger buffer replaces the first
+            B.pc_pack(ctx, gb.W, gb.pid, gb.keep, 512, 512, big.lib, gb.dt, reuse=gb.pk)
+            B.pc_conv_bwd_weight(ctx, gb.desc, gb.pk, gb.x, gb.dy, dwb)
+            B.pc_conv_bwd_weight_batch(ctx, [gs.desc, gb.desc], [gs.pk, gb.pk], [gs.x, gb.x], [gs.dy, gb.dy],
+                                       [torch.empty_like(dw), torch.empty_like(dwb)])  # and a larger one again
+            stream.synchronize()
+            for rep in range(2):
+                dw.zero_()
+                graph.replay()
+                stream.synchronize()
+                assert torch.equal(dw, ref), rep
+            pid, kp, M, Wm = oracle_masks(oracle, big)
+            assert rel_l2(gb.scatter(dwb), oracle.conv_bwd_weight(big.x, big.dy, M, 1)) <= 1e-4
+        finally:
+            gs.close()
+            gb.close()
+            B.pc_destroy(ctx)
+
+
 def test_mismatched_descriptor_is_rejected(B, ctx, oracle):
     layer = I.Layer(1, 4, 4, 8, 8, 1)
     case = Case(layer, "f32", 4, 4, tag="mismatch")
