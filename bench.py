@@ -245,7 +245,7 @@ def main() -> int:
         if args.wgrad == "auto":
             # where the weight gradients run is a launch choice: try both placements for a few replays, keep the faster.
             # Every candidate first runs eagerly, so that each context's scratch buffer has its final size before
-            # any graph is captured (a growth would free the address earlier graphs were captured with).
+            # any graph is captured (no allocation may happen during a capture).
             cands = ["group", "layer"]
             for cand in cands:
                 mode["wgrad"] = cand
