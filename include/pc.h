@@ -9,7 +9,9 @@
  *   - Pointers named *_dev are caller-owned DEVICE memory on the context's GPU (for example a
  *     torch tensor's data_ptr()). The library never frees them and does not keep them after
  *     the stream-ordered work of the call has run. Pointers named *_host are HOST memory and
- *     are copied before the call returns.
+ *     are copied before the call returns. The calls that serve several layers at once take HOST arrays with one
+ *     entry per layer; those named *_dev_host hold device pointers (the array on the host, each entry a device
+ *     tensor as in the single-layer call).
  *   - pc_ctx and pc_packed are library-owned handles, released by pc_destroy / pc_packed_free
  *     (both accept NULL).
  *   - Work is enqueued on the context's HIP stream and is asynchronous to the host unless
