@@ -2,11 +2,13 @@
 """Benchmark of the pattern-sparse convolution hot path on one MI355X.
 
 One step = pc_conv_fwd + pc_conv_bwd_data + pc_conv_bwd_weight over every layer of the workload
-(plus pc_pattern_select + pc_pack per layer when the workload's step includes re-selection), on
+(plus pc_pattern_select + pc_pack over all layers when the workload's step includes re-selection), on
 seeded synthetic inputs already resident in HBM. Prints ONE JSON line on stdout; a per-layer table
-goes to stderr.
+goes to stderr. The default workload is the largest single-GPU configuration: the VGG-16 / ImageNet
+stack at batch 32 with re-selection and re-packing inside the step.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16_cifar] [--variant auto|valu|mfma]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16_imagenet] [--variant auto|valu|mfma]
+    python bench.py --sweep          # also: gather vs matrix-core kernels over keep ratios (the "sweep" object)
 """
 from __future__ import annotations
 
@@ -35,13 +37,18 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="vgg16_cifar")
+    ap.add_argument("--workload", default="vgg16_imagenet")
     ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--no-graph", action="store_true", help="enqueue every step from the host instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
-    ap.add_argument("--cpu-sample-batch", type=int, default=128)
+    ap.add_argument("--cpu-sample-batch", type=int, default=0,
+                    help="images per layer the CPU oracle is timed on (0: as many as take it about 15 s at 5 nonzero GFLOP/s)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time one bf16 layer over a range of keep ratios with the gather kernels and with the "
+                         "matrix-core kernels (the per-layer operator choice of Section 5.2 / 5.4); adds the 'sweep' object")
+    ap.add_argument("--sweep-shape", default="128,8,8,256,256,1", help="N,H,W,C,F,stride of the swept layer")
     ap.add_argument("--update-values", action="store_true",
                     help="re-gather the kept weights of every layer in the step (pc_update_values: the per-iteration conversion of Section 5.1)")
     ap.add_argument("--no-paper-context", action="store_true", help="skip the paper's demonstration layer (profiles of the workload alone)")
@@ -182,7 +189,8 @@ def main() -> int:
                 run_batch(which)
                 if events is not None:
                     e1.record(stream)
-                    events.append((-1, which, e0, e1))
+                    events.append((-1, which, e0, e1, {"select": "pc_pattern_select_batch", "pack": "pc_pack_batch",
+                                                       "update": "pc_update_values_batch"}[which]))
         elif prep_side:
             streams_w[0].wait_stream(stream)
             for d in layers:
@@ -212,7 +220,8 @@ def main() -> int:
                     run_pass(d, which)
                 if events is not None:
                     e1.record(stream)
-                    events.append((li, which, e0, e1))
+                    events.append((li, which, e0, e1, B.pc_last_kernel(ctx) if which in ("fwd", "bwd_data", "bwd_weight")
+                                   else {"select": "pc_pattern_select", "pack": "pc_pack", "update": "pc_update_values"}[which]))
         if wg == "group":
             if events is not None:
                 e0 = torch.cuda.Event(enable_timing=True)
@@ -221,7 +230,7 @@ def main() -> int:
             wgrad_batch(ctx, 0, len(layers))
             if events is not None:
                 e1.record(stream)
-                events.append((-1, "bwd_weight", e0, e1))
+                events.append((-1, "bwd_weight", e0, e1, B.pc_last_kernel(ctx)))
         if overlap:
             for s_w in streams_w:
                 stream.wait_stream(s_w)                # join: the step ends when every stream has drained
@@ -256,6 +265,7 @@ def main() -> int:
                 mode["wgrad"] = cand
                 graphs[cand] = capture()
             trial = {c: float("inf") for c in cands}
+            mode["trial_ms"] = trial
             for _ in range(2):                                  # alternate, keep each candidate's best
                 for cand in cands:
                     for _ in range(5):
@@ -287,111 +297,128 @@ def main() -> int:
     total_flops = sum(3.0 * d["flops"] for d in layers)
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-call durations inside the same step sequence (library kernels run on torch's current stream)
+    # ---- per-call durations inside the same step sequence (library kernels run on torch's current stream), and the
+    # kernel symbol that served each call (pc_last_kernel)
     events = []
     n_inst = max(3, min(args.steps, 10))
     for _ in range(n_inst):
         step(events)
     torch.cuda.synchronize()
     per_call = {}
-    for li, which, e0, e1 in events:
+    sym_of = {}
+    for li, which, e0, e1, sym in events:
         per_call.setdefault((li, which), []).append(e0.elapsed_time(e1))
-    kinds = {}
-    # roof = the call's roofline time / its measured time, roofline time = max(algorithmic bytes / HBM peak, issued
-    # flops / unit peak): issued flops are the dense zero-filled tile flops on the matrix-core kernels (bf16 peak) and
-    # the nonzero flops on the gather kernels (float32 vector peak); select and pack are priced by bytes alone
-    t_roof_sum = 0.0
-    t_sparse_sum = 0.0
-    t_meas_sum = 0.0
-    log("%-3s %-22s %-10s %-5s %9s %10s %10s %8s %6s" % ("#", "layer", "pass", "var", "us", "nz TF/s", "dense TF/s", "GB/s", "roof"))
+        sym_of[(li, which)] = sym
+    # Roofline time of a call = max(algorithmic bytes / HBM peak, nonzero flops / peak of the unit that multiplies):
+    # the method's own work, i.e. |in| + |out| + the kept weights, and 8*N*Ho*Wo*nnzk flops per pass -- never the
+    # zero-filled flops the matrix-core kernels issue (those give "mfma_util", reported beside it). The unit peak is
+    # the bf16 matrix rate for the matrix-core kernels and the float32 vector rate for the gather kernels; select
+    # and pack are priced by bytes alone.
+    calls = []
+    log("%-3s %-22s %-10s %9s %9s %8s %6s %6s  %s" % ("#", "layer", "pass", "us", "nz TF/s", "GB/s", "roof", "mfma", "kernel"))
     for (li, which), ts in sorted(per_call.items()):
         d = layers[li]
         L = d["L"]
         us = float(np.median(ts)) * 1e3
-        var = "mfma" if d["variant"] == B.PC_VARIANT_MFMA else "valu"
+        sym = sym_of[(li, which)]
         if which in ("select", "pack", "update"):
-            kind = which
             n_pos = sum(x["L"].F * x["L"].C for x in layers) if li < 0 else L.F * L.C   # li = -1: one call for all layers
-            byts = n_pos * (74 if which == "select" else 38 + 0.0)
+            byts = n_pos * (74.0 if which == "select" else 38.0)
             fl = dfl = 0.0
+            mfma = False
         elif li < 0:                                         # the weight gradients of all layers in one call
-            var = "mfma" if all(x["variant"] == B.PC_VARIANT_MFMA for x in layers) else "valu"
-            kind = "%s_%s" % (var, which)
+            mfma = all(x["variant"] == B.PC_VARIANT_MFMA for x in layers)
             fl, dfl = sum(x["flops"] for x in layers), sum(x["dense_flops"] for x in layers)
-            byts = sum(x["act_in"] + x["act_out"] + 16 * x["nnzk"] for x in layers)
+            byts = float(sum(x["act_in"] + x["act_out"] + 16 * x["nnzk"] for x in layers))
         else:
-            kind = "%s_%s" % (var, which)
+            mfma = d["variant"] == B.PC_VARIANT_MFMA
             fl, dfl = d["flops"], d["dense_flops"]
             wbytes = d["nnzk"] * (4 * esz + 2)
-            if which == "fwd":
-                byts = d["act_in"] + d["act_out"] + wbytes
-            elif which == "bwd_data":
-                byts = d["act_out"] + d["act_in"] + wbytes
-            else:
-                byts = d["act_in"] + d["act_out"] + 16 * d["nnzk"]
-        kk = kinds.setdefault(kind, dict(us=0.0, flops=0.0, dense=0.0, bytes=0.0, n=0))
-        kk["us"] += us; kk["flops"] += fl; kk["dense"] += dfl; kk["bytes"] += byts; kk["n"] += 1
-        t_unit_us = (dfl / (PEAK_BF16_MFMA_TFLOPS * 1e6)) if var == "mfma" else (fl / (PEAK_F32_VALU_TFLOPS * 1e6))
-        t_roof_us = max(byts / (PEAK_HBM_GBS * 1e3), t_unit_us)
-        t_roof_sum += t_roof_us
-        t_sparse_sum += max(byts / (PEAK_HBM_GBS * 1e3), fl / (PEAK_F32_VALU_TFLOPS * 1e6))
-        t_meas_sum += us
-        log("%-3d %-22s %-10s %-5s %9.1f %10.2f %10.1f %8.0f %6.3f" % (
-            li, "all %d layers" % len(layers) if li < 0 else "%dx%d %d->%d s%d" % (L.H, L.W, L.C, L.F, L.stride), which, var, us,
-            fl / us / 1e6, dfl / us / 1e6, byts / us / 1e3, t_roof_us / us))
-    dom = max(kinds.items(), key=lambda kv: kv[1]["us"])
-    dk, dv = dom
-    t_hbm = dv["bytes"] / (PEAK_HBM_GBS * 1e9) * 1e6
-    if dk.startswith("mfma"):
-        # the contraction issues the dense zero-filled tile flops; its utilisation is issued / peak
-        t_unit = dv["dense"] / (PEAK_BF16_MFMA_TFLOPS * 1e12) * 1e6
-        bound, unit, peak = "mfma", "TFLOP/s", PEAK_BF16_MFMA_TFLOPS
-        achieved = dv["dense"] / dv["us"] / 1e6
-    else:
-        t_unit = dv["flops"] / (PEAK_F32_VALU_TFLOPS * 1e12) * 1e6
-        bound, unit, peak = "alu", "TFLOP/s", PEAK_F32_VALU_TFLOPS
-        achieved = dv["flops"] / dv["us"] / 1e6
-    if t_hbm > t_unit:
-        bound, unit, peak = "hbm", "GB/s", PEAK_HBM_GBS
-        achieved = dv["bytes"] / dv["us"] / 1e3
-    # HBM bytes per launch of that kernel from the committed rocprofv3 counter summary (None when absent)
+            byts = float(d["act_in"] + d["act_out"] + (16 * d["nnzk"] if which == "bwd_weight" else wbytes))
+        unit_peak = PEAK_BF16_MFMA_TFLOPS if mfma else PEAK_F32_VALU_TFLOPS
+        t_hbm_us = byts / (PEAK_HBM_GBS * 1e3)
+        t_unit_us = fl / (unit_peak * 1e6)
+        c = dict(li=li, which=which, sym=sym, family=sym.split("<")[0], us=us, bytes=byts, flops=fl, dense=dfl if mfma else 0.0,
+                 mfma=mfma, unit_peak=unit_peak, t_roof=max(t_hbm_us, t_unit_us),
+                 t_sparse=max(t_hbm_us, fl / (PEAK_F32_VALU_TFLOPS * 1e6)))
+        calls.append(c)
+        log("%-3d %-22s %-10s %9.1f %9.2f %8.0f %6.3f %6.3f  %s" % (
+            li, "all %d layers" % len(layers) if li < 0 else "%dx%d %d->%d s%d" % (L.H, L.W, L.C, L.F, L.stride), which, us,
+            fl / us / 1e6, byts / us / 1e3, c["t_roof"] / us, c["dense"] / us / 1e6 / PEAK_BF16_MFMA_TFLOPS, sym))
+
+    def summarise(cs):
+        us = sum(c["us"] for c in cs)
+        byts, fl, dense = sum(c["bytes"] for c in cs), sum(c["flops"] for c in cs), sum(c["dense"] for c in cs)
+        unit_peak = cs[0]["unit_peak"]
+        t_hbm, t_unit = byts / (PEAK_HBM_GBS * 1e3), fl / (unit_peak * 1e6)
+        if t_hbm >= t_unit:
+            bound, unit, peak, ach = "hbm", "GB/s", PEAK_HBM_GBS, byts / us / 1e3
+        else:
+            bound, unit, peak = ("mfma" if cs[0]["mfma"] else "alu"), "TFLOP/s", unit_peak
+            ach = fl / us / 1e6
+        return dict(launches_per_step=len(cs), avg_launch_us=round(us / len(cs), 2), bound=bound, achieved=round(ach, 3), peak=peak,
+                    unit=unit, frac=round(ach / peak, 4), algorithmic_mib_per_launch=round(byts / len(cs) / (1 << 20), 2),
+                    nonzero_gflop_per_launch=round(fl / len(cs) / 1e9, 3), algorithmic_gbs=round(byts / us / 1e3, 1),
+                    nonzero_tflops=round(fl / us / 1e6, 3),
+                    mfma_util=round(dense / us / 1e6 / PEAK_BF16_MFMA_TFLOPS, 4) if cs[0]["mfma"] else None,
+                    ideal_sparse_frac=round(sum(c["t_sparse"] for c in cs) / us, 4), total_us=round(us, 1))
+
+    # the dominant kernel: the kernel family (symbol without template arguments) with the largest share of the step;
+    # every instantiation of it is listed with the same figures, so each can be held against a line of a kernel trace
+    fams, syms = {}, {}
+    for c in calls:
+        fams.setdefault(c["family"], []).append(c)
+        syms.setdefault(c["sym"], []).append(c)
+    dk, dcs = max(fams.items(), key=lambda kv: sum(c["us"] for c in kv[1]))
+    dom = summarise(dcs)
+    t_all = sum(c["us"] for c in calls)
+    # HBM bytes per launch of that kernel from the committed rocprofv3 counter summary (None when absent): the rows of
+    # the family, plus the helper kernels that belong to the same library calls
     traffic = None
     prof = os.path.join(ROOT, "profiles", "%s_hbm_counters.md" % wl.name)
-    # kernels one library call of that kind launches: the first entry is the kernel that does the work (its
-    # dispatches count the calls), the others are helpers whose bytes belong to the same call
-    knames = {"mfma_bwd_weight": ("pc_mfma_wgrad", "pc_wgrad_reduce", "pc_pad_channels_kernel"),
-              "mfma_fwd": ("pc_mfma_conv", "pc_mfma_splitk_reduce_kernel"),
-              "mfma_bwd_data": ("pc_mfma_conv", "pc_mfma_splitk_reduce_kernel", "pc_unpad_channels_kernel"),
-              "valu_fwd": ("pc_gather_conv_kernel",), "valu_bwd_data": ("pc_gather_conv_kernel",),
-              "valu_bwd_weight": ("pc_wgrad_valu_kernel", "pc_wgrad_reduce")}.get(dk)
-    if knames and os.path.exists(prof):
+    helpers = {"pc_mfma_wgrad_ws_kernel": ("pc_wgrad_reduce", "pc_pad_channels_kernel"),
+               "pc_mfma_wgrad_ws_group_kernel": ("pc_wgrad_reduce", "pc_pad_channels_kernel"),
+               "pc_mfma_wgrad_kernel": ("pc_wgrad_reduce",), "pc_wgrad_valu_kernel": ("pc_wgrad_reduce",),
+               "pc_mfma_conv_ks_kernel": (), "pc_mfma_conv_kernel": ("pc_mfma_splitk_reduce_kernel",)}.get(dk, ())
+    if os.path.exists(prof):
         tot_b, tot_n = 0.0, 0
         for line in open(prof):
             cells = [c.strip() for c in line.split("|")]
-            if len(cells) > 5 and any(cells[1].startswith(k) for k in knames):
-                n_disp = int(cells[2])
-                tot_b += float(cells[5].split("=")[-1]) * n_disp
-                if cells[1].startswith(knames[0]):
+            if len(cells) > 5 and (cells[1].split("<")[0] == dk or any(cells[1].startswith(h) for h in helpers)):
+                try:
+                    n_disp = int(cells[2])
+                    tot_b += float(cells[5].split("=")[-1]) * n_disp
+                except ValueError:
+                    continue
+                if cells[1].split("<")[0] == dk:
                     tot_n += n_disp
         if tot_n:
             traffic = {"hbm_mib_per_launch": round(tot_b / tot_n, 2), "source": "profiles/%s_hbm_counters.md" % wl.name,
-                       "algorithmic_mib_per_launch": round(dv["bytes"] / dv["n"] / (1 << 20), 2)}
-    roofline = {
-        "kernel": dk, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-        "frac": round(achieved / peak, 4), "traffic": traffic,
-        "launches_per_step": dv["n"], "avg_launch_us": round(dv["us"] / dv["n"], 2),
-        "achieved_nonzero_tflops": round(dv["flops"] / dv["us"] / 1e6, 3),
-        "algorithmic_gbs": round(dv["bytes"] / dv["us"] / 1e3, 1),
-        "ideal_sparse_frac": round(max(t_hbm, dv["flops"] / (PEAK_F32_VALU_TFLOPS * 1e12) * 1e6) / dv["us"], 4),
-        "share_of_step": round(dv["us"] / sum(k["us"] for k in kinds.values()), 3),
-        # all calls of the step: sum of their roofline times / the step time
-        "path_frac": round(t_roof_sum / (ms_per_step * 1e3), 4),
-        # the same against the ideal sparse execution: max(algorithmic bytes / HBM peak, nonzero flops / float32 vector peak)
-        "path_ideal_sparse_frac": round(t_sparse_sum / (ms_per_step * 1e3), 4),
-    }
-    for kname, kv in sorted(kinds.items()):
-        log("kind %-18s launches %3d  total %9.1f us  nz %8.2f TF/s  dense %8.1f TF/s  alg %7.0f GB/s" % (
-            kname, kv["n"], kv["us"], kv["flops"] / kv["us"] / 1e6, kv["dense"] / kv["us"] / 1e6, kv["bytes"] / kv["us"] / 1e3))
+                       "algorithmic_mib_per_launch": dom["algorithmic_mib_per_launch"],
+                       "ratio": round(tot_b / tot_n / max(dom["algorithmic_mib_per_launch"], 1e-9), 3)}
+    roofline = {"kernel": dk, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"],
+                "frac": dom["frac"], "traffic": traffic}
+    roofline.update({k: dom[k] for k in ("launches_per_step", "avg_launch_us", "algorithmic_mib_per_launch", "nonzero_gflop_per_launch",
+                                          "algorithmic_gbs", "nonzero_tflops", "mfma_util", "ideal_sparse_frac")})
+    roofline["share_of_step"] = round(dom["total_us"] / t_all, 3)
+    roofline["definition"] = ("frac = achieved / peak for the bound that takes longer: algorithmic bytes (|in| + |out| + kept weights) "
+                              "at the HBM peak, or nonzero flops 8*N*Ho*Wo*nnzk at the peak of the unit that multiplies; durations are "
+                              "HIP events around each library call on its stream; mfma_util = zero-filled flops issued / bf16 matrix peak")
+    # all calls of the step: the sum of their roofline times over the step time
+    roofline["path_frac"] = round(sum(c["t_roof"] for c in calls) / (ms_per_step * 1e3), 4)
+    # the same against max(algorithmic bytes / HBM peak, nonzero flops / float32 vector peak)
+    roofline["path_ideal_sparse_frac"] = round(sum(c["t_sparse"] for c in calls) / (ms_per_step * 1e3), 4)
+    roofline["path_mfma_util"] = round(sum(c["dense"] for c in calls) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)
+    roofline["kernels"] = {}
+    for sname, cs in sorted(syms.items(), key=lambda kv: -sum(c["us"] for c in kv[1])):
+        sm = summarise(cs)
+        roofline["kernels"][sname] = {k: sm[k] for k in ("launches_per_step", "avg_launch_us", "bound", "frac", "algorithmic_mib_per_launch",
+                                                          "nonzero_gflop_per_launch", "mfma_util")}
+        log("kernel %-46s launches %3d  avg %8.1f us  %4s frac %6.3f  nz %7.2f TF/s  alg %6.0f GB/s  mfma util %s" % (
+            sname, sm["launches_per_step"], sm["avg_launch_us"], sm["bound"], sm["frac"], sm["nonzero_tflops"], sm["algorithmic_gbs"],
+            sm["mfma_util"]))
+    log("dominant kernel family %s: %d launches, %.1f us of %.1f us, bound %s, frac %.4f; whole step: path_frac %.4f" % (
+        dk, dom["launches_per_step"], dom["total_us"], t_all, dom["bound"], dom["frac"], roofline["path_frac"]))
 
     if args.calib_copy_mb > 0:
         n = args.calib_copy_mb * (1 << 20) // 4
@@ -612,11 +639,66 @@ def main() -> int:
         log("paper's demonstration layer (Section 5.1), forward: %.1f us here (bf16, keep %.2f); paper: about 3000 us "
             "SpMM on one Quadro RTX 5000 (context only)" % (us_p, wl.keep))
 
+    # ---- the per-layer operator choice as a function of sparsity (Section 5.2 / 5.4; the shape of the paper's
+    # sparsity sweep): one bf16 layer over a range of keep ratios, the three passes with the pattern-grouped gather
+    # kernels (only kept taps are multiplied) and with the matrix-core kernels (zero-filled tiles)
+    sweep = None
+    if args.sweep:
+        sN, sH, sW, sC, sF, sS = (int(v) for v in args.sweep_shape.split(","))
+        Ls = I.Layer(sN, sH, sW, sC, sF, sS)
+        Ws = up(I.gen_weights(sF, sC, I.BASE_SEED, "sweep"))
+        Gs = up(I.gen_weight_grads(sF, sC, I.BASE_SEED, "sweep"))
+        xs_ = up(I.gen_activations((sN, sH, sW, sC), I.BASE_SEED, ("sweep", "x"), True, "bf16")[1])
+        dys_ = up(I.gen_activations((sN, Ls.Ho, Ls.Wo, sF), I.BASE_SEED, ("sweep", "dy"), False, "bf16")[1])
+        ys_, dxs_ = torch.empty_like(dys_), torch.empty_like(xs_)
+        descs_ = B.make_desc(sN, sH, sW, sC, sF, sS, B.PC_BF16)
+        pids_ = torch.empty((sF, sC), dtype=torch.uint8, device="cuda")
+        keeps_ = torch.empty((sF, sC), dtype=torch.uint8, device="cuda")
+        rows = []
+        for kr in (0.02, 0.05, 0.1, 0.2, 0.3, 0.5, 1.0):
+            ks = I.kept_per_filter(kr, sC)
+            B.pc_pattern_select(ctx, Ws, Gs, sF, sC, lib, B.PC_KEEP_PER_FILTER, ks, B.PC_SCORE_RETAINED, pids_, keeps_)
+            t_us = {}
+            for vname, var in (("gather", B.PC_VARIANT_VALU), ("matrix", B.PC_VARIANT_MFMA), ("auto", B.PC_VARIANT_AUTO)):
+                B.pc_set_variant(ctx, var)
+                pks = B.pc_pack(ctx, Ws, pids_, keeps_, sF, sC, lib, B.PC_BF16)
+                nz, picked = B.pc_packed_info(ctx, pks)
+                dws = torch.empty((max(nz, 1), 4), dtype=torch.float32, device="cuda")
+                def sweep_step():
+                    B.pc_conv_fwd(ctx, descs_, pks, xs_, ys_)
+                    B.pc_conv_bwd_data(ctx, descs_, pks, dys_, dxs_)
+                    B.pc_conv_bwd_weight(ctx, descs_, pks, xs_, dys_, dws)
+                for _ in range(2):
+                    sweep_step()
+                torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(5):
+                    sweep_step()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                t_us[vname] = round(e0.elapsed_time(e1) * 1e3 / 5, 1)
+                if vname == "auto":
+                    t_us["auto_picks"] = "matrix" if picked == B.PC_VARIANT_MFMA else "gather"
+                B.pc_packed_free(pks)
+            B.pc_set_variant(ctx, {"auto": B.PC_VARIANT_AUTO, "valu": B.PC_VARIANT_VALU, "mfma": B.PC_VARIANT_MFMA}[args.variant])
+            rows.append({"keep": round(ks / sC, 4), "weight_density": round(ks / sC * 4.0 / 9.0, 4), "us": t_us})
+            log("sweep keep %.3f density %.4f: gather %.1f us, matrix %.1f us, auto %.1f us (%s)" % (
+                ks / sC, ks / sC * 4 / 9, t_us["gather"], t_us["matrix"], t_us["auto"], t_us["auto_picks"]))
+        sweep = {"layer": "N=%d %dx%d %d->%d stride %d, bf16, %d patterns" % (sN, sH, sW, sC, sF, sS, wl.P),
+                 "passes": "fwd+bwd_data+bwd_weight", "rows": rows}
+
     # ---- the CPU oracle on a bounded sample of the same workload (reported, not a target)
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import pc_oracle as oracle
-        ns = min(args.cpu_sample_batch, wl.layers[0].N)
+        # a bounded sample: the oracle runs at a few nonzero GFLOP/s, so the batch is cut to what takes it about 15 s
+        if args.cpu_sample_batch > 0:
+            ns = min(args.cpu_sample_batch, wl.layers[0].N)
+        else:
+            per_image = total_flops / wl.layers[0].N
+            ns = int(max(1, min(wl.layers[0].N, round(15.0 * 5e9 / per_image))))
         t_cpu, f_cpu = 0.0, 0.0
         for li, L in enumerate(wl.layers):
             tag = (wl.name, li)
@@ -648,6 +730,7 @@ def main() -> int:
         "config": {"workload": wl.name, "layers": len(wl.layers), "batch": wl.layers[0].N, "patterns": wl.P,
                    "keep": wl.keep, "variant": args.variant, "passes": "+".join(passes), "launch": "hip_graph" if graph is not None else "host",
                    "streams": 1 + len(ctxs_w), "wgrad": mode["wgrad"],
+                   "wgrad_trial_ms": {k: round(v, 4) for k, v in mode["trial_ms"].items()} if "trial_ms" in mode else None,
                    "nonzero_gflop_per_step": round(total_flops / 1e9, 3)},
         "roofline": roofline, "cpu_baseline": cpu,
     }
@@ -657,6 +740,8 @@ def main() -> int:
         out["train_steps"] = train_steps
     if paper_context is not None:
         out["paper_context"] = paper_context
+    if sweep is not None:
+        out["sweep"] = sweep
     print(json.dumps(out), flush=True)
     for d in layers:
         B.pc_packed_free(d["pk"])

@@ -79,13 +79,22 @@ typedef struct {
  * Fails with PC_ERR_DEVICE when the device cannot be used.
  * A context owns one device scratch buffer (partial sums of split reductions, channel-padded copies of a
  * first layer's tensors). It grows when a call needs more than any call before: that call allocates a larger
- * buffer with hipMalloc and keeps the old one until pc_destroy, so work that is already enqueued, or captured in a
- * HIP graph, keeps a valid address. No allocation may happen during a stream capture: run every layer shape once
- * before capturing. Calls on one context must not overlap (one stream, one scratch buffer). */
+ * buffer with hipMalloc (at least half as large again) and keeps every older one until pc_destroy, however many
+ * there are, so work that is already enqueued, or captured in a HIP graph, keeps a valid address (PC_ERR_NOMEM, with
+ * the current buffer unchanged, when the device or the host cannot provide the memory). No allocation may happen
+ * during a stream capture: run every layer shape once before capturing. Calls on one context must not overlap (one
+ * stream, one scratch buffer). */
 pc_status pc_create(pc_ctx **out, int device, void *hip_stream);
 void pc_destroy(pc_ctx *ctx);
 const char *pc_status_str(pc_status s);
 const char *pc_last_error(const pc_ctx *ctx);
+
+/* Symbol of the kernel that did the work of the last pc_conv_fwd / pc_conv_bwd_data / pc_conv_bwd_weight (or _relu,
+ * _batch) call on this context, with its template arguments as a profiler prints them, e.g.
+ * "pc_mfma_conv_ks_kernel<2, 2, 9, 64, 1, 0>" (helper kernels of the same call, such as the reduction of partial
+ * sums, are not named). Lets a measurement attribute a call's duration to a line of a kernel trace. Empty before the
+ * first such call; the string lives in the context and is overwritten by the next call. */
+const char *pc_last_kernel(const pc_ctx *ctx);
 
 /* Forces the kernel family for later pc_pack / pc_conv_* calls on this context (default AUTO).
  * PC_VARIANT_MFMA on a layer it cannot serve makes pc_pack return PC_ERR_UNSUPPORTED. */
@@ -146,7 +155,7 @@ pc_status pc_pattern_select(pc_ctx *ctx, const float *W_dev, const float *G_dev,
  * ascending tap index.
  * *out == NULL: a new handle is allocated (device memory sized for F*C kernels).
  * *out != NULL: that handle is re-packed in place; it must have the same F, C and dtype.
- * pid/keep values are trusted to be < P and 0/1.
+ * pid/keep values are trusted to be < P and 0/1. F*C must stay below 2^31 (32-bit slots: PC_ERR_UNSUPPORTED).
  * A pack is bound to its device, not to the context that made it: any context of that device may pass it to
  * the conv calls, on its own stream (for example pc_conv_bwd_weight on a second context and stream beside
  * pc_conv_bwd_data on the first). The caller orders the streams: the pack or value update must have run before

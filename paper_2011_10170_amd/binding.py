@@ -21,7 +21,7 @@ PC_SCORE_RETAINED, PC_SCORE_KERNEL = 0, 1
 PC_VARIANT_AUTO, PC_VARIANT_VALU, PC_VARIANT_MFMA = 0, 1, 2
 
 EXPORTS = [
-    "pc_create", "pc_destroy", "pc_status_str", "pc_last_error", "pc_set_variant", "pc_set_plan_override",
+    "pc_create", "pc_destroy", "pc_status_str", "pc_last_error", "pc_last_kernel", "pc_set_variant", "pc_set_plan_override",
     "pc_check_library", "pc_check_conv_desc", "pc_pattern_select", "pc_pack", "pc_update_values",
     "pc_packed_info", "pc_packed_free", "pc_scatter_dense", "pc_unpack_dense",
     "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
@@ -62,6 +62,8 @@ def load():
     lib.pc_status_str.restype = ct.c_char_p
     lib.pc_last_error.argtypes = [vp]
     lib.pc_last_error.restype = ct.c_char_p
+    lib.pc_last_kernel.argtypes = [vp]
+    lib.pc_last_kernel.restype = ct.c_char_p
     lib.pc_set_variant.argtypes = [vp, ct.c_int]
     lib.pc_set_plan_override.argtypes = [vp, i32, i32]
     lib.pc_check_library.argtypes = [vp, i32]
@@ -96,7 +98,7 @@ def load():
     lib.pc_act_pool_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, ct.c_int, i32, vp]
     for name in EXPORTS:
         fn = getattr(lib, name)
-        if name not in ("pc_destroy", "pc_packed_free", "pc_status_str", "pc_last_error"):
+        if name not in ("pc_destroy", "pc_packed_free", "pc_status_str", "pc_last_error", "pc_last_kernel"):
             fn.restype = ct.c_int
     _lib = lib
     return lib
@@ -138,6 +140,10 @@ def pc_create(device: int = 0, hip_stream: Optional[int] = None) -> int:
 
 def pc_destroy(ctx) -> None:
     load().pc_destroy(ctx)
+
+
+def pc_last_kernel(ctx) -> str:
+    return load().pc_last_kernel(ctx).decode()
 
 
 def pc_set_variant(ctx, variant: int) -> None:

@@ -44,6 +44,16 @@ extern "C" const char *pc_status_str(pc_status s)
 
 extern "C" const char *pc_last_error(const pc_ctx *ctx) { return ctx ? ctx->err : "no context"; }
 
+void pc_note_kernel(pc_ctx *ctx, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->last_kernel, sizeof(ctx->last_kernel), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char *pc_last_kernel(const pc_ctx *ctx) { return ctx ? ctx->last_kernel : ""; }
+
 // ------------------------------------------------------------------ host-only checks
 extern "C" pc_status pc_check_library(const uint16_t *lib, int32_t P)
 {
@@ -116,6 +126,7 @@ extern "C" void pc_destroy(pc_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->scratch) (void)hipFree(ctx->scratch);
     for (int i = 0; i < ctx->n_retired; ++i) (void)hipFree(ctx->retired[i]);
+    free(ctx->retired);
     if (ctx->nnz_pinned) (void)hipHostFree(ctx->nnz_pinned);
     delete ctx;
 }
@@ -142,19 +153,20 @@ extern "C" pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t
 pc_status pc_scratch(pc_ctx *ctx, size_t bytes, void **out)
 {
     if (bytes > ctx->scratch_bytes) {
-        // Work that is enqueued, or captured in a HIP graph, keeps the address it was given: the old buffer is not
-        // freed before pc_destroy (only when the list of old buffers is full: then after the stream has drained).
+        // Work that is enqueued, or captured in a HIP graph, keeps the address it was given: the old buffer is never
+        // freed before pc_destroy. The list of old buffers grows on the host (the buffer grows by at least half each
+        // time, so the list stays short); when it cannot grow, the call fails and the current buffer stays.
+        if (ctx->scratch && ctx->n_retired == ctx->cap_retired) {
+            const int cap = ctx->cap_retired ? 2 * ctx->cap_retired : 16;
+            void **grown = (void **)realloc(ctx->retired, sizeof(void *) * (size_t)cap);
+            if (!grown) return pc_fail(ctx, PC_ERR_NOMEM, "scratch: host allocation failed");
+            ctx->retired = grown;
+            ctx->cap_retired = cap;
+        }
         size_t want = bytes + bytes / 2 + (1u << 20);
         void *fresh = nullptr;
         PC_HIP(ctx, hipMalloc(&fresh, want));
-        if (ctx->scratch) {
-            if (ctx->n_retired < (int)(sizeof(ctx->retired) / sizeof(ctx->retired[0]))) {
-                ctx->retired[ctx->n_retired++] = ctx->scratch;
-            } else {
-                (void)hipStreamSynchronize(ctx->stream);
-                (void)hipFree(ctx->scratch);
-            }
-        }
+        if (ctx->scratch) ctx->retired[ctx->n_retired++] = ctx->scratch;
         ctx->scratch = fresh;
         ctx->scratch_bytes = want;
     }
@@ -246,7 +258,7 @@ static size_t carve(PackView *v, PackView **v_dev, char *base, int F, int C, boo
     v->slot_f = (uint16_t *)take(sizeof(uint16_t) * cap);
     v->fm_val = (float4 *)take(sizeof(float4) * cap);
     v->slot_of = (int32_t *)take(sizeof(int32_t) * cap);
-    v->kinfo = (uint32_t *)take(sizeof(uint32_t) * cap);
+    v->kinfo = cap < ((size_t)1 << 23) ? (uint32_t *)take(sizeof(uint32_t) * cap) : nullptr;   // only the matrix-core kernels read it
     v->cm_rowptr = (int32_t *)take(sizeof(int32_t) * (C + 1));
     v->cm_grp = (int32_t *)take(sizeof(int32_t) * (size_t)C * (PC_MAX_P + 1));
     v->cm_rowtot = (int32_t *)take(sizeof(int32_t) * C);
@@ -283,6 +295,8 @@ extern "C" pc_status pc_pack(pc_ctx *ctx, const float *W, const uint8_t *pid, co
     if (F < 1 || C < 1 || F > 65535 || C > 65535)
         return pc_fail(ctx, PC_ERR_BAD_SHAPE, "pc_pack: F=%d C=%d out of range", F, C);
     if (dt != PC_F32 && dt != PC_BF16) return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_pack: dtype %d", (int)dt);
+    if ((int64_t)F * C >= ((int64_t)1 << 31))   // slots and row offsets of the tables are 32-bit
+        return pc_fail(ctx, PC_ERR_UNSUPPORTED, "pc_pack: F*C = %lld kernels, the tables hold fewer than 2^31", (long long)F * C);
     pc_status s = pc_check_library(lib, P);
     if (s != PC_OK) return pc_fail(ctx, s, "pc_pack: bad library (P=%d)", P);
 

@@ -507,6 +507,7 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
     case 5: launch_cfg<1, 1, 2, 2, 64>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
     default: launch_cfg<1, 2, 2, 2, 16>(ctx->stream, grid, lds, pcl != nullptr, in, out, wz, partial, g); break;
     }
+    pc_note_kernel(ctx, "pc_mfma_conv_kernel<%d, %d, %d, %d, %d, %d, %s>", c.a, c.b, c.wm, c.wn, pcl ? 4 : 9, c.kc, pcl ? "true" : "false");
     pc_status s = pc_hip_check(ctx, hipGetLastError(), "MFMA conv launch");
     if (s != PC_OK || pick_split == 1) return s;
     int64_t n4 = n_out / 4;

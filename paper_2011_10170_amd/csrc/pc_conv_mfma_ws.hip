@@ -572,5 +572,6 @@ pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext
     default: e = launch_ks<2, 2, 128, 4>(ctx->device, ctx->stream, grid, best_lds, in, out, wz, g, act); break;
     }
     *launched = true;
+    pc_note_kernel(ctx, "pc_mfma_conv_ks_kernel<%d, %d, 9, %d, %d, %d>", kAt[best_k], kBt[best_k], kKc[best_k], kKsp[best_k], act);
     return pc_hip_check(ctx, e, "MFMA conv (wave-specialised) launch");
 }

@@ -184,6 +184,7 @@ static pc_status launch_gather(pc_ctx *ctx, pc_dtype dt, const void *in, void *o
     else
         hipLaunchKernelGGL((pc_gather_conv_kernel<uint16_t, LSTEP>), grid, dim3(256), lds, ctx->stream,
                            (const uint16_t *)in, (uint16_t *)out, g, grp, idx, val);
+    pc_note_kernel(ctx, "pc_gather_conv_kernel<%s, %d>", dt == PC_F32 ? "float" : "unsigned short", LSTEP);
     return pc_hip_check(ctx, hipGetLastError(), "VALU conv launch");
 }
 
@@ -269,7 +270,7 @@ struct WgradArgs {
 template <typename T>
 __global__ void __launch_bounds__(256)
 pc_wgrad_valu_kernel(const T *__restrict__ x, const T *__restrict__ dy, WgradArgs a, PackView v,
-                     float4 *__restrict__ partial)
+                     float4 *__restrict__ partial, int64_t pstride)
 {
     __shared__ float xs[WB_X_FLOATS];
     __shared__ float ds[WB_TH * WB_TW * (WB_NF + 1)];
@@ -342,7 +343,7 @@ pc_wgrad_valu_kernel(const T *__restrict__ x, const T *__restrict__ dy, WgradArg
             }
         }
     }
-    if (live) partial[(int64_t)blockIdx.y * nnzk + slot] = make_float4(acc0, acc1, acc2, acc3);
+    if (live) partial[(int64_t)blockIdx.y * pstride + slot] = make_float4(acc0, acc1, acc2, acc3);
 }
 
 // dw[slot] = sum over g of partial[g][slot] in a fixed order: TPS threads per slot each add every TPS-th
@@ -471,10 +472,12 @@ pc_status pc_launch_wgrad_reduce(pc_ctx *ctx, const float *partial, int G, int64
 pc_status pc_valu_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, const void *dy,
                              float *dw)
 {
-    int64_t nnzk = 0;
-    pc_status s = pc_packed_info(ctx, pk, &nnzk, nullptr);
-    if (s != PC_OK) return s;
+    // No read-back of the kept-kernel count (the call stays asynchronous and can be captured): the kernels find the
+    // live slots on the device; the host sizes the grid and strides the partial planes by the count when an earlier
+    // pc_packed_info has it, else by the pack's capacity (workgroups past the live slots return at once).
+    const int64_t nnzk = pk->nnzk >= 0 ? pk->nnzk : (int64_t)pk->v.F * pk->v.C;
     if (nnzk == 0) return PC_OK;
+    pc_status s = PC_OK;
     WgradArgs a;
     memset(&a, 0, sizeof(a));
     a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.F = d->F; a.stride = d->stride;
@@ -501,10 +504,11 @@ pc_status pc_valu_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     dim3 grid((unsigned)bx, (unsigned)G);
     if (d->dtype == PC_F32)
         hipLaunchKernelGGL((pc_wgrad_valu_kernel<float>), grid, dim3(256), 0, ctx->stream, (const float *)x,
-                           (const float *)dy, a, pk->v, (float4 *)scr);
+                           (const float *)dy, a, pk->v, (float4 *)scr, nnzk);
     else
         hipLaunchKernelGGL((pc_wgrad_valu_kernel<uint16_t>), grid, dim3(256), 0, ctx->stream, (const uint16_t *)x,
-                           (const uint16_t *)dy, a, pk->v, (float4 *)scr);
+                           (const uint16_t *)dy, a, pk->v, (float4 *)scr, nnzk);
+    pc_note_kernel(ctx, "pc_wgrad_valu_kernel<%s>", d->dtype == PC_F32 ? "float" : "unsigned short");
     s = pc_hip_check(ctx, hipGetLastError(), "VALU bwd_weight launch");
     if (s != PC_OK) return s;
     return pc_launch_wgrad_reduce(ctx, (const float *)scr, G, nnzk, nnzk, pk, dw);

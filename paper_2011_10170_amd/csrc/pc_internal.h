@@ -21,8 +21,9 @@ struct pc_ctx {
     // scratch owned by the context (grown on demand, never shrunk)
     void *scratch;
     size_t scratch_bytes;
-    void *retired[64];     // superseded scratch buffers, kept until pc_destroy: enqueued or captured work may still use them
-    int n_retired;
+    void **retired;        // superseded scratch buffers (a growing host array), kept until pc_destroy: enqueued or captured work may still use them
+    int n_retired, cap_retired;
+    char last_kernel[160]; // symbol of the kernel that did the work of the last conv call (pc_last_kernel)
     int64_t *nnz_pinned;   // pinned host word for reading back a pack's kernel count
 };
 
@@ -38,7 +39,7 @@ struct PackView {
     uint16_t *slot_f;     // [cap]   filter of the slot
     float4 *fm_val;       // [cap]   the 4 kept weights, ascending tap index
     int32_t *slot_of;     // [F][C]  slot of kernel (f,c), -1 when pruned
-    uint32_t *kinfo;      // [F][C]  (slot << 9) | 9-bit pattern mask, 0xFFFFFFFF when pruned (needs F*C < 2^23)
+    uint32_t *kinfo;      // [F][C]  (slot << 9) | 9-bit pattern mask, 0xFFFFFFFF when pruned; nullptr when F*C >= 2^23 (the slot would not fit 23 bits)
     // channel-major table for backward-data: rows = channels, kernels ordered (pattern id, filter)
     int32_t *cm_rowptr;   // [C+1]
     int32_t *cm_grp;      // [C][P+1]
@@ -84,6 +85,8 @@ inline void pc_once_done(pc_per_device_once &o, int device) { if (device >= 0 &&
 pc_status pc_fail(pc_ctx *ctx, pc_status s, const char *fmt, ...);
 pc_status pc_hip_check(pc_ctx *ctx, hipError_t e, const char *what);
 pc_status pc_scratch(pc_ctx *ctx, size_t bytes, void **out);
+// Records the symbol of the kernel a conv call launched (printf-style), for pc_last_kernel.
+void pc_note_kernel(pc_ctx *ctx, const char *fmt, ...);
 void pc_fill_lib(LibArg *la, const uint16_t *lib, int P);
 
 #define PC_HIP(ctx, call)                                              \

@@ -825,7 +825,7 @@ __device__ __forceinline__ void pc_pack_place_body(const float *__restrict__ W, 
                 v.slot_f[slot] = (uint16_t)row;
                 v.fm_val[slot] = val;
                 v.slot_of[k] = slot;
-                v.kinfo[k] = ((uint32_t)slot << 9) | lmask[code];
+                if (v.kinfo) v.kinfo[k] = ((uint32_t)slot << 9) | lmask[code];
             } else {
                 v.cm_f[slot] = (uint16_t)e;
                 v.cm_slot[slot] = v.slot_of[k];
@@ -833,7 +833,7 @@ __device__ __forceinline__ void pc_pack_place_body(const float *__restrict__ W, 
             }
         } else if (FM && e < len) {
             v.slot_of[k] = -1;
-            v.kinfo[k] = 0xFFFFFFFFu;
+            if (v.kinfo) v.kinfo[k] = 0xFFFFFFFFu;
         }
         __syncthreads();
         if (tid < P) start[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
@@ -872,7 +872,7 @@ pc_pack_regather_fm_kernel(const float *__restrict__ W, LibArg la, int bf16, Pac
 
 __global__ void __launch_bounds__(256) pc_pack_regather_cm_kernel(PackView v)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= v.cm_rowptr[v.C]) return;
     v.cm_val[i] = v.fm_val[v.cm_slot[i]];
 }

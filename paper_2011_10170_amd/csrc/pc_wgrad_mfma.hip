@@ -714,6 +714,7 @@ static pc_status pc_mfma_bwd_weight_ws(pc_ctx *ctx, const pc_conv_desc *d, const
     hipLaunchKernelGGL(pc_mfma_wgrad_ws_kernel, dim3((unsigned)ct, (unsigned)ft, (unsigned)ks), dim3(512), lds, ctx->stream,
                        (const uint16_t *)x, (const uint16_t *)dy, a, pk->v.kinfo, (float *)scr, dw);
     *launched = true;
+    pc_note_kernel(ctx, "pc_mfma_wgrad_ws_kernel");
     s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight (wave-specialised) launch");
     if (s != PC_OK || ks == 1) return s;
     return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, nslots, nslots, pk, dw);
@@ -811,6 +812,7 @@ pc_status pc_mfma_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed
     else if (a.nks <= 8) hipLaunchKernelGGL(pc_mfma_wgrad_kernel<8>, grid, dim3(256), lds, ctx->stream, xp, dyp, a, pk->v, (float *)scr);
     else if (a.nks <= 12) hipLaunchKernelGGL(pc_mfma_wgrad_kernel<12>, grid, dim3(256), lds, ctx->stream, xp, dyp, a, pk->v, (float *)scr);
     else hipLaunchKernelGGL(pc_mfma_wgrad_kernel<16>, grid, dim3(256), lds, ctx->stream, xp, dyp, a, pk->v, (float *)scr);
+    pc_note_kernel(ctx, "pc_mfma_wgrad_kernel<%d>", a.nks <= 4 ? 4 : a.nks <= 8 ? 8 : a.nks <= 12 ? 12 : 16);
     s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight launch");
     if (s != PC_OK) return s;
     return pc_launch_wgrad_reduce(ctx, (const float *)scr, ks, nslots, nslots, pk, dw);
@@ -919,6 +921,7 @@ pc_status pc_mfma_bwd_weight_group(pc_ctx *ctx, int n, const pc_conv_desc *d, co
             }
         }
         hipLaunchKernelGGL(pc_mfma_wgrad_ws_group_kernel, dim3((unsigned)g.blk0[m]), dim3(512), lds, ctx->stream, g);
+        pc_note_kernel(ctx, "pc_mfma_wgrad_ws_group_kernel");
         s = pc_hip_check(ctx, hipGetLastError(), "MFMA bwd_weight (several layers) launch");
         if (s != PC_OK) return s;
     }

@@ -94,33 +94,12 @@ def all_four_tap_masks() -> List[int]:
     return [mask_of(c) for c in itertools.combinations(range(9), 4)]
 
 
-def neighbour_reachable_masks() -> List[int]:
-    """Masks the paper's pool-generation adjacency rules can produce (Section 4.2,
-    steps 1-4): any first tap, a second tap among its 8 neighbours, then two more
-    taps among the horizontal/vertical neighbours of the first two. Sorted."""
-    def rc(t):
-        return divmod(t, 3)
-    out = set()
-    for a in range(9):
-        ra, ca = rc(a)
-        for b in range(9):
-            rb, cb = rc(b)
-            if b == a or max(abs(ra - rb), abs(ca - cb)) > 1:
-                continue
-            cand = set()
-            for t in range(9):
-                rt, ct = rc(t)
-                if t in (a, b):
-                    continue
-                if abs(rt - ra) + abs(ct - ca) == 1 or abs(rt - rb) + abs(ct - cb) == 1:
-                    cand.add(t)
-            for c1, c2 in itertools.combinations(sorted(cand), 2):
-                out.add(mask_of((a, b, c1, c2)))
-    return sorted(out)
-
-
 _BLOCKS = [(0, 1, 3, 4), (1, 2, 4, 5), (3, 4, 6, 7), (4, 5, 7, 8)]
 _TEES = [(1, 3, 4, 5), (1, 4, 5, 7), (3, 4, 5, 7), (1, 3, 4, 7)]
+# The four further masks of the 12-pattern pool, stored as constants (drawn once with this module's generator from
+# the masks the paper's pool generation can produce; tests/test_oracle_train.py checks with the oracle's own
+# enumeration that each of them can be produced).
+_EXTRA12 = [228, 402, 114, 147]
 
 
 def _draw_without_replacement(pool: Sequence[int], k: int, seed: int, stream: int) -> List[int]:
@@ -133,8 +112,8 @@ def make_library(P: int, seed: int = BASE_SEED) -> np.ndarray:
     """Pattern library of the benchmark configurations, as uint16 masks.
 
     P=4: the four 2x2 blocks containing the centre. P=8: those plus the four
-    centre+3-edge-neighbour T shapes. P=12: those plus 4 seeded draws from the
-    remaining neighbour-reachable masks. P=16: 16 seeded draws from all 126.
+    centre+3-edge-neighbour T shapes. P=12: those plus 4 stored masks of the kind
+    the pool generation produces. P=16: 16 seeded draws from all 126.
     P=126: every four-of-nine mask. Other P: the first P of a seeded shuffle of all 126.
     """
     if P == 4:
@@ -142,9 +121,7 @@ def make_library(P: int, seed: int = BASE_SEED) -> np.ndarray:
     elif P == 8:
         lib = [mask_of(t) for t in _BLOCKS + _TEES]
     elif P == 12:
-        base = [mask_of(t) for t in _BLOCKS + _TEES]
-        rest = [m for m in neighbour_reachable_masks() if m not in base]
-        lib = base + _draw_without_replacement(rest, 4, seed, stream_id("lib", 12))
+        lib = [mask_of(t) for t in _BLOCKS + _TEES] + list(_EXTRA12)
     elif P == 126:
         lib = all_four_tap_masks()
     else:

@@ -19,6 +19,66 @@ def rel_l2(a, b) -> float:
     return num / den
 
 
+# ---------------------------------------------------------------- per-element bound
+# Every output element is a sum of products. With float32 accumulation of exact products (bf16 x bf16 fits float32)
+# the error of the sum is a small multiple of 2^-24 times mag = sum of |product| (typically 2^-25 * mag even for a
+# fully sequential sum of any length, because the rounding errors add like a random walk; 2^-21 leaves a factor 16),
+# and a bf16 result adds one rounding of at most 2^-8 relative (half a unit in the last place of 8 significant bits).
+# mag comes from the same oracle routine applied to the absolute values of its inputs.
+RTOL = {"bf16": 2.0 ** -8 * (1.0 + 2.0 ** -6), "f32": 2.0 ** -22}
+ATOL_MAG = 2.0 ** -21
+# relative L2 bounds: the stated ones are 1e-4 (float32) and 2e-2 (bf16 storage); the bf16 one is held at the
+# measured level (1.7e-3: the output rounding alone) with a margin
+TOL_L2 = {"f32": 1e-4, "bf16": 4e-3}
+TOL_L2_DW = 1e-4
+
+
+def elementwise_excess(got, ref, mag, out_kind: str):
+    """(largest |got - ref| / tolerance over the elements, flat index of that element); <= 1 passes."""
+    got = np.asarray(got, dtype=np.float64).reshape(-1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(-1)
+    mag = np.asarray(mag, dtype=np.float64).reshape(-1)
+    assert got.shape == ref.shape == mag.shape
+    if got.size == 0:
+        return 0.0, -1
+    tol = RTOL[out_kind] * np.abs(ref) + ATOL_MAG * mag + 1e-37
+    ratio = np.abs(got - ref) / tol
+    ratio = np.where(np.isfinite(got), ratio, np.inf)
+    i = int(np.argmax(ratio))
+    return float(ratio[i]), i
+
+
+def assert_close(got, ref, mag, out_kind: str, l2_tol: float, what: str = ""):
+    """Both gates: the relative L2 norm of the difference, and every single element within its own bound."""
+    e = rel_l2(got, ref)
+    worst, at = elementwise_excess(got, ref, mag, out_kind)
+    print("  %s rel_l2 %.3g, worst element at %.3f of its bound (flat index %d)" % (what, e, worst, at), flush=True)
+    assert e <= l2_tol, (what, "rel_l2", e)
+    assert worst <= 1.0, (what, "element", at, "error / bound", worst)
+
+
+def stratified_indices(shape, rng, max_samples=150000):
+    """Flat indices into an NHWC tensor, one per stratum (image, row, segment of sx pixels, group of sc channels),
+    at a random place inside it: every 32-pixel x 32-channel accumulator tile of every kernel tile holds at least
+    one sample (sx = sc = 16: four), whatever tile grid the planner chose. Strata grow to 32 when there would be
+    more than max_samples of them."""
+    N, H, W, CH = shape
+    sx = sc = 16
+    count = lambda: N * H * ((W + sx - 1) // sx) * ((CH + sc - 1) // sc)
+    if count() > max_samples:
+        sc = 32
+    if count() > max_samples:
+        sx = 32
+    nx, ncg = (W + sx - 1) // sx, (CH + sc - 1) // sc
+    n, y, xs, cg = np.meshgrid(np.arange(N), np.arange(H), np.arange(nx), np.arange(ncg), indexing="ij")
+    n, y, xs, cg = (a.reshape(-1).astype(np.int64) for a in (n, y, xs, cg))
+    wx = np.minimum(sx, W - xs * sx)
+    wc = np.minimum(sc, CH - cg * sc)
+    x = xs * sx + (rng.random(n.size) * wx).astype(np.int64)
+    c = cg * sc + (rng.random(n.size) * wc).astype(np.int64)
+    return ((n * H + y) * W + x) * CH + c
+
+
 class Case:
     def __init__(self, layer: I.Layer, dtype: str, P: int, n_keep: int, seed: int = I.BASE_SEED, tag="case",
                  lib=None):

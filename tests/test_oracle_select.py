@@ -37,8 +37,6 @@ def test_pattern_count_and_tap_count_match_the_paper():
     # the 4-, 8- and 12-pattern pools keep the centre tap in every pattern
     for P in (4, 8):
         assert all(int(m) & 16 for m in I.make_library(P))
-    reach = I.neighbour_reachable_masks()
-    assert len(reach) == 44 and sum(1 for m in reach if m & 16) == 32
 
 
 @pytest.mark.parametrize("P", [1, 4, 8, 12, 16, 126])

@@ -67,6 +67,9 @@ def test_reachable_patterns_exhaustive():
     got = set(int(m) for m in T.dppg_candidate_masks(W, G).reshape(-1))
     assert got <= reach
     assert len(got) == 44          # 2000 random kernels reach every one of them
+    # the 12-pattern benchmark pool consists of masks the construction can produce
+    from paper_2011_10170_amd import inputs as I
+    assert all(int(m) in reach for m in I.make_library(12))
 
 
 def test_candidate_masks_against_brute_force():
