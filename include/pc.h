@@ -249,6 +249,18 @@ pc_status pc_conv_bwd_data_relu(pc_ctx *ctx, const pc_conv_desc *desc, const pc_
 pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
                              const void *x_dev, const void *dy_dev, float *dw_compact_dev);
 
+/* pc_conv_bwd_weight for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc. Same arguments, same kernels and the same result, bit for bit, as
+ * pc_conv_bwd_weight with the same pack state; but the partial sums (and the channel-padded copy of a first layer's
+ * x) live in a fixed buffer of 32 MiB that the library's code object holds on every GPU it is loaded on until the
+ * process ends, and the call makes no hipMalloc / hipFree and grows no context buffer. A layer that needs more
+ * (the partial sums take at most 16 MiB; a first layer with C not a multiple of 8 adds N*H*W*16 bytes) is rejected
+ * with PC_ERR_UNSUPPORTED before anything is launched. All contexts of a GPU share that one buffer and it keeps the
+ * last call's contents (nothing in it needs to start at zero): calls that overlap on one GPU, from different
+ * contexts or streams, race; the caller serialises them. */
+pc_status pc_conv_bwd_weight_noalloc(pc_ctx *ctx, const pc_conv_desc *desc, const pc_packed *pk,
+                                     const void *x_dev, const void *dy_dev, float *dw_compact_dev);
+
 /* pc_conv_bwd_weight for several layers at once. The weight gradients of a network's layers do not depend on each
  * other (dE/dW of a layer needs only its own a_prev and delta, Section 5.2), so once every x and dy exists they can
  * all be computed together: the matrix-core layers in one launch per 20 layers plus one reduction launch (the

@@ -24,7 +24,7 @@ EXPORTS = [
     "pc_create", "pc_destroy", "pc_status_str", "pc_last_error", "pc_last_kernel", "pc_set_variant", "pc_set_plan_override",
     "pc_check_library", "pc_check_conv_desc", "pc_pattern_select", "pc_pack", "pc_update_values",
     "pc_packed_info", "pc_packed_free", "pc_scatter_dense", "pc_unpack_dense",
-    "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight",
+    "pc_conv_fwd", "pc_conv_bwd_data", "pc_conv_bwd_weight", "pc_conv_bwd_weight_noalloc",
     "pc_dppg_accumulate", "pc_dppg_pool", "pc_finalize_count", "pc_finalize_pick", "pc_group_lasso_grad",
     "pc_act_pool_fwd", "pc_act_pool_bwd", "pc_pattern_select_batch", "pc_pack_batch", "pc_update_values_batch",
     "pc_dppg_accumulate_batch", "pc_finalize_count_batch", "pc_finalize_pick_batch", "pc_group_lasso_grad_batch", "pc_conv_bwd_weight_batch", "pc_conv_fwd_relu", "pc_conv_bwd_data_relu",
@@ -79,6 +79,7 @@ def load():
     lib.pc_conv_fwd.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp]
     lib.pc_conv_bwd_data.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp]
     lib.pc_conv_bwd_weight.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp, vp]
+    lib.pc_conv_bwd_weight_noalloc.argtypes = [vp, ct.POINTER(pc_conv_desc), vp, vp, vp, vp]
     lib.pc_dppg_accumulate.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.pc_dppg_pool.argtypes = [vp, vp, i32, vp, vp, ct.POINTER(i32)]
     lib.pc_finalize_count.argtypes = [vp, vp, i32, i32, i32, vp]
@@ -209,6 +210,10 @@ def pc_conv_bwd_data(ctx, desc, pk, dy, dx) -> None:
 
 def pc_conv_bwd_weight(ctx, desc, pk, x, dy, dw_compact) -> None:
     _check(ctx, load().pc_conv_bwd_weight(ctx, ct.byref(desc), pk, _ptr(x), _ptr(dy), _ptr(dw_compact)))
+
+
+def pc_conv_bwd_weight_noalloc(ctx, desc, pk, x, dy, dw_compact) -> None:
+    _check(ctx, load().pc_conv_bwd_weight_noalloc(ctx, ct.byref(desc), pk, _ptr(x), _ptr(dy), _ptr(dw_compact)))
 
 
 def pc_dppg_accumulate(ctx, W, G, F, C, hist, masks=None) -> None:

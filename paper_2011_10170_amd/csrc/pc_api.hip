@@ -92,6 +92,25 @@ void pc_fill_lib(LibArg *la, const uint16_t *lib, int P)
     }
 }
 
+// ------------------------------------------------------------------ fixed scratch buffer
+// Device memory for the entry point that must not allocate (pc_conv_bwd_weight_noalloc): a file-scope array, so it
+// exists on every GPU the library's code is loaded on, from then until the process ends. In host code the array's
+// name is only a handle for hipGetSymbolAddress; the address kernels and copies use is looked up once per device,
+// with that device current, and kept here.
+#define PC_FIXED_SCRATCH_BYTES (32u << 20)
+static __device__ __align__(256) unsigned char pc_fixed_scratch_mem[PC_FIXED_SCRATCH_BYTES];
+static void *g_fixed_scratch[PC_MAX_DEVICES];
+
+// The calling thread's current device must be `device`.
+static hipError_t pc_fixed_scratch_lookup(int device)
+{
+    if (device < 0 || device >= PC_MAX_DEVICES || g_fixed_scratch[device]) return hipSuccess;
+    void *p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(pc_fixed_scratch_mem));
+    if (e == hipSuccess) g_fixed_scratch[device] = p;
+    return e;
+}
+
 // ------------------------------------------------------------------ context
 extern "C" pc_status pc_create(pc_ctx **out, int device, void *hip_stream)
 {
@@ -100,6 +119,7 @@ extern "C" pc_status pc_create(pc_ctx **out, int device, void *hip_stream)
     int n = 0;
     if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return PC_ERR_DEVICE;
     if (hipSetDevice(device) != hipSuccess) return PC_ERR_DEVICE;
+    if (pc_fixed_scratch_lookup(device) != hipSuccess) return PC_ERR_DEVICE;
     pc_ctx *ctx = new (std::nothrow) pc_ctx();
     if (!ctx) return PC_ERR_NOMEM;
     memset(ctx, 0, sizeof(*ctx));
@@ -152,6 +172,15 @@ extern "C" pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t
 
 pc_status pc_scratch(pc_ctx *ctx, size_t bytes, void **out)
 {
+    if (ctx->fixed_scratch) {
+        void *p = ctx->device < PC_MAX_DEVICES ? g_fixed_scratch[ctx->device] : nullptr;
+        if (!p) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "no fixed scratch buffer on device %d", ctx->device);
+        if (bytes > PC_FIXED_SCRATCH_BYTES)
+            return pc_fail(ctx, PC_ERR_UNSUPPORTED, "this layer needs %zu bytes of scratch, the fixed buffer holds %u", bytes,
+                           (unsigned)PC_FIXED_SCRATCH_BYTES);
+        *out = p;
+        return PC_OK;
+    }
     if (bytes > ctx->scratch_bytes) {
         // Work that is enqueued, or captured in a HIP graph, keeps the address it was given: the old buffer is never
         // freed before pc_destroy. The list of old buffers grows on the host (the buffer grows by at least half each
@@ -545,6 +574,19 @@ extern "C" pc_status pc_conv_bwd_weight(pc_ctx *ctx, const pc_conv_desc *d, cons
     if (s != PC_OK) return s;
     return pk->variant == PC_VARIANT_MFMA ? pc_mfma_bwd_weight(ctx, d, pk, x, dy, dw)
                                           : pc_valu_bwd_weight(ctx, d, pk, x, dy, dw);
+}
+
+extern "C" pc_status pc_conv_bwd_weight_noalloc(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x,
+                                                const void *dy, float *dw)
+{
+    if (!ctx) return PC_ERR_INVALID_ARG;
+    pc_status s = check_conv(ctx, "pc_conv_bwd_weight_noalloc", d, pk, x, dy, dw);
+    if (s != PC_OK) return s;
+    // the same kernels as pc_conv_bwd_weight; every scratch request of the call is served from the fixed buffer
+    ctx->fixed_scratch = true;
+    s = pk->variant == PC_VARIANT_MFMA ? pc_mfma_bwd_weight(ctx, d, pk, x, dy, dw) : pc_valu_bwd_weight(ctx, d, pk, x, dy, dw);
+    ctx->fixed_scratch = false;
+    return s;
 }
 
 extern "C" pc_status pc_conv_bwd_weight_batch(pc_ctx *ctx, int32_t n_layers, const pc_conv_desc *descs, const pc_packed *const *packs,

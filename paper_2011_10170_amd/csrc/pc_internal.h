@@ -23,6 +23,8 @@ struct pc_ctx {
     size_t scratch_bytes;
     void **retired;        // superseded scratch buffers (a growing host array), kept until pc_destroy: enqueued or captured work may still use them
     int n_retired, cap_retired;
+    bool fixed_scratch;    // set for the duration of an entry point that must not allocate: pc_scratch then hands out the
+                           // device's fixed buffer, or fails when the request exceeds it
     char last_kernel[160]; // symbol of the kernel that did the work of the last conv call (pc_last_kernel)
     int64_t *nnz_pinned;   // pinned host word for reading back a pack's kernel count
 };
