@@ -63,7 +63,14 @@ typedef enum { PC_SCORE_RETAINED = 0, PC_SCORE_KERNEL = 1 } pc_score_mode;
 typedef enum {
     PC_VARIANT_AUTO = 0,  /* chosen at pack time from dtype and shape */
     PC_VARIANT_VALU = 1,  /* pattern-grouped gather on the vector ALUs: only kept taps are multiplied */
-    PC_VARIANT_MFMA = 2   /* bf16 only: matrix-core contraction over tap-major zero-filled weight tiles */
+    PC_VARIANT_MFMA = 2,  /* bf16 only: matrix-core contraction over tap-major zero-filled weight tiles */
+    /* bf16 only, never chosen by AUTO: as MFMA, but the forward / backward-data passes of stride-1 layers with at
+     * least 64 reduction channels multiply with the structured-sparse matrix instruction (2 nonzeros in 4 reduction
+     * entries, twice the reduction length per instruction); the weights that exceed that form go through a second
+     * instruction, issued only where needed, so results are exact for any mask and the instruction count falls
+     * with the keep ratio. Measured faster than MFMA below a keep ratio of about 0.12 only (the operand delivery,
+     * not the matrix pipe, bounds these kernels). The pack holds both operand forms. */
+    PC_VARIANT_MFMA_SPARSE = 3
 } pc_variant;
 
 typedef struct {
@@ -97,7 +104,8 @@ const char *pc_last_error(const pc_ctx *ctx);
 const char *pc_last_kernel(const pc_ctx *ctx);
 
 /* Forces the kernel family for later pc_pack / pc_conv_* calls on this context (default AUTO).
- * PC_VARIANT_MFMA on a layer it cannot serve makes pc_pack return PC_ERR_UNSUPPORTED. */
+ * PC_VARIANT_MFMA or PC_VARIANT_MFMA_SPARSE on a layer it cannot serve makes pc_pack return PC_ERR_UNSUPPORTED. A handle
+ * that is re-packed keeps the operand forms it was created with. */
 pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
 
 /* Tuning aid for tests and sweeps: forces a kernel of the matrix-core family instead of the automatic
@@ -111,6 +119,7 @@ pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
  *   17, 18 as 13, 16 with 16-channel chunks (first layers); 19 as 13 with tiles of 32 output channels;
  *          20 as 16 with 64-channel chunks; 21 as 8 with 128-channel chunks
  *   10, 11 backward-weight: the cooperative / the wave-specialised kernel (the other passes stay automatic)
+ *   22     forward/backward-data: the structured-sparse kernel (packs made under PC_VARIANT_MFMA_SPARSE only)
  * The wave-specialised forward/backward-data kernel takes 9-tap launches only: a stride-2 backward-data pass
  * (one launch of the cooperative kernel over the four parity classes of input pixels) takes 0..6 and uses the
  * automatic choice otherwise. split_k > 0 forces that many splits of the reduction in the

@@ -18,7 +18,7 @@ PC_ERR_INVALID_ARG, PC_ERR_BAD_LIBRARY, PC_ERR_BAD_SHAPE, PC_ERR_UNSUPPORTED, PC
 PC_F32, PC_BF16 = 0, 1
 PC_KEEP_PER_FILTER, PC_KEEP_PER_LAYER = 0, 1
 PC_SCORE_RETAINED, PC_SCORE_KERNEL = 0, 1
-PC_VARIANT_AUTO, PC_VARIANT_VALU, PC_VARIANT_MFMA = 0, 1, 2
+PC_VARIANT_AUTO, PC_VARIANT_VALU, PC_VARIANT_MFMA, PC_VARIANT_MFMA_SPARSE = 0, 1, 2, 3
 
 EXPORTS = [
     "pc_create", "pc_destroy", "pc_status_str", "pc_last_error", "pc_last_kernel", "pc_set_variant", "pc_set_plan_override",

@@ -154,7 +154,7 @@ extern "C" void pc_destroy(pc_ctx *ctx)
 extern "C" pc_status pc_set_variant(pc_ctx *ctx, pc_variant v)
 {
     if (!ctx) return PC_ERR_INVALID_ARG;
-    if (v != PC_VARIANT_AUTO && v != PC_VARIANT_VALU && v != PC_VARIANT_MFMA)
+    if (v != PC_VARIANT_AUTO && v != PC_VARIANT_VALU && v != PC_VARIANT_MFMA && v != PC_VARIANT_MFMA_SPARSE)
         return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_set_variant: unknown variant %d", (int)v);
     ctx->forced = v;
     return PC_OK;
@@ -163,7 +163,7 @@ extern "C" pc_status pc_set_variant(pc_ctx *ctx, pc_variant v)
 extern "C" pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t split_k)
 {
     if (!ctx) return PC_ERR_INVALID_ARG;
-    if (tile_cfg < -1 || tile_cfg > 21 || tile_cfg == 12 || split_k < 0 || split_k > 64)
+    if (tile_cfg < -1 || tile_cfg > 22 || tile_cfg == 12 || split_k < 0 || split_k > 64)
         return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_set_plan_override: tile_cfg %d split_k %d out of range", tile_cfg, split_k);
     ctx->plan_cfg = tile_cfg;
     ctx->plan_split = split_k;
@@ -263,7 +263,7 @@ extern "C" pc_status pc_pattern_select_batch(pc_ctx *ctx, int32_t n_layers, cons
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Carves the slab. With base == nullptr only the size is computed.
-static size_t carve(PackView *v, PackView **v_dev, char *base, int F, int C, bool mfma)
+static size_t carve(PackView *v, PackView **v_dev, char *base, int F, int C, bool mfma, bool sparse)
 {
     size_t off = 0;
     size_t cap = (size_t)F * C;
@@ -300,6 +300,18 @@ static size_t carve(PackView *v, PackView **v_dev, char *base, int F, int C, boo
     } else {
         v->wz_fwd = v->wz_bwd = nullptr;
     }
+    if (mfma && sparse) {
+        v->ws_fwd_val = (uint16_t *)take(sizeof(uint16_t) * 9 * (size_t)v->Fp * v->Ck);
+        v->ws_bwd_val = (uint16_t *)take(sizeof(uint16_t) * 9 * (size_t)v->Cp * v->Fk);
+        v->ws_fwd_idx = (uint32_t *)take(sizeof(uint32_t) * 64 * 9 * (size_t)(v->Fp / 32) * (v->Ck / 32));
+        v->ws_bwd_idx = (uint32_t *)take(sizeof(uint32_t) * 64 * 9 * (size_t)(v->Cp / 32) * (v->Fk / 32));
+        v->ws_fwd_flag = (uint16_t *)take(sizeof(uint16_t) * (size_t)(v->Fp / 32) * (v->Ck / 32));
+        v->ws_bwd_flag = (uint16_t *)take(sizeof(uint16_t) * (size_t)(v->Cp / 32) * (v->Fk / 32));
+    } else {
+        v->ws_fwd_val = v->ws_bwd_val = nullptr;
+        v->ws_fwd_idx = v->ws_bwd_idx = nullptr;
+        v->ws_fwd_flag = v->ws_bwd_flag = nullptr;
+    }
     return off;
 }
 
@@ -331,7 +343,8 @@ extern "C" pc_status pc_pack(pc_ctx *ctx, const float *W, const uint8_t *pid, co
 
     int variant;
     bool can_mfma = (dt == PC_BF16) && pc_mfma_supports(F, C);
-    if (ctx->forced == PC_VARIANT_MFMA) {
+    const bool want_sparse = ctx->forced == PC_VARIANT_MFMA_SPARSE;
+    if (ctx->forced == PC_VARIANT_MFMA || want_sparse) {
         if (!can_mfma)
             return pc_fail(ctx, PC_ERR_UNSUPPORTED, "pc_pack: MFMA variant needs bf16 and supported F=%d C=%d", F, C);
         variant = PC_VARIANT_MFMA;
@@ -354,13 +367,13 @@ extern "C" pc_status pc_pack(pc_ctx *ctx, const float *W, const uint8_t *pid, co
         pk->device = ctx->device;
         pk->dtype = dt;
         bool tiles = (dt == PC_BF16) && pc_mfma_supports(F, C);
-        pk->slab_bytes = carve(&pk->v, &pk->v_dev, nullptr, F, C, tiles);
+        pk->slab_bytes = carve(&pk->v, &pk->v_dev, nullptr, F, C, tiles, want_sparse);
         hipError_t e = hipMalloc(&pk->slab, pk->slab_bytes);
         if (e != hipSuccess) {
             delete pk;
             return pc_hip_check(ctx, e, "pc_pack: hipMalloc");
         }
-        carve(&pk->v, &pk->v_dev, (char *)pk->slab, F, C, tiles);
+        carve(&pk->v, &pk->v_dev, (char *)pk->slab, F, C, tiles, want_sparse);
         e = hipMemcpy(pk->v_dev, &pk->v, sizeof(PackView), hipMemcpyHostToDevice);   // pointers and extents: fixed for the handle's life
         if (e != hipSuccess) {
             (void)hipFree(pk->slab);
@@ -486,7 +499,7 @@ extern "C" pc_status pc_packed_info(pc_ctx *ctx, const pc_packed *pk, int64_t *n
         }
         *nnz = m->nnzk;
     }
-    if (variant) *variant = pk->variant;
+    if (variant) *variant = (pk->variant == PC_VARIANT_MFMA && pk->v.ws_fwd_val) ? (int32_t)PC_VARIANT_MFMA_SPARSE : pk->variant;
     return PC_OK;
 }
 

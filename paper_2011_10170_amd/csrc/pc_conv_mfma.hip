@@ -383,8 +383,9 @@ static void launch_cfg(hipStream_t st, dim3 grid, size_t lds, bool classes, cons
 // launch and writes the output tensor itself; *fused then becomes true. Otherwise the plain conv runs and the caller
 // applies the step.
 static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, const int *tr, const int *tc,
-                               const uint16_t *in, uint16_t *out, const uint16_t *wz, const ParityClasses *pcl = nullptr,
-                               int act = PC_ACT_NONE, const uint16_t *act_mask = nullptr, bool *fused = nullptr)
+                               const uint16_t *in, uint16_t *out, const uint16_t *wz, const SparseOperand &sp,
+                               const ParityClasses *pcl = nullptr, int act = PC_ACT_NONE, const uint16_t *act_mask = nullptr,
+                               bool *fused = nullptr)
 {
     g.act_mask = nullptr;
     int plan_cfg = (ctx->plan_cfg >= 10 && ctx->plan_cfg < 13) ? -1 : ctx->plan_cfg;   // 10 and 11 select a backward-weight kernel
@@ -416,7 +417,7 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
             bool launched = false;
             const int act_here = (fused && !pad_out) ? act : PC_ACT_NONE;
             gw.act_mask = act_here == PC_ACT_RELU_MASK ? act_mask : nullptr;
-            pc_status s = pc_run_mfma_conv_ws(ctx, plan_cfg, gw, ext, tr, tc, inw, outw, wz, &launched, act_here);
+            pc_status s = pc_run_mfma_conv_ws(ctx, plan_cfg, gw, ext, tr, tc, inw, outw, wz, sp, &launched, act_here);
             if (s != PC_OK) return s;
             if (launched) {
                 if (fused) *fused = act_here != PC_ACT_NONE;
@@ -528,7 +529,8 @@ pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, c
     g.KS = pk->v.Ck / 16;
     int tr[9], tc[9];
     for (int t = 0; t < 9; ++t) { g.tap_w[t] = t; tr[t] = t / 3; tc[t] = t % 3; }
-    return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)x, (uint16_t *)y, pk->v.wz_fwd, nullptr, act, nullptr, fused);
+    const SparseOperand sp = {pk->v.ws_fwd_val, pk->v.ws_fwd_idx, pk->v.ws_fwd_flag};
+    return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)x, (uint16_t *)y, pk->v.wz_fwd, sp, nullptr, act, nullptr, fused);
 }
 
 pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx, int act,
@@ -542,10 +544,11 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
     g.KS = pk->v.Fk / 16;
     g.lstep = 1; g.iscale = 1;
     int tr[9], tc[9];
+    const SparseOperand sp = {pk->v.ws_bwd_val, pk->v.ws_bwd_idx, pk->v.ws_bwd_flag};
     if (st == 1) {
         g.GH = d->H; g.GW = d->W; g.oscale = 1; g.ioff_y = g.ioff_x = -1;
         for (int t = 0; t < 9; ++t) { g.tap_w[t] = t; tr[t] = 2 - t / 3; tc[t] = 2 - t % 3; }
-        return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd, nullptr, act,
+        return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd, sp, nullptr, act,
                              (const uint16_t *)act_mask, fused);
     }
     // stride 2: input pixel (iy, ix) of parity class (py, px) = (iy % 2, ix % 2) receives the taps (r, s) with
@@ -571,5 +574,5 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
     }
     g.GH = (d->H + 1) / 2; g.GW = (d->W + 1) / 2;
     g.oscale = 2; g.ioff_y = g.ioff_x = 0;
-    return run_mfma_conv(ctx, g, 2, 4, nullptr, nullptr, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd, &pcl);
+    return run_mfma_conv(ctx, g, 2, 4, nullptr, nullptr, (const uint16_t *)dy, (uint16_t *)dx, pk->v.wz_bwd, sp, &pcl);
 }

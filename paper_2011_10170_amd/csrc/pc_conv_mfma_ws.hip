@@ -46,6 +46,156 @@ __device__ __forceinline__ uint32_t pc_mask_bf16x2(uint32_t u, uint32_t a)
     return u & (lo | hi);
 }
 
+// The loader wavefronts of the wave-specialised kernels (wavefronts 4..7 of a workgroup of 8): they stage the input
+// halo tile of the NEXT item (tile, chunk of KC channels) into one of two LDS buffers, their global loads KS_DEPTH
+// items ahead in registers, and execute one workgroup barrier after the first staged item and one per item.
+//   vb, G: index of this workgroup in the tile order and the number of workgroups; ntile_blk tiles of nch chunks each
+template <int KC, int NV>
+__device__ __forceinline__ void pc_ks_loader_role(const uint16_t *__restrict__ in, const MfmaArgs &g, unsigned char *lds, int vb, int G,
+                                                  int ntile_blk, int nch)
+{
+    constexpr int PITCH = 2 * KC + 16;
+    constexpr int PARTS = KC / 8;
+    const int I = ntile_blk * nch;
+    // ------------------------------------------------------------ loaders
+    const int tl = threadIdx.x - 256;
+    const int part = tl % PARTS;
+    // The input is read with buffer loads: an offset past the end of the tensor returns zeros, which
+    // serves every element that is not a real input value (zero padding around the image, images
+    // past the batch, channels past the last one, unused loader slots) without a branch. Loads and
+    // LDS writes stay unconditional, so the compiler can count the loads in flight and wait for
+    // exactly the oldest register set.
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(in), 0, g.in_bytes, 0x00020000);
+    constexpr uint32_t OOB = 0x80000000u;   // past any tensor this kernel accepts, and no wrap-around with the chunk offset
+    const bool part_in_last = (nch - 1) * KC + part * 8 < g.in_CH;   // this thread's channels exist in the last chunk
+    int pk[NV], loff[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int e = tl + 256 * v;
+        const uint32_t q = (uint32_t)e / PARTS;
+        const uint32_t t2 = pc_udiv(q, g.mg_IW);
+        const int ix = (int)(q - t2 * g.IW);
+        const uint32_t ti = pc_udiv(t2, g.mg_IH);
+        const int iy = (int)(t2 - ti * g.IH);
+        pk[v] = e < g.nelem ? (int)((ti << 20) | (iy << 10) | ix) : -1;
+        loff[v] = e < g.nelem ? (int)q * PITCH + part * 16 : g.xbuf - 16;
+    }
+    int lk = 0, lch = 0;              // cursor of the next item to load
+    uint32_t voff[NV];             // byte offset of every element's pixel (+ its 16-byte part) in the tensor
+    auto tile_offsets = [&](int k) {
+        const uint32_t tq = pc_udiv((uint32_t)(vb + k * G), g.mg_fd);
+        const uint32_t pt = g.m_fast ? tq : (uint32_t)(vb + k * G) - tq * g.fdiv;
+        const uint32_t u = pc_udiv(pt, g.mg_tx);
+        const int tx = (int)(pt - u * g.tiles_x);
+        const uint32_t tnn = pc_udiv(u, g.mg_ty);
+        const int ty = (int)(u - tnn * g.tiles_y);
+        const int ltn = (int)tnn * g.TI;
+        const int ly0 = ty * g.TH * g.iscale + g.ioff_y;
+        const int lx0 = tx * g.TW * g.iscale + g.ioff_x;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int n = ltn + (pk[v] >> 20), y = ly0 + ((pk[v] >> 10) & 1023), x = lx0 + (pk[v] & 1023);
+            const bool ok = pk[v] >= 0 && n < g.N && (unsigned)y < (unsigned)g.in_H && (unsigned)x < (unsigned)g.in_W;
+            voff[v] = ok ? (uint32_t)((n * g.in_H + y) * g.in_W + x) * (uint32_t)(g.in_CH * 2) + part * 16 : OOB;
+        }
+    };
+    tile_offsets(0);
+    auto issue = [&](uint4 (&R)[NV]) {
+        const int so = lch * (KC * 2);
+        const bool cut = (lch == nch - 1 && !part_in_last) || lk >= ntile_blk;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const v4u32 val = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(cut ? OOB : voff[v]), so, 0);
+            R[v] = make_uint4(val.x, val.y, val.z, val.w);
+        }
+        if (lk < ntile_blk && ++lch == nch) {
+            lch = 0;
+            if (++lk < ntile_blk) tile_offsets(lk);
+        }
+    };
+    auto put = [&](const uint4 (&R)[NV], int bufoff) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) *reinterpret_cast<uint4 *>(lds + bufoff + loff[v]) = R[v];
+    };
+    uint4 R0[NV], R1[NV], R2[NV];
+    issue(R0); issue(R1);
+    put(R0, 0);
+    __syncthreads();
+    issue(R2); issue(R0);
+    // item i: while the MFMA wavefronts work on buffer i&1, write item i+1 (register set (i+1)%3) to the
+    // other buffer (past the last item: zeros, never read) and refill that set with item i+4
+    auto lstep = [&](int i, uint4 (&R)[NV]) {
+        put(R, ((i + 1) & 1) * g.xbuf);
+        issue(R);
+        __syncthreads();
+    };
+    int i = 0;
+    for (; i + 3 <= I; i += 3) {
+        lstep(i, R1);
+        lstep(i + 1, R2);
+        lstep(i + 2, R0);
+    }
+    if (i < I) {
+        lstep(i, R1);
+        if (i + 1 < I) lstep(i + 1, R2);
+    }
+}
+
+// End of a tile when the MFMA wavefronts split the pixels: every wavefront stores its own 32*B_T pixels, 64 at a time
+// through a private LDS area (pixel-major bf16 rows): read back, 8 consecutive lanes hold the 128 contiguous bytes of
+// one pixel's 64 channels and the stores are whole 16-byte pieces of full lines instead of scattered 8-byte ones.
+template <int A_T, int B_T, int ACT>
+__device__ __forceinline__ void pc_ks_store_pixels(const f32x16 (&acc)[A_T][B_T], unsigned char *lds, const MfmaArgs &g, int w, int lane,
+                                                   int mt, int tn, int gy0, int gx0, int npix, __amdgpu_buffer_rsrc_t osrc,
+                                                   __amdgpu_buffer_rsrc_t msrc)
+{
+    constexpr uint32_t OOB_OUT = 0x80000000u;
+    // Every wavefront stores its own 32*B_T pixels, 64 at a time through a private LDS area (pixel-major
+    // bf16 rows): read back, 8 consecutive lanes hold the 128 contiguous bytes of one pixel's 64 channels
+    // and the stores are whole 16-byte pieces of full lines instead of scattered 8-byte ones.
+    unsigned char *stg = lds + g.red_off + w * (64 * 144);
+#pragma unroll
+    for (int half = 0; half < B_T / 2; ++half) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int j = half * 2 + jj;
+                    uint2 pkd;
+                    pkd.x = pc_pack_bf16x2(acc[ii][j][q4 * 4 + 0], acc[ii][j][q4 * 4 + 1]);
+                    pkd.y = pc_pack_bf16x2(acc[ii][j][q4 * 4 + 2], acc[ii][j][q4 * 4 + 3]);
+                    *reinterpret_cast<uint2 *>(stg + (jj * 32 + (lane & 31)) * 144 + (ii * 32 + q4 * 8 + (lane >> 5) * 4) * 2) = pkd;
+                }
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int px = it * 8 + (lane >> 3), c16 = lane & 7;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + px * 144 + c16 * 16);
+            const int q = (w * B_T + half * 2) * 32 + px;
+            const int ti = (int)pc_udiv((uint32_t)q, g.mg_THTW);
+            const int rem = q - ti * g.TH * g.TW;
+            const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
+            const int n = tn + ti, gy = gy0 + y, gx = gx0 + x;
+            const int m = mt * (32 * A_T) + c16 * 8;
+            const bool ok = q < npix && n < g.N && gy < g.GH && gx < g.GW && m < g.out_CH && c16 < 4 * A_T;
+            const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
+            const uint32_t off = ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) + (uint32_t)(m * 2) : OOB_OUT;
+            v4u32 pv = {v.x, v.y, v.z, v.w};
+            if (ACT == PC_ACT_RELU) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pv[e] = pc_relu_bf16x2(pv[e]);
+            } else if (ACT == PC_ACT_RELU_MASK) {
+                const v4u32 mk = __builtin_amdgcn_raw_buffer_load_b128(msrc, (int)off, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pv[e] = pc_mask_bf16x2(pv[e], mk[e]);
+            }
+            __builtin_amdgcn_raw_buffer_store_b128(pv, osrc, (int)off, 0, 0);
+        }
+    }
+}
+
 // ACT: PC_ACT_NONE, or a fused step on the stored values: PC_ACT_RELU (negative outputs become +0) or
 // PC_ACT_RELU_MASK (outputs are kept where g.act_mask, a tensor of the output's shape, is positive).
 template <int A_T, int B_T, int NTAPS, int KC, int KSP, int ACT = PC_ACT_NONE>
@@ -82,89 +232,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     const int I = ntile_blk * nch;
 
     if (wave >= 4) {
-        // ------------------------------------------------------------ loaders
-        const int tl = threadIdx.x - 256;
-        const int part = tl % PARTS;
-        // The input is read with buffer loads: an offset past the end of the tensor returns zeros, which
-        // serves every element that is not a real input value (zero padding around the image, images
-        // past the batch, channels past the last one, unused loader slots) without a branch. Loads and
-        // LDS writes stay unconditional, so the compiler can count the loads in flight and wait for
-        // exactly the oldest register set.
-        const __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(in), 0, g.in_bytes, 0x00020000);
-        constexpr uint32_t OOB = 0x80000000u;   // past any tensor this kernel accepts, and no wrap-around with the chunk offset
-        const bool part_in_last = (nch - 1) * KC + part * 8 < g.in_CH;   // this thread's channels exist in the last chunk
-        int pk[NV], loff[NV];
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int e = tl + 256 * v;
-            const uint32_t q = (uint32_t)e / PARTS;
-            const uint32_t t2 = pc_udiv(q, g.mg_IW);
-            const int ix = (int)(q - t2 * g.IW);
-            const uint32_t ti = pc_udiv(t2, g.mg_IH);
-            const int iy = (int)(t2 - ti * g.IH);
-            pk[v] = e < g.nelem ? (int)((ti << 20) | (iy << 10) | ix) : -1;
-            loff[v] = e < g.nelem ? (int)q * PITCH + part * 16 : g.xbuf - 16;
-        }
-        int lk = 0, lch = 0;              // cursor of the next item to load
-        uint32_t voff[NV];             // byte offset of every element's pixel (+ its 16-byte part) in the tensor
-        auto tile_offsets = [&](int k) {
-            const uint32_t tq = pc_udiv((uint32_t)(vb + k * G), g.mg_fd);
-            const uint32_t pt = g.m_fast ? tq : (uint32_t)(vb + k * G) - tq * g.fdiv;
-            const uint32_t u = pc_udiv(pt, g.mg_tx);
-            const int tx = (int)(pt - u * g.tiles_x);
-            const uint32_t tnn = pc_udiv(u, g.mg_ty);
-            const int ty = (int)(u - tnn * g.tiles_y);
-            const int ltn = (int)tnn * g.TI;
-            const int ly0 = ty * g.TH * g.iscale + g.ioff_y;
-            const int lx0 = tx * g.TW * g.iscale + g.ioff_x;
-#pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const int n = ltn + (pk[v] >> 20), y = ly0 + ((pk[v] >> 10) & 1023), x = lx0 + (pk[v] & 1023);
-                const bool ok = pk[v] >= 0 && n < g.N && (unsigned)y < (unsigned)g.in_H && (unsigned)x < (unsigned)g.in_W;
-                voff[v] = ok ? (uint32_t)((n * g.in_H + y) * g.in_W + x) * (uint32_t)(g.in_CH * 2) + part * 16 : OOB;
-            }
-        };
-        tile_offsets(0);
-        auto issue = [&](uint4 (&R)[NV]) {
-            const int so = lch * (KC * 2);
-            const bool cut = (lch == nch - 1 && !part_in_last) || lk >= ntile_blk;
-#pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const v4u32 val = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(cut ? OOB : voff[v]), so, 0);
-                R[v] = make_uint4(val.x, val.y, val.z, val.w);
-            }
-            if (lk < ntile_blk && ++lch == nch) {
-                lch = 0;
-                if (++lk < ntile_blk) tile_offsets(lk);
-            }
-        };
-        auto put = [&](const uint4 (&R)[NV], int bufoff) {
-#pragma unroll
-            for (int v = 0; v < NV; ++v) *reinterpret_cast<uint4 *>(lds + bufoff + loff[v]) = R[v];
-        };
-        uint4 R0[NV], R1[NV], R2[NV];
-        issue(R0); issue(R1);
-        put(R0, 0);
-        __syncthreads();
-        issue(R2); issue(R0);
-        // item i: while the MFMA wavefronts work on buffer i&1, write item i+1 (register set (i+1)%3) to the
-        // other buffer (past the last item: zeros, never read) and refill that set with item i+4
-        auto lstep = [&](int i, uint4 (&R)[NV]) {
-            put(R, ((i + 1) & 1) * g.xbuf);
-            issue(R);
-            __syncthreads();
-        };
-        int i = 0;
-        for (; i + 3 <= I; i += 3) {
-            lstep(i, R1);
-            lstep(i + 1, R2);
-            lstep(i + 2, R0);
-        }
-        if (i < I) {
-            lstep(i, R1);
-            if (i + 1 < I) lstep(i + 1, R2);
-        }
+        pc_ks_loader_role<KC, NV>(in, g, lds, vb, G, ntile_blk, nch);
         return;
     }
 
@@ -317,51 +385,7 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         }
         __syncthreads();
 
-        if (KSP == 1 && ch == nch - 1) {
-            // Every wavefront stores its own 32*B_T pixels, 64 at a time through a private LDS area (pixel-major
-            // bf16 rows): read back, 8 consecutive lanes hold the 128 contiguous bytes of one pixel's 64 channels
-            // and the stores are whole 16-byte pieces of full lines instead of scattered 8-byte ones.
-            unsigned char *stg = lds + g.red_off + w * (64 * 144);
-#pragma unroll
-            for (int half = 0; half < B_T / 2; ++half) {
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-                    for (int ii = 0; ii < A_T; ++ii)
-#pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4) {
-                            const int j = half * 2 + jj;
-                            uint2 pkd;
-                            pkd.x = pc_pack_bf16x2(acc[ii][j][q4 * 4 + 0], acc[ii][j][q4 * 4 + 1]);
-                            pkd.y = pc_pack_bf16x2(acc[ii][j][q4 * 4 + 2], acc[ii][j][q4 * 4 + 3]);
-                            *reinterpret_cast<uint2 *>(stg + (jj * 32 + (lane & 31)) * 144 + (ii * 32 + q4 * 8 + (lane >> 5) * 4) * 2) = pkd;
-                        }
-#pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const int px = it * 8 + (lane >> 3), c16 = lane & 7;
-                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + px * 144 + c16 * 16);
-                    const int q = (w * B_T + half * 2) * 32 + px;
-                    const int ti = (int)pc_udiv((uint32_t)q, g.mg_THTW);
-                    const int rem = q - ti * g.TH * g.TW;
-                    const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
-                    const int n = tn + ti, gy = gy0 + y, gx = gx0 + x;
-                    const int m = mt * (32 * A_T) + c16 * 8;
-                    const bool ok = q < npix && n < g.N && gy < g.GH && gx < g.GW && m < g.out_CH && c16 < 4 * A_T;
-                    const int oy = gy * g.oscale + g.ooff_y, ox = gx * g.oscale + g.ooff_x;
-                    const uint32_t off = ok ? (uint32_t)((n * g.out_H + oy) * g.out_W + ox) * (uint32_t)(g.out_CH * 2) + (uint32_t)(m * 2) : OOB_OUT;
-                    v4u32 pv = {v.x, v.y, v.z, v.w};
-                    if (ACT == PC_ACT_RELU) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) pv[e] = pc_relu_bf16x2(pv[e]);
-                    } else if (ACT == PC_ACT_RELU_MASK) {
-                        const v4u32 mk = __builtin_amdgcn_raw_buffer_load_b128(msrc, (int)off, 0, 0);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) pv[e] = pc_mask_bf16x2(pv[e], mk[e]);
-                    }
-                    __builtin_amdgcn_raw_buffer_store_b128(pv, osrc, (int)off, 0, 0);
-                }
-            }
-        }
+        if (KSP == 1 && ch == nch - 1) pc_ks_store_pixels<A_T, B_T, ACT>(acc, lds, g, w, lane, mt, tn, gy0, gx0, npix, osrc, msrc);
         if (KSP == 4 && ch == nch - 1) {
             const int n = tn + o_ti, gy = gy0 + o_y, gx = gx0 + o_x;
             const bool pix_ok = qo < npix && n < g.N && gy < g.GH && gx < g.GW;
@@ -421,6 +445,230 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     }
 }
 
+// ------------------------------------------------------------------ structured-sparse variant
+// The same kernel with the pixels split over the MFMA wavefronts (tiles of 64 output channels x 128*B_T/... pixels),
+// multiplying with v_smfmac_f32_32x32x32_bf16: the weight operand holds at most 2 nonzeros in every 4 consecutive
+// reduction entries of a row and the instruction covers 32 reduction entries in the time the dense one covers 16.
+// A hard-pruned layer has a weight density of keep * 4/9 per (filter, tap, channel), so nearly every group of 4
+// channels holds at most 2 kept weights; the rest (third and fourth nonzeros of a group) form a second operand of
+// the same kind whose instruction is issued only for the (row tile, tap, step) fragments where it is not all zero
+// (flag bits written at pack time). Both together are exact for any mask; the number of instructions falls with
+// the sparsity. Operand layout (measured): the B operand of one instruction is the B operands of two consecutive
+// dense steps (16 entries per lane); lane l of the A operand holds row l % 32 and, of the 16 entries of dense step
+// l / 32, two stored values per group of 4 with their 2-bit positions in the low (part 1) or high (part 2) half of
+// the index word (selected by the instruction's last operand).
+typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
+
+template <int B_T, int KC, int ACT = PC_ACT_NONE>
+__global__ void __launch_bounds__(512, 1)
+pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const uint16_t *__restrict__ wsv,
+                       const uint32_t *__restrict__ wsi, const uint16_t *__restrict__ wsf, MfmaArgs g)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int A_T = 2;
+    constexpr int SS = KC / 32;           // sparse steps per tap and chunk
+    constexpr int NV = KS_NV1;
+    constexpr int S = 9 * SS;             // steps per item
+    constexpr int NSET = S * A_T;         // operand sets (part 1, part 2, index word) per item
+    constexpr int PFD = pc_ring_depth(NSET, 6);   // sets in flight: what the registers hold beside accumulators and B operands
+    constexpr int PITCH = 2 * KC + 16;
+    constexpr int DBS = B_T >= 4 ? 1 : 2; // B operands are read this many steps ahead
+    constexpr int RB = DBS + 1;
+    static_assert(KC == 32 || KC == 64, "one or two sparse steps per tap and chunk");
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = wave & 3;
+    const int G = gridDim.x;
+    int vb = blockIdx.x;
+    if ((G & 7) == 0) vb = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
+    const int ntile_blk = (g.total_tiles - vb + G - 1) / G;
+    const int nch = g.nchunks;
+    const int I = ntile_blk * nch;
+
+    if (wave >= 4) {
+        pc_ks_loader_role<KC, NV>(in, g, lds, vb, G, ntile_blk, nch);
+        return;
+    }
+
+    const int npix = g.TI * g.TH * g.TW;
+    int base[B_T];
+#pragma unroll
+    for (int j = 0; j < B_T; ++j) {
+        int q = (w * B_T + j) * 32 + (lane & 31);
+        if (q >= npix) q = npix - 1;
+        const int ti = (int)pc_udiv((uint32_t)q, g.mg_THTW);
+        const int rem = q - ti * g.TH * g.TW;
+        const int y = (int)pc_udiv((uint32_t)rem, g.mg_TW), x = rem - y * g.TW;
+        base[j] = ((ti * g.IH + y * g.lstep) * g.IW + x * g.lstep) * PITCH + (lane >> 5) * 16;
+    }
+    const __amdgpu_buffer_rsrc_t osrc = __builtin_amdgcn_make_buffer_rsrc(out, 0, g.out_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t msrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(ACT == PC_ACT_RELU_MASK ? g.act_mask : out), 0, g.out_bytes, 0x00020000);
+    // Operand sets are read with buffer loads, the lane's bytes as the vector offset and everything else scalar:
+    // set (row tile ii, tap t, step s) of an item lies (ii*9 + t) * KS32 + s sets past the item's first one; a set is
+    // 2 KiB of values (part 1, part 2) and 256 bytes of index words.
+    const int KS32 = g.KS >> 1;
+    const __amdgpu_buffer_rsrc_t vsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(wsv), 0, g.wz_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t isrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(wsi), 0, g.wz_bytes >> 3, 0x00020000);
+    const int v_voff = lane * 16, i_voff = lane * 4;
+    const int ksb = KS32 * 2048;          // bytes of values between the sets of two taps
+    auto set_off = [&](int p) -> int {    // p: compile-time set index inside the item
+        const int st = p / A_T, ii = p % A_T;
+        return (ii * 9 + st / SS) * ksb + (st % SS) * 2048;
+    };
+    // (live = false: the lane's offset is past the buffer, the load returns zeros and moves nothing; the part-2 loads of
+    // fragments without a nonzero are switched off this way, so that every load stays unconditional and the compiler
+    // can count the loads in flight)
+    auto load_vals = [&](int item_base, int p, int part, bool live = true) -> bf16x8 {
+        const v4u32 r = __builtin_amdgcn_raw_buffer_load_b128(vsrc, live ? v_voff : (int)0x80000000u, item_base + set_off(p) + part * 1024, 0);
+        bf16x8 o;
+        __builtin_memcpy(&o, &r, 16);
+        return o;
+    };
+    auto load_idx = [&](int item_base, int p) -> uint32_t {
+        return __builtin_amdgcn_raw_buffer_load_b32(isrc, i_voff, (item_base + set_off(p)) >> 3, 0);
+    };
+    // flag bits of the part-2 operands of an item: bit 16*s + t of word ii (KC = 64), bit t (KC = 32)
+    auto load_flags = [&](int mt_, int ch_, uint32_t &f0, uint32_t &f1) {
+        const int r0 = (mt_ * A_T) * KS32 + ch_ * SS, r1 = r0 + KS32;
+        uint32_t a, b;
+        if (SS == 2) {
+            a = reinterpret_cast<const uint32_t *>(wsf)[r0 >> 1];
+            b = reinterpret_cast<const uint32_t *>(wsf)[r1 >> 1];
+        } else {
+            a = wsf[r0];
+            b = wsf[r1];
+        }
+        f0 = __builtin_amdgcn_readfirstlane(a);
+        f1 = __builtin_amdgcn_readfirstlane(b);
+    };
+    auto flag_of = [&](uint32_t f0, uint32_t f1, int p) -> bool {
+        const int st = p / A_T, ii = p % A_T;
+        return (((ii ? f1 : f0) >> (16 * (st % SS) + st / SS)) & 1u) != 0u;
+    };
+    auto tap_off = [&](int t) -> int { return g.tap_o0 + (t / 3) * g.tap_dr + (t % 3) * g.tap_ds; };
+    int mt = 0, tn = 0, gy0 = 0, gx0 = 0;
+    auto tile_of = [&](int k, int &mt_, int &tn_, int &gy0_, int &gx0_) {
+        const uint32_t t = (uint32_t)(vb + k * G);
+        const uint32_t tq = pc_udiv(t, g.mg_fd), trm = t - tq * g.fdiv;
+        const uint32_t pt = g.m_fast ? tq : trm;
+        mt_ = (int)(g.m_fast ? trm : tq);
+        const uint32_t u = pc_udiv(pt, g.mg_tx);
+        const int tx = (int)(pt - u * g.tiles_x);
+        const uint32_t tnn = pc_udiv(u, g.mg_ty);
+        const int ty = (int)(u - tnn * g.tiles_y);
+        tn_ = (int)tnn * g.TI;
+        gy0_ = ty * g.TH;
+        gx0_ = tx * g.TW;
+    };
+    auto a_base = [&](int mt_, int ch_) -> int { return ((mt_ * A_T * 9) * KS32 + ch_ * SS) * 2048; };
+    tile_of(0, mt, tn, gy0, gx0);
+    int k = 0, ch = 0;
+    int ab = a_base(mt, 0);
+    uint32_t fl0, fl1;
+    load_flags(mt, 0, fl0, fl1);
+
+    f32x16 acc[A_T][B_T];
+#pragma unroll
+    for (int i = 0; i < A_T; ++i)
+#pragma unroll
+        for (int j = 0; j < B_T; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 r1[PFD], r2[PFD];
+    uint32_t rx[PFD];
+#pragma unroll
+    for (int p = 0; p < PFD; ++p) {
+        r1[p] = load_vals(ab, p, 0);
+        rx[p] = load_idx(ab, p);
+        r2[p] = load_vals(ab, p, 1, flag_of(fl0, fl1, p));
+    }
+
+    __syncthreads();
+    for (int i = 0; i < I; ++i) {
+        int nk = k, nchk = ch + 1, nmt = mt, ntn = tn, ngy0 = gy0, ngx0 = gx0;
+        if (nchk == nch) {
+            nchk = 0;
+            nk = k + 1;
+            if (nk < ntile_blk) tile_of(nk, nmt, ntn, ngy0, ngx0);
+            else nchk = ch;
+        }
+        const int abn = a_base(nmt, nchk);
+        uint32_t nfl0, nfl1;
+        load_flags(nmt, nchk, nfl0, nfl1);
+        const unsigned char *xb = lds + (i & 1) * g.xbuf;
+
+        auto read_b = [&](int st, int j) -> bf16x16 {   // the B operands of dense steps 2s and 2s+1 of the tap
+            const unsigned char *pb = xb + base[j] + tap_off(st / SS) + (st % SS) * 64;
+            const bf16x8 lo = *reinterpret_cast<const bf16x8 *>(pb), hi = *reinterpret_cast<const bf16x8 *>(pb + 32);
+            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+        };
+        bf16x16 bring[RB][B_T];
+#pragma unroll
+        for (int d = 0; d < DBS; ++d)
+#pragma unroll
+            for (int j = 0; j < B_T; ++j) bring[d % RB][j] = read_b(d, j);
+#pragma unroll
+        for (int st = 0; st < S; ++st) {
+            if (st + DBS < S) {
+#pragma unroll
+                for (int j = 0; j < B_T; ++j) bring[(st + DBS) % RB][j] = read_b(st + DBS, j);
+            }
+            bf16x8 a1[A_T], a2[A_T];
+            uint32_t ax[A_T];
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii) {
+                const int p = st * A_T + ii, np = p + PFD;
+                a1[ii] = r1[p % PFD];
+                a2[ii] = r2[p % PFD];
+                ax[ii] = rx[p % PFD];
+                // refill the slot with the set PFD ahead: of this item, or of the next one
+                r1[p % PFD] = np < NSET ? load_vals(ab, np < NSET ? np : 0, 0) : load_vals(abn, np < NSET ? 0 : np - NSET, 0);
+                rx[p % PFD] = np < NSET ? load_idx(ab, np < NSET ? np : 0) : load_idx(abn, np < NSET ? 0 : np - NSET);
+                r2[p % PFD] = np < NSET ? load_vals(ab, np < NSET ? np : 0, 1, flag_of(fl0, fl1, np < NSET ? np : 0))
+                                        : load_vals(abn, np < NSET ? 0 : np - NSET, 1, flag_of(nfl0, nfl1, np < NSET ? 0 : np - NSET));
+            }
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+                    acc[ii][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a1[ii], bring[st % RB][j], acc[ii][j], (int)ax[ii], 0, 0);
+#pragma unroll
+            for (int m = 0; m < A_T * B_T; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);       // address arithmetic
+                if (m < B_T) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // the two LDS reads of a B operand
+                else if (m < B_T + A_T) __builtin_amdgcn_sched_group_barrier(0x020, 3, 0);   // both value parts and the index word of a set
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // the second parts: only where the pack found a nonzero (uniform branches on scalar bits)
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii) {
+                if (flag_of(fl0, fl1, st * A_T + ii)) {
+#pragma unroll
+                    for (int j = 0; j < B_T; ++j)
+                        acc[ii][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a2[ii], bring[st % RB][j], acc[ii][j], (int)ax[ii], 0, 1);
+                }
+            }
+        }
+        __syncthreads();
+        if (ch == nch - 1) {
+            pc_ks_store_pixels<A_T, B_T, ACT>(acc, lds, g, w, lane, mt, tn, gy0, gx0, npix, osrc, msrc);
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                for (int j = 0; j < B_T; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[ii][j][r] = 0.0f;
+        }
+        k = nk; ch = nchk; mt = nmt; tn = ntn; gy0 = ngy0; gx0 = ngx0;
+        ab = abn;
+        fl0 = nfl0; fl1 = nfl1;
+    }
+}
+
 // ---- wave-specialised kernel: plan and launch (9-tap launches whose channel count is a multiple of 8)
 #define KS_LDS_MAX (160 * 1024)
 
@@ -446,6 +694,31 @@ static hipError_t launch_ks(int device, hipStream_t st, int grid, size_t lds, co
     if (act == PC_ACT_RELU) return launch_ks_act<A_T, B_T, KC, KSP, PC_ACT_RELU>(device, st, grid, lds, in, out, wz, g);
     if (act == PC_ACT_RELU_MASK) return launch_ks_act<A_T, B_T, KC, KSP, PC_ACT_RELU_MASK>(device, st, grid, lds, in, out, wz, g);
     return launch_ks_act<A_T, B_T, KC, KSP, PC_ACT_NONE>(device, st, grid, lds, in, out, wz, g);
+}
+
+template <int B_T, int KC, int ACT>
+static hipError_t launch_sp_act(int device, hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out,
+                                const SparseOperand &sp, const MfmaArgs &g)
+{
+    static pc_per_device_once attr;
+    if (pc_once_pending(attr, device)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pc_mfma_conv_sp_kernel<B_T, KC, ACT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, KS_LDS_MAX);
+        if (e != hipSuccess) return e;
+        pc_once_done(attr, device);
+    }
+    hipLaunchKernelGGL((pc_mfma_conv_sp_kernel<B_T, KC, ACT>), dim3((unsigned)grid), dim3(512), lds, st, in, out, sp.val, sp.idx,
+                       sp.flag, g);
+    return hipGetLastError();
+}
+
+template <int B_T, int KC>
+static hipError_t launch_sp(int device, hipStream_t st, int grid, size_t lds, const uint16_t *in, uint16_t *out,
+                            const SparseOperand &sp, const MfmaArgs &g, int act)
+{
+    if (act == PC_ACT_RELU) return launch_sp_act<B_T, KC, PC_ACT_RELU>(device, st, grid, lds, in, out, sp, g);
+    if (act == PC_ACT_RELU_MASK) return launch_sp_act<B_T, KC, PC_ACT_RELU_MASK>(device, st, grid, lds, in, out, sp, g);
+    return launch_sp_act<B_T, KC, PC_ACT_NONE>(device, st, grid, lds, in, out, sp, g);
 }
 
 // Fills the tile plan; false when the staged tile does not fit. ksp = 4: the MFMA wavefronts split the
@@ -520,9 +793,33 @@ static bool plan_ks(const MfmaArgs &g, int ext, int at, int bt, int ksp, int kc,
 
 // PC_OK: launched. PC_ERR_UNSUPPORTED without a message: not applicable, the caller uses the other kernel.
 pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext, const int *tr, const int *tc,
-                              const uint16_t *in, uint16_t *out, const uint16_t *wz, bool *launched, int act)
+                              const uint16_t *in, uint16_t *out, const uint16_t *wz, const SparseOperand &sp, bool *launched, int act)
 {
     *launched = false;
+    // The structured-sparse kernel (override code 22; automatic from 64 reduction channels up): 64 x 256 tiles,
+    // 64-channel chunks, pixels split over the MFMA wavefronts.
+    if (sp.val && (pcfg == 22 || (pcfg < 0 && g0.in_CH >= 64))) {
+        MfmaArgs t;
+        size_t lds;
+        double est;
+        bool ok = plan_ks(g0, ext, 2, 2, 1, 64, &t, &lds, &est, ctx->num_cu);
+        for (int q = 0; q < 9 && ok; ++q)
+            if (t.tap_w[q] != q || tr[q] != (tr[0] ? 2 - q / 3 : q / 3) || tc[q] != (tc[0] ? 2 - q % 3 : q % 3)) ok = false;
+        if (ok) {
+            const int pitch = 2 * 64 + 16;
+            t.tap_dr = (tr[0] ? -1 : 1) * t.IW * pitch;
+            t.tap_ds = (tc[0] ? -1 : 1) * pitch;
+            t.tap_o0 = (tr[0] * t.IW + tc[0]) * pitch;
+            t.wz_bytes = (uint32_t)((size_t)((t.out_CH + 127) / 128 * 4) * 9 * t.KS * 1024);
+            const int grid = t.total_tiles < ctx->num_cu ? t.total_tiles : ctx->num_cu;
+            const hipError_t e = launch_sp<2, 64>(ctx->device, ctx->stream, grid, lds, in, out, sp, t, act);
+            *launched = true;
+            pc_note_kernel(ctx, "pc_mfma_conv_sp_kernel<2, 64, %d>", act);
+            return pc_hip_check(ctx, e, "MFMA conv (structured-sparse) launch");
+        }
+        if (pcfg == 22) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA conv: the structured-sparse kernel does not fit this launch");
+    }
+    if (pcfg == 22) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA conv: the pack holds no structured-sparse operand");
     // candidates: (pixel-tile factor, reduction split); override codes 7, 8, 9 and 13 force one of them
     enum { NCAND = 12 };
     static const int kAt[NCAND] = {2, 2, 2, 2, 2, 1, 2, 2, 2, 1, 2, 2}, kBt[NCAND] = {4, 2, 1, 4, 1, 1, 2, 4, 2, 4, 2, 2},

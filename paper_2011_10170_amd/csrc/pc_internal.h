@@ -52,6 +52,16 @@ struct PackView {
     // MFMA operand tiles (bf16 bit patterns, zero at every pruned position), fragment order
     uint16_t *wz_fwd;     // A operand of the forward pass
     uint16_t *wz_bwd;     // A operand of the backward-data pass
+    // The same operands for the structured-sparse matrix instruction (at most 2 nonzeros in every 4 consecutive
+    // reduction entries of a row): row tile rt of 32 rows, tap, step ss of 32 reduction entries.
+    //   ws_*_val [rt][tap][ss][2][64 lanes][8]: part 0 holds the first two nonzeros of every group of 4, part 1 the
+    //            third and fourth (zero almost everywhere: the two parts together are exact for any mask);
+    //   ws_*_idx [rt][tap][ss][64 lanes]: the 2-bit positions of the 8 stored values of a lane, part 0 in the low
+    //            half of the word, part 1 in the high half;
+    //   ws_*_flag [rt][ss]: bit t set when part 1 of tap t has a nonzero (the instruction for it is skipped otherwise)
+    uint16_t *ws_fwd_val, *ws_bwd_val;
+    uint32_t *ws_fwd_idx, *ws_bwd_idx;
+    uint16_t *ws_fwd_flag, *ws_bwd_flag;
     int32_t Fp, Cp;       // F and C rounded up to 128 (row extent of the operand tiles)
     int32_t Fk, Ck;       // F and C rounded up to 64, the largest channel chunk a kernel walks (reduction extent of the operand tiles)
 };

@@ -48,10 +48,19 @@ inline uint32_t pc_udiv_magic(int d) { return d == 1 ? 0u : (uint32_t)((((uint64
 // Pixel tile of about BN output pixels (TI images x TH x TW) and its staged input extent; ext = reach of the taps.
 void pc_plan_mfma_tiles(MfmaArgs *g, int BN, int ext);
 
+// The weight operand in the form the structured-sparse matrix instruction takes (PackView::ws_*_val, _idx, _flag of
+// the pass's orientation); val == nullptr: the pack has none.
+struct SparseOperand {
+    const uint16_t *val;
+    const uint32_t *idx;
+    const uint16_t *flag;
+};
+
 // Wave-specialised forward/backward-data kernel for full 3x3 tap lists. pcfg: -1 = take it when the plan says it
 // wins, >= 7 = the forced variant. *launched stays false when the launch is left to the cooperative kernel.
 pc_status pc_run_mfma_conv_ws(pc_ctx *ctx, int pcfg, const MfmaArgs &g0, int ext, const int *tr, const int *tc,
-                              const uint16_t *in, uint16_t *out, const uint16_t *wz, bool *launched, int act = PC_ACT_NONE);
+                              const uint16_t *in, uint16_t *out, const uint16_t *wz, const SparseOperand &sp, bool *launched,
+                              int act = PC_ACT_NONE);
 
 // Copies between a tensor with C < 8 channels per pixel and one with 8-channel (16-byte) pixel rows.
 void pc_launch_pad_channels(pc_ctx *ctx, const uint16_t *x, void *xp, int64_t npix, int C, int Cp);

@@ -573,6 +573,48 @@ __device__ __forceinline__ void pc_pack_count_row(const uint8_t *__restrict__ pi
 // wz_bwd has the roles of filter and channel exchanged (rows = channels, k = filters).
 // The pattern mask of a kernel comes from pid/keep, or (FROM_KINFO) from the kinfo table of an earlier pack.
 #define PC_TILE_PITCH 40   // bf16 elements per LDS row: 32 + 8 keeps 16-byte alignment and spreads the banks
+
+// 16 consecutive reduction entries of one row (bf16 bit patterns) as operands of the structured-sparse matrix
+// instruction: for each of the 4 groups of 4 entries, part 1 stores the first two nonzeros and part 2 the third and
+// fourth (stored value 2g + m of a part belongs to group g; an unused place holds zero), idx their 2-bit positions in
+// the group: bits [4g+1:4g] and [4g+3:4g+2] for part 1, the same 16 bits higher for part 2. A place without a
+// nonzero points at a position none of the part's nonzeros uses.
+__device__ __forceinline__ void pc_sparse_compress16(const uint16_t *src, uint4 *part1, uint4 *part2, uint32_t *idx)
+{
+    uint32_t w1[4] = {0u, 0u, 0u, 0u}, w2[4] = {0u, 0u, 0u, 0u};
+    uint32_t ix = 0u;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        // values and positions of the nonzeros of the group, in ascending position
+        uint32_t val[4] = {0u, 0u, 0u, 0u}, pos[4] = {0u, 0u, 0u, 0u};
+        int n = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t u = src[4 * g + e];
+            if (u & 0x7FFFu) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (k == n) { val[k] = u; pos[k] = (uint32_t)e; }
+                ++n;
+            }
+        }
+#pragma unroll
+        for (int part = 0; part < 2; ++part) {
+            const int m = n - 2 * part;                 // nonzeros left for this part
+            uint32_t a = 0u, b = 0u, pa = 0u, pb = 1u;  // none: zeros at positions 0 and 1
+            if (m >= 2) { a = val[2 * part]; b = val[2 * part + 1]; pa = pos[2 * part]; pb = pos[2 * part + 1]; }
+            else if (m == 1) {
+                const uint32_t p = pos[2 * part], x = val[2 * part];
+                if (p < 3u) { a = x; pa = p; pb = 3u; } else { b = x; pa = 0u; pb = 3u; }
+            }
+            (part ? w2 : w1)[g] = a | (b << 16);
+            ix |= (pa | (pb << 2)) << (4 * g + 16 * part);
+        }
+    }
+    *part1 = make_uint4(w1[0], w1[1], w1[2], w1[3]);
+    *part2 = make_uint4(w2[0], w2[1], w2[2], w2[3]);
+    *idx = ix;
+}
 template <bool FROM_KINFO>
 __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, const uint8_t *__restrict__ pid,
                                                    const uint8_t *__restrict__ keep, const LibArg &la, const PackView &v,
@@ -648,6 +690,8 @@ __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, 
             tB[tap][cl][r] = val;
         }
     }
+    __shared__ uint32_t lflag[2];
+    if (tid < 2) lflag[tid] = 0u;
     __syncthreads();
     const int KSf = v.Ck / 16, KSb = v.Fk / 16;
     uint4 *of = reinterpret_cast<uint4 *>(v.wz_fwd), *ob = reinterpret_cast<uint4 *>(v.wz_bwd);
@@ -659,6 +703,29 @@ __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, 
         if (2 * fb + sl < KSb)
             ob[((int64_t)(cb * 9 + tap) * KSb + 2 * fb + sl) * 64 + lane] = *reinterpret_cast<const uint4 *>(&tB[tap][row][col]);
     }
+    // The operands of the structured-sparse instruction: this block is one step of 32 reduction entries of row tile fb
+    // (forward) and of row tile cb (backward-data). Lane l of a fragment holds row l % 32 and the entries
+    // 16 * (l / 32) .. + 15 of the step.
+    if (!v.ws_fwd_val) return;            // uniform: only packs made for the structured-sparse kernel hold these
+    const int KS32f = v.Ck / 32, KS32b = v.Fk / 32;
+    for (int o = tid; o < 2 * 9 * 64; o += 256) {
+        const int lane = o & 63, q = o >> 6, tap = q % 9, bwd = q / 9;
+        const int rt = bwd ? cb : fb, ss = bwd ? fb : cb;
+        if (ss >= (bwd ? KS32b : KS32f)) continue;
+        const uint16_t *src = bwd ? &tB[tap][lane & 31][16 * (lane >> 5)] : &tA[tap][lane & 31][16 * (lane >> 5)];
+        uint4 p1, p2;
+        uint32_t idx;
+        pc_sparse_compress16(src, &p1, &p2, &idx);
+        const int64_t fr = (int64_t)(rt * 9 + tap) * (bwd ? KS32b : KS32f) + ss;
+        uint4 *ov = reinterpret_cast<uint4 *>(bwd ? v.ws_bwd_val : v.ws_fwd_val);
+        ov[(fr * 2 + 0) * 64 + lane] = p1;
+        ov[(fr * 2 + 1) * 64 + lane] = p2;
+        (bwd ? v.ws_bwd_idx : v.ws_fwd_idx)[fr * 64 + lane] = idx;
+        if (p2.x | p2.y | p2.z | p2.w) atomicOr(&lflag[bwd], 1u << tap);
+    }
+    __syncthreads();
+    if (tid == 0 && cb < KS32f) v.ws_fwd_flag[(int64_t)fb * KS32f + cb] = (uint16_t)lflag[0];
+    if (tid == 1 && fb < KS32b) v.ws_bwd_flag[(int64_t)cb * KS32b + fb] = (uint16_t)lflag[1];
 }
 
 // First launch of a pack: workgroups [0, F) count the filter rows, [F, F + ncm) the channel rows (ncm = C for the

@@ -148,6 +148,36 @@ def test_wave_specialised_kernel(B, ctx, oracle, cfg, shape):
         B.pc_set_plan_override(ctx, -1, 0)
 
 
+# The structured-sparse kernel (packs made under PC_VARIANT_MFMA_SPARSE): keep ratios from nearly every group of 4
+# channels within the instruction's 2-of-4 form (0.05) to none of them (1.0: every kept kernel's neighbours are kept
+# too, so the second operand part carries half of the weights); partial channel chunks, more tiles than workgroups.
+SPARSE_SHAPES = [
+    (3, 12, 20, 72, 96, 1),
+    (20, 2, 2, 128, 64, 1),
+    (5, 4, 4, 192, 80, 1),
+    (12, 32, 32, 64, 128, 1),
+    (2, 28, 28, 256, 64, 1),
+]
+
+
+@pytest.mark.parametrize("keep", [0.05, 0.2, 0.45, 1.0])
+@pytest.mark.parametrize("shape", SPARSE_SHAPES)
+def test_structured_sparse_kernel(B, ctx, oracle, keep, shape):
+    B.pc_set_plan_override(ctx, 22, 0)       # fail rather than fall back to another kernel
+    try:
+        v = run_case(B, ctx, oracle, shape, "bf16", 16, keep, B.PC_VARIANT_MFMA_SPARSE, ("sparse", keep))
+        assert v == B.PC_VARIANT_MFMA_SPARSE
+        assert B.pc_last_kernel(ctx).startswith("pc_mfma_wgrad")      # the weight gradient ran last
+    finally:
+        B.pc_set_plan_override(ctx, -1, 0)
+
+
+def test_structured_sparse_variant_other_layers(B, ctx, oracle):
+    """Layers the structured-sparse kernel does not take (few channels, stride 2) use the pack's dense tiles."""
+    for shape in [(2, 16, 16, 3, 64, 1), (3, 9, 11, 40, 24, 2), (2, 14, 14, 96, 32, 2)]:
+        run_case(B, ctx, oracle, shape, "bf16", 8, 0.3, B.PC_VARIANT_MFMA_SPARSE, "sparse_other")
+
+
 # Filter counts that are multiples of 8 (what the wave-specialised kernel takes): several pixel tiles per
 # workgroup, strided and tiny-image layers, partial channel tiles, short image groups; both backward-weight
 # kernels (10 = cooperative, 11 = wave-specialised).
