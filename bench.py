@@ -38,7 +38,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vgg16_imagenet")
-    ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma", "sparse"],
+                    help="kernel family of the packs: automatic, the gather kernels, the zero-filled matrix-core kernels, or the "
+                         "structured-sparse matrix-core kernels for the layers they take")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every step from the host instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
@@ -95,7 +97,7 @@ def main() -> int:
     stream = torch.cuda.Stream()          # every library call and every event of this run uses this stream
     torch.cuda.set_stream(stream)
     ctx = B.pc_create(0, stream.cuda_stream)
-    B.pc_set_variant(ctx, {"auto": B.PC_VARIANT_AUTO, "valu": B.PC_VARIANT_VALU, "mfma": B.PC_VARIANT_MFMA}[args.variant])
+    B.pc_set_variant(ctx, {"auto": B.PC_VARIANT_AUTO, "valu": B.PC_VARIANT_VALU, "mfma": B.PC_VARIANT_MFMA, "sparse": B.PC_VARIANT_MFMA_SPARSE}[args.variant])
     # a pack belongs to no context: another context on another stream may use it, ordered by events
     streams_w = [torch.cuda.Stream() for _ in range(args.wgrad_streams)]
     ctxs_w = [B.pc_create(0, s.cuda_stream) for s in streams_w]
@@ -327,11 +329,11 @@ def main() -> int:
             fl = dfl = 0.0
             mfma = False
         elif li < 0:                                         # the weight gradients of all layers in one call
-            mfma = all(x["variant"] == B.PC_VARIANT_MFMA for x in layers)
+            mfma = all(x["variant"] in (B.PC_VARIANT_MFMA, B.PC_VARIANT_MFMA_SPARSE) for x in layers)
             fl, dfl = sum(x["flops"] for x in layers), sum(x["dense_flops"] for x in layers)
             byts = float(sum(x["act_in"] + x["act_out"] + 16 * x["nnzk"] for x in layers))
         else:
-            mfma = d["variant"] == B.PC_VARIANT_MFMA
+            mfma = d["variant"] in (B.PC_VARIANT_MFMA, B.PC_VARIANT_MFMA_SPARSE)
             fl, dfl = d["flops"], d["dense_flops"]
             wbytes = d["nnzk"] * (4 * esz + 2)
             byts = float(d["act_in"] + d["act_out"] + (16 * d["nnzk"] if which == "bwd_weight" else wbytes))
@@ -659,7 +661,8 @@ def main() -> int:
             ks = I.kept_per_filter(kr, sC)
             B.pc_pattern_select(ctx, Ws, Gs, sF, sC, lib, B.PC_KEEP_PER_FILTER, ks, B.PC_SCORE_RETAINED, pids_, keeps_)
             t_us = {}
-            for vname, var in (("gather", B.PC_VARIANT_VALU), ("matrix", B.PC_VARIANT_MFMA), ("auto", B.PC_VARIANT_AUTO)):
+            for vname, var in (("gather", B.PC_VARIANT_VALU), ("matrix", B.PC_VARIANT_MFMA), ("sparse", B.PC_VARIANT_MFMA_SPARSE),
+                               ("auto", B.PC_VARIANT_AUTO)):
                 B.pc_set_variant(ctx, var)
                 pks = B.pc_pack(ctx, Ws, pids_, keeps_, sF, sC, lib, B.PC_BF16)
                 nz, picked = B.pc_packed_info(ctx, pks)
@@ -680,12 +683,12 @@ def main() -> int:
                 torch.cuda.synchronize()
                 t_us[vname] = round(e0.elapsed_time(e1) * 1e3 / 5, 1)
                 if vname == "auto":
-                    t_us["auto_picks"] = "matrix" if picked == B.PC_VARIANT_MFMA else "gather"
+                    t_us["auto_picks"] = {B.PC_VARIANT_MFMA: "matrix", B.PC_VARIANT_MFMA_SPARSE: "sparse"}.get(picked, "gather")
                 B.pc_packed_free(pks)
-            B.pc_set_variant(ctx, {"auto": B.PC_VARIANT_AUTO, "valu": B.PC_VARIANT_VALU, "mfma": B.PC_VARIANT_MFMA}[args.variant])
+            B.pc_set_variant(ctx, {"auto": B.PC_VARIANT_AUTO, "valu": B.PC_VARIANT_VALU, "mfma": B.PC_VARIANT_MFMA, "sparse": B.PC_VARIANT_MFMA_SPARSE}[args.variant])
             rows.append({"keep": round(ks / sC, 4), "weight_density": round(ks / sC * 4.0 / 9.0, 4), "us": t_us})
-            log("sweep keep %.3f density %.4f: gather %.1f us, matrix %.1f us, auto %.1f us (%s)" % (
-                ks / sC, ks / sC * 4 / 9, t_us["gather"], t_us["matrix"], t_us["auto"], t_us["auto_picks"]))
+            log("sweep keep %.3f density %.4f: gather %.1f us, matrix %.1f us, structured-sparse matrix %.1f us, auto %.1f us (%s)" % (
+                ks / sC, ks / sC * 4 / 9, t_us["gather"], t_us["matrix"], t_us["sparse"], t_us["auto"], t_us["auto_picks"]))
         sweep = {"layer": "N=%d %dx%d %d->%d stride %d, bf16, %d patterns" % (sN, sH, sW, sC, sF, sS, wl.P),
                  "passes": "fwd+bwd_data+bwd_weight", "rows": rows}
 

@@ -307,10 +307,26 @@ static size_t carve(PackView *v, PackView **v_dev, char *base, int F, int C, boo
         v->ws_bwd_idx = (uint32_t *)take(sizeof(uint32_t) * 64 * 9 * (size_t)(v->Cp / 32) * (v->Fk / 32));
         v->ws_fwd_flag = (uint16_t *)take(sizeof(uint16_t) * (size_t)(v->Fp / 32) * (v->Ck / 32));
         v->ws_bwd_flag = (uint16_t *)take(sizeof(uint16_t) * (size_t)(v->Cp / 32) * (v->Fk / 32));
+        const size_t lf = (size_t)(v->Fp / 32) * (v->Ck / 64), lb = (size_t)(v->Cp / 32) * (v->Fk / 64);
+        v->ov_fwd_cnt = (uint32_t *)take(sizeof(uint32_t) * lf);
+        v->ov_bwd_cnt = (uint32_t *)take(sizeof(uint32_t) * lb);
+        v->ov_fwd_a = (uint16_t *)take((size_t)1024 * PC_OV_STEPS * lf);
+        v->ov_bwd_a = (uint16_t *)take((size_t)1024 * PC_OV_STEPS * lb);
+        v->ov_fwd_col = (uint32_t *)take((size_t)64 * PC_OV_STEPS * lf);
+        v->ov_bwd_col = (uint32_t *)take((size_t)64 * PC_OV_STEPS * lb);
+        v->ov_fwd_sub_cnt = (uint32_t *)take(sizeof(uint32_t) * 2 * lf);
+        v->ov_bwd_sub_cnt = (uint32_t *)take(sizeof(uint32_t) * 2 * lb);
+        v->ov_fwd_sub_ent = (uint2 *)take(sizeof(uint2) * PC_OV_SUB * 2 * lf);
+        v->ov_bwd_sub_ent = (uint2 *)take(sizeof(uint2) * PC_OV_SUB * 2 * lb);
     } else {
         v->ws_fwd_val = v->ws_bwd_val = nullptr;
         v->ws_fwd_idx = v->ws_bwd_idx = nullptr;
         v->ws_fwd_flag = v->ws_bwd_flag = nullptr;
+        v->ov_fwd_cnt = v->ov_bwd_cnt = nullptr;
+        v->ov_fwd_a = v->ov_bwd_a = nullptr;
+        v->ov_fwd_col = v->ov_bwd_col = nullptr;
+        v->ov_fwd_sub_cnt = v->ov_bwd_sub_cnt = nullptr;
+        v->ov_fwd_sub_ent = v->ov_bwd_sub_ent = nullptr;
     }
     return off;
 }

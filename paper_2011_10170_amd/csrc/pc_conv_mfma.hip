@@ -529,7 +529,7 @@ pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, c
     g.KS = pk->v.Ck / 16;
     int tr[9], tc[9];
     for (int t = 0; t < 9; ++t) { g.tap_w[t] = t; tr[t] = t / 3; tc[t] = t % 3; }
-    const SparseOperand sp = {pk->v.ws_fwd_val, pk->v.ws_fwd_idx, pk->v.ws_fwd_flag};
+    const SparseOperand sp = {pk->v.ws_fwd_val, pk->v.ws_fwd_idx, pk->v.ws_fwd_flag, pk->v.ov_fwd_cnt, pk->v.ov_fwd_a, pk->v.ov_fwd_col};
     return run_mfma_conv(ctx, g, 3, 9, tr, tc, (const uint16_t *)x, (uint16_t *)y, pk->v.wz_fwd, sp, nullptr, act, nullptr, fused);
 }
 
@@ -544,7 +544,7 @@ pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *
     g.KS = pk->v.Fk / 16;
     g.lstep = 1; g.iscale = 1;
     int tr[9], tc[9];
-    const SparseOperand sp = {pk->v.ws_bwd_val, pk->v.ws_bwd_idx, pk->v.ws_bwd_flag};
+    const SparseOperand sp = {pk->v.ws_bwd_val, pk->v.ws_bwd_idx, pk->v.ws_bwd_flag, pk->v.ov_bwd_cnt, pk->v.ov_bwd_a, pk->v.ov_bwd_col};
     if (st == 1) {
         g.GH = d->H; g.GW = d->W; g.oscale = 1; g.ioff_y = g.ioff_x = -1;
         for (int t = 0; t < 9; ++t) { g.tap_w[t] = t; tr[t] = 2 - t / 3; tc[t] = 2 - t % 3; }

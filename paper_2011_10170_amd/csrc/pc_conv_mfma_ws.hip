@@ -459,38 +459,30 @@ pc_mfma_conv_ks_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 // the index word (selected by the instruction's last operand).
 typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
 
-template <int B_T, int KC, int ACT = PC_ACT_NONE>
-__global__ void __launch_bounds__(512, 1)
-pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const uint16_t *__restrict__ wsv,
-                       const uint32_t *__restrict__ wsi, const uint16_t *__restrict__ wsf, MfmaArgs g)
+// The MFMA wavefronts of the structured-sparse kernel. OVF: the overflow weights (third and fourth nonzeros of a
+// group of 4) are multiplied as extra reduction columns of a dense matrix instruction at the end of every item, from
+// the lists the pack wrote; else through the second operand part, one more sparse instruction wherever a fragment
+// holds any. Both are exact; the lists are the cheaper form (a handful of columns per item) but have a fixed
+// capacity, which a pack reports per list.
+template <int B_T, int KC, int ACT, bool OVF>
+__device__ __forceinline__ void pc_sp_mfma_role(uint16_t *__restrict__ out, const SparseOperand &sp, const MfmaArgs &g, unsigned char *lds,
+                                                int vb, int G, int ntile_blk, int nch, int lane, int w)
 {
-    extern __shared__ __align__(16) unsigned char lds[];
     constexpr int A_T = 2;
     constexpr int SS = KC / 32;           // sparse steps per tap and chunk
-    constexpr int NV = KS_NV1;
     constexpr int S = 9 * SS;             // steps per item
     constexpr int NSET = S * A_T;         // operand sets (part 1, part 2, index word) per item
-    constexpr int PFD = pc_ring_depth(NSET, 6);   // sets in flight: what the registers hold beside accumulators and B operands
+    // sets in flight (what the registers hold beside accumulators and B operands): the kernel's speed follows this depth
+    // (56 x 56, 256 -> 256, batch 32, forward, overflow lists: 116 / 111 / 104 us at 6 / 9 / 12 sets)
+    constexpr int PFD = pc_ring_depth(NSET, OVF ? 12 : 6);
     constexpr int PITCH = 2 * KC + 16;
-    constexpr int DBS = B_T >= 4 ? 1 : 2; // B operands are read this many steps ahead
+    constexpr int DBS = (B_T >= 4 || OVF) ? 1 : 2;   // B operands are read this many steps ahead
     constexpr int RB = DBS + 1;
-    static_assert(KC == 32 || KC == 64, "one or two sparse steps per tap and chunk");
-
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int w = wave & 3;
-    const int G = gridDim.x;
-    int vb = blockIdx.x;
-    if ((G & 7) == 0) vb = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
-    const int ntile_blk = (g.total_tiles - vb + G - 1) / G;
-    const int nch = g.nchunks;
+    static_assert(!OVF || KC == 64, "the overflow lists are per chunk of 64 reduction entries");
+    const uint16_t *__restrict__ wsv = sp.val;
+    const uint32_t *__restrict__ wsi = sp.idx;
+    const uint16_t *__restrict__ wsf = sp.flag;
     const int I = ntile_blk * nch;
-
-    if (wave >= 4) {
-        pc_ks_loader_role<KC, NV>(in, g, lds, vb, G, ntile_blk, nch);
-        return;
-    }
-
     const int npix = g.TI * g.TH * g.TW;
     int base[B_T];
 #pragma unroll
@@ -511,6 +503,11 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     const int KS32 = g.KS >> 1;
     const __amdgpu_buffer_rsrc_t vsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(wsv), 0, g.wz_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t isrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(wsi), 0, g.wz_bytes >> 3, 0x00020000);
+    const int nlists_all = ((g.out_CH + 127) / 128 * 4) * (KS32 >> 1);
+    const __amdgpu_buffer_rsrc_t oasrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(sp.ov_a), 0,
+                                                                            OVF ? nlists_all * (PC_OV_STEPS * 1024) : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ocsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(sp.ov_col), 0,
+                                                                            OVF ? nlists_all * (PC_OV_STEPS * 64) : 0, 0x00020000);
     const int v_voff = lane * 16, i_voff = lane * 4;
     const int ksb = KS32 * 2048;          // bytes of values between the sets of two taps
     auto set_off = [&](int p) -> int {    // p: compile-time set index inside the item
@@ -531,6 +528,12 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     };
     // flag bits of the part-2 operands of an item: bit 16*s + t of word ii (KC = 64), bit t (KC = 32)
     auto load_flags = [&](int mt_, int ch_, uint32_t &f0, uint32_t &f1) {
+        if (OVF) {                                   // the step counts of the item's two overflow lists instead
+            const int l0 = (mt_ * A_T) * (KS32 >> 1) + ch_;
+            f0 = __builtin_amdgcn_readfirstlane(sp.ov_cnt[l0]);
+            f1 = __builtin_amdgcn_readfirstlane(sp.ov_cnt[l0 + (KS32 >> 1)]);
+            return;
+        }
         const int r0 = (mt_ * A_T) * KS32 + ch_ * SS, r1 = r0 + KS32;
         uint32_t a, b;
         if (SS == 2) {
@@ -544,6 +547,7 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         f1 = __builtin_amdgcn_readfirstlane(b);
     };
     auto flag_of = [&](uint32_t f0, uint32_t f1, int p) -> bool {
+        if (OVF) return false;
         const int st = p / A_T, ii = p % A_T;
         return (((ii ? f1 : f0) >> (16 * (st % SS) + st / SS)) & 1u) != 0u;
     };
@@ -583,8 +587,33 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
     for (int p = 0; p < PFD; ++p) {
         r1[p] = load_vals(ab, p, 0);
         rx[p] = load_idx(ab, p);
-        r2[p] = load_vals(ab, p, 1, flag_of(fl0, fl1, p));
+        if (!OVF) r2[p] = load_vals(ab, p, 1, flag_of(fl0, fl1, p));
     }
+
+    // Overflow lists (OVF): the first step's A operand and columns of an item's two lists are requested during the item
+    // before, decoded and gathered from the staged tile during the first steps of the item, and multiplied there.
+    bf16x8 oa0[A_T];
+    v4u32 oc0[A_T][2];
+    auto load_ovf = [&](int mt_, int ch_) {
+#pragma unroll
+        for (int ii = 0; ii < A_T; ++ii) {
+            const int l = (mt_ * A_T + ii) * (KS32 >> 1) + ch_;
+            const v4u32 t = __builtin_amdgcn_raw_buffer_load_b128(oasrc, v_voff, l * (PC_OV_STEPS * 1024), 0);
+            __builtin_memcpy(&oa0[ii], &t, 16);
+            oc0[ii][0] = __builtin_amdgcn_raw_buffer_load_b128(ocsrc, (lane >> 5) * 32, l * (PC_OV_STEPS * 64), 0);
+            oc0[ii][1] = __builtin_amdgcn_raw_buffer_load_b128(ocsrc, (lane >> 5) * 32 + 16, l * (PC_OV_STEPS * 64), 0);
+        }
+    };
+    if (OVF) load_ovf(mt, 0);
+    auto col_off = [&](uint32_t c) -> int {
+        return g.tap_o0 + __mul24((int)(c >> 12), g.tap_dr) + __mul24((int)((c >> 8) & 15u), g.tap_ds) + (int)(c & 255u) * 2;
+    };
+    auto as_b = [&](const uint32_t (&h)[8]) -> bf16x8 {
+        const uint32_t wd[4] = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        bf16x8 o;
+        __builtin_memcpy(&o, wd, 16);
+        return o;
+    };
 
     __syncthreads();
     for (int i = 0; i < I; ++i) {
@@ -605,6 +634,8 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
             const bf16x8 lo = *reinterpret_cast<const bf16x8 *>(pb), hi = *reinterpret_cast<const bf16x8 *>(pb + 32);
             return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
         };
+        int ooff[A_T][8];
+        bf16x8 obg[A_T][B_T];
         bf16x16 bring[RB][B_T];
 #pragma unroll
         for (int d = 0; d < DBS; ++d)
@@ -622,13 +653,14 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
             for (int ii = 0; ii < A_T; ++ii) {
                 const int p = st * A_T + ii, np = p + PFD;
                 a1[ii] = r1[p % PFD];
-                a2[ii] = r2[p % PFD];
+                if (!OVF) a2[ii] = r2[p % PFD];
                 ax[ii] = rx[p % PFD];
                 // refill the slot with the set PFD ahead: of this item, or of the next one
                 r1[p % PFD] = np < NSET ? load_vals(ab, np < NSET ? np : 0, 0) : load_vals(abn, np < NSET ? 0 : np - NSET, 0);
                 rx[p % PFD] = np < NSET ? load_idx(ab, np < NSET ? np : 0) : load_idx(abn, np < NSET ? 0 : np - NSET);
-                r2[p % PFD] = np < NSET ? load_vals(ab, np < NSET ? np : 0, 1, flag_of(fl0, fl1, np < NSET ? np : 0))
-                                        : load_vals(abn, np < NSET ? 0 : np - NSET, 1, flag_of(nfl0, nfl1, np < NSET ? 0 : np - NSET));
+                if (!OVF)
+                    r2[p % PFD] = np < NSET ? load_vals(ab, np < NSET ? np : 0, 1, flag_of(fl0, fl1, np < NSET ? np : 0))
+                                            : load_vals(abn, np < NSET ? 0 : np - NSET, 1, flag_of(nfl0, nfl1, np < NSET ? 0 : np - NSET));
             }
 #pragma unroll
             for (int ii = 0; ii < A_T; ++ii)
@@ -640,7 +672,32 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one matrix instruction
                 __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);       // address arithmetic
                 if (m < B_T) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // the two LDS reads of a B operand
-                else if (m < B_T + A_T) __builtin_amdgcn_sched_group_barrier(0x020, 3, 0);   // both value parts and the index word of a set
+                else if (m < B_T + A_T) __builtin_amdgcn_sched_group_barrier(0x020, OVF ? 2 : 3, 0);   // the value parts and the index word of a set
+            }
+            if (OVF) {
+                // the first overflow step of the item's two lists, spread over the first steps of the item
+                if (st == 0) {
+#pragma unroll
+                    for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) ooff[ii][e] = col_off(e < 4 ? oc0[ii][0][e] : oc0[ii][1][e - 4]);
+                }
+                if (st >= 1 && st <= A_T * B_T) {            // one (row tile, pixel sub-tile) gather per step
+                    const int ii = (st - 1) / B_T, j = (st - 1) % B_T;
+                    const unsigned char *pb = xb + base[j] - (lane >> 5) * 16;
+                    uint32_t h[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) h[e] = *reinterpret_cast<const uint16_t *>(pb + ooff[ii][e]);
+                    obg[ii][j] = as_b(h);
+                }
+                if (st == A_T * B_T + 2) {
+#pragma unroll
+                    for (int ii = 0; ii < A_T; ++ii)
+#pragma unroll
+                        for (int j = 0; j < B_T; ++j)
+                            acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa0[ii], obg[ii][j], acc[ii][j], 0, 0, 0);
+                }
+                if (st == A_T * B_T + 4) load_ovf(nmt, nchk);  // the next item's (past the end: this one's again, unused)
             }
             __builtin_amdgcn_sched_barrier(0);
             // the second parts: only where the pack found a nonzero (uniform branches on scalar bits)
@@ -650,6 +707,38 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
 #pragma unroll
                     for (int j = 0; j < B_T; ++j)
                         acc[ii][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a2[ii], bring[st % RB][j], acc[ii][j], (int)ax[ii], 0, 1);
+                }
+            }
+        }
+        if (OVF) {
+            // Further steps of a list (more than 16 overflow weights: the exception): every column of a step is one
+            // overflow weight; its B operand is gathered element by element from the staged tile (lane l: pixel l % 32,
+            // columns 8 * (l / 32) .. + 7), its A operand has the weight in the row it belongs to and zeros elsewhere.
+#pragma unroll
+            for (int ii = 0; ii < A_T; ++ii) {
+                const int nst = (int)(ii ? fl1 : fl0);
+                const int l = (mt * A_T + ii) * (KS32 >> 1) + ch;
+                for (int s = 1; s < nst; ++s) {
+                    const v4u32 t = __builtin_amdgcn_raw_buffer_load_b128(oasrc, v_voff, (l * PC_OV_STEPS + s) * 1024, 0);
+                    bf16x8 oa;
+                    __builtin_memcpy(&oa, &t, 16);
+                    const v4u32 c0 = __builtin_amdgcn_raw_buffer_load_b128(ocsrc, (lane >> 5) * 32, (l * PC_OV_STEPS + s) * 64, 0);
+                    const v4u32 c1 = __builtin_amdgcn_raw_buffer_load_b128(ocsrc, (lane >> 5) * 32 + 16, (l * PC_OV_STEPS + s) * 64, 0);
+                    int off[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) off[e] = col_off(e < 4 ? c0[e] : c1[e - 4]);
+                    bf16x8 bg[B_T];
+#pragma unroll
+                    for (int j = 0; j < B_T; ++j) {
+                        const unsigned char *pb = xb + base[j] - (lane >> 5) * 16;
+                        uint32_t h[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) h[e] = *reinterpret_cast<const uint16_t *>(pb + off[e]);
+                        bg[j] = as_b(h);
+                    }
+#pragma unroll
+                    for (int j = 0; j < B_T; ++j)
+                        acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, bg[j], acc[ii][j], 0, 0, 0);
                 }
             }
         }
@@ -666,6 +755,41 @@ pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ o
         k = nk; ch = nchk; mt = nmt; tn = ntn; gy0 = ngy0; gx0 = ngx0;
         ab = abn;
         fl0 = nfl0; fl1 = nfl1;
+    }
+}
+
+template <int B_T, int KC, int ACT = PC_ACT_NONE>
+__global__ void __launch_bounds__(512, 1)
+pc_mfma_conv_sp_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out, SparseOperand sp, MfmaArgs g)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int NV = KS_NV1;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = wave & 3;
+    const int G = gridDim.x;
+    int vb = blockIdx.x;
+    if ((G & 7) == 0) vb = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
+    const int ntile_blk = (g.total_tiles - vb + G - 1) / G;
+    const int nch = g.nchunks;
+
+    if (wave >= 4) {
+        pc_ks_loader_role<KC, NV>(in, g, lds, vb, G, ntile_blk, nch);
+        return;
+    }
+    // Does every overflow list of the layer fit? Every MFMA wavefront reads all the counters (a few hundred) and
+    // reaches the same answer, so the four need not talk to each other before they pick their loop.
+    bool fits = KC == 64 && sp.ov_cnt != nullptr;
+    if (fits) {
+        const int nlists = ((g.out_CH + 127) / 128 * 4) * (g.KS >> 2);
+        bool bad = false;
+        for (int l = lane; l < nlists; l += 64) bad |= sp.ov_cnt[l] == PC_OV_BAD;
+        fits = __ballot(bad) == 0ull;
+    }
+    if (fits) {
+        if constexpr (KC == 64) pc_sp_mfma_role<B_T, KC, ACT, true>(out, sp, g, lds, vb, G, ntile_blk, nch, lane, w);
+    } else {
+        pc_sp_mfma_role<B_T, KC, ACT, false>(out, sp, g, lds, vb, G, ntile_blk, nch, lane, w);
     }
 }
 
@@ -707,8 +831,7 @@ static hipError_t launch_sp_act(int device, hipStream_t st, int grid, size_t lds
         if (e != hipSuccess) return e;
         pc_once_done(attr, device);
     }
-    hipLaunchKernelGGL((pc_mfma_conv_sp_kernel<B_T, KC, ACT>), dim3((unsigned)grid), dim3(512), lds, st, in, out, sp.val, sp.idx,
-                       sp.flag, g);
+    hipLaunchKernelGGL((pc_mfma_conv_sp_kernel<B_T, KC, ACT>), dim3((unsigned)grid), dim3(512), lds, st, in, out, sp, g);
     return hipGetLastError();
 }
 

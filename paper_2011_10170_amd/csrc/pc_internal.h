@@ -9,6 +9,9 @@
 #include "pc.h"
 
 #define PC_MAX_P 126
+#define PC_OV_STEPS 4          // steps of 16 overflow columns per (row tile, 64-entry chunk) list
+#define PC_OV_SUB 32           // overflow weights a 32 x 32 block's list holds
+#define PC_OV_BAD 0xFFFFFFFFu
 
 struct pc_ctx {
     int device;
@@ -62,6 +65,20 @@ struct PackView {
     uint16_t *ws_fwd_val, *ws_bwd_val;
     uint32_t *ws_fwd_idx, *ws_bwd_idx;
     uint16_t *ws_fwd_flag, *ws_bwd_flag;
+    // The part-1 operand leaves out the third and fourth nonzeros of a group ("overflow" weights, well under 1 % of
+    // the kept weights at the keep ratios of the workloads). Besides part 2 they are kept as lists, one per row tile
+    // of 32 rows and chunk of 64 reduction entries, ready to be multiplied as extra reduction columns of a dense
+    // matrix instruction: up to PC_OV_STEPS steps of 16 columns, each column one (tap, reduction entry) pair.
+    //   ov_*_cnt [rt][chunk]: steps of the list, PC_OV_BAD when the list does not fit (the kernel then uses part 2)
+    //   ov_*_a   [rt][chunk][step][64 lanes][8]: the A operand of a step (one nonzero per column)
+    //   ov_*_col [rt][chunk][step][16]: (tap row << 12) | (tap column << 8) | entry inside the chunk
+    //   ov_*_sub_cnt / _sub_ent: the lists of the 32 x 32 blocks as the tile builder leaves them (sorted), merged by
+    //            pc_pack_ovf_merge_kernel; entry = (tap << 11 | row << 6 | entry inside the block or chunk, bf16 weight)
+    uint32_t *ov_fwd_cnt, *ov_bwd_cnt;
+    uint16_t *ov_fwd_a, *ov_bwd_a;
+    uint32_t *ov_fwd_col, *ov_bwd_col;
+    uint32_t *ov_fwd_sub_cnt, *ov_bwd_sub_cnt;
+    uint2 *ov_fwd_sub_ent, *ov_bwd_sub_ent;
     int32_t Fp, Cp;       // F and C rounded up to 128 (row extent of the operand tiles)
     int32_t Fk, Ck;       // F and C rounded up to 64, the largest channel chunk a kernel walks (reduction extent of the operand tiles)
 };

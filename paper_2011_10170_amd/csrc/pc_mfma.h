@@ -54,6 +54,10 @@ struct SparseOperand {
     const uint16_t *val;
     const uint32_t *idx;
     const uint16_t *flag;
+    // the overflow weights as lists of extra reduction columns (PackView::ov_*_cnt, _a, _col)
+    const uint32_t *ov_cnt;
+    const uint16_t *ov_a;
+    const uint32_t *ov_col;
 };
 
 // Wave-specialised forward/backward-data kernel for full 3x3 tap lists. pcfg: -1 = take it when the plan says it

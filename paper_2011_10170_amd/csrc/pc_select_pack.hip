@@ -579,8 +579,12 @@ __device__ __forceinline__ void pc_pack_count_row(const uint8_t *__restrict__ pi
 // fourth (stored value 2g + m of a part belongs to group g; an unused place holds zero), idx their 2-bit positions in
 // the group: bits [4g+1:4g] and [4g+3:4g+2] for part 1, the same 16 bits higher for part 2. A place without a
 // nonzero points at a position none of the part's nonzeros uses.
-__device__ __forceinline__ void pc_sparse_compress16(const uint16_t *src, uint4 *part1, uint4 *part2, uint32_t *idx)
+// ovf_pos / ovf_val (may be null): the up to 8 overflow weights (third and fourth nonzeros of a group) with their
+// positions 0..15, *n_ovf their count.
+__device__ __forceinline__ void pc_sparse_compress16(const uint16_t *src, uint4 *part1, uint4 *part2, uint32_t *idx,
+                                                     uint32_t *ovf_pos, uint32_t *ovf_val, int *n_ovf)
 {
+    int no = 0;
     uint32_t w1[4] = {0u, 0u, 0u, 0u}, w2[4] = {0u, 0u, 0u, 0u};
     uint32_t ix = 0u;
 #pragma unroll
@@ -599,6 +603,14 @@ __device__ __forceinline__ void pc_sparse_compress16(const uint16_t *src, uint4 
             }
         }
 #pragma unroll
+        for (int k = 2; k < 4; ++k)
+            if (k < n) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (q == no) { ovf_pos[q] = 4u * g + pos[k]; ovf_val[q] = val[k]; }
+                ++no;
+            }
+#pragma unroll
         for (int part = 0; part < 2; ++part) {
             const int m = n - 2 * part;                 // nonzeros left for this part
             uint32_t a = 0u, b = 0u, pa = 0u, pb = 1u;  // none: zeros at positions 0 and 1
@@ -614,6 +626,7 @@ __device__ __forceinline__ void pc_sparse_compress16(const uint16_t *src, uint4 
     *part1 = make_uint4(w1[0], w1[1], w1[2], w1[3]);
     *part2 = make_uint4(w2[0], w2[1], w2[2], w2[3]);
     *idx = ix;
+    *n_ovf = no;
 }
 template <bool FROM_KINFO>
 __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, const uint8_t *__restrict__ pid,
@@ -691,7 +704,9 @@ __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, 
         }
     }
     __shared__ uint32_t lflag[2];
-    if (tid < 2) lflag[tid] = 0u;
+    __shared__ uint32_t ocnt[2];                     // overflow weights of this block, forward / backward-data orientation
+    __shared__ uint2 oent[2][PC_OV_SUB];
+    if (tid < 2) { lflag[tid] = 0u; ocnt[tid] = 0u; }
     __syncthreads();
     const int KSf = v.Ck / 16, KSb = v.Fk / 16;
     uint4 *of = reinterpret_cast<uint4 *>(v.wz_fwd), *ob = reinterpret_cast<uint4 *>(v.wz_bwd);
@@ -714,8 +729,16 @@ __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, 
         if (ss >= (bwd ? KS32b : KS32f)) continue;
         const uint16_t *src = bwd ? &tB[tap][lane & 31][16 * (lane >> 5)] : &tA[tap][lane & 31][16 * (lane >> 5)];
         uint4 p1, p2;
-        uint32_t idx;
-        pc_sparse_compress16(src, &p1, &p2, &idx);
+        uint32_t idx, opos[8], oval[8];
+        int no;
+        pc_sparse_compress16(src, &p1, &p2, &idx, opos, oval, &no);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (q < no) {
+                const uint32_t at = atomicAdd(&ocnt[bwd], 1u);
+                if (at < PC_OV_SUB)
+                    oent[bwd][at] = make_uint2(((uint32_t)tap << 11) | ((uint32_t)(lane & 31) << 6) | (16u * (lane >> 5) + opos[q]), oval[q]);
+            }
         const int64_t fr = (int64_t)(rt * 9 + tap) * (bwd ? KS32b : KS32f) + ss;
         uint4 *ov = reinterpret_cast<uint4 *>(bwd ? v.ws_bwd_val : v.ws_fwd_val);
         ov[(fr * 2 + 0) * 64 + lane] = p1;
@@ -726,7 +749,82 @@ __device__ __forceinline__ void pc_pack_tile_block(const float *__restrict__ W, 
     __syncthreads();
     if (tid == 0 && cb < KS32f) v.ws_fwd_flag[(int64_t)fb * KS32f + cb] = (uint16_t)lflag[0];
     if (tid == 1 && fb < KS32b) v.ws_bwd_flag[(int64_t)cb * KS32b + fb] = (uint16_t)lflag[1];
+    // The block's overflow weights, in the order of their keys (tap, row, entry): the order the atomic counter gave
+    // them is not reproducible, their rank among the keys is. A list that does not fit only leaves its count.
+    if (tid < 2 * PC_OV_SUB) {
+        const int bwd = tid / PC_OV_SUB, e = tid % PC_OV_SUB;
+        const int rt = bwd ? cb : fb, ss = bwd ? fb : cb;
+        const int n = (int)ocnt[bwd];
+        if (ss < (bwd ? KS32b : KS32f)) {
+            const int64_t sub = (int64_t)rt * (bwd ? KS32b : KS32f) + ss;
+            if (e == 0) (bwd ? v.ov_bwd_sub_cnt : v.ov_fwd_sub_cnt)[sub] = (uint32_t)n;
+            if (e < n && n <= PC_OV_SUB) {
+                const uint2 mine = oent[bwd][e];
+                int rank = 0;
+                for (int q = 0; q < n; ++q) rank += oent[bwd][q].x < mine.x;
+                (bwd ? v.ov_bwd_sub_ent : v.ov_fwd_sub_ent)[sub * PC_OV_SUB + rank] = mine;
+            }
+        }
+    }
 }
+
+// Merges the overflow lists of the two 32 x 32 blocks of a (row tile, 64-entry chunk) pair into the steps the
+// structured-sparse kernel multiplies: list = blockIdx (forward lists first), 64 threads.
+__device__ __forceinline__ void pc_pack_ovf_merge_body(const PackView &v, int list)
+{
+    __shared__ uint2 ent[2 * PC_OV_SUB];
+    const int nf = (v.Fp / 32) * (v.Ck / 64);
+    const bool bwd = list >= nf;
+    const int l = bwd ? list - nf : list;
+    const uint32_t *scnt = bwd ? v.ov_bwd_sub_cnt : v.ov_fwd_sub_cnt;
+    const uint2 *sent = bwd ? v.ov_bwd_sub_ent : v.ov_fwd_sub_ent;
+    uint32_t *cnt = bwd ? v.ov_bwd_cnt : v.ov_fwd_cnt;
+    uint4 *oa = reinterpret_cast<uint4 *>(bwd ? v.ov_bwd_a : v.ov_fwd_a);
+    uint32_t *ocol = bwd ? v.ov_bwd_col : v.ov_fwd_col;
+    // sub-lists 2l and 2l + 1: the chunk's two steps of 32 entries ([rt][ss] with ss = 2 * chunk + half)
+    const uint32_t n0 = scnt[2 * (int64_t)l], n1 = scnt[2 * (int64_t)l + 1];
+    const int tid = threadIdx.x;
+    if (n0 > PC_OV_SUB || n1 > PC_OV_SUB) {
+        if (tid == 0) cnt[l] = PC_OV_BAD;
+        return;
+    }
+    const int n = (int)(n0 + n1);
+    if (tid < n) {
+        const int half = tid >= (int)n0;
+        uint2 e = sent[(2 * (int64_t)l + half) * PC_OV_SUB + (half ? tid - (int)n0 : tid)];
+        e.x += half ? 32u : 0u;                      // entry inside the chunk
+        ent[tid] = e;
+    }
+    __syncthreads();
+    const int steps = (n + 15) / 16;
+    if (tid == 0) cnt[l] = (uint32_t)steps;
+    const int row = tid & 31, g = tid >> 5;
+    // (the first step is always written: the kernel multiplies it without looking at the count)
+    for (int s = 0; s < (steps > 1 ? steps : 1); ++s) {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int q = s * 16 + 8 * g + e;
+            if (q < n) {
+                const uint2 en = ent[q];
+                if ((int)((en.x >> 6) & 31u) == row) w[e >> 1] |= (en.y & 0xFFFFu) << ((e & 1) * 16);
+            }
+        }
+        oa[((int64_t)l * PC_OV_STEPS + s) * 64 + tid] = make_uint4(w[0], w[1], w[2], w[3]);
+        if (tid < 16) {
+            const int q = s * 16 + tid;
+            uint32_t c = 0u;                         // unused columns: tap 0, entry 0 (a valid address; their weights are 0)
+            if (q < n) {
+                const uint32_t key = ent[q].x, tap = key >> 11;
+                c = ((tap / 3u) << 12) | ((tap % 3u) << 8) | (key & 63u);
+            }
+            ocol[((int64_t)l * PC_OV_STEPS + s) * 16 + tid] = c;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(64) pc_pack_ovf_merge_kernel(PackView v) { pc_pack_ovf_merge_body(v, (int)blockIdx.x); }
+
 
 // First launch of a pack: workgroups [0, F) count the filter rows, [F, F + ncm) the channel rows (ncm = C for the
 // gather variant, else 0), the rest write the operand tiles (matrix-core variant), one 32 x 32 block each.
@@ -944,6 +1042,33 @@ __global__ void __launch_bounds__(256) pc_pack_regather_cm_kernel(PackView v)
     v.cm_val[i] = v.fm_val[v.cm_slot[i]];
 }
 
+// The overflow lists of a pack made for the structured-sparse kernel (no-op for other packs).
+static int pc_ovf_lists(const PackView &v) { return v.ov_fwd_cnt ? (v.Fp / 32) * (v.Ck / 64) + (v.Cp / 32) * (v.Fk / 64) : 0; }
+static void pc_launch_ovf_merge(pc_ctx *ctx, const PackView &v)
+{
+    const int n = pc_ovf_lists(v);
+    if (n > 0) hipLaunchKernelGGL(pc_pack_ovf_merge_kernel, dim3((unsigned)n), dim3(64), 0, ctx->stream, v);
+}
+
+// The same for several packs in one launch.
+__global__ void __launch_bounds__(64) pc_pack_ovf_merge_batch_kernel(PackBatchArg b)
+{
+    const int l = pc_batch_find(b.blk0, b.n, (int)blockIdx.x);
+    pc_pack_ovf_merge_body(*b.view[l], (int)blockIdx.x - b.blk0[l]);
+}
+
+static void pc_launch_ovf_merge_batch(pc_ctx *ctx, int m, pc_packed *const *pk)
+{
+    PackBatchArg a;
+    memset(&a, 0, sizeof(a));
+    a.n = m;
+    for (int i = 0; i < m; ++i) {
+        a.view[i] = pk[i]->v_dev;
+        a.blk0[i + 1] = a.blk0[i] + pc_ovf_lists(pk[i]->v);
+    }
+    if (a.blk0[m] > 0) hipLaunchKernelGGL(pc_pack_ovf_merge_batch_kernel, dim3((unsigned)a.blk0[m]), dim3(64), 0, ctx->stream, a);
+}
+
 pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8_t *pid, const uint8_t *keep)
 {
     PackView v = pk->v;
@@ -962,6 +1087,7 @@ pc_status pc_launch_pack(pc_ctx *ctx, pc_packed *pk, const float *W, const uint8
     if (!mfma)
         hipLaunchKernelGGL(pc_pack_place_kernel<false>, dim3(v.C), dim3(256), 0, st, W, pid, keep, v.C, v.F, (int64_t)1,
                            (int64_t)v.C, la, bf16, v);
+    pc_launch_ovf_merge(ctx, v);
     return pc_hip_check(ctx, hipGetLastError(), "pack launch");
 }
 
@@ -997,6 +1123,7 @@ pc_status pc_launch_pack_batch(pc_ctx *ctx, int n, pc_packed *const *pk, const f
         hipLaunchKernelGGL(pc_pack_place_batch_kernel<true>, dim3((unsigned)fm.blk0[m]), dim3(256), 0, ctx->stream, fm, la);
         if (cm.blk0[m] > 0)
             hipLaunchKernelGGL(pc_pack_place_batch_kernel<false>, dim3((unsigned)cm.blk0[m]), dim3(256), 0, ctx->stream, cm, la);
+        pc_launch_ovf_merge_batch(ctx, m, pk + l0);
         pc_status s = pc_hip_check(ctx, hipGetLastError(), "pack (several layers) launch");
         if (s != PC_OK) return s;
     }
@@ -1009,11 +1136,13 @@ pc_status pc_launch_update_values_batch(pc_ctx *ctx, int n, pc_packed *const *pk
 {
     PackBatchArg b;
     memset(&b, 0, sizeof(b));
+    pc_packed *bpk[PC_BATCH_MAX];
     LibArg la;
     const pc_packed *first = nullptr;
     auto flush = [&]() -> pc_status {
         if (b.n == 0) return PC_OK;
         hipLaunchKernelGGL(pc_pack_revalue_batch_kernel, dim3((unsigned)b.blk0[b.n]), dim3(256), 0, ctx->stream, b, la);
+        pc_launch_ovf_merge_batch(ctx, b.n, bpk);
         b.n = 0;
         return pc_hip_check(ctx, hipGetLastError(), "update_values (several layers) launch");
     };
@@ -1032,6 +1161,7 @@ pc_status pc_launch_update_values_batch(pc_ctx *ctx, int n, pc_packed *const *pk
             continue;
         }
         const int i = b.n;
+        bpk[i] = p;
         b.W[i] = W[l];
         b.view[i] = p->v_dev;
         b.tiles_c[i] = p->v.Cp / 32;
@@ -1058,6 +1188,7 @@ pc_status pc_launch_update_values(pc_ctx *ctx, pc_packed *pk, const float *W)
         const int tiles_c = v.Cp / 32, ntiles = (v.Fp / 32) * tiles_c;
         hipLaunchKernelGGL(pc_pack_revalue_kernel, dim3((unsigned)ntiles + blocks), dim3(256), 0, ctx->stream, W, la, bf16, v,
                            tiles_c, ntiles);
+        pc_launch_ovf_merge(ctx, v);
     } else {
         hipLaunchKernelGGL(pc_pack_regather_fm_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, la, bf16, v);
         hipLaunchKernelGGL(pc_pack_regather_cm_kernel, dim3(blocks), dim3(256), 0, ctx->stream, v);

@@ -298,3 +298,43 @@ def test_fused_relu_in_every_tile_configuration(B, ctx, cfg):
     finally:
         B.pc_set_plan_override(ctx, -1, 0)
         g.close()
+
+
+@pytest.mark.parametrize("keep", [0.2, 0.6])
+def test_fused_relu_in_the_structured_sparse_kernel(B, ctx, keep):
+    """The fused step at the store of the structured-sparse kernel, with the overflow weights as lists (keep 0.2) and
+    through the second operand part (keep 0.6: the lists do not fit): bit-identical to the plain launch followed by
+    the step, and the plain launch equals the zero-filled kernel's result up to the float32 order of additions."""
+    import torch
+    from tests._harness import Case, GpuLayer, rel_l2, from_dev_f32
+    layer = I.Layer(6, 10, 9, 128, 160, 1)
+    case = Case(layer, "bf16", 16, I.kept_per_filter(keep, layer.C), tag=("fused_sparse", keep))
+    g = GpuLayer(B, ctx, case, variant=B.PC_VARIANT_MFMA_SPARSE)
+    gd = GpuLayer(B, ctx, case, variant=B.PC_VARIANT_MFMA)
+    try:
+        assert g.variant == B.PC_VARIANT_MFMA_SPARSE
+        B.pc_set_plan_override(ctx, 22, 0)
+        L = layer
+        y = torch.empty((L.N, L.Ho, L.Wo, L.F), dtype=torch.bfloat16, device="cuda")
+        a = torch.full_like(y, float("nan"))
+        dx = torch.empty((L.N, L.H, L.W, L.C), dtype=torch.bfloat16, device="cuda")
+        dz = torch.full_like(dx, float("nan"))
+        B.pc_conv_fwd(ctx, g.desc, g.pk, g.x, y)
+        assert B.pc_last_kernel(ctx).startswith("pc_mfma_conv_sp_kernel")
+        B.pc_conv_fwd_relu(ctx, g.desc, g.pk, g.x, a)
+        B.pc_conv_bwd_data(ctx, g.desc, g.pk, g.dy, dx)
+        B.pc_conv_bwd_data_relu(ctx, g.desc, g.pk, g.dy, g.x, dz)
+        torch.cuda.synchronize()
+        assert torch.equal(a.view(torch.int16), torch.where(y > 0, y, torch.zeros_like(y)).view(torch.int16))
+        assert torch.equal(dz.view(torch.int16), torch.where(g.x > 0, dx, torch.zeros_like(dx)).view(torch.int16))
+        B.pc_set_plan_override(ctx, -1, 0)
+        yd = torch.empty_like(y)
+        dxd = torch.empty_like(dx)
+        B.pc_conv_fwd(ctx, gd.desc, gd.pk, gd.x, yd)
+        B.pc_conv_bwd_data(ctx, gd.desc, gd.pk, gd.dy, dxd)
+        torch.cuda.synchronize()
+        assert rel_l2(from_dev_f32(y), from_dev_f32(yd)) <= 3e-3 and rel_l2(from_dev_f32(dx), from_dev_f32(dxd)) <= 3e-3
+    finally:
+        B.pc_set_plan_override(ctx, -1, 0)
+        g.close()
+        gd.close()
