@@ -95,9 +95,20 @@ pc_gather_conv_kernel(const T *__restrict__ in, T *__restrict__ out, GatherArgs 
                     const int s_end = gr[p + 1];
                     if (s_end > s_begin) {
                         const int o0 = g.tapoff[p][0], o1 = g.tapoff[p][1], o2 = g.tapoff[p][2], o3 = g.tapoff[p][3];
-                        for (int slot = s_begin; slot < s_end; ++slot) {
+                        // The slots of a pattern group are ordered by channel: with several channel chunks, start at
+                        // the first slot of this chunk (binary search) and stop at the first one past it, instead of
+                        // walking the whole group once per chunk.
+                        int first = s_begin;
+                        if (c0 > 0) {
+                            int hi = s_end;
+                            while (first < hi) {
+                                const int mid = (first + hi) >> 1;
+                                if ((int)idx[mid] < c0) first = mid + 1; else hi = mid;
+                            }
+                        }
+                        for (int slot = first; slot < s_end; ++slot) {
                             const int c = idx[slot];
-                            if (c < c0 || c >= c0 + cc) continue;
+                            if (c >= c0 + cc) break;
                             const float4 w = val[slot];
                             const float *t = tile + (c - c0) * g.plane + lbase;
                             if (o0 >= 0) {
