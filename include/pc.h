@@ -120,6 +120,8 @@ pc_status pc_set_variant(pc_ctx *ctx, pc_variant v);
  *          20 as 16 with 64-channel chunks; 21 as 8 with 128-channel chunks
  *   10, 11 backward-weight: the cooperative / the wave-specialised kernel (the other passes stay automatic)
  *   22     forward/backward-data: the structured-sparse kernel (packs made under PC_VARIANT_MFMA_SPARSE only)
+ *   23     the first-layer kernels (stride 1, at most 4 input channels): the automatic choice takes them wherever
+ *          they apply; any other code here keeps such a layer on the general kernels
  * The wave-specialised forward/backward-data kernel takes 9-tap launches only: a stride-2 backward-data pass
  * (one launch of the cooperative kernel over the four parity classes of input pixels) takes 0..6 and uses the
  * automatic choice otherwise. split_k > 0 forces that many splits of the reduction in the

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpatconv.so")
 SOURCES = ["pc_api.hip", "pc_select_pack.hip", "pc_conv_valu.hip", "pc_conv_mfma.hip", "pc_conv_mfma_ws.hip",
-           "pc_wgrad_mfma.hip", "pc_train_steps.hip", "pc_act_pool.hip"]
+           "pc_wgrad_mfma.hip", "pc_train_steps.hip", "pc_act_pool.hip", "pc_conv_thin.hip"]
 
 # Contraction is off so that the selection arithmetic keeps its written order; the conv kernels
 # call fmaf explicitly. Packed fp32 instructions are disabled for the device pass.

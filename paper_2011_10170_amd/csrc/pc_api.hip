@@ -163,7 +163,7 @@ extern "C" pc_status pc_set_variant(pc_ctx *ctx, pc_variant v)
 extern "C" pc_status pc_set_plan_override(pc_ctx *ctx, int32_t tile_cfg, int32_t split_k)
 {
     if (!ctx) return PC_ERR_INVALID_ARG;
-    if (tile_cfg < -1 || tile_cfg > 22 || tile_cfg == 12 || split_k < 0 || split_k > 64)
+    if (tile_cfg < -1 || tile_cfg > 23 || tile_cfg == 12 || split_k < 0 || split_k > 64)
         return pc_fail(ctx, PC_ERR_INVALID_ARG, "pc_set_plan_override: tile_cfg %d split_k %d out of range", tile_cfg, split_k);
     ctx->plan_cfg = tile_cfg;
     ctx->plan_split = split_k;

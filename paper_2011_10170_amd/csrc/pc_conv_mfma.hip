@@ -517,8 +517,28 @@ static pc_status run_mfma_conv(pc_ctx *ctx, MfmaArgs g, int ext, int ntaps, cons
     return pc_hip_check(ctx, hipGetLastError(), "split-K reduce launch");
 }
 
+// The first-layer kernels take a launch under the automatic choice or override code 23. A requested ReLU is fused
+// into the forward launch; the mask of the backward pass is left to the caller (*fused = false).
+static pc_status try_thin(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *in, void *out, bool fwd, int act,
+                          bool *fused, bool *taken)
+{
+    *taken = false;
+    if ((ctx->plan_cfg >= 0 && ctx->plan_cfg != 23) || ctx->plan_split != 0) return PC_OK;
+    const int act_here = (fwd && fused && act == PC_ACT_RELU) ? PC_ACT_RELU : PC_ACT_NONE;
+    const pc_status s = fwd ? pc_thin_fwd(ctx, d, pk, in, out, act_here, taken) : pc_thin_bwd_data(ctx, d, pk, in, out, taken);
+    if (s != PC_OK) return s;
+    if (*taken && fused) *fused = act != PC_ACT_NONE && act_here == act;
+    if (!*taken && ctx->plan_cfg == 23) return pc_fail(ctx, PC_ERR_UNSUPPORTED, "MFMA conv: the first-layer kernels do not take this layer");
+    return PC_OK;
+}
+
 pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y, int act, bool *fused)
 {
+    {
+        bool taken = false;
+        const pc_status s = try_thin(ctx, d, pk, x, y, true, act, fused, &taken);
+        if (s != PC_OK || taken) return s;
+    }
     MfmaArgs g;
     memset(&g, 0, sizeof(g));
     const int st = d->stride;
@@ -536,6 +556,11 @@ pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, c
 pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx, int act,
                            const void *act_mask, bool *fused)
 {
+    {
+        bool taken = false;
+        const pc_status s = try_thin(ctx, d, pk, dy, dx, false, act, fused, &taken);
+        if (s != PC_OK || taken) return s;
+    }
     MfmaArgs g;
     memset(&g, 0, sizeof(g));
     const int st = d->stride;

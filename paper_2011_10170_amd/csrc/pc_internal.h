@@ -171,6 +171,9 @@ pc_status pc_mfma_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, c
                       bool *fused = nullptr);
 pc_status pc_mfma_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx, int act = 0,
                            const void *act_mask = nullptr, bool *fused = nullptr);
+// First-layer kernels (stride 1, at most 4 input channels); *launched stays false when the layer is outside what they take.
+pc_status pc_thin_fwd(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *x, void *y, int act, bool *launched);
+pc_status pc_thin_bwd_data(pc_ctx *ctx, const pc_conv_desc *d, const pc_packed *pk, const void *dy, void *dx, bool *launched);
 // In-place ReLU of n elements; and in-place "keep where the matching element of a is positive, else +0".
 pc_status pc_launch_relu(pc_ctx *ctx, void *z, int64_t n, pc_dtype dtype);
 pc_status pc_launch_relu_mask(pc_ctx *ctx, void *dz, const void *a, int64_t n, pc_dtype dtype);
