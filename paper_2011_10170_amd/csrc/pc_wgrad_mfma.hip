@@ -289,6 +289,7 @@ pc_mfma_wgrad_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict_
 struct WgradWsArgs {
     int32_t N, H, W, C, F, Ho, Wo, stride;   // C: channels of the x tensor the kernel reads (padded to a multiple of 8)
     int32_t Creal;                           // channels of the layer (row length of the kinfo table)
+    int32_t thin;                            // at most 3 channels: the (tap, channel) pairs are the 32 columns of one MFMA tile
     int32_t TR, TC, npos, ng, IR, IC, xs_per_g, xslots, xplane;
     int32_t tiles_r, tiles_c, n_ktiles, ksplit, pstride;
     int32_t buf_bytes;                     // one LDS buffer: dyT planes, then xT planes
@@ -379,7 +380,14 @@ __device__ __forceinline__ void pc_mfma_wgrad_ws_body(const uint16_t *__restrict
                 for (int j = 0; j < 4; ++j) {
                     const int t = __builtin_ctz(m);
                     m &= m - 1u;
-                    o[j] = ob[t * (32 * WG_T)];
+                    if (a.thin) {
+                        // parked as [wavefront][filter half][column = tap * channels + channel][filter]: the four
+                        // wavefronts' shares of the pixels, added in wavefront order
+                        const float *q = ot + (fh * 32 + t * a.Creal + (p & 63)) * 32 + (p >> 6);
+                        o[j] = ((q[0] + q[2 * 32 * 32]) + q[4 * 32 * 32]) + q[6 * 32 * 32];
+                    } else {
+                        o[j] = ob[t * (32 * WG_T)];
+                    }
                 }
                 *reinterpret_cast<float4 *>(pout + (int64_t)(info >> 9) * 4) = make_float4(o[0], o[1], o[2], o[3]);
             }
@@ -476,6 +484,55 @@ __device__ __forceinline__ void pc_mfma_wgrad_ws_body(const uint16_t *__restrict
         }
         if (i < nt) { put(A1, B1, a.buf_bytes); issue(A1, B1); sync(); }
         __syncthreads();
+        __syncthreads();
+        gather(0);
+        gather(1);
+    } else if (a.thin) {
+        // ------------------------------------------------------------ MFMA wavefronts, at most 3 channels
+        // The 9 * C <= 27 (tap, channel) pairs are the columns of ONE 32-column tile: column n of the x operand is
+        // channel n % C at the slot of tap n / C, a per-lane slot offset instead of a per-instruction one. Two matrix
+        // instructions (the two filter halves) per k-step instead of 36; wavefront w takes k-steps w and w + 4 of
+        // every pixel tile and the four partial tiles are added in the epilogue.
+        load_kinfo();
+        const int g = lane >> 5, n = lane & 31;
+        const int ncol = 9 * a.Creal;
+        const int tapn = n < ncol ? n / a.Creal : 0, cn = n < ncol ? n - tapn * a.Creal : 0;   // columns past the last: any valid address
+        const int toffn = (tapn / 3) * a.IC + (tapn % 3);
+        f32x16 acc[2];
+#pragma unroll
+        for (int fh = 0; fh < 2; ++fh)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fh][r] = 0.0f;
+        int xbq[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) xbq[q] = ws_xb_tab(a, 2 * (wave + 4 * q) + g);
+        const int fl = lane & 31;
+        const int o_a0 = fl * WS_DY_PLANE + (fl >> 3) * 16 + g * 16;
+        const int o_a1 = (fl + 32) * WS_DY_PLANE + ((fl + 32) >> 3) * 16 + g * 16;
+        const int o_b = XT_OFF + cn * a.xplane + (cn >> 3) * 16;
+        __syncthreads();
+        for (int i = 0; i < nt; ++i) {
+            const unsigned char *bufp = lds + (i & 1) * a.buf_bytes;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int kk = wave + 4 * q;
+                const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(bufp + o_a0 + kk * 32);
+                const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(bufp + o_a1 + kk * 32);
+                const bf16x8 b = *reinterpret_cast<const bf16x8 *>(bufp + o_b + ((xbq[q] + toffn) << 4));
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1], 0, 0, 0);
+            }
+            __syncthreads();
+        }
+        float *otw = reinterpret_cast<float *>(lds);
+        __syncthreads();
+#pragma unroll
+        for (int fh = 0; fh < 2; ++fh)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int fr = 8 * (i >> 2) + 4 * g + (i & 3);
+                otw[((wave * 2 + fh) * 32 + n) * 32 + fr] = acc[fh][i];
+            }
         __syncthreads();
         gather(0);
         gather(1);
@@ -622,6 +679,8 @@ static bool ws_plan(const pc_ctx *ctx, const pc_conv_desc *d, int64_t nslots, Wg
     // cooperative kernel, which reads by element.
     if (a.F & 7) return false;
     const bool pad_x = a.C != a.Creal;
+    // (override code 11 keeps a first layer on the general form of the kernel)
+    a.thin = d->C <= 3 && (ctx->plan_cfg < 0 || ctx->plan_cfg == 23);
     const int64_t xb = (int64_t)a.N * a.H * a.W * a.C * 2, db = (int64_t)a.N * a.Ho * a.Wo * a.F * 2;
     if (xb >= ((int64_t)1 << 31) || db >= ((int64_t)1 << 31)) return false;
     const int ft = (a.F + WG_T - 1) / WG_T, ct = (a.C + WG_T - 1) / WG_T;
