@@ -564,23 +564,28 @@ __device__ __forceinline__ void pc_mfma_wgrad_ws_body(const uint16_t *__restrict
         const int o_b = XT_OFF + cl * a.xplane + (cl >> 3) * 16;
 
         __syncthreads();
-        for (int i = 0; i < nt; ++i) {
+        // The fragments of a k-step are read one k-step ahead of its matrix instructions, also across the barrier
+        // between two pixel tiles: the last k-step of a tile is multiplied after the barrier, behind the first reads
+        // of the next tile, so that the LDS latency at the start of a tile is covered as well.
+        bf16x8 aq[2][2], bq[2][5];
+        auto read_frags = [&](int i, int kk, int slot) __attribute__((always_inline)) {
             const unsigned char *bufp = lds + (i & 1) * a.buf_bytes;
-            const unsigned char *ar0 = bufp + o_a0, *ar1 = bufp + o_a1, *bc = bufp + o_b;
-            bf16x8 aq[2][2], bq[2][5];
-            aq[0][0] = *reinterpret_cast<const bf16x8 *>(ar0);
-            aq[0][1] = *reinterpret_cast<const bf16x8 *>(ar1);
+            aq[slot][0] = *reinterpret_cast<const bf16x8 *>(bufp + o_a0 + kk * 32);
+            aq[slot][1] = *reinterpret_cast<const bf16x8 *>(bufp + o_a1 + kk * 32);
+            const unsigned char *bk = bufp + o_b + (xb[kk] << 4);
 #pragma unroll
-            for (int b = 0; b < 5; ++b) bq[0][b] = *reinterpret_cast<const bf16x8 *>(bc + ((xb[0] + toff[b]) << 4));
+            for (int b = 0; b < 5; ++b) bq[slot][b] = *reinterpret_cast<const bf16x8 *>(bk + (toff[b] << 4));
+        };
+        if (nt > 0) read_frags(0, 0, 0);
+        for (int i = 0; i < nt; ++i) {
 #pragma unroll
             for (int kk = 0; kk < WS_NKS; ++kk) {
                 const int cur = kk & 1, nxt = cur ^ 1;
                 if (kk + 1 < WS_NKS) {
-                    aq[nxt][0] = *reinterpret_cast<const bf16x8 *>(ar0 + (kk + 1) * 32);
-                    aq[nxt][1] = *reinterpret_cast<const bf16x8 *>(ar1 + (kk + 1) * 32);
-                    const unsigned char *bk = bc + (xb[kk + 1 < WS_NKS ? kk + 1 : 0] << 4);
-#pragma unroll
-                    for (int b = 0; b < 5; ++b) bq[nxt][b] = *reinterpret_cast<const bf16x8 *>(bk + (toff[b] << 4));
+                    read_frags(i, kk + 1, nxt);
+                } else {
+                    __syncthreads();        // the tile's buffer is free; the next tile's is complete
+                    if (i + 1 < nt) read_frags(i + 1, 0, nxt);
                 }
 #pragma unroll
                 for (int u = 0; u < 9; ++u)
@@ -594,7 +599,6 @@ __device__ __forceinline__ void pc_mfma_wgrad_ws_body(const uint16_t *__restrict
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            __syncthreads();
         }
         // epilogue: park both filter halves' tiles as out[half][tap][filter][channel] (2 x 72 KiB), then gather
         float *otw = reinterpret_cast<float *>(lds);
