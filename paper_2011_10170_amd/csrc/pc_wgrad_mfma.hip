@@ -444,15 +444,31 @@ __device__ __forceinline__ void pc_mfma_wgrad_ws_body(const uint16_t *__restrict
             const uint32_t vo1 = ok1 ? (uint32_t)(rel1 + org_x) : OOB;
             // images of the task's group that exist (the last group of a batch that is no multiple of 8 is short)
             const int nv0 = a.N - (n0 + ig0 * 8), nv1 = a.N - (n0 + ig1 * 8);
+            // (the image offset sits in the scalar offset, which the range check of a buffer load does not see: a
+            // short group needs its missing images switched off one by one; a batch of whole groups of 8 does not, and
+            // saves a compare and a select per load on a SIMD whose vector issue the MFMA wavefront needs)
+            if (a.N & 7) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const v4u32 t0 = __builtin_amdgcn_raw_buffer_load_b128(src0, (int)(i < nv0 ? vo0 : OOB), i * img0, 0);
-                A[i] = make_uint4(t0.x, t0.y, t0.z, t0.w);
-            }
+                for (int i = 0; i < 8; ++i) {
+                    const v4u32 t0 = __builtin_amdgcn_raw_buffer_load_b128(src0, (int)(i < nv0 ? vo0 : OOB), i * img0, 0);
+                    A[i] = make_uint4(t0.x, t0.y, t0.z, t0.w);
+                }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const v4u32 t1 = __builtin_amdgcn_raw_buffer_load_b128(xsrc, (int)(i < nv1 ? vo1 : OOB), i * x_img, 0);
-                B[i] = make_uint4(t1.x, t1.y, t1.z, t1.w);
+                for (int i = 0; i < 8; ++i) {
+                    const v4u32 t1 = __builtin_amdgcn_raw_buffer_load_b128(xsrc, (int)(i < nv1 ? vo1 : OOB), i * x_img, 0);
+                    B[i] = make_uint4(t1.x, t1.y, t1.z, t1.w);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const v4u32 t0 = __builtin_amdgcn_raw_buffer_load_b128(src0, (int)vo0, i * img0, 0);
+                    A[i] = make_uint4(t0.x, t0.y, t0.z, t0.w);
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const v4u32 t1 = __builtin_amdgcn_raw_buffer_load_b128(xsrc, (int)vo1, i * x_img, 0);
+                    B[i] = make_uint4(t1.x, t1.y, t1.z, t1.w);
+                }
             }
             kt += a.ksplit;
         };
